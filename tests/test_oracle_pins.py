@@ -1,0 +1,439 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+* an independent numpy-slicing formulation of every layout (tests/textbook.py),
+* brute force over every element of tiny models (inverse maps, replica counts),
+* closed forms (parameter counts, pure-TP / pure-DP byte counts),
+* invariants (identity, round trip, region algebra of Section 4.2.1),
+* the worked example of Figure 4 (rank 3, (TP,PP) = (2,2) -> (4,1)).
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+import textbook
+from datagen import configs as cf
+from datagen import pattern
+
+P = cf.parallel
+
+LAYOUT_CASES = [
+    ("gpt-tp2dp2z1", cf.TINY_GPT, P(tp=2, dp=2, zero=1)),
+    ("gpt-tp1dp4z0", cf.TINY_GPT, P(tp=1, dp=4, zero=0)),
+    ("gpt-tp4pp2dp1", cf.TINY_GPT, P(tp=4, pp=2, dp=1, zero=1)),
+    ("gpt-tp2pp4dp3-blocked-rev", cf.TINY_GPT, P(tp=2, pp=4, dp=3, zero=1, qkv_layout=1, flat_order=1)),
+    ("gpt-odd-tp3pp3dp2", cf.ODD_GPT, P(tp=3, pp=3, dp=2, zero=1)),
+    ("gpt-odd-tp2dp5-blocked", cf.ODD_GPT, P(tp=2, pp=2, dp=5, zero=1, qkv_layout=1)),
+    ("gqa-tp4pp2dp2", cf.TINY_GQA, P(tp=4, pp=2, dp=2, zero=1)),
+    ("gqa-tp2pp1dp3-blocked", cf.TINY_GQA, P(tp=2, pp=1, dp=3, zero=1, qkv_layout=1)),
+    ("moe-ep4dp2pp2", cf.TINY_MOE, P(tp=1, pp=2, dp=2, ep=4, zero=1)),
+    ("moe-ep8dp1pp4-transposed", cf.TINY_MOE, P(tp=1, pp=4, dp=1, ep=8, zero=1, expert_layout=1)),
+    ("moe-tp2ep2dp2-transposed-rev", cf.TINY_MOE, P(tp=2, pp=1, dp=2, ep=2, zero=1, expert_layout=1, flat_order=1)),
+    ("moe-odd-ep3dp2pp2z0", cf.ODD_MOE, P(tp=1, pp=2, dp=2, ep=3, zero=0)),
+    ("moe-odd-tp2ep2dp3-blocked-transposed", cf.ODD_MOE, P(tp=2, pp=3, dp=3, ep=2, zero=1, qkv_layout=1, expert_layout=1)),
+]
+
+TRANSITIONS = [
+    ("gpt-zero-to-replicated", cf.TINY_GPT, P(tp=2, dp=2, zero=1), P(tp=1, dp=4, zero=0)),
+    ("gpt-tp-pp", cf.TINY_GPT, P(tp=4, pp=2, dp=1), P(tp=2, pp=4, dp=1)),
+    ("gpt-blocked-rev", cf.TINY_GPT, P(tp=2, pp=2, dp=2), P(tp=4, pp=1, dp=2, qkv_layout=1, flat_order=1)),
+    ("gpt-odd", cf.ODD_GPT, P(tp=3, pp=1, dp=2), P(tp=2, pp=3, dp=1, qkv_layout=1)),
+    ("gpt-world-grows", cf.TINY_GPT, P(tp=2, pp=2, dp=2), P(tp=4, pp=4, dp=1)),
+    ("gqa", cf.TINY_GQA, P(tp=4, pp=1, dp=2), P(tp=2, pp=2, dp=2, qkv_layout=1)),
+    ("moe-ep", cf.TINY_MOE, P(tp=1, pp=4, dp=2, ep=2), P(tp=1, pp=2, dp=2, ep=4)),
+    ("moe-transposed", cf.TINY_MOE, P(tp=2, pp=2, dp=1, ep=2), P(tp=1, pp=2, dp=2, ep=2, expert_layout=1)),
+    ("moe-odd", cf.ODD_MOE, P(tp=1, pp=2, dp=2, ep=3), P(tp=2, pp=1, dp=3, ep=2, expert_layout=1, flat_order=1)),
+]
+
+
+# ----------------------------------------------------------------------------- inventory
+
+def _closed_form_params(m):
+    h, d, q, kv, L, V = m["hidden"], m["head_dim"], m["q_heads"], m["kv_heads"], m["layers"], m["vocab"]
+    qkv = (q + 2 * kv) * d * h
+    if m["family"] == cf.FAMILY_GPT:
+        per = 2 * h + qkv + (q + 2 * kv) * d + h * q * d + h + 2 * h + 2 * m["ffn"] * h + m["ffn"] + h
+        return L * per + 2 * V * h + 2 * h
+    if m["family"] == cf.FAMILY_GQA:
+        return L * (2 * h + qkv + h * q * d + 3 * m["ffn"] * h) + 2 * V * h + h
+    E, ef = m["experts"], m["expert_ffn"]
+    return L * (2 * h + qkv + 2 * d + h * q * d + E * h + E * 3 * ef * h) + 2 * V * h + h
+
+
+@pytest.mark.parametrize("name,tensors,params", [
+    ("toy", 28, 2_104_320), ("gpt1p3b", 292, 1_414_647_808), ("gqa8b", 195, 8_030_261_248),
+    ("gqa70b", 483, 70_553_706_496), ("moe235b", 24_725, 235_093_634_560)])
+def test_inventory_matches_architecture_closed_form(name, tensors, params):
+    w = cf.WORKLOADS[name]
+    c = oracle.Config(w["model"], w["src"])
+    assert c.num_tensors == tensors
+    assert c.total_params == params == _closed_form_params(w["model"])
+    assert c.world == cf.world(w["src"])
+    assert oracle.Config(w["model"], w["dst"]).world == cf.world(w["dst"])
+
+
+def test_70b_replica_state_is_about_1p26_tb():
+    # Section 2.3 (C3): one DP replica of a 70B model in bf16-fp32 training holds about 1.26 TB
+    # (2 B param + 4 B grad + 4 B master + 4 B m + 4 B v per parameter).
+    w = cf.WORKLOADS["gqa70b"]
+    n = oracle.Config(w["model"], w["src"]).total_params
+    assert abs(n * 18 / 1.26e12 - 1) < 0.01
+    # Without gradients (collected before a switch) the migrated state is 14 B per parameter:
+    a = oracle.Config(w["model"], w["src"])
+    tot = 0
+    for pp in range(8):
+        for tp in range(8):
+            r = tp + 8 * (0 + 2 * pp)
+            tot += 2 * a.payload_elems(r, 0)
+            for dp in range(2):
+                rr = tp + 8 * (dp + 2 * pp)
+                tot += sum(4 * a.payload_elems(rr, k) for k in (1, 2, 3))
+    # norms are replicated over TP, so the sum is slightly above 14 B/param
+    assert tot == 14 * (n + 7 * 161 * 8192)  # 161 norm vectors, 7 extra TP copies each
+
+
+@pytest.mark.parametrize("bad", [P(tp=3), P(tp=16), P(pp=5), P(ep=2)])
+def test_indivisible_degrees_are_rejected(bad):
+    with pytest.raises(oracle.OracleError):
+        oracle.Config(cf.TINY_GPT, bad)
+    with pytest.raises(oracle.OracleError):
+        oracle.Config(cf.TINY_MOE, P(ep=3))
+
+
+# ----------------------------------------------------------------------------- layouts
+
+@pytest.mark.parametrize("name,m,p", LAYOUT_CASES, ids=[c[0] for c in LAYOUT_CASES])
+def test_fill_equals_textbook_layout(name, m, p):
+    """coord_P against numpy slicing, every slot of every rank and buffer."""
+    c = oracle.Config(m, p)
+    layout = textbook.address_layout(m, p)
+    assert c.world == cf.world(p)
+    seed = 0xABCDEF
+    for rank in range(c.world):
+        for buf in range(8):
+            tid, lin = layout[(rank, buf)]
+            assert c.buffer_elems(rank, buf) == tid.size
+            assert c.payload_elems(rank, buf) == int((tid >= 0).sum())
+            got = c.fill(rank, buf, seed, pad_word=0xA5A5A5A5)
+            want = np.full(tid.size, 0xA5A5A5A5 & (0xFFFF if buf % 4 == 0 else 0xFFFFFFFF), dtype=got.dtype)
+            for t in np.unique(tid[tid >= 0]):
+                sel = tid == t
+                want[sel] = pattern.word(seed, buf % 4, int(t), lin[sel].astype(np.uint64))
+            assert np.array_equal(got, want), (rank, buf)
+            with pytest.raises(IndexError):
+                c.coord(rank, buf, tid.size)
+
+
+@pytest.mark.parametrize("name,m,p", LAYOUT_CASES, ids=[c[0] for c in LAYOUT_CASES])
+def test_owners_is_inverse_of_coord_bruteforce(name, m, p):
+    """owners_P against the set of slots that the textbook layout gives; replica counts."""
+    c = oracle.Config(m, p)
+    layout = textbook.address_layout(m, p)
+    slots = {}
+    for (rank, buf), (tid, lin) in layout.items():
+        for pos in np.nonzero(tid >= 0)[0]:
+            slots.setdefault((buf % 4, int(tid[pos]), int(lin[pos])), []).append((rank, buf, int(pos)))
+    DDP = p["dp"] * p["ep"]
+    total = 0
+    for t in range(c.num_tensors):
+        info = c.tensor_info(t)
+        shape = info["shape"]
+        for kind in range(4):
+            D = DDP if info["group"] == 0 else p["dp"]
+            replicas = (p["tp"] if info["tp_axis"] < 0 else 1) * (1 if (kind and p["zero"]) else D)
+            step = 1 if kind in (0, 1) else 7  # kinds 2, 3 behave like kind 1: sample them
+            for lin_idx in range(0, int(np.prod(shape)), step):
+                cd = np.unravel_index(lin_idx, shape)
+                own = c.owners(kind, t, [int(x) for x in cd], max_owners=256)
+                assert c.linear(t, [int(x) for x in cd]) == lin_idx
+                assert len(own) == replicas
+                assert sorted(own) == sorted(slots[(kind, t, lin_idx)])
+                assert [o[0] for o in own] == sorted(o[0] for o in own)
+                for (r, b, o) in own[:2]:
+                    assert c.coord(r, b, o) == (t, tuple(int(x) for x in cd))
+                total += len(own)
+    assert total > 0
+
+
+# ----------------------------------------------------------------------------- transitions
+
+def _random_full(m, rng):
+    inv = textbook.inventory(m)
+    full = {}
+    for t, (shape, *_rest) in enumerate(inv):
+        n = int(np.prod(shape))
+        full[(0, t)] = rng.integers(0, 1 << 16, n, dtype=np.uint16)
+        for k in (1, 2, 3):
+            full[(k, t)] = rng.integers(0, 1 << 32, n, dtype=np.uint32)
+    return inv, full
+
+
+def _oracle_transition_all(a, b, src):
+    out = {}
+    for j in range(b.world):
+        for buf in range(8):
+            n = b.buffer_elems(j, buf)
+            dst = np.full(n, 0xA5A5, dtype=oracle.kind_dtype(buf))
+            if n:
+                oracle.transition(a, b, j, buf, src, dst)
+            out[(j, buf)] = dst
+    return out
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_transition_equals_assemble_then_slice(name, m, pa, pb):
+    """The per-element transition against the textbook reshard: gather every logical tensor
+    from the source shards, cut it again for the destination configuration."""
+    rng = np.random.default_rng(7)
+    inv, full = _random_full(m, rng)
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    la, lb = textbook.address_layout(m, pa), textbook.address_layout(m, pb)
+    src = textbook.scatter(full, la, oracle.kind_dtype, pad_word=0x5A5A)
+    again = textbook.assemble(src, la, inv)
+    for key in full:
+        assert np.array_equal(again[key], full[key])
+    want = textbook.scatter(full, lb, oracle.kind_dtype, pad_word=0xA5A5)
+    got = _oracle_transition_all(a, b, src)
+    for key in want:
+        assert np.array_equal(got[key], want[key]), key
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_expected_is_layout_b_fill_and_roundtrip(name, m, pa, pb):
+    """With coordinate-hash payloads: A->B gives the layout-B fill; A->B->A is the identity."""
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    seed = 99
+    srcA = {(r, buf): a.fill(r, buf, seed, pad_word=0x1111) for r in range(a.world) for buf in range(8)}
+    mid = _oracle_transition_all(a, b, srcA)
+    for j in range(b.world):
+        for buf in range(8):
+            fillB = b.fill(j, buf, seed, pad_word=0xA5A5)
+            assert np.array_equal(mid[(j, buf)], fillB)
+            assert np.array_equal(oracle.expected(a, b, j, buf, seed, pad_word=0xA5A5), fillB)
+    back = _oracle_transition_all(b, a, mid)
+    for r in range(a.world):
+        for buf in range(8):
+            pay = a.payload_elems(r, buf)
+            # payload identical, padding untouched by the transition
+            tid_ok = np.array([a.coord(r, buf, o) is not None for o in range(a.buffer_elems(r, buf))], dtype=bool)
+            assert int(tid_ok.sum()) == pay
+            assert np.array_equal(back[(r, buf)][tid_ok], srcA[(r, buf)][tid_ok])
+            assert (back[(r, buf)][~tid_ok] == 0xA5A5).all()
+
+
+@pytest.mark.parametrize("name,m,p", LAYOUT_CASES[:6] + LAYOUT_CASES[8:10], ids=[c[0] for c in LAYOUT_CASES[:6] + LAYOUT_CASES[8:10]])
+def test_identity_transition_moves_nothing(name, m, p):
+    """Only shards affected by the change move (Section 6.2): A->A retains everything."""
+    a = oracle.Config(m, p)
+    for j in range(a.world):
+        rb = oracle.route_bytes(a, a, j)
+        pay = sum(a.payload_elems(j, buf) * oracle.KIND_BYTES[buf % 4] for buf in range(8))
+        assert rb[j] == pay and rb.sum() == pay
+        sb = oracle.send_bytes(a, a, j)
+        assert sb[j] == pay and sb.sum() == pay
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_send_and_receive_byte_counts_agree(name, m, pa, pb):
+    """Buffer byte counts match on both sides: what i sends to j is what j takes from i, the
+    received plus retained volume is the destination payload."""
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    recv = np.stack([oracle.route_bytes(a, b, j) for j in range(b.world)])      # [j, i]
+    send = np.stack([oracle.send_bytes(a, b, i) for i in range(a.world)])       # [i, j]
+    assert np.array_equal(recv, send.T)
+    for j in range(b.world):
+        pay = sum(b.payload_elems(j, buf) * oracle.KIND_BYTES[buf % 4] for buf in range(8))
+        assert recv[j].sum() == pay
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_region_algebra_and_selection_rule(name, m, pa, pb):
+    """Section 4.2.1: per rank, T_retain = R_src & R_dst is exactly what is copied locally,
+    T_recv = R_dst - R_src is exactly what arrives from peers, T_send = R_src - R_dst never
+    stays.  The chosen source is always an owner; a same-node owner wins over a remote one."""
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    la, lb = textbook.address_layout(m, pa), textbook.address_layout(m, pb)
+
+    def region(layout, rank):
+        s = set()
+        for buf in range(8):
+            if (rank, buf) not in layout:
+                continue
+            tid, lin = layout[(rank, buf)]
+            ok = tid >= 0
+            s.update(zip(itertools.repeat(buf % 4), tid[ok].tolist(), lin[ok].tolist()))
+        return s
+
+    node = pa["gpus_per_node"]
+    for j in range(b.world):
+        r_dst = region(lb, j)
+        r_src = region(la, j) if j < a.world else set()
+        retained, received = set(), set()
+        for buf in range(8):
+            tid, lin = lb[(j, buf)]
+            for pos in np.nonzero(tid >= 0)[0][::3]:
+                t = int(tid[pos])
+                cd = [int(x) for x in np.unravel_index(int(lin[pos]), b.tensor_info(t)["shape"])]
+                own = a.owners(buf % 4, t, cd, max_owners=256)
+                r, sb, so = oracle.select_source(a, b, j, buf % 4, t, cd)
+                assert (r, sb, so) in own
+                owner_ranks = [o[0] for o in own]
+                if j in owner_ranks:
+                    assert r == j
+                elif any(o // node == j // node for o in owner_ranks):
+                    assert r // node == j // node
+                (retained if r == j else received).add((buf % 4, t, int(lin[pos])))
+        assert retained <= (r_src & r_dst)
+        assert received <= (r_dst - r_src)
+        assert not (retained & received)
+        assert (r_src - r_dst).isdisjoint(r_dst)
+
+
+# ----------------------------------------------------------------------------- closed forms
+
+def test_pure_tp_change_closed_form():
+    """TP 2 -> 4 on one pipeline stage, no DP: a column- or row-parallel tensor is cut into 4
+    pieces of numel/4; destination tp rank j takes its quarter from source tp rank j//2.
+    Replicated tensors come from the rule's pick among both source ranks."""
+    m = cf.TINY_GPT
+    a, b = oracle.Config(m, P(tp=2, zero=0)), oracle.Config(m, P(tp=4, zero=0))
+    sharded = sum(a.tensor_info(t)["tp_axis"] >= 0 and int(np.prod(a.tensor_info(t)["shape"])) for t in range(a.num_tensors))
+    repl = sum(a.tensor_info(t)["tp_axis"] < 0 and int(np.prod(a.tensor_info(t)["shape"])) for t in range(a.num_tensors))
+    per_elem = 2 + 3 * 4
+    for j in range(4):
+        rb = oracle.route_bytes(a, b, j)
+        want = np.zeros(2, dtype=np.uint64)
+        want[j // 2] += sharded // 4 * per_elem
+        # replicated: j in {0,1} owns them already; j in {2,3} has dp index 0 -> first owner
+        want[j if j < 2 else 0] += repl * per_elem
+        assert np.array_equal(rb, want)
+
+
+def test_pure_dp_change_with_zero_closed_form():
+    """DP 2 -> 4 with sharded fp32 state: volumes are overlaps of the even flat ranges."""
+    m = cf.TINY_GPT
+    a, b = oracle.Config(m, P(dp=2, zero=1)), oracle.Config(m, P(dp=4, zero=1))
+    L = a.total_params
+    la, lb = a.buffer_elems(0, 0), b.buffer_elems(0, 0)
+    assert la == -(-L // 16) * 16 and lb == -(-L // 32) * 32
+    for j in range(4):
+        rb = oracle.route_bytes(a, b, j, buf_mask=0b1110)
+        for i in range(2):
+            lo = max(i * la // 2, j * lb // 4)
+            hi = min((i + 1) * la // 2, (j + 1) * lb // 4, L)
+            assert rb[i] == 3 * 4 * max(0, hi - lo)
+        rb0 = oracle.route_bytes(a, b, j, buf_mask=0b0001)
+        src = j if j < 2 else j % 2  # owner itself, else owners[dp index mod 2]
+        assert rb0[src] == 2 * L and rb0.sum() == 2 * L
+
+
+def test_pure_pp_change_moves_whole_tensors():
+    m = cf.TINY_GPT
+    a, b = oracle.Config(m, P(pp=2, zero=0)), oracle.Config(m, P(pp=4, zero=0))
+    per = 2 + 12
+    sizes = [int(np.prod(a.tensor_info(t)["shape"])) for t in range(a.num_tensors)]
+    layer = [a.tensor_info(t)["layer"] for t in range(a.num_tensors)]
+    for j in range(4):
+        rb = oracle.route_bytes(a, b, j)
+        want = np.zeros(2, dtype=np.uint64)
+        for t, n in enumerate(sizes):
+            sa = 0 if layer[t] < 2 else 1          # 4 layers over 2 stages; embedding first, head last
+            sb = min(max(layer[t], 0), 3)
+            if sb == j:
+                want[sa] += n * per
+        assert np.array_equal(rb, want)
+
+
+# ----------------------------------------------------------------------------- worked examples
+
+def _peers(a, b, rank, tensor_filter):
+    """(sources rank receives from, destinations rank sends to) restricted to some tensors."""
+    srcs, dsts = set(), set()
+    for j in range(b.world):
+        for buf in range(8):
+            for off in range(b.buffer_elems(j, buf)):
+                e = b.coord(j, buf, off)
+                if e is None or not tensor_filter(e[0]):
+                    continue
+                r, _, _ = oracle.select_source(a, b, j, buf % 4, e[0], list(e[1]))
+                if j == rank:
+                    srcs.add(r)
+                if r == rank:
+                    dsts.add(j)
+    return srcs, dsts
+
+
+def test_figure4_worked_example_rank3():
+    """Figure 4: rank 3 switching (TP,PP) = (2,2) -> (4,1) has a non-empty send, retain and
+    receive set.  With TP as the fastest rank digit it holds the upper half of the stage-1
+    layers; afterwards the last quarter of every layer.  It therefore keeps the last quarter
+    of stage 1, sends the third quarter of stage 1 to rank 2 and receives the last quarter of
+    stage 0 from rank 1."""
+    m = cf.model(cf.FAMILY_GPT, 4, 8, 4, 4, 2, 16, 16)
+    a, b = oracle.Config(m, P(tp=2, pp=2, zero=0)), oracle.Config(m, P(tp=4, pp=1, zero=0))
+    sharded = lambda t: a.tensor_info(t)["tp_axis"] >= 0
+    srcs, dsts = _peers(a, b, 3, sharded)
+    assert srcs == {1, 3} and dsts == {2, 3}
+    rb = oracle.route_bytes(a, b, 3)
+    assert rb[3] > 0 and rb[1] > 0 and oracle.send_bytes(a, b, 3)[2] > 0
+    # the retained sharded part is exactly the stage-1 share of rank 3's new quarter
+    stage1 = sum(int(np.prod(a.tensor_info(t)["shape"])) // 4 for t in range(a.num_tensors)
+                 if sharded(t) and a.tensor_info(t)["layer"] >= 2)
+    stage0 = sum(int(np.prod(a.tensor_info(t)["shape"])) // 4 for t in range(a.num_tensors)
+                 if sharded(t) and a.tensor_info(t)["layer"] < 2)
+    repl1 = sum(int(np.prod(a.tensor_info(t)["shape"])) for t in range(a.num_tensors)
+                if not sharded(t) and a.tensor_info(t)["layer"] >= 2)
+    assert rb[3] == (stage1 + repl1) * 14
+    assert rb[1] == stage0 * 14
+
+
+def test_figure6_sharded_optimizer_same_transition():
+    """Figure 6: the same switch with two DP ranks and sharded optimizer state.  Both DP ranks
+    of a TP/PP position hold the same bf16 shard but disjoint halves of the fp32 flat buffer;
+    every half is routed to whichever rank owns those flat offsets afterwards."""
+    m = cf.model(cf.FAMILY_GPT, 4, 8, 4, 4, 2, 16, 16)
+    a = oracle.Config(m, P(tp=2, pp=2, dp=2, zero=1))
+    b = oracle.Config(m, P(tp=4, pp=1, dp=2, zero=1))
+    for tp in range(2):
+        for pp in range(2):
+            r0, r1 = tp + 2 * (0 + 2 * pp), tp + 2 * (1 + 2 * pp)
+            assert np.array_equal(a.fill(r0, 0, 5), a.fill(r1, 0, 5))            # same params
+            n = a.buffer_elems(r0, 1)
+            e0 = {a.coord(r0, 1, o) for o in range(n)} - {None}
+            e1 = {a.coord(r1, 1, o) for o in range(n)} - {None}
+            assert e0 and e1 and not (e0 & e1)                                   # slices 1 and 2
+    # every fp32 element has exactly one source and one destination; bytes are conserved
+    recv = np.stack([oracle.route_bytes(a, b, j, buf_mask=0b1110) for j in range(8)])
+    send = np.stack([oracle.send_bytes(a, b, i, buf_mask=0b1110) for i in range(8)])
+    assert np.array_equal(recv, send.T)
+    tp_repl = sum(int(np.prod(a.tensor_info(t)["shape"])) for t in range(a.num_tensors) if a.tensor_info(t)["tp_axis"] < 0)
+    assert recv.sum() == 12 * (a.total_params + 3 * tp_repl)   # TP-replicated tensors: 4 copies
+    # a flat half crosses tensor edges: some rank receives fp32 data from more than one peer
+    assert max(int((recv[j] > 0).sum()) for j in range(8)) >= 2
+
+
+def test_70b_mid_pipeline_rank_keeps_all_fp32_state():
+    """Special case of the 70B switch (TP8,PP8,DP2) -> (TP8,PP4,DP4): for a rank away from the
+    first and last stage the fp32 flat range covers the same five layers before and after,
+    so every fp32 element is retained.  Checked on sampled offsets."""
+    w = cf.WORKLOADS["gqa70b"]
+    a, b = oracle.Config(w["model"], w["src"]), oracle.Config(w["model"], w["dst"])
+    rng = np.random.default_rng(3)
+    j = 43
+    n = b.buffer_elems(j, 1)
+    assert n == a.buffer_elems(j, 1)
+    offs = np.concatenate([[0, 1, n - 2, n - 1], rng.integers(0, n, 3000)])
+    for off in offs:
+        e = b.coord(j, 1, int(off))
+        assert e is not None
+        r, sb, so = oracle.select_source(a, b, j, 1, e[0], list(e[1]))
+        assert (r, sb, so) == (j, 1, int(off))
+    # a first-stage rank is different: the embedding shifts its flat range off layer edges
+    j = 11
+    moved = 0
+    for off in rng.integers(0, b.buffer_elems(j, 1), 500):
+        e = b.coord(j, 1, int(off))
+        if e is not None and oracle.select_source(a, b, j, 1, e[0], list(e[1]))[0] != j:
+            moved += 1
+    assert moved > 0
