@@ -1,0 +1,198 @@
+/* vps.h - C ABI of the MI355X Virtual Parameter Space state-transition engine.
+ *
+ * The library implements the data path of a parallelism switch as described in the DynaTrain
+ * paper: every training-state tensor exists once in a global logical coordinate space (the
+ * VPS, Section 4.1); a parallel configuration P maps each rank to a region of that space
+ * (F_P, Section 4.1); a switch from configuration A to B is the set of intersections between
+ * source and destination regions (Section 4.2.1), including ZeRO flat-buffer shards mapped
+ * back into the same space (Section 4.2.2); outgoing slices are packed into one contiguous
+ * buffer per peer, exchanged, and unpacked into the new local layout (Algorithm 1, lines
+ * 7-8 and 17; Section 4.3 "Memory-Aware Contiguous Buffer").
+ *
+ * All mapping, planning and copying runs in HIP kernels on the current device.  The library
+ * never allocates payload memory: state buffers, send/receive buffers and scratch are owned
+ * by the caller (device memory), and must stay alive until the stream has executed the work.
+ *
+ * Conventions
+ *   state kinds     0 = bf16 parameters (2-byte words), 1 = fp32 master weights,
+ *                   2 = fp32 Adam m, 3 = fp32 Adam v (4-byte words).  Payload is opaque.
+ *   local buffers   every rank has 8 buffers, index = group*4 + kind; group 0 = dense
+ *                   tensors, group 1 = expert tensors.  Empty buffers have 0 bytes.
+ *   flat layout     per (rank, group) the local tensor shards are concatenated in tensor-id
+ *                   order without gaps and the tail is padded to a multiple of 8*D elements
+ *                   (D = data-parallel group size).  Kind 0 holds the whole padded buffer;
+ *                   kinds 1..3 hold the rank's 1/D range when zero_stage = 1.
+ *   ranks           rank = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp, DDP = EP*DP.
+ *   return values   0 on success, a negative vps_status otherwise; vps_last_error() returns
+ *                   a thread-local message.  Functions never throw and never synchronise the
+ *                   stream, except where stated.  On error no device work has been enqueued.
+ */
+#ifndef VPS_H
+#define VPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum vps_status {
+    VPS_OK = 0,
+    VPS_ERR_INVALID_ARG = -1,
+    VPS_ERR_INDIVISIBLE = -2,      /* a parallel degree does not divide the axis it shards */
+    VPS_ERR_RANK_RANGE = -3,
+    VPS_ERR_MODEL_MISMATCH = -4,   /* the two configurations describe different models */
+    VPS_ERR_SCRATCH_TOO_SMALL = -5,
+    VPS_ERR_OOM = -6,
+    VPS_ERR_HIP = -7               /* a HIP call failed (no device, launch error, ...) */
+} vps_status;
+
+enum { VPS_FAMILY_GPT = 0, VPS_FAMILY_GQA = 1, VPS_FAMILY_MOE = 2 };
+enum { VPS_NUM_KINDS = 4, VPS_NUM_BUFFERS = 8 };
+
+/* Model shape.  The tensor inventory follows from the family:
+ *   GPT  per layer ln1.w ln1.b qkv.w qkv.b proj.w proj.b ln2.w ln2.b fc1.w fc1.b fc2.w fc2.b
+ *   GQA  per layer in_norm qkv.w o.w post_norm gate_up.w down.w
+ *   MOE  per layer in_norm qkv.w q_norm k_norm o.w post_norm router.w, then per expert
+ *        gate_up.w down.w
+ * preceded by the word embedding and followed by the final norm(s) and the output layer.
+ * Tensor ids ascend in that order. */
+typedef struct vps_model_desc {
+    int32_t family, layers, hidden, q_heads, kv_heads, head_dim, ffn, vocab, experts, expert_ffn;
+} vps_model_desc;
+
+/* Parallel configuration.  World size = tp*pp*dp*ep; dp is the data-parallel degree of the
+ * expert group, dense tensors are replicated over dp*ep ranks. */
+typedef struct vps_parallel_desc {
+    int32_t tp, pp, dp, ep;
+    int32_t zero_stage;    /* 0 or 1 */
+    int32_t gpus_per_node; /* used by the replica source rule */
+    int32_t qkv_layout;    /* 0 interleaved per kv group, 1 blocked [all Q | all K | all V] */
+    int32_t expert_layout; /* 0 row-major, 1 transposed storage (gate_up as (h,2,f), down as (f,h)) */
+    int32_t flat_order;    /* 0 ascending tensor id, 1 descending */
+} vps_parallel_desc;
+
+typedef struct vps_config vps_config; /* a configuration mapped onto the VPS (device tables) */
+typedef struct vps_plan vps_plan;     /* the routing plan of one transition (device tables) */
+
+/* One piece of a rank's region: an axis-aligned box of one logical tensor that is stored as a
+ * strided block of one local buffer (Section 4.1, sub-VPS: resident regions with their local
+ * partition attributes). */
+typedef struct vps_piece {
+    int32_t tensor, rank, kind, buf;
+    int32_t lo[4], ext[4]; /* box in global coordinates (4-D, leading axes of extent 1) */
+    int64_t off;           /* element offset of the lo corner in the local buffer */
+    int64_t stride[4];     /* elements per unit step along each global axis */
+} vps_piece;
+
+/* One routed sub-box: the intersection of a source piece with a destination piece for which
+ * the source rank is the selected owner (Section 4.2.1; a retain entry when src_rank ==
+ * dst_rank).  send_pos/recv_pos are byte offsets of its payload (row-major in global axis
+ * order, 16-byte aligned) in the source rank's send buffer and the destination rank's
+ * receive buffer; both are UINT64_MAX for retained boxes or non-resident sides. */
+typedef struct vps_box {
+    int32_t tensor, kind, src_rank, dst_rank, src_buf, dst_buf;
+    int32_t lo[4], ext[4];
+    int64_t src_off, dst_off;             /* element offsets of the lo corner */
+    int64_t src_stride[4], dst_stride[4]; /* element strides per global axis */
+    uint64_t send_pos, recv_pos;
+} vps_box;
+
+typedef struct vps_plan_stats_t {
+    int64_t num_boxes, num_retain_boxes, num_send_boxes, num_recv_boxes;
+    int64_t num_pack_tiles, num_unpack_tiles, num_retain_tiles;
+    int64_t num_peers_out, num_peers_in; /* single-rank plans; 0 otherwise */
+    double plan_ms;                      /* host wall time of vps_plan_intersections */
+} vps_plan_stats_t;
+
+/* F_P (Section 4.1, Section 4.2.2): map configuration `par` of `model` onto the VPS.
+ * rank = -1 maps every rank (needed for planning); rank >= 0 keeps only that rank's pieces.
+ * Both descriptors are caller-owned host structs, copied on entry.  *out is library-owned;
+ * release with vps_config_destroy.  Synchronises the device internally.
+ * Errors: VPS_ERR_INVALID_ARG (null pointers, non-positive sizes), VPS_ERR_INDIVISIBLE,
+ * VPS_ERR_RANK_RANGE, VPS_ERR_HIP. */
+int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
+                        vps_config** out);
+
+/* Section 4.2.1 / 4.2.2: intersect the source and destination regions and resolve every
+ * destination element to exactly one source rank.  rank >= 0 plans the share of one rank (its
+ * retained, outgoing and incoming boxes; the rank index is used on both sides and must be
+ * < max(world_src, world_dst)); rank = -1 plans all ranks (all virtual ranks resident).
+ * Source rule for replicated data: the destination rank itself if it is an owner, else the
+ * owners on its node if any, else all owners; ascending; index = destination data-parallel
+ * index modulo count.  `stream` (hipStream_t) orders the device work; the call synchronises it
+ * before returning.  Both configs must have been described with rank = -1 for the same model
+ * (VPS_ERR_MODEL_MISMATCH otherwise).  *out is library-owned (vps_plan_destroy). */
+int vps_plan_intersections(const vps_config* src, const vps_config* dst, int32_t rank,
+                           void* stream, vps_plan** out);
+
+/* Algorithm 1 line 8 (PackData): copy every outgoing sub-box of `rank` from its old local
+ * buffers into its send buffer.  src_bufs: host array of 8 device pointers (entries of empty
+ * buffers may be NULL).  send_buf: device, >= send_total bytes (vps_plan_buffer_bytes), 16-byte
+ * aligned.  Peer segments are laid out in ascending peer order; inside a segment boxes are
+ * ordered by (kind 1,2,3,0; tensor id; lo corner), each row-major, each starting at a multiple
+ * of 16 bytes; pad bytes are not written.  rank must be the planned rank, or any source rank for
+ * an all-ranks plan. */
+int vps_pack(const vps_plan* plan, int32_t rank, const void* const* src_bufs, void* send_buf,
+             void* stream);
+
+/* Algorithm 1 line 17 (UnpackData): copy every incoming sub-box of `rank` from its receive
+ * buffer (same layout rules, segments in ascending source-rank order) into the new local
+ * buffers.  dst_bufs: host array of 8 device pointers.  Padding elements of dst are never
+ * written. */
+int vps_unpack(const vps_plan* plan, int32_t rank, const void* recv_buf, void* const* dst_bufs,
+               void* stream);
+
+/* Algorithm 1 lines 6-19 for the resident ranks, in one call: retained boxes are copied
+ * old-local -> new-local directly, outgoing boxes are packed, incoming ones unpacked.
+ *   single-rank plan: rank = planned rank; src_bufs/dst_bufs are 8 pointers each; scratch holds
+ *     [send buffer | receive buffer] at the offsets reported by vps_plan_buffer_bytes.  The
+ *     peers are not resident, so the receive part must already hold the peers' packed data.
+ *   all-ranks plan: rank = -1; src_bufs is [world_src][8], dst_bufs is [world_dst][8]; scratch
+ *     holds every rank's send buffer and the exchange is done by reading the peer's segment
+ *     in place.
+ * VPS_ERR_SCRATCH_TOO_SMALL if scratch_bytes < scratch_needed. */
+int vps_apply_transition(const vps_plan* plan, int32_t rank, const void* const* src_bufs,
+                         void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
+                         void* stream);
+
+/* ---- queries (host side, no device work unless stated) ---- */
+int vps_config_world(const vps_config* cfg, int32_t* world);
+int vps_config_num_tensors(const vps_config* cfg, int32_t* n);
+int vps_config_buffer_bytes(const vps_config* cfg, int32_t rank, int32_t buf, uint64_t* bytes);
+int vps_config_num_pieces(const vps_config* cfg, int64_t* n);
+/* Copies up to `max` pieces (ordered by tensor, kind, tp, dp index) to host memory. */
+int vps_config_get_pieces(const vps_config* cfg, vps_piece* out, int64_t max);
+
+/* Payload bytes (without alignment pad) that src_rank sends to dst_rank (retained volume when
+ * equal).  Pairs outside a single-rank plan report 0. */
+int vps_plan_pair_bytes(const vps_plan* plan, int32_t src_rank, int32_t dst_rank, uint64_t* bytes);
+/* As seen from `rank`: payload bytes it sends to and receives from `peer`. */
+int vps_plan_peer_bytes(const vps_plan* plan, int32_t rank, int32_t peer, uint64_t* send,
+                        uint64_t* recv);
+/* Buffer sizes of `rank` including alignment pad: send buffer, receive buffer, retained payload
+ * and the scratch size for vps_apply_transition (rank = -1: the all-ranks scratch).
+ * recv_offset_in_scratch is where the receive part starts for single-rank plans. */
+int vps_plan_buffer_bytes(const vps_plan* plan, int32_t rank, uint64_t* send_total,
+                          uint64_t* recv_total, uint64_t* retain_total, uint64_t* scratch_needed,
+                          uint64_t* recv_offset_in_scratch);
+/* Byte range of the segment src_rank -> dst_rank inside the sender's send buffer and the
+ * receiver's receive buffer (bytes includes alignment pad between boxes). */
+int vps_plan_peer_segment(const vps_plan* plan, int32_t src_rank, int32_t dst_rank,
+                          uint64_t* send_off, uint64_t* recv_off, uint64_t* bytes);
+int vps_plan_num_boxes(const vps_plan* plan, int64_t* n);
+int vps_plan_get_boxes(const vps_plan* plan, vps_box* out, int64_t max);
+int vps_plan_stats(const vps_plan* plan, vps_plan_stats_t* out);
+
+void vps_config_destroy(vps_config* cfg);
+void vps_plan_destroy(vps_plan* plan);
+const char* vps_last_error(void);
+
+/* Tuning knob for benchmarks: target payload bytes per workgroup tile (power of two between
+ * 4 KiB and 1 MiB; default 32 KiB).  Applies to plans created afterwards. */
+int vps_set_tile_bytes(uint32_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VPS_H */

@@ -1,0 +1,427 @@
+// vps_api_impl.h - the C entry points of include/vps.h, written over the backend interface.
+// Included exactly once by a translation unit that defines VPS_BACKEND (the backend class) and
+// VPS_FN(name) (the exported symbol name).  The product library uses the HIP backend and the
+// names of include/vps.h.
+#pragma once
+
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "vps_pipeline.h"
+
+namespace vps {
+
+static thread_local std::string g_last_error;
+static uint32_t g_tile_bytes = 32u << 10;
+
+inline int fail(int code, const std::string& msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+// Which pointer-table slots an operation dereferences, per plan.
+inline void mark_used_slots(const PlanData& p, std::vector<uint8_t> used[3])
+{
+    const int ns = num_slots(p.layout);
+    for (int op = 0; op < 3; ++op) used[op].assign((size_t)ns, 0);
+    for (const vps_box& b : p.boxes_send_order) {
+        const bool retained = b.src_rank == b.dst_rank;
+        const bool src_res = p.rank < 0 || b.src_rank == p.rank;
+        const bool dst_res = p.rank < 0 || b.dst_rank == p.rank;
+        if (retained && src_res) {
+            used[OP_RETAIN][(size_t)slot_src(p.layout, b.src_rank, b.src_buf)] = 1;
+            used[OP_RETAIN][(size_t)slot_dst(p.layout, b.dst_rank, b.dst_buf)] = 1;
+        }
+        if (!retained && src_res) {
+            used[OP_PACK][(size_t)slot_src(p.layout, b.src_rank, b.src_buf)] = 1;
+            used[OP_PACK][(size_t)slot_send(p.layout, b.src_rank)] = 1;
+        }
+        if (!retained && dst_res) {
+            used[OP_UNPACK][(size_t)slot_recv(p.layout, b.dst_rank)] = 1;
+            used[OP_UNPACK][(size_t)slot_dst(p.layout, b.dst_rank, b.dst_buf)] = 1;
+        }
+    }
+}
+
+}  // namespace vps
+
+struct vps_config {
+    vps::ConfigData d;
+};
+
+struct vps_plan {
+    vps::PlanData d;
+    std::vector<uint8_t> used[3];
+};
+
+#define VPS_TRY try {
+#define VPS_CATCH                                                            \
+    }                                                                        \
+    catch (const vps::Error& e) { return vps::fail(e.code, e.msg); }         \
+    catch (const std::bad_alloc&) { return vps::fail(VPS_ERR_OOM, "host allocation failed"); } \
+    catch (...) { return vps::fail(VPS_ERR_INVALID_ARG, "unexpected failure"); }
+
+extern "C" {
+
+const char* VPS_FN(last_error)(void) { return vps::g_last_error.c_str(); }
+
+int VPS_FN(set_tile_bytes)(uint32_t bytes)
+{
+    if (bytes < 4096 || bytes > (1u << 20) || (bytes & (bytes - 1)))
+        return vps::fail(VPS_ERR_INVALID_ARG, "tile bytes must be a power of two in [4 KiB, 1 MiB]");
+    vps::g_tile_bytes = bytes;
+    return VPS_OK;
+}
+
+int VPS_FN(describe_config)(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
+                            vps_config** out)
+{
+    if (!model || !par || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    VPS_TRY
+    vps_config* c = new vps_config();
+    VPS_BACKEND be(nullptr);
+    try {
+        vps::build_config(be, *model, *par, rank, c->d);
+    } catch (...) {
+        be.release_all();
+        delete c;
+        throw;
+    }
+    be.commit();
+    *out = c;
+    return VPS_OK;
+    VPS_CATCH
+}
+
+void VPS_FN(config_destroy)(vps_config* c)
+{
+    if (!c) return;
+    VPS_BACKEND be(nullptr);
+    vps::free_config(be, c->d);
+    delete c;
+}
+
+int VPS_FN(plan_intersections)(const vps_config* src, const vps_config* dst, int32_t rank, void* stream,
+                               vps_plan** out)
+{
+    if (!src || !dst || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    VPS_TRY
+    vps_plan* p = new vps_plan();
+    VPS_BACKEND be(stream);
+    try {
+        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, p->d);
+        vps::mark_used_slots(p->d, p->used);
+    } catch (...) {
+        be.release_all();
+        delete p;
+        throw;
+    }
+    be.commit();
+    *out = p;
+    return VPS_OK;
+    VPS_CATCH
+}
+
+void VPS_FN(plan_destroy)(vps_plan* p)
+{
+    if (!p) return;
+    VPS_BACKEND be(nullptr);
+    vps::free_plan(be, p->d);
+    delete p;
+}
+
+}  // extern "C"
+
+namespace vps {
+
+// Launch the tiles [t0, t1) with the given pointers.  ptrs has num_slots entries (host).
+template <class BE>
+int launch_ops(BE& be, const vps_plan* plan, int64_t t0, int64_t t1, const std::vector<void*>& ptrs,
+               int alias)
+{
+    if (t1 <= t0) return VPS_OK;
+    const PlanData& p = plan->d;
+    PtrArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    if (p.layout.all_ranks) {
+        be.set_ptr_table(p.ptr_table, ptrs.data(), (int)ptrs.size());
+        pa.tbl = (char* const*)p.ptr_table;
+    } else {
+        for (int s = 0; s < PT_INLINE; ++s) pa.inl[s] = (char*)ptrs[(size_t)s];
+    }
+    be.launch_copy(p.descs, p.tiles, t0, t1 - t0, pa, alias);
+    return VPS_OK;
+}
+
+inline int check_used(const vps_plan* plan, int op, int32_t rank, const std::vector<void*>& ptrs,
+                      bool alias)
+{
+    const PlanData& p = plan->d;
+    const std::vector<uint8_t>& u = plan->used[op];
+    for (size_t s = 0; s < u.size(); ++s) {
+        if (!u[s] || ptrs[s]) continue;
+        // a slot of another rank does not matter when only `rank` is launched
+        if (p.layout.all_ranks && rank >= 0) {
+            const int32_t nb = (p.layout.wa + p.layout.wb) * 8;
+            int32_t owner;
+            if ((int32_t)s < p.layout.wa * 8) owner = (int32_t)s / 8;
+            else if ((int32_t)s < nb) owner = ((int32_t)s - p.layout.wa * 8) / 8;
+            else if ((int32_t)s < nb + p.layout.wa) owner = (int32_t)s - nb;
+            else owner = (int32_t)s - nb - p.layout.wa;
+            if (owner != rank) continue;
+        }
+        if (alias && op == OP_UNPACK && (int32_t)s >= (p.layout.wa + p.layout.wb) * 8 + p.layout.wa) continue;
+        return fail(VPS_ERR_INVALID_ARG, "a buffer that the plan reads or writes is NULL (slot " + std::to_string(s) + ")");
+    }
+    return VPS_OK;
+}
+
+inline int check_rank_arg(const PlanData& p, int32_t rank, int32_t world, bool allow_all)
+{
+    if (p.rank >= 0) {
+        if (rank != p.rank) return fail(VPS_ERR_RANK_RANGE, "plan was made for another rank");
+        return VPS_OK;
+    }
+    if (rank == -1 && allow_all) return VPS_OK;
+    if (rank < 0 || rank >= world) return fail(VPS_ERR_RANK_RANGE, "rank outside the world");
+    return VPS_OK;
+}
+
+}  // namespace vps
+
+extern "C" {
+
+int VPS_FN(pack)(const vps_plan* plan, int32_t rank, const void* const* src_bufs, void* send_buf, void* stream)
+{
+    if (!plan || !src_bufs) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    const vps::PlanData& p = plan->d;
+    if (int rc = vps::check_rank_arg(p, rank, p.A.world, false)) return rc;
+    if ((uintptr_t)send_buf & 15) return vps::fail(VPS_ERR_INVALID_ARG, "send_buf must be 16-byte aligned");
+    std::vector<void*> ptrs((size_t)vps::num_slots(p.layout), nullptr);
+    if (rank < p.A.world) {
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_src(p.layout, rank, b)] = (void*)src_bufs[b];
+        ptrs[(size_t)vps::slot_send(p.layout, rank)] = send_buf;
+    }
+    if (int rc = vps::check_used(plan, vps::OP_PACK, rank, ptrs, false)) return rc;
+    int64_t t0, t1;
+    vps::plan_tile_range(p, vps::OP_PACK, p.rank >= 0 ? -1 : rank, t0, t1);
+    VPS_BACKEND be(stream);
+    return vps::launch_ops(be, plan, t0, t1, ptrs, 0);
+    VPS_CATCH
+}
+
+int VPS_FN(unpack)(const vps_plan* plan, int32_t rank, const void* recv_buf, void* const* dst_bufs, void* stream)
+{
+    if (!plan || !dst_bufs) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    const vps::PlanData& p = plan->d;
+    if (int rc = vps::check_rank_arg(p, rank, p.B.world, false)) return rc;
+    if ((uintptr_t)recv_buf & 15) return vps::fail(VPS_ERR_INVALID_ARG, "recv_buf must be 16-byte aligned");
+    std::vector<void*> ptrs((size_t)vps::num_slots(p.layout), nullptr);
+    if (rank < p.B.world) {
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_dst(p.layout, rank, b)] = dst_bufs[b];
+        ptrs[(size_t)vps::slot_recv(p.layout, rank)] = (void*)recv_buf;
+    }
+    if (int rc = vps::check_used(plan, vps::OP_UNPACK, rank, ptrs, false)) return rc;
+    int64_t t0, t1;
+    vps::plan_tile_range(p, vps::OP_UNPACK, p.rank >= 0 ? -1 : rank, t0, t1);
+    VPS_BACKEND be(stream);
+    return vps::launch_ops(be, plan, t0, t1, ptrs, 0);
+    VPS_CATCH
+}
+
+int VPS_FN(plan_buffer_bytes)(const vps_plan* plan, int32_t rank, uint64_t* send_total, uint64_t* recv_total,
+                              uint64_t* retain_total, uint64_t* scratch_needed, uint64_t* recv_offset)
+{
+    if (!plan) return vps::fail(VPS_ERR_INVALID_ARG, "null plan");
+    const vps::PlanData& p = plan->d;
+    const int32_t W = p.A.world > p.B.world ? p.A.world : p.B.world;
+    if (rank < -1 || rank >= W) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside both worlds");
+    if (p.rank >= 0 && rank != p.rank) return vps::fail(VPS_ERR_RANK_RANGE, "plan was made for another rank");
+    uint64_t s = 0, r = 0, k = 0, need = 0, roff = 0;
+    if (rank >= 0) {
+        s = p.send_base[(size_t)rank + 1] - p.send_base[(size_t)rank];
+        r = p.recv_base[(size_t)rank + 1] - p.recv_base[(size_t)rank];
+        if (rank < p.A.world && rank < p.B.world) k = p.pair_bytes[(size_t)rank * (size_t)p.B.world + (size_t)rank];
+        roff = (s + 255) & ~255ull;
+        need = roff + r;
+    } else {
+        s = p.send_base[(size_t)W];
+        r = p.recv_base[(size_t)W];
+        for (int32_t q = 0; q < p.A.world && q < p.B.world; ++q) k += p.pair_bytes[(size_t)q * (size_t)p.B.world + (size_t)q];
+        need = s;
+    }
+    if (send_total) *send_total = s;
+    if (recv_total) *recv_total = r;
+    if (retain_total) *retain_total = k;
+    if (scratch_needed) *scratch_needed = need;
+    if (recv_offset) *recv_offset = roff;
+    return VPS_OK;
+}
+
+int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* const* src_bufs,
+                             void* const* dst_bufs, void* scratch, uint64_t scratch_bytes, void* stream)
+{
+    if (!plan || !src_bufs || !dst_bufs) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    const vps::PlanData& p = plan->d;
+    if (p.rank >= 0 ? rank != p.rank : rank != -1)
+        return vps::fail(VPS_ERR_RANK_RANGE, "rank must be the planned rank (or -1 for an all-ranks plan)");
+    uint64_t s, r, k, need, roff;
+    VPS_FN(plan_buffer_bytes)(plan, rank, &s, &r, &k, &need, &roff);
+    if (scratch_bytes < need) return vps::fail(VPS_ERR_SCRATCH_TOO_SMALL, "scratch smaller than scratch_needed");
+    if (need && (!scratch || ((uintptr_t)scratch & 15))) return vps::fail(VPS_ERR_INVALID_ARG, "scratch must be a 16-byte aligned device pointer");
+    const vps::PtrLayout& L = p.layout;
+    std::vector<void*> ptrs((size_t)vps::num_slots(L), nullptr);
+    const int64_t n = p.nboxes;
+    VPS_BACKEND be(stream);
+    if (p.rank >= 0) {
+        for (int b = 0; b < 8; ++b) {
+            ptrs[(size_t)vps::slot_src(L, rank, b)] = (void*)src_bufs[b];
+            ptrs[(size_t)vps::slot_dst(L, rank, b)] = dst_bufs[b];
+        }
+        ptrs[(size_t)vps::slot_send(L, rank)] = scratch;
+        ptrs[(size_t)vps::slot_recv(L, rank)] = (char*)scratch + roff;
+        for (int op = 0; op < 3; ++op)
+            if (int rc = vps::check_used(plan, op, rank, ptrs, false)) return rc;
+        // the three operations touch disjoint destinations: one launch over every tile
+        return vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(3 * n)], ptrs, 0);
+    }
+    for (int32_t q = 0; q < p.A.world; ++q) {
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_src(L, q, b)] = (void*)src_bufs[(size_t)q * 8 + b];
+        ptrs[(size_t)vps::slot_send(L, q)] = (char*)scratch + p.send_base[(size_t)q];
+    }
+    for (int32_t q = 0; q < p.B.world; ++q)
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_dst(L, q, b)] = dst_bufs[(size_t)q * 8 + b];
+    for (int op = 0; op < 3; ++op)
+        if (int rc = vps::check_used(plan, op, -1, ptrs, true)) return rc;
+    // retain + pack for every rank, then unpack straight out of the senders' segments
+    if (int rc = vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(2 * n)], ptrs, 0)) return rc;
+    return vps::launch_ops(be, plan, p.tile_base[(size_t)(2 * n)], p.tile_base[(size_t)(3 * n)], ptrs, 1);
+    VPS_CATCH
+}
+
+int VPS_FN(config_world)(const vps_config* c, int32_t* world)
+{
+    if (!c || !world) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *world = c->d.P.world;
+    return VPS_OK;
+}
+
+int VPS_FN(config_num_tensors)(const vps_config* c, int32_t* n)
+{
+    if (!c || !n) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *n = c->d.P.nt;
+    return VPS_OK;
+}
+
+int VPS_FN(config_buffer_bytes)(const vps_config* c, int32_t rank, int32_t buf, uint64_t* bytes)
+{
+    if (!c || !bytes) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    if (rank < 0 || rank >= c->d.P.world) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
+    if (buf < 0 || buf >= 8) return vps::fail(VPS_ERR_INVALID_ARG, "buffer index must be 0..7");
+    *bytes = vps::config_buffer_elems(c->d, rank, buf) * vps::kind_bytes(buf % 4);
+    return VPS_OK;
+}
+
+int VPS_FN(config_num_pieces)(const vps_config* c, int64_t* n)
+{
+    if (!c || !n) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *n = c->d.npieces;
+    return VPS_OK;
+}
+
+int VPS_FN(config_get_pieces)(const vps_config* c, vps_piece* out, int64_t max)
+{
+    if (!c || (!out && max > 0)) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    VPS_BACKEND be(nullptr);
+    const int64_t n = max < c->d.npieces ? max : c->d.npieces;
+    if (n > 0) be.download(out, c->d.pieces, sizeof(vps_piece) * (size_t)n);
+    return VPS_OK;
+    VPS_CATCH
+}
+
+int VPS_FN(plan_pair_bytes)(const vps_plan* plan, int32_t src_rank, int32_t dst_rank, uint64_t* bytes)
+{
+    if (!plan || !bytes) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    const vps::PlanData& p = plan->d;
+    if (src_rank < 0 || src_rank >= p.A.world || dst_rank < 0 || dst_rank >= p.B.world)
+        return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
+    *bytes = p.pair_bytes[(size_t)src_rank * (size_t)p.B.world + (size_t)dst_rank];
+    return VPS_OK;
+}
+
+int VPS_FN(plan_peer_bytes)(const vps_plan* plan, int32_t rank, int32_t peer, uint64_t* send, uint64_t* recv)
+{
+    if (!plan) return vps::fail(VPS_ERR_INVALID_ARG, "null plan");
+    const vps::PlanData& p = plan->d;
+    const int32_t W = p.A.world > p.B.world ? p.A.world : p.B.world;
+    if (rank < 0 || rank >= W || peer < 0 || peer >= W) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside both worlds");
+    uint64_t s = 0, r = 0;
+    if (rank < p.A.world && peer < p.B.world) s = p.pair_bytes[(size_t)rank * (size_t)p.B.world + (size_t)peer];
+    if (peer < p.A.world && rank < p.B.world) r = p.pair_bytes[(size_t)peer * (size_t)p.B.world + (size_t)rank];
+    if (send) *send = s;
+    if (recv) *recv = r;
+    return VPS_OK;
+}
+
+int VPS_FN(plan_peer_segment)(const vps_plan* plan, int32_t src_rank, int32_t dst_rank, uint64_t* send_off,
+                              uint64_t* recv_off, uint64_t* bytes)
+{
+    if (!plan) return vps::fail(VPS_ERR_INVALID_ARG, "null plan");
+    const vps::PlanData& p = plan->d;
+    if (src_rank < 0 || src_rank >= p.A.world || dst_rank < 0 || dst_rank >= p.B.world)
+        return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
+    uint64_t so = UINT64_MAX, ro = UINT64_MAX, nb = 0;
+    if (src_rank != dst_rank) {
+        // boxes are sorted by (src, dst, ...): binary search the pair's range
+        const std::vector<vps_box>& bx = p.boxes_send_order;
+        auto key = [](const vps_box& b) { return ((uint64_t)b.src_rank << 32) | (uint32_t)b.dst_rank; };
+        const uint64_t want = ((uint64_t)src_rank << 32) | (uint32_t)dst_rank;
+        size_t lo = 0, hi = bx.size();
+        while (lo < hi) { size_t mid = (lo + hi) / 2; if (key(bx[mid]) < want) lo = mid + 1; else hi = mid; }
+        size_t end = lo;
+        while (end < bx.size() && key(bx[end]) == want) ++end;
+        if (end > lo) {
+            const vps_box& f = bx[lo];
+            const vps_box& l = bx[end - 1];
+            so = f.send_pos; ro = f.recv_pos;
+            if (f.send_pos != UINT64_MAX) nb = l.send_pos + vps::box_slot_bytes(l) - f.send_pos;
+            else if (f.recv_pos != UINT64_MAX) nb = l.recv_pos + vps::box_slot_bytes(l) - f.recv_pos;
+        }
+    }
+    if (send_off) *send_off = so;
+    if (recv_off) *recv_off = ro;
+    if (bytes) *bytes = nb;
+    return VPS_OK;
+}
+
+int VPS_FN(plan_num_boxes)(const vps_plan* plan, int64_t* n)
+{
+    if (!plan || !n) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *n = plan->d.nboxes;
+    return VPS_OK;
+}
+
+int VPS_FN(plan_get_boxes)(const vps_plan* plan, vps_box* out, int64_t max)
+{
+    if (!plan || (!out && max > 0)) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    const int64_t n = max < plan->d.nboxes ? max : plan->d.nboxes;
+    if (n > 0) memcpy(out, plan->d.boxes_send_order.data(), sizeof(vps_box) * (size_t)n);
+    return VPS_OK;
+}
+
+int VPS_FN(plan_stats)(const vps_plan* plan, vps_plan_stats_t* out)
+{
+    if (!plan || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *out = plan->d.stats;
+    return VPS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,628 @@
+// vps_core.h - per-item arithmetic of the mapper, the planner and the copy engine.
+//
+// Every function here handles one work item (one tensor shard, one piece pair, one copy
+// slot) and is callable from a HIP kernel lane.  The same source also compiles as plain C++
+// so that bounds and index logic can be exercised in a CPU build by the test-suite; the
+// product library only ever runs it on the device.
+//
+// Paper references: the VPS and F_P (DynaTrain Section 4.1), region intersection and
+// send/retain/receive classification (Section 4.2.1), inversion of ZeRO flat-buffer shards
+// into VPS sub-regions (Section 4.2.2), per-peer contiguous buffers (Section 4.3).
+#pragma once
+
+#include <stdint.h>
+
+#include "../../include/vps.h"
+
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define VPS_HD __host__ __device__ inline
+#else
+#define VPS_HD inline
+#endif
+
+namespace vps {
+
+enum { PERM_NONE = 0, PERM_GATE_UP = 1, PERM_DOWN = 2 };
+
+// One logical tensor of the VPS: complete unsharded shape plus its position attributes
+// (layer, expert, group) and partitioning attributes (TP axis, fused-QKV slot axis, which
+// transposed storage applies).  Section 4.1.
+struct TensorRec {
+    int32_t shape[4];
+    int8_t tp_axis;   // -1: replicated over TP
+    int8_t group;     // 0 dense, 1 expert
+    int8_t blk_axis;  // axis holding the Q/K/V slot index of a fused QKV tensor, or -1
+    int8_t perm;      // PERM_*
+    int32_t layer;    // -1 before the first layer, `layers` after the last
+    int32_t expert;   // -1 or expert id
+};
+
+// Constants of one parallel configuration, passed to kernels by value.
+struct ParConst {
+    int32_t tp, pp, dp, ep, zero, gpn, qkv_layout, expert_layout, flat_order;
+    int32_t ddp;      // dense data-parallel degree = dp*ep
+    int32_t world;    // tp*pp*ddp
+    int32_t layers, experts, q_per_g;
+    int32_t nt;       // logical tensors
+    int32_t ncls;     // flat-buffer classes: pp dense + pp*ep expert
+};
+
+// Where a tensor's local shard sits in the flat buffer of the ranks that hold it.
+struct TensorLayout {
+    uint64_t start;      // offset in the unsharded flat buffer
+    uint64_t shard_len;  // elements of one local shard
+    int32_t cls;         // flat-buffer class: dense -> pp, expert -> PP + pp*EP + ep
+    int32_t pad_;
+};
+
+struct ClassRec {
+    uint64_t len;     // unpadded flat length
+    uint64_t padded;  // rounded up to 8*D
+};
+
+struct RankCoord {
+    int32_t tp, ddp, pp, ep, edp;
+};
+
+VPS_HD RankCoord decode_rank(const ParConst& P, int32_t r)
+{
+    RankCoord c;
+    c.tp = r % P.tp;
+    const int32_t q = r / P.tp;
+    c.ddp = q % P.ddp;
+    c.pp = q / P.ddp;
+    c.ep = c.ddp % P.ep;
+    c.edp = c.ddp / P.ep;
+    return c;
+}
+
+VPS_HD int32_t encode_rank(const ParConst& P, int32_t tp, int32_t ddp, int32_t pp)
+{
+    return tp + P.tp * (ddp + P.ddp * pp);
+}
+
+// Pipeline stage of a layer when stage p owns layers [floor(p*L/PP), floor((p+1)*L/PP)):
+// the largest p with p*L/PP < layer+1.  The embedding (-1) is on the first stage, everything
+// after the last layer on the last one.
+VPS_HD int32_t stage_of_layer(const ParConst& P, int32_t layer)
+{
+    if (layer < 0) return 0;
+    if (layer >= P.layers) return P.pp - 1;
+    return (int32_t)((((int64_t)layer + 1) * P.pp + P.layers - 1) / P.layers) - 1;
+}
+
+VPS_HD int32_t class_of_tensor(const ParConst& P, const TensorRec& x)
+{
+    const int32_t pp = stage_of_layer(P, x.layer);
+    if (x.group == 0) return pp;
+    return P.pp + pp * P.ep + x.expert / (P.experts / P.ep);
+}
+
+VPS_HD uint64_t numel4(const int32_t* s)
+{
+    return (uint64_t)s[0] * (uint64_t)s[1] * (uint64_t)s[2] * (uint64_t)s[3];
+}
+
+VPS_HD uint64_t shard_elems(const ParConst& P, const TensorRec& x)
+{
+    return numel4(x.shape) / (uint64_t)(x.tp_axis >= 0 ? P.tp : 1);
+}
+
+// ------------------------------------------------------------------------------------------
+// Mapper: one item per (tensor, kind, tp index, data-parallel index).
+// ------------------------------------------------------------------------------------------
+
+struct MapCtx {
+    ParConst P;
+    const TensorRec* T;
+    const TensorLayout* TL;
+    const ClassRec* C;
+    int32_t rank_filter;  // -1: all ranks
+};
+
+VPS_HD int64_t map_num_items(const ParConst& P) { return (int64_t)P.nt * 4 * P.tp * P.ddp; }
+
+VPS_HD int64_t map_group_item(const ParConst& P, int32_t tensor, int32_t kind)
+{
+    return ((int64_t)tensor * 4 + kind) * P.tp * P.ddp;
+}
+
+// Cut the linear range [v0, v1) of a row-major array with dimensions n[0..3] into the
+// canonical minimal set of boxes (at most 7): climb to coarser axes while the position is
+// aligned and the unit still fits, descend again near the end.  Calls emit(start, axis, count)
+// for each box: it begins at linear position `start`, spans `count` units of `axis` and is
+// full on all finer axes.
+template <class Emit>
+VPS_HD int split_linear_range(const int64_t* n, uint64_t v0, uint64_t v1, Emit emit)
+{
+    uint64_t st[4];
+    st[3] = 1;
+    st[2] = (uint64_t)n[3];
+    st[1] = st[2] * (uint64_t)n[2];
+    st[0] = st[1] * (uint64_t)n[1];
+    int count = 0;
+    uint64_t cur = v0;
+    while (cur < v1) {
+        int q = 3;
+        while (q > 0 && cur % st[q - 1] == 0 && cur + st[q - 1] <= v1) --q;
+        const uint64_t cq = (cur / st[q]) % (uint64_t)n[q];
+        uint64_t cnt = (uint64_t)n[q] - cq;
+        const uint64_t fit = (v1 - cur) / st[q];
+        if (fit < cnt) cnt = fit;
+        emit(cur, q, cnt);
+        cur += cnt * st[q];
+        ++count;
+    }
+    return count;
+}
+
+// Pieces of one (tensor, kind, tp, dp-index) item: the part of the local shard that lies in
+// the rank's flat range, as boxes in global coordinates with local offsets and strides.
+// Returns the number of pieces; writes them when out != nullptr.
+VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
+{
+    const ParConst& P = c.P;
+    const int32_t didx = (int32_t)(item % P.ddp);
+    int64_t r = item / P.ddp;
+    const int32_t tp = (int32_t)(r % P.tp);
+    r /= P.tp;
+    const int32_t kind = (int32_t)(r % 4);
+    const int32_t t = (int32_t)(r / 4);
+    const TensorRec x = c.T[t];
+    const int32_t D = x.group ? P.dp : P.ddp;
+    if (didx >= D) return 0;
+    const int32_t pp = stage_of_layer(P, x.layer);
+    const int32_t ddp = x.group ? x.expert / (P.experts / P.ep) + P.ep * didx : didx;
+    const int32_t rank = encode_rank(P, tp, ddp, pp);
+    if (c.rank_filter >= 0 && rank != c.rank_filter) return 0;
+
+    const TensorLayout tl = c.TL[t];
+    const ClassRec cl = c.C[tl.cls];
+    const bool sharded = P.zero == 1 && kind != 0;
+    const uint64_t per = cl.padded / (uint64_t)D;
+    const uint64_t r0 = sharded ? per * (uint64_t)didx : 0;
+    const uint64_t r1 = sharded ? r0 + per : cl.padded;
+    const uint64_t f0 = tl.start > r0 ? tl.start : r0;
+    const uint64_t fe = tl.start + tl.shard_len;
+    const uint64_t f1 = fe < r1 ? fe : r1;
+    if (f0 >= f1) return 0;
+    const uint64_t u0 = f0 - tl.start, u1 = f1 - tl.start;
+
+    // the shard's box in global coordinates
+    int32_t slo[4], sext[4];
+    for (int a = 0; a < 4; ++a) { slo[a] = 0; sext[a] = x.shape[a]; }
+    if (x.tp_axis >= 0) {
+        sext[x.tp_axis] = x.shape[x.tp_axis] / P.tp;
+        slo[x.tp_axis] = tp * sext[x.tp_axis];
+    }
+    // storage order of the axes, outermost first
+    int order[4] = { 0, 1, 2, 3 };
+    if (P.expert_layout == 1 && x.perm == PERM_GATE_UP) { order[1] = 3; order[2] = 1; order[3] = 2; }
+    if (P.expert_layout == 1 && x.perm == PERM_DOWN) { order[2] = 3; order[3] = 2; }
+    const bool blocked = x.blk_axis >= 0 && P.qkv_layout == 1;
+    const int nblk = blocked ? 3 : 1;
+
+    int npieces = 0;
+    uint64_t bbase = 0;
+    for (int b = 0; b < nblk; ++b) {
+        int32_t bo = 0, bl = 0;
+        if (blocked) {
+            bo = b == 0 ? 0 : (b == 1 ? P.q_per_g : P.q_per_g + 1);
+            bl = b == 0 ? P.q_per_g : 1;
+        }
+        int64_t n[4];
+        for (int q = 0; q < 4; ++q) n[q] = (blocked && order[q] == x.blk_axis) ? bl : sext[order[q]];
+        const uint64_t bvol = (uint64_t)n[0] * (uint64_t)n[1] * (uint64_t)n[2] * (uint64_t)n[3];
+        const uint64_t lo = u0 > bbase ? u0 : bbase;
+        const uint64_t hi = u1 < bbase + bvol ? u1 : bbase + bvol;
+        if (lo < hi) {
+            int64_t st[4];
+            st[3] = 1; st[2] = n[3]; st[1] = n[3] * n[2]; st[0] = n[3] * n[2] * n[1];
+            int k = npieces;
+            npieces += split_linear_range(n, lo - bbase, hi - bbase,
+                [&](uint64_t start, int axis, uint64_t cnt) {
+                    if (!out) return;
+                    vps_piece& p = out[k++];
+                    p.tensor = t; p.rank = rank; p.kind = kind; p.buf = x.group * 4 + kind;
+                    uint64_t rem = start;
+                    for (int q = 0; q < 4; ++q) {
+                        const int a = order[q];
+                        const int64_t cq = (int64_t)(rem / (uint64_t)st[q]);
+                        rem -= (uint64_t)cq * (uint64_t)st[q];
+                        p.lo[a] = slo[a] + ((blocked && a == x.blk_axis) ? bo : 0) + (int32_t)cq;
+                        p.ext[a] = q < axis ? 1 : (q == axis ? (int32_t)cnt : (int32_t)n[q]);
+                        p.stride[a] = st[q];
+                    }
+                    p.off = (int64_t)(tl.start + bbase + start - r0);
+                });
+        }
+        bbase += bvol;
+    }
+    return npieces;
+}
+
+// ------------------------------------------------------------------------------------------
+// Planner: one item per destination piece; it walks the source pieces of the same
+// (tensor, kind).
+// ------------------------------------------------------------------------------------------
+
+// The source rank selected for destination rank j among the ranks that hold the same data as
+// source rank i (i's TP replicas when the tensor is TP-replicated, i's data-parallel replicas
+// when the kind is not ZeRO-sharded).  Rule: j itself if it is among them; else those on j's
+// node if any, else all; in ascending rank order take index (data-parallel index of j under
+// the destination configuration) modulo count.  Section 4.3 asks for a proximity-based choice;
+// the tie-break is a convention of this library.
+VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const TensorRec& x,
+                                  int32_t kind, int32_t i, int32_t j)
+{
+    const RankCoord ci = decode_rank(A, i);
+    const bool sharded = A.zero == 1 && kind != 0;
+    const int32_t D = x.group ? A.dp : A.ddp;
+    const int32_t di = x.group ? ci.edp : ci.ddp;
+    const int32_t t0 = x.tp_axis < 0 ? 0 : ci.tp, t1 = x.tp_axis < 0 ? A.tp : ci.tp + 1;
+    const int32_t d0 = sharded ? di : 0, d1 = sharded ? di + 1 : D;
+    const int32_t node = j / A.gpn;
+    int32_t n_all = 0, n_node = 0;
+    for (int32_t d = d0; d < d1; ++d) {
+        const int32_t ddp = x.group ? ci.ep + A.ep * d : d;
+        for (int32_t tp = t0; tp < t1; ++tp) {
+            const int32_t r = encode_rank(A, tp, ddp, ci.pp);
+            if (r == j) return j;
+            ++n_all;
+            if (r / A.gpn == node) ++n_node;
+        }
+    }
+    const RankCoord cj = decode_rank(B, j);
+    const int32_t dpj = x.group ? cj.edp : cj.ddp;
+    const bool local = n_node > 0;
+    int32_t want = dpj % (local ? n_node : n_all);
+    for (int32_t d = d0; d < d1; ++d) {
+        const int32_t ddp = x.group ? ci.ep + A.ep * d : d;
+        for (int32_t tp = t0; tp < t1; ++tp) {
+            const int32_t r = encode_rank(A, tp, ddp, ci.pp);
+            if (local && r / A.gpn != node) continue;
+            if (want-- == 0) return r;
+        }
+    }
+    return -1;
+}
+
+struct PlanCtx {
+    ParConst A, B;
+    const TensorRec* T;
+    const vps_piece* SP;       // source pieces, grouped by (tensor, kind)
+    const vps_piece* DP;       // destination pieces
+    const int64_t* sbase;      // source piece index of every mapper item (exclusive scan)
+    int32_t rank;              // planned rank or -1
+};
+
+VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t d, vps_box* out)
+{
+    const vps_piece dp = c.DP[d];
+    const int64_t sa = c.sbase[map_group_item(c.A, dp.tensor, dp.kind)];
+    const int64_t sb = c.sbase[map_group_item(c.A, dp.tensor, dp.kind) + (int64_t)c.A.tp * c.A.ddp];
+    const TensorRec x = c.T[dp.tensor];
+    int n = 0;
+    for (int64_t s = sa; s < sb; ++s) {
+        const vps_piece sp = c.SP[s];
+        if (c.rank >= 0 && sp.rank != c.rank && dp.rank != c.rank) continue;
+        int32_t lo[4], ext[4];
+        bool empty = false;
+        for (int a = 0; a < 4; ++a) {
+            const int32_t l = sp.lo[a] > dp.lo[a] ? sp.lo[a] : dp.lo[a];
+            const int32_t hs = sp.lo[a] + sp.ext[a], hd = dp.lo[a] + dp.ext[a];
+            const int32_t h = hs < hd ? hs : hd;
+            if (l >= h) empty = true;
+            lo[a] = l; ext[a] = h - l;
+        }
+        if (empty) continue;
+        if (select_source_rank(c.A, c.B, x, dp.kind, sp.rank, dp.rank) != sp.rank) continue;
+        if (out) {
+            vps_box& b = out[n];
+            b.tensor = dp.tensor; b.kind = dp.kind;
+            b.src_rank = sp.rank; b.dst_rank = dp.rank;
+            b.src_buf = sp.buf; b.dst_buf = dp.buf;
+            b.src_off = sp.off; b.dst_off = dp.off;
+            for (int a = 0; a < 4; ++a) {
+                b.lo[a] = lo[a]; b.ext[a] = ext[a];
+                b.src_stride[a] = sp.stride[a]; b.dst_stride[a] = dp.stride[a];
+                b.src_off += (int64_t)(lo[a] - sp.lo[a]) * sp.stride[a];
+                b.dst_off += (int64_t)(lo[a] - dp.lo[a]) * dp.stride[a];
+            }
+            b.send_pos = UINT64_MAX; b.recv_pos = UINT64_MAX;
+        }
+        ++n;
+    }
+    return n;
+}
+
+VPS_HD uint64_t box_volume(const vps_box& b)
+{
+    return (uint64_t)b.ext[0] * (uint64_t)b.ext[1] * (uint64_t)b.ext[2] * (uint64_t)b.ext[3];
+}
+
+VPS_HD uint32_t kind_bytes(int32_t kind) { return kind == 0 ? 2u : 4u; }
+
+// Payload bytes of a box inside a peer buffer: every box starts on a 16-byte boundary.
+VPS_HD uint64_t box_slot_bytes(const vps_box& b)
+{
+    return (box_volume(b) * kind_bytes(b.kind) + 15ull) & ~15ull;
+}
+
+// Order inside a peer buffer: kinds 1,2,3 then 0; tensor id; lo corner in row-major order.
+VPS_HD uint64_t box_major_key(const vps_box& b, bool by_dst)
+{
+    const uint64_t first = (uint64_t)(by_dst ? b.dst_rank : b.src_rank);
+    const uint64_t second = (uint64_t)(by_dst ? b.src_rank : b.dst_rank);
+    const uint64_t korder = (uint64_t)((b.kind + 3) & 3);
+    return (((first << 16 | second) << 2 | korder) << 24) | (uint64_t)b.tensor;
+}
+
+VPS_HD uint64_t box_minor_key(const vps_box& b, const TensorRec& x)
+{
+    return (((uint64_t)b.lo[0] * (uint64_t)x.shape[1] + (uint64_t)b.lo[1]) * (uint64_t)x.shape[2] +
+            (uint64_t)b.lo[2]) * (uint64_t)x.shape[3] + (uint64_t)b.lo[3];
+}
+
+// ------------------------------------------------------------------------------------------
+// Copy engine: strided box -> strided box, descriptor driven.
+// ------------------------------------------------------------------------------------------
+
+enum { OP_RETAIN = 0, OP_PACK = 1, OP_UNPACK = 2 };
+enum { MODE_RUN = 0, MODE_ELEM = 1, MODE_XPOSE = 2 };
+
+// Pointer table slots of a single-rank plan.  All-ranks plans use
+// [src: rank*8+buf][dst: WA*8 + rank*8+buf][send: (WA+WB)*8 + rank][recv: (WA+WB)*8 + WA + rank].
+enum { PT_SRC = 0, PT_DST = 8, PT_SEND = 16, PT_RECV = 17, PT_INLINE = 18 };
+
+struct CopyDesc {
+    uint64_t src_byte;    // byte offset of the first element in its buffer
+    uint64_t dst_byte;
+    int64_t sstr[4];      // element strides after axis collapse (outer -> inner)
+    int64_t dstr[4];
+    uint32_t ext[4];
+    int32_t src_slot;     // pointer-table slot of the source buffer
+    int32_t dst_slot;
+    int32_t alt_src_slot; // unpack only: the sender's send buffer, for in-place exchange
+    uint32_t es;          // element bytes
+    uint64_t alt_src_byte;
+    uint32_t mode;
+    uint32_t rows_per_tile;  // RUN short rows: rows per tile.  ELEM: elements per tile
+    uint32_t vec_window;     // RUN: aligned 16-byte vectors per row handled by one tile
+    uint32_t chunks_per_row; // RUN long rows: tiles per row (0 = short-row tiling)
+    uint32_t ntiles;
+    uint32_t pad_;
+};
+
+struct PtrLayout {
+    int32_t all_ranks;  // 0: single-rank table of PT_INLINE slots
+    int32_t wa, wb;
+};
+
+VPS_HD int32_t slot_src(const PtrLayout& L, int32_t rank, int32_t buf)
+{
+    return L.all_ranks ? rank * 8 + buf : PT_SRC + buf;
+}
+VPS_HD int32_t slot_dst(const PtrLayout& L, int32_t rank, int32_t buf)
+{
+    return L.all_ranks ? L.wa * 8 + rank * 8 + buf : PT_DST + buf;
+}
+VPS_HD int32_t slot_send(const PtrLayout& L, int32_t rank)
+{
+    return L.all_ranks ? (L.wa + L.wb) * 8 + rank : PT_SEND;
+}
+VPS_HD int32_t slot_recv(const PtrLayout& L, int32_t rank)
+{
+    return L.all_ranks ? (L.wa + L.wb) * 8 + L.wa + rank : PT_RECV;
+}
+VPS_HD int32_t num_slots(const PtrLayout& L)
+{
+    return L.all_ranks ? (L.wa + L.wb) * 9 : PT_INLINE;
+}
+
+// Build the copy descriptor of one box for one operation.  resident(rank) tells whether the
+// rank's buffers exist on this GPU (planned rank, or every rank for all-ranks plans); boxes
+// whose operation does not apply get ntiles = 0.
+VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t planned_rank,
+                           uint32_t tile_bytes, CopyDesc& d)
+{
+    const bool retained = b.src_rank == b.dst_rank;
+    const bool src_res = planned_rank < 0 || b.src_rank == planned_rank;
+    const bool dst_res = planned_rank < 0 || b.dst_rank == planned_rank;
+    d = CopyDesc();
+    d.alt_src_slot = -1;
+    d.es = kind_bytes(b.kind);
+    bool active;
+    int64_t ss[4], ds[4];
+    // row-major strides of the box itself: its layout inside a peer buffer
+    int64_t bs[4];
+    bs[3] = 1; bs[2] = b.ext[3]; bs[1] = (int64_t)b.ext[3] * b.ext[2];
+    bs[0] = (int64_t)b.ext[3] * b.ext[2] * b.ext[1];
+    if (op == OP_RETAIN) {
+        active = retained && src_res;
+        d.src_slot = slot_src(L, b.src_rank, b.src_buf);
+        d.dst_slot = slot_dst(L, b.dst_rank, b.dst_buf);
+        d.src_byte = (uint64_t)b.src_off * d.es;
+        d.dst_byte = (uint64_t)b.dst_off * d.es;
+        for (int a = 0; a < 4; ++a) { ss[a] = b.src_stride[a]; ds[a] = b.dst_stride[a]; }
+    } else if (op == OP_PACK) {
+        active = !retained && src_res;
+        d.src_slot = slot_src(L, b.src_rank, b.src_buf);
+        d.dst_slot = slot_send(L, b.src_rank);
+        d.src_byte = (uint64_t)b.src_off * d.es;
+        d.dst_byte = b.send_pos;
+        for (int a = 0; a < 4; ++a) { ss[a] = b.src_stride[a]; ds[a] = bs[a]; }
+    } else {
+        active = !retained && dst_res;
+        d.src_slot = slot_recv(L, b.dst_rank);
+        d.alt_src_slot = slot_send(L, b.src_rank);
+        d.dst_slot = slot_dst(L, b.dst_rank, b.dst_buf);
+        d.src_byte = b.recv_pos;
+        d.alt_src_byte = b.send_pos;
+        d.dst_byte = (uint64_t)b.dst_off * d.es;
+        for (int a = 0; a < 4; ++a) { ss[a] = bs[a]; ds[a] = b.dst_stride[a]; }
+    }
+    if (!active) { d.ntiles = 0; return; }
+
+    // Collapse: drop unit axes, order by destination stride (largest first), merge axes that
+    // are contiguous on both sides.
+    int64_t e[4]; int n = 0;
+    int64_t s2[4], d2[4];
+    for (int a = 0; a < 4; ++a)
+        if (b.ext[a] != 1) { e[n] = b.ext[a]; s2[n] = ss[a]; d2[n] = ds[a]; ++n; }
+    for (int i = 1; i < n; ++i)  // insertion sort, descending destination stride
+        for (int k = i; k > 0 && d2[k - 1] < d2[k]; --k) {
+            int64_t t;
+            t = e[k]; e[k] = e[k - 1]; e[k - 1] = t;
+            t = s2[k]; s2[k] = s2[k - 1]; s2[k - 1] = t;
+            t = d2[k]; d2[k] = d2[k - 1]; d2[k - 1] = t;
+        }
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+        if (m > 0 && s2[m - 1] == s2[i] * e[i] && d2[m - 1] == d2[i] * e[i]) {
+            e[m - 1] *= e[i]; s2[m - 1] = s2[i]; d2[m - 1] = d2[i];
+        } else {
+            e[m] = e[i]; s2[m] = s2[i]; d2[m] = d2[i]; ++m;
+        }
+    }
+    for (int a = 0; a < 4; ++a) { d.ext[a] = 1; d.sstr[a] = 0; d.dstr[a] = 0; }
+    for (int i = 0; i < m; ++i) {
+        d.ext[4 - m + i] = (uint32_t)e[i]; d.sstr[4 - m + i] = s2[i]; d.dstr[4 - m + i] = d2[i];
+    }
+    if (m == 0) { d.sstr[3] = 1; d.dstr[3] = 1; }
+
+    const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
+    if (d.sstr[3] == 1 && d.dstr[3] == 1) {
+        d.mode = MODE_RUN;
+        const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
+        const uint64_t rows = vol / d.ext[3];
+        const uint64_t nv_max = (run_bytes + 30) / 16;  // aligned vectors a run can touch
+        const uint64_t vt = tile_bytes / 16;
+        if (nv_max > vt) {
+            d.chunks_per_row = (uint32_t)((nv_max + vt - 1) / vt);
+            d.vec_window = (uint32_t)vt;
+            d.rows_per_tile = 1;
+            d.ntiles = (uint32_t)(rows * d.chunks_per_row);
+        } else {
+            d.chunks_per_row = 0;
+            d.vec_window = (uint32_t)nv_max;
+            uint64_t k = vt / nv_max;
+            if (k < 1) k = 1;
+            if (k > rows) k = rows;
+            d.rows_per_tile = (uint32_t)k;
+            d.ntiles = (uint32_t)((rows + k - 1) / k);
+        }
+    } else {
+        d.mode = MODE_ELEM;
+        uint64_t per = tile_bytes / (4 * d.es);
+        if (per < 256) per = 256;
+        d.rows_per_tile = (uint32_t)per;
+        d.ntiles = (uint32_t)((vol + per - 1) / per);
+    }
+}
+
+struct PtrArgs {
+    char* inl[PT_INLINE];  // single-rank plans: the 18 buffer pointers by value
+    char* const* tbl;      // all-ranks plans: table in device memory (nullptr otherwise)
+};
+
+struct TileRef {
+    uint32_t desc;
+    uint32_t q;  // tile index inside the descriptor
+};
+
+// Geometry of tile q of a RUN descriptor: rows [row0, row0+nrows), and for each row the window
+// [w0, w0+nw) of aligned destination vectors.
+VPS_HD void run_tile_geometry(const CopyDesc& d, uint32_t q, uint32_t& row0, uint32_t& nrows,
+                              uint32_t& w0, uint32_t& nw)
+{
+    nw = d.vec_window;
+    if (d.chunks_per_row) {
+        row0 = q / d.chunks_per_row;
+        nrows = 1;
+        w0 = (q % d.chunks_per_row) * d.vec_window;
+    } else {
+        const uint32_t rows = d.ext[0] * d.ext[1] * d.ext[2];
+        row0 = q * d.rows_per_tile;
+        nrows = rows - row0 < d.rows_per_tile ? rows - row0 : d.rows_per_tile;
+        w0 = 0;
+    }
+}
+
+// Byte addresses of the first element of a row.
+VPS_HD void run_row_address(const CopyDesc& d, uint32_t row, const char* sbase, char* dbase,
+                            const char*& s, char*& t)
+{
+    const uint32_t c2 = row % d.ext[2];
+    const uint32_t r1 = row / d.ext[2];
+    const uint32_t c1 = r1 % d.ext[1];
+    const uint32_t c0 = r1 / d.ext[1];
+    const int64_t so = (int64_t)c0 * d.sstr[0] + (int64_t)c1 * d.sstr[1] + (int64_t)c2 * d.sstr[2];
+    const int64_t to = (int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2];
+    s = sbase + so * (int64_t)d.es;
+    t = dbase + to * (int64_t)d.es;
+}
+
+// The part of aligned destination vector w (relative to the row's first vector) that lies in
+// the run: returns its byte count (0..16) and the matching source/destination addresses.
+VPS_HD uint32_t run_vector_span(const char* srow, char* drow, uint64_t run_bytes, uint32_t w,
+                                const char*& s, char*& t)
+{
+    const uintptr_t d0 = (uintptr_t)drow;
+    const uintptr_t v = (d0 & ~(uintptr_t)15) + (uintptr_t)16 * w;
+    const uintptr_t lo = v > d0 ? v : d0;
+    const uintptr_t end = d0 + run_bytes;
+    const uintptr_t hi = v + 16 < end ? v + 16 : end;
+    if (lo >= hi) return 0;
+    s = srow + (lo - d0);
+    t = (char*)lo;
+    return (uint32_t)(hi - lo);
+}
+
+// Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.
+VPS_HD void elem_offsets(const CopyDesc& d, uint64_t k, int64_t& so, int64_t& to)
+{
+    const uint32_t c3 = (uint32_t)(k % d.ext[3]); k /= d.ext[3];
+    const uint32_t c2 = (uint32_t)(k % d.ext[2]); k /= d.ext[2];
+    const uint32_t c1 = (uint32_t)(k % d.ext[1]);
+    const uint32_t c0 = (uint32_t)(k / d.ext[1]);
+    so = ((int64_t)c0 * d.sstr[0] + (int64_t)c1 * d.sstr[1] + (int64_t)c2 * d.sstr[2] +
+          (int64_t)c3 * d.sstr[3]) * (int64_t)d.es;
+    to = ((int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2] +
+          (int64_t)c3 * d.dstr[3]) * (int64_t)d.es;
+}
+
+// Accumulate into a counter shared by all items of a step.
+VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    atomicAdd((unsigned long long*)p, (unsigned long long)v);
+#else
+    *p += v;
+#endif
+}
+
+template <class T>
+VPS_HD int64_t upper_bound_idx(const T* a, int64_t n, T v)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if (a[mid] <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+template <class T>
+VPS_HD int64_t lower_bound_idx(const T* a, int64_t n, T v)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if (a[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+}  // namespace vps

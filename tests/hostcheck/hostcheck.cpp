@@ -1,0 +1,138 @@
+// hostcheck.cpp - TEST INFRASTRUCTURE: a CPU build of the library's per-item code.
+//
+// The mapper, planner and tile-geometry functions of paper_2605_18815_amd/csrc are written so
+// that they also compile as plain C++.  This file instantiates the same pipeline with a
+// sequential backend (one loop iteration per kernel lane, std::stable_sort, a serial scan) and
+// exports it as vpsh_* so that the test-suite can check index arithmetic and buffer bounds
+// against the CPU oracle on a machine without a GPU.  Every access of the copy step is bounds
+// checked against the buffer sizes registered with vpsh_set_bounds.  It is never linked into,
+// or loaded by, the product library.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "../../paper_2605_18815_amd/csrc/vps_core.h"
+#include "../../paper_2605_18815_amd/csrc/vps_inventory.h"
+
+namespace vps {
+
+struct Bounds {
+    const char* lo;
+    const char* hi;
+};
+static std::vector<Bounds> g_bounds;
+static long g_violations = 0;
+
+static bool in_bounds(const void* p, size_t n)
+{
+    const char* c = (const char*)p;
+    for (const Bounds& b : g_bounds)
+        if (c >= b.lo && c + n <= b.hi) return true;
+    return false;
+}
+
+class HostBackend {
+public:
+    explicit HostBackend(void*) {}
+    template <class T> T* alloc(int64_t n) { return (T*)calloc((size_t)(n > 0 ? n : 1), sizeof(T)); }
+    void free(void* p) { ::free(p); }
+    void commit() {}
+    void release_all() {}
+    template <class F> void for_each(int64_t n, F f) { for (int64_t i = 0; i < n; ++i) f(i); }
+    void exclusive_scan(const int64_t* in, int64_t* out, int64_t n)
+    {
+        int64_t acc = 0;
+        for (int64_t i = 0; i <= n; ++i) { out[i] = acc; acc += in[i]; }
+    }
+    void sort_pairs(uint64_t* keys, uint32_t* vals, int64_t n)
+    {
+        std::vector<int64_t> idx((size_t)n);
+        std::iota(idx.begin(), idx.end(), 0);
+        std::stable_sort(idx.begin(), idx.end(), [&](int64_t a, int64_t b) { return keys[a] < keys[b]; });
+        std::vector<uint64_t> k2((size_t)n);
+        std::vector<uint32_t> v2((size_t)n);
+        for (int64_t i = 0; i < n; ++i) { k2[(size_t)i] = keys[idx[(size_t)i]]; v2[(size_t)i] = vals[idx[(size_t)i]]; }
+        memcpy(keys, k2.data(), sizeof(uint64_t) * (size_t)n);
+        memcpy(vals, v2.data(), sizeof(uint32_t) * (size_t)n);
+    }
+    void upload(void* d, const void* h, size_t b) { if (b) memcpy(d, h, b); }
+    void download(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
+    void zero(void* d, size_t b) { if (b) memset(d, 0, b); }
+    void sync() {}
+    void set_ptr_table(void** table, void* const* host_ptrs, int n) { memcpy(table, host_ptrs, sizeof(void*) * (size_t)n); }
+
+    // Same slot walk as the device kernel, one lane at a time, with bounds checks.
+    void launch_copy(const CopyDesc* descs, const TileRef* tiles, int64_t tile0, int64_t ntiles,
+                     const PtrArgs& pa, int alias_exchange)
+    {
+        auto slot_ptr = [&](int32_t s) { return pa.tbl ? pa.tbl[s] : pa.inl[s]; };
+        auto move = [&](const char* s, char* t, size_t n) {
+            if (!in_bounds(s, n) || !in_bounds(t, n)) { ++g_violations; return; }
+            memcpy(t, s, n);
+        };
+        for (int64_t ti = 0; ti < ntiles; ++ti) {
+            const TileRef tr = tiles[tile0 + ti];
+            const CopyDesc d = descs[tr.desc];
+            const bool alias = alias_exchange && d.alt_src_slot >= 0;
+            const char* sbase = alias ? slot_ptr(d.alt_src_slot) + d.alt_src_byte : slot_ptr(d.src_slot) + d.src_byte;
+            char* dbase = slot_ptr(d.dst_slot) + d.dst_byte;
+            if (d.mode == MODE_RUN) {
+                uint32_t row0, nrows, w0, nw;
+                run_tile_geometry(d, tr.q, row0, nrows, w0, nw);
+                const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
+                const uint32_t total = nrows * nw;
+                for (uint32_t slot = 0; slot < total; ++slot) {
+                    const uint32_t r = slot / nw;
+                    const uint32_t w = nrows == 1 ? w0 + slot : slot - r * nw;
+                    const char* srow; char* drow;
+                    run_row_address(d, row0 + r, sbase, dbase, srow, drow);
+                    const char* s; char* t;
+                    const uint32_t nb = run_vector_span(srow, drow, run_bytes, w, s, t);
+                    if (nb) move(s, t, nb);
+                }
+            } else {
+                const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
+                const uint64_t k0 = (uint64_t)tr.q * d.rows_per_tile;
+                const uint64_t k1 = k0 + d.rows_per_tile < vol ? k0 + d.rows_per_tile : vol;
+                for (uint64_t k = k0; k < k1; ++k) {
+                    int64_t so, to;
+                    elem_offsets(d, k, so, to);
+                    move(sbase + so, dbase + to, d.es);
+                }
+            }
+        }
+    }
+};
+
+}  // namespace vps
+
+#define VPS_BACKEND vps::HostBackend
+#define VPS_FN(name) vpsh_##name
+#include "../../paper_2605_18815_amd/csrc/vps_api_impl.h"
+
+extern "C" {
+
+// Register the address ranges the copy step may touch (pairs of lo, hi); clears the counter.
+void vpsh_set_bounds(const void* const* lo_hi, int n)
+{
+    vps::g_bounds.clear();
+    for (int i = 0; i < n; ++i) vps::g_bounds.push_back({ (const char*)lo_hi[2 * i], (const char*)lo_hi[2 * i + 1] });
+    vps::g_violations = 0;
+}
+
+long vpsh_bounds_violations(void) { return vps::g_violations; }
+
+// Split a linear range of a row-major array: writes (start, axis, count) triples, returns n.
+int vpsh_split_linear_range(const int64_t* dims, uint64_t v0, uint64_t v1, int64_t* out, int max)
+{
+    int k = 0;
+    return vps::split_linear_range(dims, v0, v1, [&](uint64_t start, int axis, uint64_t cnt) {
+        if (k < max) { out[3 * k] = (int64_t)start; out[3 * k + 1] = axis; out[3 * k + 2] = (int64_t)cnt; }
+        ++k;
+    });
+}
+
+}  // extern "C"

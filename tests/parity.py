@@ -1,0 +1,359 @@
+"""Shared parity procedures: drive the C ABI on seeded inputs and compare with the CPU oracle.
+
+The same procedures run against the HIP library on device memory (``-m gpu`` tests) and
+against the CPU build of the library's per-item code on host memory (tests/hostcheck).
+Inputs always come from the oracle (``Config.fill``) or from the seeded pattern generator;
+expected values always come from the oracle.
+"""
+import ctypes as C
+
+import numpy as np
+
+import oracle
+from datagen import boxfill, pattern
+
+SENTINEL = 0xA5
+SENT16, SENT32 = 0xA5A5, 0xA5A5A5A5
+
+
+# ----------------------------------------------------------------------------- memory providers
+
+class HostMem:
+    """numpy-backed 'device' memory for the CPU build."""
+
+    def __init__(self, lib=None):
+        self.lib = lib
+        self.live = []
+
+    def alloc(self, nbytes, fill=SENTINEL):
+        a = np.full(max(int(nbytes), 16) + 16, fill, dtype=np.uint8)
+        off = (-a.ctypes.data) % 16
+        v = a[off:off + max(int(nbytes), 0)]
+        self.live.append((a, v))
+        return v
+
+    def ptr(self, v):
+        return v.ctypes.data if v.size else 0
+
+    def upload(self, v, host_bytes):
+        v[:] = np.frombuffer(host_bytes, dtype=np.uint8) if not isinstance(host_bytes, np.ndarray) else host_bytes.view(np.uint8).ravel()
+
+    def download(self, v):
+        return v.copy()
+
+    def copy(self, dst, doff, src, soff, n):
+        dst[doff:doff + n] = src[soff:soff + n]
+
+    def sync(self):
+        pass
+
+    def register_bounds(self):
+        if self.lib is None:
+            return
+        arr = (C.c_void_p * (2 * len(self.live)))()
+        for i, (_, v) in enumerate(self.live):
+            arr[2 * i] = v.ctypes.data
+            arr[2 * i + 1] = v.ctypes.data + v.size
+        self.lib._dll.vpsh_set_bounds(arr, len(self.live))
+
+    def violations(self):
+        if self.lib is None:
+            return 0
+        self.lib._dll.vpsh_bounds_violations.restype = C.c_long
+        return self.lib._dll.vpsh_bounds_violations()
+
+
+class GpuMem:
+    """torch-backed device memory (torch is only the allocator and the copy engine here)."""
+
+    def __init__(self):
+        import torch
+        self.torch = torch
+        self.dev = torch.device("cuda:0")
+
+    def alloc(self, nbytes, fill=SENTINEL):
+        t = self.torch.empty(max(int(nbytes), 0), dtype=self.torch.uint8, device=self.dev)
+        if t.numel():
+            t.fill_(fill)
+        return t
+
+    def ptr(self, v):
+        return v.data_ptr() if v.numel() else 0
+
+    def upload(self, v, host):
+        h = host.view(np.uint8).ravel() if isinstance(host, np.ndarray) else np.frombuffer(host, dtype=np.uint8)
+        if h.size:
+            v.copy_(self.torch.from_numpy(np.ascontiguousarray(h)))
+
+    def download(self, v):
+        return v.cpu().numpy()
+
+    def copy(self, dst, doff, src, soff, n):
+        if n:
+            dst[doff:doff + n].copy_(src[soff:soff + n])
+
+    def sync(self):
+        self.torch.cuda.synchronize()
+
+    def register_bounds(self):
+        pass
+
+    def violations(self):
+        return 0
+
+
+# ----------------------------------------------------------------------------- helpers
+
+def kind_dtype(buf):
+    return np.uint16 if buf % 4 == 0 else np.uint32
+
+
+def to_oracle_parallel(p):
+    return p
+
+
+def check_config_against_oracle(cfg, orc):
+    assert cfg.world == orc.world
+    assert cfg.num_tensors == orc.num_tensors
+    for r in range(orc.world):
+        for b in range(8):
+            assert cfg.buffer_bytes(r, b) == orc.buffer_elems(r, b) * oracle.KIND_BYTES[b % 4], (r, b)
+
+
+def boxes_to_oracle_arrays(boxes):
+    n = boxes.shape[0]
+    ints = np.zeros((n, 16), dtype=np.int32)
+    offs = np.zeros((n, 10), dtype=np.int64)
+    ints[:, 0] = boxes["kind"]; ints[:, 1] = boxes["tensor"]
+    ints[:, 2] = boxes["src_rank"]; ints[:, 3] = boxes["dst_rank"]
+    ints[:, 4] = boxes["src_buf"]; ints[:, 5] = boxes["dst_buf"]
+    ints[:, 6:10] = boxes["lo"]; ints[:, 10:14] = boxes["ext"]
+    offs[:, 0] = boxes["src_off"]; offs[:, 1] = boxes["dst_off"]
+    offs[:, 2:6] = boxes["src_stride"]; offs[:, 6:10] = boxes["dst_stride"]
+    return ints, offs
+
+
+def box_volume(b):
+    return int(np.prod(b["ext"].astype(np.int64)))
+
+
+def box_linear_indices(b, shape):
+    """Global row-major linear indices of the elements of a box, in the box's row-major order."""
+    lo, ext = b["lo"].astype(np.int64), b["ext"].astype(np.int64)
+    idx = np.zeros(tuple(ext), dtype=np.int64)
+    mult = 1
+    for ax in (3, 2, 1, 0):
+        shp = [1, 1, 1, 1]
+        shp[ax] = int(ext[ax])
+        idx = idx + (np.arange(lo[ax], lo[ax] + ext[ax], dtype=np.int64) * mult).reshape(shp)
+        mult *= int(shape[ax])
+    return idx.ravel()
+
+
+def gather_box(buf_words, off, strides, ext):
+    """Elements of a strided box of a local buffer (numpy words), row-major in global axes."""
+    ext = [int(e) for e in ext]
+    strides = [int(s) for s in strides]
+    idx = np.full((1, 1, 1, 1), int(off), dtype=np.int64)
+    for ax in range(4):
+        shp = [1, 1, 1, 1]
+        shp[ax] = ext[ax]
+        idx = idx + (np.arange(ext[ax], dtype=np.int64) * strides[ax]).reshape(shp)
+    return buf_words[idx.ravel()]
+
+
+def validate_boxes(a, b, boxes, planned_rank, samples=0):
+    """Per-element validation of the plan by the oracle, plus exact coverage counts."""
+    ints, offs = boxes_to_oracle_arrays(boxes)
+    bad, first = oracle.check_boxes(a, b, ints, offs, samples=samples)
+    assert bad == 0, f"{bad} element violations, first bad box {first}: {boxes[first] if first >= 0 else None}"
+    vols = np.prod(boxes["ext"].astype(np.int64), axis=1)
+    es = np.where(boxes["kind"] == 0, 2, 4)
+    ranks = range(b.world) if planned_rank < 0 else [planned_rank] if planned_rank < b.world else []
+    for j in ranks:
+        sel = boxes["dst_rank"] == j
+        got = int((vols[sel] * es[sel]).sum())
+        want = sum(b.payload_elems(j, buf) * oracle.KIND_BYTES[buf % 4] for buf in range(8))
+        assert got == want, f"dst rank {j}: boxes cover {got} bytes, payload is {want}"
+    # inside a peer buffer boxes are 16-byte aligned, disjoint and dense in their order
+    for key, pos_key in (("src_rank", "send_pos"), ("dst_rank", "recv_pos")):
+        moving = boxes[(boxes["src_rank"] != boxes["dst_rank"]) & (boxes[pos_key] != np.uint64(2**64 - 1))]
+        for r in np.unique(moving[key]):
+            bx = moving[moving[key] == r]
+            order = np.argsort(bx[pos_key], kind="stable")
+            pos = bx[pos_key][order].astype(np.int64)
+            size = ((np.prod(bx["ext"].astype(np.int64), axis=1) * np.where(bx["kind"] == 0, 2, 4))[order] + 15) // 16 * 16
+            assert (pos % 16 == 0).all()
+            assert pos[0] == 0 and (pos[1:] == pos[:-1] + size[:-1]).all()
+            peer = bx["dst_rank" if key == "src_rank" else "src_rank"][order]
+            assert (np.diff(peer) >= 0).all(), "peer segments must ascend"
+
+
+# ----------------------------------------------------------------------------- all ranks resident
+
+def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_payload=True):
+    """Every virtual rank resident: apply_transition(rank=-1), then per-rank pack / exchange /
+    unpack; dst buffers, per-pair byte counts and send payloads against the oracle."""
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    check_config_against_oracle(ca, a)
+    check_config_against_oracle(cb, b)
+    plan = lib.plan_intersections(ca, cb, -1)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, -1)
+
+    src_host = {(r, buf): a.fill(r, buf, seed, rank_salt, pad_word=0x3C3C3C3C) for r in range(a.world) for buf in range(8)}
+    src = {k: mem.alloc(v.nbytes) for k, v in src_host.items()}
+    for k, v in src_host.items():
+        mem.upload(src[k], v)
+    want = {(j, buf): oracle.expected(a, b, j, buf, seed, rank_salt, pad_word=SENT32) for j in range(b.world) for buf in range(8)}
+
+    # byte counts
+    for j in range(b.world):
+        rb = oracle.route_bytes(a, b, j)
+        for i in range(a.world):
+            assert plan.pair_bytes(i, j) == rb[i], (i, j)
+
+    def fresh_dst():
+        return {k: mem.alloc(v.nbytes) for k, v in want.items()}
+
+    def compare(dst, tag):
+        for k, v in want.items():
+            got = mem.download(dst[k]).view(v.dtype)
+            if not np.array_equal(got, v):
+                bad = np.nonzero(got != v)[0]
+                raise AssertionError(f"{tag}: dst {k} differs at {bad.size} of {v.size} elements, first offsets {bad[:5]}")
+
+    # (1) one call for everything
+    info = plan.buffer_bytes(-1)
+    scratch = mem.alloc(info["scratch_needed"])
+    dst = fresh_dst()
+    mem.register_bounds()
+    lib.apply_transition(plan, -1, [mem.ptr(src[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                         [mem.ptr(dst[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                         mem.ptr(scratch), info["scratch_needed"])
+    mem.sync()
+    assert mem.violations() == 0
+    compare(dst, "apply_transition(all)")
+
+    # (2) per rank: pack, exchange segment by segment, unpack
+    sends = {}
+    for i in range(a.world):
+        bi = plan.buffer_bytes(i)
+        sends[i] = mem.alloc(bi["send_total"])
+    recvs = {j: mem.alloc(plan.buffer_bytes(j)["recv_total"]) for j in range(b.world)}
+    dst2 = fresh_dst()
+    mem.register_bounds()
+    for i in range(a.world):
+        lib.pack(plan, i, [mem.ptr(src[(i, buf)]) for buf in range(8)], mem.ptr(sends[i]))
+    mem.sync()
+    moved = 0
+    for i in range(a.world):
+        for j in range(b.world):
+            seg = plan.peer_segment(i, j)
+            if seg["bytes"]:
+                mem.copy(recvs[j], seg["recv_off"], sends[i], seg["send_off"], seg["bytes"])
+                moved += seg["bytes"]
+    for j in range(b.world):
+        lib.unpack(plan, j, mem.ptr(recvs[j]), [mem.ptr(dst2[(j, buf)]) for buf in range(8)])
+    mem.sync()
+    assert mem.violations() == 0
+    # retained data does not travel: dst2 is complete only after the retain copies, which
+    # pack/unpack do not perform; compare the received part box by box instead
+    for j in range(b.world):
+        got = {buf: mem.download(dst2[(j, buf)]).view(kind_dtype(buf)) for buf in range(8)}
+        for bx in boxes[(boxes["dst_rank"] == j) & (boxes["src_rank"] != j)]:
+            buf = int(bx["dst_buf"])
+            g = gather_box(got[buf], bx["dst_off"], bx["dst_stride"], bx["ext"])
+            w = gather_box(want[(j, buf)], bx["dst_off"], bx["dst_stride"], bx["ext"])
+            assert np.array_equal(g, w), ("unpack", j, bx)
+        for bx in boxes[(boxes["dst_rank"] == j) & (boxes["src_rank"] == j)]:
+            buf = int(bx["dst_buf"])
+            g = gather_box(got[buf], bx["dst_off"], bx["dst_stride"], bx["ext"])
+            assert (g == (SENT16 if buf % 4 == 0 else SENT32)).all(), "unpack wrote a retained box"
+
+    # (3) send payloads: row-major box contents at send_pos
+    if check_send_payload:
+        for i in range(a.world):
+            sb = mem.download(sends[i])
+            for bx in boxes[(boxes["src_rank"] == i) & (boxes["dst_rank"] != i)]:
+                buf = int(bx["src_buf"])
+                w = gather_box(src_host[(i, buf)], bx["src_off"], bx["src_stride"], bx["ext"])
+                pos = int(bx["send_pos"])
+                g = sb[pos:pos + w.nbytes].view(w.dtype)
+                assert np.array_equal(g, w), ("send payload", i, bx)
+    return dict(boxes=len(boxes), moved=moved, stats=plan.stats())
+
+
+# ----------------------------------------------------------------------------- one rank resident
+
+def synth_recv_buffer(a, boxes, rank, nbytes, seed, rank_salt):
+    """What the peers would have packed for `rank`: for every incoming box the pattern words of
+    its elements (row-major in global axes) at the box's position in the receive buffer."""
+    out = np.full(int(nbytes), SENTINEL, dtype=np.uint8)
+    for bx in boxes[(boxes["dst_rank"] == rank) & (boxes["src_rank"] != rank)]:
+        t, kind = int(bx["tensor"]), int(bx["kind"])
+        sd = pattern.seed_for_rank(seed, rank_salt, int(bx["src_rank"]))
+        pos, n = int(bx["recv_pos"]), box_volume(bx)
+        w = out[pos:pos + n * (2 if kind == 0 else 4)].view(np.uint16 if kind == 0 else np.uint32)
+        boxfill.fill_box(sd, kind, t, a.tensor_info(t)["shape"], bx["lo"], bx["ext"], w)
+    return out
+
+
+def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_samples=0,
+                    full_compare=True, chunk=1 << 24):
+    """One rank's share: retain + pack + unpack in one apply_transition call, peers' buffers
+    synthesized from the seeded pattern."""
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plan = lib.plan_intersections(ca, cb, rank)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    info = plan.buffer_bytes(rank)
+
+    in_a, in_b = rank < a.world, rank < b.world
+    src_host, src, dst = {}, {}, {}
+    for buf in range(8):
+        n = a.buffer_elems(rank, buf) if in_a else 0
+        src_host[buf] = a.fill(rank, buf, seed, rank_salt, pad_word=0x3C3C3C3C) if n else np.zeros(0, kind_dtype(buf))
+        src[buf] = mem.alloc(src_host[buf].nbytes)
+        mem.upload(src[buf], src_host[buf])
+        dst[buf] = mem.alloc((b.buffer_elems(rank, buf) if in_b else 0) * oracle.KIND_BYTES[buf % 4])
+    scratch = mem.alloc(info["scratch_needed"])
+    recv = synth_recv_buffer(a, boxes, rank, info["recv_total"], seed, rank_salt)
+    if recv.size:
+        mem.upload(scratch[info["recv_offset"]:info["recv_offset"] + recv.size], recv)
+    mem.register_bounds()
+    lib.apply_transition(plan, rank, [mem.ptr(src[buf]) for buf in range(8)],
+                         [mem.ptr(dst[buf]) for buf in range(8)], mem.ptr(scratch), info["scratch_needed"])
+    mem.sync()
+    assert mem.violations() == 0
+
+    # destination buffers against the oracle
+    if in_b:
+        for buf in range(8):
+            n = b.buffer_elems(rank, buf)
+            got = mem.download(dst[buf]).view(kind_dtype(buf))
+            for o in range(0, n, chunk):
+                m = min(chunk, n - o)
+                want = oracle.expected(a, b, rank, buf, seed, rank_salt, off0=o, n=m, pad_word=SENT32)
+                if not np.array_equal(got[o:o + m], want):
+                    bad = np.nonzero(got[o:o + m] != want)[0]
+                    raise AssertionError(f"dst buf {buf}: {bad.size} wrong elements from offset {o + bad[0]}")
+    # byte counts seen from this rank
+    if in_b:
+        rb = oracle.route_bytes(a, b, rank)
+        for i in range(a.world):
+            assert plan.pair_bytes(i, rank) == rb[i], (i, rank)
+    if in_a:
+        sbytes = oracle.send_bytes(a, b, rank)
+        for j in range(b.world):
+            assert plan.pair_bytes(rank, j) == sbytes[j], (rank, j)
+    # send payload
+    sb = mem.download(scratch)[:info["send_total"]]
+    for bx in boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]:
+        buf = int(bx["src_buf"])
+        w = gather_box(src_host[buf], bx["src_off"], bx["src_stride"], bx["ext"])
+        pos = int(bx["send_pos"])
+        assert np.array_equal(sb[pos:pos + w.nbytes].view(w.dtype), w), ("send payload", bx)
+    return dict(boxes=len(boxes), info=info, stats=plan.stats())

@@ -1,0 +1,46 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import parity
+from datagen import configs as cf
+from test_oracle_pins import TRANSITIONS
+from test_hostcheck_parity import SINGLE
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_18815_amd as vps
+    return vps.load()
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_all_ranks_resident(lib, name, m, pa, pb):
+    out = parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0x5EED + len(name))
+    assert out["boxes"] > 0
+
+
+@pytest.mark.parametrize("name,rank", SINGLE, ids=[f"{n}-r{r}" for n, r in SINGLE])
+def test_single_rank_share(lib, name, rank):
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=0xBEEF + rank)
+
+
+def test_toy_workload_all_ranks(lib):
+    w = cf.WORKLOADS["toy"]
+    out = parity.run_all_ranks(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], seed=cf.seed_of("toy"))
+    assert out["moved"] > 0
+
+
+@pytest.mark.parametrize("tile", [4096, 262144])
+def test_tile_size_does_not_change_results(lib, tile):
+    lib.set_tile_bytes(tile)
+    try:
+        _, m, pa, pb = TRANSITIONS[3]
+        parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=77)
+        w = cf.WORKLOADS["toy"]
+        parity.run_single_rank(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], 1, seed=78)
+    finally:
+        lib.set_tile_bytes(32768)

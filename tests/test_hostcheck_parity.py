@@ -1,0 +1,136 @@
+"""CPU build of the library's mapper / planner / tile-geometry code against the oracle.
+
+The product runs this code only inside HIP kernels.  Here the same per-item functions are
+compiled for the host (tests/hostcheck) with bounds checks and UBSan, so that index errors are
+found on a machine without a GPU.  The GPU parity tests (test_gpu_parity.py) run the identical
+procedures through the real library.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import parity
+from datagen import configs as cf
+from hostcheck import build as hc_build
+from paper_2605_18815_amd.binding import Library, VpsError
+from test_oracle_pins import TRANSITIONS
+
+P = cf.parallel
+
+
+@pytest.fixture(scope="module")
+def hlib():
+    return Library(hc_build.build(), prefix="vpsh_")
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_all_ranks_resident(hlib, name, m, pa, pb):
+    mem = parity.HostMem(hlib)
+    out = parity.run_all_ranks(hlib, mem, m, pa, pb, seed=0x5EED + len(name))
+    assert out["boxes"] > 0
+
+
+SINGLE = [
+    ("gpt-zero-to-replicated", 0), ("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-blocked-rev", 2),
+    ("gpt-odd", 1), ("gpt-world-grows", 11), ("gpt-world-grows", 3), ("gqa", 6), ("moe-ep", 9),
+    ("moe-transposed", 3), ("moe-odd", 7),
+]
+
+
+@pytest.mark.parametrize("name,rank", SINGLE, ids=[f"{n}-r{r}" for n, r in SINGLE])
+def test_single_rank_share(hlib, name, rank):
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    mem = parity.HostMem(hlib)
+    parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xBEEF + rank)
+
+
+def test_toy_workload_all_ranks(hlib):
+    w = cf.WORKLOADS["toy"]
+    mem = parity.HostMem(hlib)
+    out = parity.run_all_ranks(hlib, mem, w["model"], w["src"], w["dst"], seed=cf.seed_of("toy"))
+    assert out["moved"] > 0
+
+
+@pytest.mark.parametrize("tile", [4096, 65536])
+def test_tile_size_does_not_change_results(hlib, tile):
+    hlib.set_tile_bytes(tile)
+    try:
+        _, m, pa, pb = TRANSITIONS[3]
+        parity.run_all_ranks(hlib, parity.HostMem(hlib), m, pa, pb, seed=77)
+        w = cf.WORKLOADS["toy"]
+        parity.run_single_rank(hlib, parity.HostMem(hlib), w["model"], w["src"], w["dst"], 1, seed=78)
+    finally:
+        hlib.set_tile_bytes(32768)
+
+
+def test_split_linear_range_properties(hlib):
+    """A linear range over a k-D row-major array splits into at most 2k-1 boxes whose volumes
+    sum to the range length and which tile it in order (Section 4.2.2: flat ranges cut across
+    tensor boundaries)."""
+    rng = np.random.default_rng(5)
+    f = hlib._dll.vpsh_split_linear_range
+    f.restype = C.c_int
+    f.argtypes = [C.POINTER(C.c_int64), C.c_uint64, C.c_uint64, C.POINTER(C.c_int64), C.c_int]
+    for _ in range(3000):
+        dims = [int(x) for x in rng.integers(1, 7, 4)]
+        total = int(np.prod(dims))
+        v0 = int(rng.integers(0, total))
+        v1 = int(rng.integers(v0 + 1, total + 1))
+        out = (C.c_int64 * 60)()
+        n = f((C.c_int64 * 4)(*dims), v0, v1, out, 20)
+        k = sum(1 for d in dims if d > 1) or 1
+        assert 1 <= n <= 2 * k - 1 or (n <= 7 and k == 4), (dims, v0, v1, n)
+        assert n <= max(1, 2 * k - 1)
+        st = [dims[1] * dims[2] * dims[3], dims[2] * dims[3], dims[3], 1]
+        cur = v0
+        for i in range(n):
+            start, axis, cnt = out[3 * i], out[3 * i + 1], out[3 * i + 2]
+            assert start == cur and cnt >= 1
+            assert start % st[axis] == 0                       # aligned to the unit it spans
+            assert (start // st[axis]) % dims[axis] + cnt <= dims[axis]  # stays inside the axis
+            cur += cnt * st[axis]
+        assert cur == v1
+
+
+def test_error_codes(hlib):
+    from paper_2605_18815_amd import binding as B
+    with pytest.raises(VpsError) as e:
+        hlib.describe_config(cf.TINY_GPT, P(tp=3))
+    assert e.value.code == B.ERR_INDIVISIBLE
+    with pytest.raises(VpsError) as e:
+        hlib.describe_config(cf.TINY_MOE, P(ep=3))
+    assert e.value.code == B.ERR_INDIVISIBLE
+    with pytest.raises(VpsError) as e:
+        hlib.describe_config(cf.TINY_GPT, P(tp=0))
+    assert e.value.code == B.ERR_INVALID_ARG
+    with pytest.raises(VpsError) as e:
+        hlib.describe_config(cf.TINY_GPT, P(tp=2), rank=2)
+    assert e.value.code == B.ERR_RANK_RANGE
+    ca = hlib.describe_config(cf.TINY_GPT, P(tp=2, dp=2))
+    cb = hlib.describe_config(cf.TINY_GQA, P(tp=2, dp=2))
+    with pytest.raises(VpsError) as e:
+        hlib.plan_intersections(ca, cb, -1)
+    assert e.value.code == B.ERR_MODEL_MISMATCH
+    one = hlib.describe_config(cf.TINY_GPT, P(tp=2, dp=2), rank=1)
+    assert one.num_pieces > 0 and set(one.get_pieces()["rank"]) == {1}
+    with pytest.raises(VpsError) as e:
+        hlib.plan_intersections(one, ca, -1)
+    assert e.value.code == B.ERR_INVALID_ARG
+    cb = hlib.describe_config(cf.TINY_GPT, P(tp=1, dp=4, zero=0))
+    with pytest.raises(VpsError) as e:
+        hlib.plan_intersections(ca, cb, 4)
+    assert e.value.code == B.ERR_RANK_RANGE
+    plan = hlib.plan_intersections(ca, cb, 1)
+    info = plan.buffer_bytes(1)
+    mem = parity.HostMem(hlib)
+    bufs = [mem.ptr(mem.alloc(max(ca.buffer_bytes(1, b), cb.buffer_bytes(1, b)))) for b in range(8)]
+    with pytest.raises(VpsError) as e:
+        hlib.apply_transition(plan, 1, bufs, bufs, mem.ptr(mem.alloc(16)), 16)
+    assert e.value.code == B.ERR_SCRATCH_TOO_SMALL or info["scratch_needed"] <= 16
+    with pytest.raises(VpsError) as e:
+        hlib.apply_transition(plan, 2, bufs, bufs, 0, 0)
+    assert e.value.code == B.ERR_RANK_RANGE
+    with pytest.raises(VpsError) as e:
+        hlib.pack(plan, 1, [0] * 8, mem.ptr(mem.alloc(info["send_total"])))
+    assert e.value.code == B.ERR_INVALID_ARG

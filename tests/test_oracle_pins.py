@@ -437,3 +437,18 @@ def test_70b_mid_pipeline_rank_keeps_all_fp32_state():
         if e is not None and oracle.select_source(a, b, j, 1, e[0], list(e[1]))[0] != j:
             moved += 1
     assert moved > 0
+
+
+def test_boxfill_generator_matches_numpy_pattern():
+    """The C box generator (inputs only) against the numpy twin of the pattern."""
+    from datagen import boxfill
+    rng = np.random.default_rng(11)
+    for kind in (0, 1, 3):
+        shape = [int(x) for x in rng.integers(2, 9, 4)]
+        lo = [int(rng.integers(0, s)) for s in shape]
+        ext = [int(rng.integers(1, s - l + 1)) for s, l in zip(shape, lo)]
+        out = np.zeros(int(np.prod(ext)), dtype=np.uint16 if kind == 0 else np.uint32)
+        boxfill.fill_box(1234, kind, 17, shape, lo, ext, out)
+        idx = np.arange(int(np.prod(shape)), dtype=np.uint64).reshape(shape)
+        idx = idx[lo[0]:lo[0] + ext[0], lo[1]:lo[1] + ext[1], lo[2]:lo[2] + ext[2], lo[3]:lo[3] + ext[3]]
+        assert np.array_equal(out, pattern.word(1234, kind, 17, idx.ravel()))
