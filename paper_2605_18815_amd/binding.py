@@ -78,6 +78,11 @@ class Library:
     def __init__(self, path=None, prefix="vps_"):
         self.path = path or _build.library_path()
         self.prefix = prefix
+        if prefix == "vps_":
+            # PyTorch bundles its own HIP runtime under the same soname.  Loading torch first
+            # makes this library bind to that copy, so that the process has one runtime and
+            # torch-allocated memory and streams are valid in our calls.
+            import torch  # noqa: F401
         self._dll = C.CDLL(self.path)
         vp, i32, i64, u64, u32 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_uint32
         P = C.POINTER
