@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the VPS state transition on one MI355X.
+
+One step = one pass of the whole path for one rank's share of the workload: map both
+configurations onto the VPS (vps_describe_config x2), plan the intersections
+(vps_plan_intersections) and move the data (vps_apply_transition: retain + pack + unpack in one
+launch).  State buffers and the peers' receive buffer are resident in HBM before the timed
+region.  The JSON line reports bytes moved (read + write) per second over the whole step, and
+for the copy kernel alone the achieved HBM rate against the 8 TB/s peak.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gqa70b")
+    ap.add_argument("--rank", type=int, default=None)
+    ap.add_argument("--tile-bytes", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every virtual rank or one rank's share is "
+              "resident on a single MI355X); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2605_18815_amd as vps
+    from datagen import configs as cf
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    lib = vps.load()
+    if args.tile_bytes:
+        lib.set_tile_bytes(args.tile_bytes)
+    w = cf.WORKLOADS[args.workload]
+    model, pa, pb = w["model"], w["src"], w["dst"]
+    rank = args.rank if args.rank is not None else (w["rank"] if w["rank"] is not None else -1)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    # ---- resident state: source buffers (seeded random bytes), destination buffers, scratch
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plan = lib.plan_intersections(ca, cb, rank, stream)
+    info = plan.buffer_bytes(rank)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cf.seed_of(args.workload))
+
+    def alloc(nbytes, rand):
+        t = torch.empty(int(nbytes), dtype=torch.uint8, device=dev)
+        if rand and nbytes:
+            t.view(torch.int32)[: nbytes // 4].random_(generator=gen) if nbytes % 4 == 0 else t.random_(generator=gen)
+        return t
+
+    src_ranks = [rank] if rank >= 0 else list(range(ca.world))
+    dst_ranks = [rank] if rank >= 0 else list(range(cb.world))
+    src = [alloc(ca.buffer_bytes(r, b) if r < ca.world else 0, True) for r in src_ranks for b in range(8)]
+    dst = [alloc(cb.buffer_bytes(r, b) if r < cb.world else 0, False) for r in dst_ranks for b in range(8)]
+    scratch = alloc(info["scratch_needed"], True)   # the receive part stands in for the peers' packed data
+    sp = [t.data_ptr() if t.numel() else 0 for t in src]
+    dp = [t.data_ptr() if t.numel() else 0 for t in dst]
+    payload = info["send_total"] + info["recv_total"] + info["retain_total"]
+    if rank < 0:
+        payload = 2 * info["send_total"] + info["retain_total"]   # every byte is packed and unpacked here
+    bytes_moved = 2 * payload
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t_desc, t_plan = [], []
+
+    def one_step(k=None):
+        t0 = time.perf_counter()
+        if args.apply_only:
+            p = plan
+        else:
+            a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
+            t1 = time.perf_counter()
+            p = lib.plan_intersections(a2, b2, rank, stream)
+            t2 = time.perf_counter()
+            if k is not None:
+                t_desc.append((t1 - t0) * 1e3)
+                t_plan.append((t2 - t1) * 1e3)
+        if k is not None:
+            ev[k][0].record()
+        lib.apply_transition(p, rank, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
+        if k is not None:
+            ev[k][1].record()
+        return p
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    keep = [one_step(k) for k in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    del keep
+    ms_per_step = wall * 1e3 / args.steps
+    apply_ms = sorted(a.elapsed_time(b) for a, b in ev)
+    apply_avg = sum(apply_ms) / len(apply_ms)
+
+    st = plan.stats()
+    launches = 1 if rank >= 0 else 2
+    roofline = dict(bound="hbm", achieved=bytes_moved / (apply_avg * 1e-3) / 1e9, peak=HBM_PEAK_GBPS,
+                    unit="GB/s", frac=bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, traffic=None,
+                    kernel="k_copy_tiles", launches_per_step=launches, kernel_ms_avg=apply_avg,
+                    kernel_ms_median=apply_ms[len(apply_ms) // 2], algorithmic_bytes_per_step=bytes_moved)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(model, pa, pb, rank if rank >= 0 else 0, cf.seed_of(args.workload))
+
+    out = {
+        "metric": "resharded state GB/s (read+write)", "value": bytes_moved / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u16+u32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} rank {rank}" if rank >= 0 else f"{args.workload} all ranks",
+                   "src": pa, "dst": pb, "step": "apply only" if args.apply_only else "describe x2 + plan + apply",
+                   "tile_bytes": args.tile_bytes or 32768},
+        "breakdown_ms": {"describe_x2": _avg(t_desc), "plan": _avg(t_plan), "apply_kernels": apply_avg},
+        "apply_gbps": bytes_moved / (apply_avg * 1e-3) / 1e9,
+        "pct_hbm_peak_apply": 100.0 * bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+        "bytes": {"send": info["send_total"], "recv": info["recv_total"], "retain": info["retain_total"],
+                  "moved_read_plus_write": bytes_moved},
+        "plan": {k: st[k] for k in ("num_boxes", "num_retain_tiles", "num_pack_tiles", "num_unpack_tiles",
+                                    "num_peers_out", "num_peers_in")},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def _avg(v):
+    return sum(v) / len(v) if v else None
+
+
+def cpu_baseline(model, pa, pb, rank, seed, target_elems=48_000_000):
+    """The per-element oracle on the host cores, on a bounded sample of the same rank's share:
+    the first target_elems/num_buffers offsets of every destination buffer."""
+    import oracle
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    bufs = [buf for buf in range(8) if b.buffer_elems(rank, buf)]
+    per = target_elems // max(len(bufs), 1)
+    nbytes = 0
+    t0 = time.perf_counter()
+    for buf in bufs:
+        n = min(per, b.buffer_elems(rank, buf))
+        oracle.expected(a, b, rank, buf, seed, n=n)
+        nbytes += n * oracle.KIND_BYTES[buf % 4]
+    dt = time.perf_counter() - t0
+    return dict(value=2 * nbytes / dt / 1e9, unit="GB/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"first {per} elements of each of the {len(bufs)} destination buffers of rank {rank} "
+                       f"({nbytes} bytes) through the per-element oracle (coordinate, owners, source rule, word)",
+                seconds=dt)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,13 +1,16 @@
 // vps_copy_kernel.h - the descriptor-driven strided-box copy engine (PackData / UnpackData
 // of DynaTrain Algorithm 1, plus the direct old-local -> new-local copy of retained slices).
 //
-// One workgroup per tile.  A tile is a slice of one box of roughly tile_bytes payload:
+// One workgroup (4 wavefronts of 64 lanes) per tile.  A tile is a slice of one box of roughly
+// tile_bytes payload:
 //   RUN   both sides are contiguous along the innermost collapsed axis.  Lanes own 16-byte
 //         destination-aligned vectors: aligned 16-byte stores, 16-byte loads at whatever
 //         element alignment the source has; the (at most two) partial vectors at the ends of
-//         a run are moved in 2-byte units.  Long runs are cut into chunks, short runs are
-//         batched several rows per tile.
+//         a run are moved in 2-byte units by a few lanes.  A long run is cut into chunks (one
+//         chunk per workgroup); short runs are batched, one run per wavefront at a time.
 //   ELEM  fallback when the two sides have no common contiguous axis: one element per lane.
+// All per-tile and per-run quantities are wave-uniform and kept in scalar registers; the lane
+// state is a handful of addresses, so eight waves per SIMD stay resident and hide HBM latency.
 // HBM-bound: every payload byte is read once and written once; descriptors and the tile
 // table add well under 1 % of traffic.
 #pragma once
@@ -21,18 +24,75 @@ namespace vps {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_any __attribute__((aligned(2)));  // source vectors: element alignment only
 
-__device__ __forceinline__ char* slot_ptr(const PtrArgs& pa, int32_t slot)
-{
-    return pa.tbl ? pa.tbl[slot] : pa.inl[slot];
-}
+#define VPS_GLOBAL __attribute__((address_space(1)))
+typedef const VPS_GLOBAL u32x4_any* gsrc16_t;
+typedef VPS_GLOBAL u32x4* gdst16_t;
+typedef const VPS_GLOBAL uint16_t* gsrc2_t;
+typedef VPS_GLOBAL uint16_t* gdst2_t;
+typedef const VPS_GLOBAL uint32_t* gsrc4_t;
+typedef VPS_GLOBAL uint32_t* gdst4_t;
 
 constexpr int COPY_THREADS = 256;
+constexpr int COPY_WAVES = COPY_THREADS / 64;
 constexpr int COPY_UNROLL = 4;
 
-__device__ __forceinline__ void copy_partial(const char* s, char* t, uint32_t nb)
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
 {
-    for (uint32_t b = 0; b < nb; b += 2)
-        *reinterpret_cast<uint16_t*>(t + b) = *reinterpret_cast<const uint16_t*>(s + b);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ uint64_t slot_addr(const PtrArgs& pa, int32_t slot)
+{
+    return (uint64_t)(uintptr_t)(pa.tbl ? pa.tbl[slot] : pa.inl[slot]);
+}
+
+// Full vectors [wbeg, wend) of one run: vector w sits at dst `dvec + 16*w` (16-byte aligned)
+// and src `svec + 16*w`.  `lane` strides by `nlanes`.
+__device__ __forceinline__ void copy_full_vectors(uint64_t svec, uint64_t dvec, uint32_t wbeg,
+                                                  uint32_t wend, uint32_t lane, uint32_t nlanes)
+{
+    uint32_t w = wbeg + lane;
+    // all COPY_UNROLL loads are issued before the first store
+    for (; w + (COPY_UNROLL - 1) * nlanes < wend; w += COPY_UNROLL * nlanes) {
+        u32x4 v[COPY_UNROLL];
+#pragma unroll
+        for (int u = 0; u < COPY_UNROLL; ++u)
+            v[u] = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)(w + u * nlanes) * 16));
+#pragma unroll
+        for (int u = 0; u < COPY_UNROLL; ++u)
+            __builtin_nontemporal_store(v[u], (gdst16_t)(dvec + (uint64_t)(w + u * nlanes) * 16));
+    }
+    u32x4 v[COPY_UNROLL - 1];
+#pragma unroll
+    for (int u = 0; u < COPY_UNROLL - 1; ++u)
+        if (w + u * nlanes < wend)
+            v[u] = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)(w + u * nlanes) * 16));
+#pragma unroll
+    for (int u = 0; u < COPY_UNROLL - 1; ++u)
+        if (w + u * nlanes < wend)
+            __builtin_nontemporal_store(v[u], (gdst16_t)(dvec + (uint64_t)(w + u * nlanes) * 16));
+}
+
+// Fewer than 16 bytes (a multiple of 2): lane t moves 2-byte unit t.
+__device__ __forceinline__ void copy_units(uint64_t s, uint64_t t, uint32_t nbytes, uint32_t lane)
+{
+    if (lane * 2 < nbytes) *(gdst2_t)(t + lane * 2) = *(gsrc2_t)(s + lane * 2);
+}
+
+// One run, the part that falls into the window [w0, w0 + nw) of its destination vectors.
+__device__ __forceinline__ void copy_run_window(uint64_t srow, uint64_t drow, uint64_t run_bytes,
+                                                uint32_t w0, uint32_t nw, uint32_t lane,
+                                                uint32_t nlanes)
+{
+    const RunWindow g = run_window(srow, drow, run_bytes, w0, nw);
+    if (g.wbeg < g.wend) copy_full_vectors(g.svec, g.dvec, g.wbeg, g.wend, lane, nlanes);
+    if (g.head_bytes) copy_units(srow, drow, g.head_bytes, lane);
+    // lanes from the far end of the group, so that head and tail do not share lanes
+    if (g.tail_bytes) copy_units(g.svec + g.tail_off, g.dvec + g.tail_off, g.tail_bytes, nlanes - 1 - lane);
 }
 
 __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __restrict__ descs,
@@ -40,66 +100,53 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
                                                              uint32_t tile0, PtrArgs pa,
                                                              int alias_exchange)
 {
-    const TileRef tr = tiles[tile0 + blockIdx.x];
-    const CopyDesc d = descs[tr.desc];
-    const bool alias = alias_exchange && d.alt_src_slot >= 0;
-    const char* sbase = (alias ? slot_ptr(pa, d.alt_src_slot) + d.alt_src_byte
-                               : slot_ptr(pa, d.src_slot) + d.src_byte);
-    char* dbase = slot_ptr(pa, d.dst_slot) + d.dst_byte;
+    const TileRef* tp = tiles + (tile0 + blockIdx.x);
+    const uint32_t di = uniform32(tp->desc);
+    const uint32_t q = uniform32(tp->q);
+    const CopyDesc* __restrict__ d = descs + di;
+    const bool alias = alias_exchange && d->alt_src_slot >= 0;
+    const uint64_t sbase = uniform64(alias ? slot_addr(pa, d->alt_src_slot) + d->alt_src_byte
+                                           : slot_addr(pa, d->src_slot) + d->src_byte);
+    const uint64_t dbase = uniform64(slot_addr(pa, d->dst_slot) + d->dst_byte);
+    const uint32_t es = d->es;
     const uint32_t tid = threadIdx.x;
 
-    if (d.mode == MODE_RUN) {
-        uint32_t row0, nrows, w0, nw;
-        run_tile_geometry(d, tr.q, row0, nrows, w0, nw);
-        const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-        const uint32_t total = nrows * nw;
-        const char* srow0 = nullptr;
-        char* drow0 = nullptr;
-        if (nrows == 1) run_row_address(d, row0, sbase, dbase, srow0, drow0);
-        for (uint32_t base = 0; base < total; base += COPY_THREADS * COPY_UNROLL) {
-            u32x4 v[COPY_UNROLL];
-            char* tp[COPY_UNROLL];
-            bool full[COPY_UNROLL];
-#pragma unroll
-            for (int u = 0; u < COPY_UNROLL; ++u) {
-                const uint32_t slot = base + u * COPY_THREADS + tid;
-                full[u] = false;
-                if (slot < total) {
-                    const char* srow = srow0;
-                    char* drow = drow0;
-                    uint32_t w = w0 + slot;
-                    if (nrows != 1) {
-                        const uint32_t r = slot / nw;
-                        w = slot - r * nw;
-                        run_row_address(d, row0 + r, sbase, dbase, srow, drow);
-                    }
-                    const char* s;
-                    char* t;
-                    const uint32_t nb = run_vector_span(srow, drow, run_bytes, w, s, t);
-                    if (nb == 16) {
-                        full[u] = true;
-                        tp[u] = t;
-                        v[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_any*>(s));
-                    } else if (nb) {
-                        copy_partial(s, t, nb);
-                    }
-                }
+    if (d->mode == MODE_RUN) {
+        const uint64_t run_bytes = (uint64_t)d->ext[3] * es;
+        const uint32_t cpr = d->chunks_per_row;
+        if (cpr) {
+            // a chunk of one long run: the whole workgroup walks its vectors
+            const uint32_t row = uniform32(q / cpr);
+            const uint32_t w0 = uniform32((q - row * cpr) * d->vec_window);
+            uint64_t so, to;
+            run_row_offsets(*d, row, so, to);
+            const uint64_t srow = uniform64(sbase + so);
+            const uint64_t drow = uniform64(dbase + to);
+            copy_run_window(srow, drow, run_bytes, w0, d->vec_window, tid, COPY_THREADS);
+        } else {
+            // several short runs: one run per wavefront at a time
+            const uint32_t rows = d->ext[0] * d->ext[1] * d->ext[2];
+            const uint32_t rpt = d->rows_per_tile;
+            const uint32_t row0 = q * rpt;
+            const uint32_t nrows = rows - row0 < rpt ? rows - row0 : rpt;
+            const uint32_t wave = uniform32(tid >> 6), lane = tid & 63;
+            for (uint32_t r = wave; r < nrows; r += COPY_WAVES) {
+                uint64_t so, to;
+                run_row_offsets(*d, row0 + r, so, to);
+                const uint64_t srow = uniform64(sbase + so);
+                const uint64_t drow = uniform64(dbase + to);
+                copy_run_window(srow, drow, run_bytes, 0, d->vec_window, lane, 64);
             }
-#pragma unroll
-            for (int u = 0; u < COPY_UNROLL; ++u)
-                if (full[u]) __builtin_nontemporal_store(v[u], reinterpret_cast<u32x4*>(tp[u]));
         }
     } else {
-        const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
-        const uint64_t k0 = (uint64_t)tr.q * d.rows_per_tile;
-        const uint64_t k1 = k0 + d.rows_per_tile < vol ? k0 + d.rows_per_tile : vol;
+        const uint64_t vol = (uint64_t)d->ext[0] * d->ext[1] * d->ext[2] * d->ext[3];
+        const uint64_t k0 = (uint64_t)q * d->rows_per_tile;
+        const uint64_t k1 = k0 + d->rows_per_tile < vol ? k0 + d->rows_per_tile : vol;
         for (uint64_t k = k0 + tid; k < k1; k += COPY_THREADS) {
             int64_t so, to;
-            elem_offsets(d, k, so, to);
-            if (d.es == 2)
-                *reinterpret_cast<uint16_t*>(dbase + to) = *reinterpret_cast<const uint16_t*>(sbase + so);
-            else
-                *reinterpret_cast<uint32_t*>(dbase + to) = *reinterpret_cast<const uint32_t*>(sbase + so);
+            elem_offsets(*d, k, so, to);
+            if (es == 2) *(gdst2_t)(dbase + to) = *(gsrc2_t)(sbase + so);
+            else *(gdst4_t)(dbase + to) = *(gsrc4_t)(sbase + so);
         }
     }
 }

@@ -550,34 +550,48 @@ VPS_HD void run_tile_geometry(const CopyDesc& d, uint32_t q, uint32_t& row0, uin
     }
 }
 
-// Byte addresses of the first element of a row.
-VPS_HD void run_row_address(const CopyDesc& d, uint32_t row, const char* sbase, char* dbase,
-                            const char*& s, char*& t)
+// How one run is moved by the caller responsible for the window [w0, w0 + nw) of its
+// destination-aligned 16-byte vectors.  The run covers dst bytes [drow, drow + run_bytes) and
+// the same number of src bytes from srow.  Vector w is dst [dvec + 16w, +16), src svec + 16w.
+struct RunWindow {
+    uint64_t svec, dvec;     // src / dst address of vector 0 (dvec is 16-byte aligned)
+    uint32_t wbeg, wend;     // full vectors [wbeg, wend) to move with 16-byte accesses
+    uint32_t head_bytes;     // partial first vector: bytes to move from srow to drow (0 = none)
+    uint32_t tail_bytes;     // partial last vector: bytes to move at offset tail_off (0 = none)
+    uint64_t tail_off;       // byte offset from svec / dvec
+};
+
+VPS_HD RunWindow run_window(uint64_t srow, uint64_t drow, uint64_t run_bytes, uint32_t w0, uint32_t nw)
+{
+    RunWindow g;
+    const uint32_t head = (uint32_t)(drow & 15);        // bytes of vector 0 before the run
+    const uint64_t span = (uint64_t)head + run_bytes;     // run end relative to vector 0
+    const uint32_t wf = head ? 1u : 0u;                   // first full vector
+    const uint32_t wl = (uint32_t)(span >> 4);            // one past the last full vector
+    const uint32_t wend_win = w0 + nw;
+    g.dvec = drow - head;
+    g.svec = srow - head;
+    g.wbeg = w0 > wf ? w0 : wf;
+    g.wend = wend_win < wl ? wend_win : wl;
+    if (g.wend < g.wbeg) g.wend = g.wbeg;
+    g.head_bytes = (head && w0 == 0) ? (span < 16 ? (uint32_t)run_bytes : 16 - head) : 0;
+    const uint32_t tailb = (uint32_t)(span & 15);
+    // the last partial vector, unless it is the same vector as the head one
+    const bool has_tail = tailb && !(wl == 0 && head) && wl >= w0 && wl < wend_win;
+    g.tail_bytes = has_tail ? tailb : 0;
+    g.tail_off = (uint64_t)wl * 16;
+    return g;
+}
+
+// Byte offsets of the first element of run `row` relative to the descriptor bases.
+VPS_HD void run_row_offsets(const CopyDesc& d, uint32_t row, uint64_t& so, uint64_t& to)
 {
     const uint32_t c2 = row % d.ext[2];
     const uint32_t r1 = row / d.ext[2];
     const uint32_t c1 = r1 % d.ext[1];
     const uint32_t c0 = r1 / d.ext[1];
-    const int64_t so = (int64_t)c0 * d.sstr[0] + (int64_t)c1 * d.sstr[1] + (int64_t)c2 * d.sstr[2];
-    const int64_t to = (int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2];
-    s = sbase + so * (int64_t)d.es;
-    t = dbase + to * (int64_t)d.es;
-}
-
-// The part of aligned destination vector w (relative to the row's first vector) that lies in
-// the run: returns its byte count (0..16) and the matching source/destination addresses.
-VPS_HD uint32_t run_vector_span(const char* srow, char* drow, uint64_t run_bytes, uint32_t w,
-                                const char*& s, char*& t)
-{
-    const uintptr_t d0 = (uintptr_t)drow;
-    const uintptr_t v = (d0 & ~(uintptr_t)15) + (uintptr_t)16 * w;
-    const uintptr_t lo = v > d0 ? v : d0;
-    const uintptr_t end = d0 + run_bytes;
-    const uintptr_t hi = v + 16 < end ? v + 16 : end;
-    if (lo >= hi) return 0;
-    s = srow + (lo - d0);
-    t = (char*)lo;
-    return (uint32_t)(hi - lo);
+    so = (uint64_t)(((int64_t)c0 * d.sstr[0] + (int64_t)c1 * d.sstr[1] + (int64_t)c2 * d.sstr[2]) * (int64_t)d.es);
+    to = (uint64_t)(((int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2]) * (int64_t)d.es);
 }
 
 // Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.

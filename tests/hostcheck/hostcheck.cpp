@@ -83,15 +83,17 @@ public:
                 uint32_t row0, nrows, w0, nw;
                 run_tile_geometry(d, tr.q, row0, nrows, w0, nw);
                 const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-                const uint32_t total = nrows * nw;
-                for (uint32_t slot = 0; slot < total; ++slot) {
-                    const uint32_t r = slot / nw;
-                    const uint32_t w = nrows == 1 ? w0 + slot : slot - r * nw;
-                    const char* srow; char* drow;
-                    run_row_address(d, row0 + r, sbase, dbase, srow, drow);
-                    const char* s; char* t;
-                    const uint32_t nb = run_vector_span(srow, drow, run_bytes, w, s, t);
-                    if (nb) move(s, t, nb);
+                for (uint32_t r = 0; r < nrows; ++r) {
+                    uint64_t so, to;
+                    run_row_offsets(d, row0 + r, so, to);
+                    const uint64_t srow = (uint64_t)(uintptr_t)sbase + so, drow = (uint64_t)(uintptr_t)dbase + to;
+                    const RunWindow g = run_window(srow, drow, run_bytes, w0, nw);
+                    for (uint32_t w = g.wbeg; w < g.wend; ++w) {
+                        if ((g.dvec + 16ull * w) & 15) ++g_violations;
+                        move((const char*)(uintptr_t)(g.svec + 16ull * w), (char*)(uintptr_t)(g.dvec + 16ull * w), 16);
+                    }
+                    if (g.head_bytes) move((const char*)(uintptr_t)srow, (char*)(uintptr_t)drow, g.head_bytes);
+                    if (g.tail_bytes) move((const char*)(uintptr_t)(g.svec + g.tail_off), (char*)(uintptr_t)(g.dvec + g.tail_off), g.tail_bytes);
                 }
             } else {
                 const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
