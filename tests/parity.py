@@ -357,3 +357,148 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
         pos = int(bx["send_pos"])
         assert np.array_equal(sb[pos:pos + w.nbytes].view(w.dtype), w), ("send payload", bx)
     return dict(boxes=len(boxes), info=info, stats=plan.stats())
+
+
+# ----------------------------------------------------------------------------- full size
+
+def _sample_chunks(n, chunk, fraction, edges, rng):
+    """Chunk indices to verify: every chunk that holds a box edge, the first and last chunk, and
+    a random fraction of the rest."""
+    nchunks = -(-n // chunk)
+    pick = set([0, nchunks - 1])
+    for e in edges:
+        if 0 <= e < n:
+            pick.add(int(e) // chunk)
+    pick.update(np.nonzero(rng.random(nchunks) < fraction)[0].tolist())
+    return sorted(pick)
+
+
+def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05, chunk=1 << 20,
+                             box_samples=32, rows_per_box=4, log=print):
+    """One rank's share at full size, in the launch configuration the benchmark times.
+
+    The source buffers are filled by the oracle (every element), the receive buffer with the
+    pattern of the incoming boxes.  After one vps_apply_transition the destination buffers are
+    compared with the oracle on sampled 1 Mi-element chunks (all chunks holding a box edge, plus
+    a random fraction), the padding must be untouched, every box is validated by the oracle on
+    its corners and random interior points, and sampled rows of every outgoing box are compared
+    with the send buffer."""
+    import time
+    t0 = time.time()
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plan = lib.plan_intersections(ca, cb, rank)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    info = plan.buffer_bytes(rank)
+    log(f"  plan: {len(boxes)} boxes, send {info['send_total'] >> 20} MiB, recv {info['recv_total'] >> 20} MiB, "
+        f"retain {info['retain_total'] >> 20} MiB ({time.time() - t0:.1f}s)")
+
+    src_host, src, dst = {}, {}, {}
+    for buf in range(8):
+        n = a.buffer_elems(rank, buf) if rank < a.world else 0
+        src_host[buf] = a.fill(rank, buf, seed, 0, pad_word=0x3C3C3C3C) if n else np.zeros(0, kind_dtype(buf))
+        src[buf] = mem.alloc(src_host[buf].nbytes, fill=0)
+        mem.upload(src[buf], src_host[buf])
+        dst[buf] = mem.alloc((b.buffer_elems(rank, buf) if rank < b.world else 0) * oracle.KIND_BYTES[buf % 4])
+    log(f"  source filled by the oracle and uploaded ({time.time() - t0:.1f}s)")
+    scratch = mem.alloc(info["scratch_needed"])
+    recv = synth_recv_buffer(a, boxes, rank, info["recv_total"], seed, 0)
+    if recv.size:
+        mem.upload(scratch[info["recv_offset"]:info["recv_offset"] + recv.size], recv)
+    del recv
+    log(f"  receive buffer synthesized ({time.time() - t0:.1f}s)")
+    lib.apply_transition(plan, rank, [mem.ptr(src[buf]) for buf in range(8)],
+                         [mem.ptr(dst[buf]) for buf in range(8)], mem.ptr(scratch), info["scratch_needed"])
+    mem.sync()
+    log(f"  transition done ({time.time() - t0:.1f}s)")
+
+    rng = np.random.default_rng(seed & 0xFFFF)
+    checked = 0
+    for buf in range(8):
+        n = b.buffer_elems(rank, buf) if rank < b.world else 0
+        if not n:
+            continue
+        got = mem.download(dst[buf]).view(kind_dtype(buf))
+        mine = boxes[(boxes["dst_rank"] == rank) & (boxes["dst_buf"] == buf)]
+        edges = np.concatenate([mine["dst_off"], mine["dst_off"] - 1]) if len(mine) else np.zeros(0, np.int64)
+        for c in _sample_chunks(n, chunk, fraction, edges, rng):
+            o, m = c * chunk, min(chunk, n - c * chunk)
+            want = b.fill(rank, buf, seed, 0, off0=o, n=m, pad_word=SENT32)
+            if not np.array_equal(got[o:o + m], want):
+                bad = np.nonzero(got[o:o + m] != want)[0]
+                raise AssertionError(f"dst buf {buf}: {bad.size} wrong elements in chunk at {o}, first {o + bad[0]}")
+            checked += m
+        pay = b.payload_elems(rank, buf)
+        sent = SENT16 if buf % 4 == 0 else SENT32
+        assert (got[pay:] == sent).all(), f"padding of dst buf {buf} was written"
+        del got
+    log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
+
+    sb = mem.download(scratch[:info["send_total"]]) if info["send_total"] else np.zeros(0, np.uint8)
+    nrows_checked = 0
+    for bx in boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]:
+        ext = [int(e) for e in bx["ext"]]
+        rows = ext[0] * ext[1] * ext[2]
+        es = 2 if bx["kind"] == 0 else 4
+        for r in sorted(set([0, rows - 1] + rng.integers(0, rows, rows_per_box).tolist())):
+            c2, c1, c0 = r % ext[2], (r // ext[2]) % ext[1], r // (ext[2] * ext[1])
+            so = int(bx["src_off"]) + c0 * int(bx["src_stride"][0]) + c1 * int(bx["src_stride"][1]) + c2 * int(bx["src_stride"][2])
+            idx = so + np.arange(ext[3], dtype=np.int64) * int(bx["src_stride"][3])
+            w = src_host[int(bx["src_buf"])][idx]
+            pos = int(bx["send_pos"]) + r * ext[3] * es
+            assert np.array_equal(sb[pos:pos + ext[3] * es].view(w.dtype), w), ("send payload", bx, r)
+            nrows_checked += 1
+    log(f"  {nrows_checked} rows of outgoing boxes compared with the send buffer ({time.time() - t0:.1f}s)")
+    return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
+
+
+def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 << 22, box_samples=16, log=print):
+    """Every virtual rank resident at full size: one vps_apply_transition(rank=-1) call, all
+    destination buffers against the oracle (layout-B fill of the same coordinate hash)."""
+    import time
+    t0 = time.time()
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    check_config_against_oracle(ca, a)
+    check_config_against_oracle(cb, b)
+    plan = lib.plan_intersections(ca, cb, -1)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, -1, samples=box_samples)
+    info = plan.buffer_bytes(-1)
+    log(f"  plan: {len(boxes)} boxes, exchanged {info['send_total'] >> 20} MiB, retained {info['retain_total'] >> 20} MiB ({time.time() - t0:.1f}s)")
+    src, dst = {}, {}
+    for r in range(a.world):
+        for buf in range(8):
+            h = a.fill(r, buf, seed, 0, pad_word=0x3C3C3C3C) if a.buffer_elems(r, buf) else np.zeros(0, kind_dtype(buf))
+            src[(r, buf)] = mem.alloc(h.nbytes, fill=0)
+            mem.upload(src[(r, buf)], h)
+    for j in range(b.world):
+        for buf in range(8):
+            dst[(j, buf)] = mem.alloc(b.buffer_elems(j, buf) * oracle.KIND_BYTES[buf % 4])
+    scratch = mem.alloc(info["scratch_needed"])
+    log(f"  sources filled by the oracle and uploaded ({time.time() - t0:.1f}s)")
+    lib.apply_transition(plan, -1, [mem.ptr(src[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                         [mem.ptr(dst[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                         mem.ptr(scratch), info["scratch_needed"])
+    mem.sync()
+    log(f"  transition done ({time.time() - t0:.1f}s)")
+    rng = np.random.default_rng(seed & 0xFFFF)
+    checked = 0
+    for j in range(b.world):
+        for buf in range(8):
+            n = b.buffer_elems(j, buf)
+            if not n:
+                continue
+            got = mem.download(dst[(j, buf)]).view(kind_dtype(buf))
+            mine = boxes[(boxes["dst_rank"] == j) & (boxes["dst_buf"] == buf)]
+            edges = np.concatenate([mine["dst_off"], mine["dst_off"] - 1]) if len(mine) else np.zeros(0, np.int64)
+            for c in _sample_chunks(n, chunk, fraction, edges, rng):
+                o, m = c * chunk, min(chunk, n - c * chunk)
+                want = b.fill(j, buf, seed, 0, off0=o, n=m, pad_word=SENT32)
+                if not np.array_equal(got[o:o + m], want):
+                    bad = np.nonzero(got[o:o + m] != want)[0]
+                    raise AssertionError(f"dst ({j},{buf}): {bad.size} wrong elements in chunk at {o}, first {o + bad[0]}")
+                checked += m
+    log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
+    return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())

@@ -1,0 +1,83 @@
+"""GPU parity at the benchmark's full sizes (one rank's share of the large workloads)."""
+import os
+
+import pytest
+
+import parity
+from datagen import configs as cf
+
+pytestmark = pytest.mark.gpu
+
+FRACTION = float(os.environ.get("VPS_FULLSIZE_FRACTION", "1.0"))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2605_18815_amd as vps
+    return vps.load()
+
+
+def _run(lib, name, rank=None, src_over=None, dst_over=None):
+    w = cf.WORKLOADS[name]
+    pa, pb = dict(w["src"]), dict(w["dst"])
+    pa.update(src_over or {})
+    pb.update(dst_over or {})
+    rank = w["rank"] if rank is None else rank
+    print(f"\n{name} rank {rank}", flush=True)
+    out = parity.run_single_rank_fullsize(lib, parity.GpuMem(), w["model"], pa, pb, rank,
+                                          seed=cf.seed_of(name), fraction=FRACTION,
+                                          log=lambda s: print(s, flush=True))
+    assert out["checked"] > 0
+    return out
+
+
+@pytest.mark.timeout(600)
+def test_gqa70b_rank11_full_size(lib):
+    out = _run(lib, "gqa70b")
+    # first-stage rank: the embedding shifts the flat edges, fp32 state really moves
+    assert out["info"]["send_total"] > 0 and out["info"]["recv_total"] > 0
+
+
+@pytest.mark.timeout(600)
+def test_gqa70b_mid_stage_rank_keeps_fp32(lib):
+    out = _run(lib, "gqa70b", rank=43)
+    w = cf.WORKLOADS["gqa70b"]
+    import oracle
+    b = oracle.Config(w["model"], w["dst"])
+    fp32 = sum(4 * b.payload_elems(43, k) for k in (1, 2, 3))
+    assert out["info"]["retain_total"] >= fp32
+
+
+@pytest.mark.timeout(600)
+def test_gqa8b_rank5_full_size(lib):
+    out = _run(lib, "gqa8b")
+    assert out["stats"]["num_peers_in"] >= 2
+
+
+@pytest.mark.timeout(600)
+def test_gqa8b_rank5_destination_blocked_qkv(lib):
+    """Variant: the destination stores fused QKV as [all Q | all K | all V] blocks."""
+    _run(lib, "gqa8b", dst_over=dict(qkv_layout=1))
+
+
+@pytest.mark.timeout(600)
+def test_gqa70b_rank11_reverse_flat_order(lib):
+    """Variant: descending tensor order in the flat buffers, so that all fp32 state moves."""
+    out = _run(lib, "gqa70b", src_over=dict(flat_order=1))
+    assert out["info"]["recv_total"] > 0
+
+
+@pytest.mark.timeout(900)
+def test_moe235b_rank37_full_size(lib):
+    out = _run(lib, "moe235b")
+    assert out["stats"]["num_boxes"] > 1000
+
+
+@pytest.mark.timeout(900)
+def test_gpt1p3b_all_ranks_full_size(lib):
+    w = cf.WORKLOADS["gpt1p3b"]
+    print("\ngpt1p3b all 32 ranks", flush=True)
+    out = parity.run_all_ranks_fullsize(lib, parity.GpuMem(), w["model"], w["src"], w["dst"],
+                                        seed=cf.seed_of("gpt1p3b"), fraction=FRACTION,
+                                        log=lambda s: print(s, flush=True))
+    assert out["checked"] > 0
