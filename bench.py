@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="also run one plain device-to-device copy of MIB MiB (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every virtual rank or one rank's share is "
@@ -80,17 +82,11 @@ def main():
     t_desc, t_plan = [], []
 
     def one_step(k=None):
-        t0 = time.perf_counter()
         if args.apply_only:
             p = plan
         else:
             a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
-            t1 = time.perf_counter()
             p = lib.plan_intersections(a2, b2, rank, stream)
-            t2 = time.perf_counter()
-            if k is not None:
-                t_desc.append((t1 - t0) * 1e3)
-                t_plan.append((t2 - t1) * 1e3)
         if k is not None:
             ev[k][0].record()
         lib.apply_transition(p, rank, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
@@ -98,8 +94,28 @@ def main():
             ev[k][1].record()
         return p
 
+    if args.calibrate_copy:
+        n = args.calibrate_copy << 20
+        x = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+        y = torch.empty(n, dtype=torch.uint8, device=dev)
+        y.copy_(x)   # a plain copy kernel of known size: n bytes read, n bytes written
+        torch.cuda.synchronize()
+        del x, y
+
     for _ in range(args.warmup):
         one_step()
+    torch.cuda.synchronize()
+    # host wall time of mapping and planning with an idle device (not part of the timed region)
+    for _ in range(5):
+        torch.cuda.synchronize()
+        ta = time.perf_counter()
+        a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
+        tb = time.perf_counter()
+        p2 = lib.plan_intersections(a2, b2, rank, stream)
+        tc = time.perf_counter()
+        t_desc.append((tb - ta) * 1e3)
+        t_plan.append((tc - tb) * 1e3)
+        del a2, b2, p2
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     keep = [one_step(k) for k in range(args.steps)]
@@ -128,7 +144,7 @@ def main():
         "dtype": "u16+u32", "data": "synthetic",
         "config": {"workload": f"{args.workload} rank {rank}" if rank >= 0 else f"{args.workload} all ranks",
                    "src": pa, "dst": pb, "step": "apply only" if args.apply_only else "describe x2 + plan + apply",
-                   "tile_bytes": args.tile_bytes or 32768},
+                   "tile_bytes": args.tile_bytes or 8192},
         "breakdown_ms": {"describe_x2": _avg(t_desc), "plan": _avg(t_plan), "apply_kernels": apply_avg},
         "apply_gbps": bytes_moved / (apply_avg * 1e-3) / 1e9,
         "pct_hbm_peak_apply": 100.0 * bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,

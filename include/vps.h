@@ -189,7 +189,7 @@ void vps_plan_destroy(vps_plan* plan);
 const char* vps_last_error(void);
 
 /* Tuning knob for benchmarks: target payload bytes per workgroup tile (power of two between
- * 4 KiB and 1 MiB; default 32 KiB).  Applies to plans created afterwards. */
+ * 4 KiB and 1 MiB; default 8 KiB).  Applies to plans created afterwards. */
 int vps_set_tile_bytes(uint32_t bytes);
 
 #ifdef __cplusplus

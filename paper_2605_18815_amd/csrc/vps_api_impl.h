@@ -13,7 +13,7 @@
 namespace vps {
 
 static thread_local std::string g_last_error;
-static uint32_t g_tile_bytes = 32u << 10;
+static uint32_t g_tile_bytes = 8u << 10;
 
 inline int fail(int code, const std::string& msg)
 {
@@ -130,6 +130,7 @@ void VPS_FN(plan_destroy)(vps_plan* p)
 {
     if (!p) return;
     VPS_BACKEND be(nullptr);
+    be.quiesce();  // queued copy kernels may still read the plan's tables
     vps::free_plan(be, p->d);
     delete p;
 }

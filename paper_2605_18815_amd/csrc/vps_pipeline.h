@@ -30,6 +30,31 @@
 
 namespace vps {
 
+// One tag per data-parallel step: it names the kernel in profiles.
+namespace step {
+struct map_tensor_class {};
+struct map_shard_lengths {};
+struct map_class_bounds {};
+struct map_class_lengths {};
+struct map_tensor_offsets {};
+struct map_count_pieces {};
+struct map_emit_pieces {};
+struct plan_count_boxes {};
+struct plan_emit_boxes {};
+struct plan_key_lo {};
+struct plan_key_send {};
+struct plan_key_recv {};
+struct plan_slot_sizes {};
+struct plan_rank_bounds {};
+struct plan_positions {};
+struct plan_rank_bases {};
+struct plan_pair_bytes {};
+struct plan_copy_descs {};
+struct plan_tile_table {};
+struct plan_sorted_boxes {};
+struct plan_recv_perm {};
+}  // namespace step
+
 struct ConfigData {
     vps_model_desc model;
     vps_parallel_desc par;
@@ -109,7 +134,7 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     int64_t* cbeg = be.template alloc<int64_t>(P.ncls + 1);
     {
         const TensorRec* T = c.T; TensorLayout* TL = c.TL;
-        be.for_each(nt, [=] VPS_LAMBDA(int64_t q) {
+        be.for_each(step::map_tensor_class(), nt, [=] VPS_LAMBDA(int64_t q) {
             const int32_t t = P.flat_order ? nt - 1 - (int32_t)q : (int32_t)q;
             const TensorRec x = T[t];
             TensorLayout tl;
@@ -125,14 +150,14 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     be.sort_pairs(key, val, nt);
     {
         const TensorLayout* TL = c.TL;
-        be.for_each(nt + 1, [=] VPS_LAMBDA(int64_t k) { len[k] = k < nt ? (int64_t)TL[val[k]].shard_len : 0; });
+        be.for_each(step::map_shard_lengths(), nt + 1, [=] VPS_LAMBDA(int64_t k) { len[k] = k < nt ? (int64_t)TL[val[k]].shard_len : 0; });
     }
     be.exclusive_scan(len, ofs, nt);
     // (3) class boundaries, lengths and padding
     {
         ClassRec* C = c.C;
-        be.for_each(P.ncls + 1, [=] VPS_LAMBDA(int64_t cls) { cbeg[cls] = lower_bound_idx(key, (int64_t)nt, (uint64_t)cls); });
-        be.for_each(P.ncls, [=] VPS_LAMBDA(int64_t cls) {
+        be.for_each(step::map_class_bounds(), P.ncls + 1, [=] VPS_LAMBDA(int64_t cls) { cbeg[cls] = lower_bound_idx(key, (int64_t)nt, (uint64_t)cls); });
+        be.for_each(step::map_class_lengths(), P.ncls, [=] VPS_LAMBDA(int64_t cls) {
             ClassRec r;
             r.len = (uint64_t)(ofs[cbeg[cls + 1]] - ofs[cbeg[cls]]);
             const uint64_t quantum = 8ull * (uint64_t)(cls < P.pp ? P.ddp : P.dp);
@@ -140,7 +165,7 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
             C[cls] = r;
         });
         TensorLayout* TL = c.TL;
-        be.for_each(nt, [=] VPS_LAMBDA(int64_t k) {
+        be.for_each(step::map_tensor_offsets(), nt, [=] VPS_LAMBDA(int64_t k) {
             TL[val[k]].start = (uint64_t)(ofs[k] - ofs[cbeg[key[k]]]);
         });
     }
@@ -152,19 +177,19 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     c.piece_base = be.template alloc<int64_t>(nitems + 1);
     MapCtx mc;
     mc.P = P; mc.T = c.T; mc.TL = c.TL; mc.C = c.C; mc.rank_filter = rank_filter;
-    be.for_each(nitems + 1, [=] VPS_LAMBDA(int64_t i) { cnt[i] = i < nitems ? map_item_pieces(mc, i, nullptr) : 0; });
+    be.for_each(step::map_count_pieces(), nitems + 1, [=] VPS_LAMBDA(int64_t i) { cnt[i] = i < nitems ? map_item_pieces(mc, i, nullptr) : 0; });
     be.exclusive_scan(cnt, c.piece_base, nitems);
     be.download(&c.npieces, c.piece_base + nitems, sizeof(int64_t));
     c.pieces = be.template alloc<vps_piece>(c.npieces);
     {
         const int64_t* pb = c.piece_base; vps_piece* pieces = c.pieces;
-        be.for_each(nitems, [=] VPS_LAMBDA(int64_t i) {
+        be.for_each(step::map_emit_pieces(), nitems, [=] VPS_LAMBDA(int64_t i) {
             if (pb[i + 1] > pb[i]) map_item_pieces(mc, i, pieces + pb[i]);
         });
     }
     be.free(cnt);
     c.hC.resize((size_t)P.ncls);
-    be.download(c.hC.data(), c.C, sizeof(ClassRec) * (size_t)P.ncls);
+    be.download_later(c.hC.data(), c.C, sizeof(ClassRec) * (size_t)P.ncls);
     be.sync();
 }
 
@@ -202,14 +227,14 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     const int64_t nd = cb.npieces;
     int64_t* cnt = be.template alloc<int64_t>(nd + 1);
     int64_t* bbase = be.template alloc<int64_t>(nd + 1);
-    be.for_each(nd + 1, [=] VPS_LAMBDA(int64_t d) { cnt[d] = d < nd ? plan_item_boxes(pc, d, nullptr) : 0; });
+    be.for_each(step::plan_count_boxes(), nd + 1, [=] VPS_LAMBDA(int64_t d) { cnt[d] = d < nd ? plan_item_boxes(pc, d, nullptr) : 0; });
     be.exclusive_scan(cnt, bbase, nd);
     int64_t n = 0;
     be.download(&n, bbase + nd, sizeof(int64_t));
     if (n >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 boxes" };
     p.nboxes = n;
     vps_box* boxes = be.template alloc<vps_box>(n);
-    be.for_each(nd, [=] VPS_LAMBDA(int64_t d) {
+    be.for_each(step::plan_emit_boxes(), nd, [=] VPS_LAMBDA(int64_t d) {
         if (bbase[d + 1] > bbase[d]) plan_item_boxes(pc, d, boxes + bbase[d]);
     });
     be.free(cnt); be.free(bbase);
@@ -222,11 +247,11 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     uint32_t* ord_r = be.template alloc<uint32_t>(n);
     {
         const TensorRec* T = ca.T;
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); by_lo[k] = (uint32_t)k; });
+        be.for_each(step::plan_key_lo(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); by_lo[k] = (uint32_t)k; });
         be.sort_pairs(kmin, by_lo, n);
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], false); });
+        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], false); });
         be.sort_pairs(kmaj, ord_s, n);
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], true); });
+        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], true); });
         be.sort_pairs(kmaj, ord_r, n);
     }
     be.free(kmin); be.free(kmaj); be.free(by_lo);
@@ -236,11 +261,12 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     int64_t* pos = be.template alloc<int64_t>(n + 1);
     int32_t* owner = be.template alloc<int32_t>(n);
     int64_t* first = be.template alloc<int64_t>(W + 1);
+    uint64_t* rbase = be.template alloc<uint64_t>(2 * (W + 1));
     p.first_send.assign((size_t)W + 1, 0); p.first_recv.assign((size_t)W + 1, 0);
     p.send_base.assign((size_t)W + 1, 0); p.recv_base.assign((size_t)W + 1, 0);
     for (int side = 0; side < 2; ++side) {
         const uint32_t* ord = side == 0 ? ord_s : ord_r;
-        be.for_each(n + 1, [=] VPS_LAMBDA(int64_t k) {
+        be.for_each(step::plan_slot_sizes(), n + 1, [=] VPS_LAMBDA(int64_t k) {
             if (k == n) { sz[k] = 0; return; }
             const vps_box& b = boxes[ord[k]];
             const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
@@ -249,8 +275,8 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             sz[k] = (b.src_rank != b.dst_rank && resident) ? (int64_t)box_slot_bytes(b) : 0;
         });
         be.exclusive_scan(sz, pos, n);
-        be.for_each(W + 1, [=] VPS_LAMBDA(int64_t r) { first[r] = lower_bound_idx(owner, n, (int32_t)r); });
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) {
+        be.for_each(step::plan_rank_bounds(), W + 1, [=] VPS_LAMBDA(int64_t r) { first[r] = lower_bound_idx(owner, n, (int32_t)r); });
+        be.for_each(step::plan_positions(), n, [=] VPS_LAMBDA(int64_t k) {
             vps_box& b = boxes[ord[k]];
             if (sz[k] == 0) return;
             const uint64_t rel = (uint64_t)(pos[k] - pos[first[owner[k]]]);
@@ -258,22 +284,21 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         });
         std::vector<int64_t>& hf = side == 0 ? p.first_send : p.first_recv;
         std::vector<uint64_t>& hb = side == 0 ? p.send_base : p.recv_base;
-        be.download(hf.data(), first, sizeof(int64_t) * (size_t)(W + 1));
-        std::vector<int64_t> hpos((size_t)n + 1);
-        be.download(hpos.data(), pos, sizeof(int64_t) * (size_t)(n + 1));
-        for (int r = 0; r <= W; ++r) hb[(size_t)r] = (uint64_t)hpos[(size_t)hf[(size_t)r]];
+        be.for_each(step::plan_rank_bases(), W + 1, [=] VPS_LAMBDA(int64_t r) { rbase[side * (W + 1) + r] = (uint64_t)pos[first[r]]; });
+        be.download_later(hf.data(), first, sizeof(int64_t) * (size_t)(W + 1));
+        be.download_later(hb.data(), rbase + side * (W + 1), sizeof(uint64_t) * (size_t)(W + 1));
     }
-    be.free(sz); be.free(pos); be.free(owner); be.free(first);
+    be.free(sz); be.free(pos); be.free(owner); be.free(first); be.free(rbase);
 
     // (4) payload bytes per (source, destination) pair
     uint64_t* pairs = be.template alloc<uint64_t>((int64_t)WA * WB);
     be.zero(pairs, sizeof(uint64_t) * (size_t)WA * (size_t)WB);
-    be.for_each(n, [=] VPS_LAMBDA(int64_t k) {
+    be.for_each(step::plan_pair_bytes(), n, [=] VPS_LAMBDA(int64_t k) {
         const vps_box& b = boxes[k];
         be_atomic_add(&pairs[(int64_t)b.src_rank * WB + b.dst_rank], box_volume(b) * kind_bytes(b.kind));
     });
     p.pair_bytes.resize((size_t)WA * (size_t)WB);
-    be.download(p.pair_bytes.data(), pairs, sizeof(uint64_t) * (size_t)WA * (size_t)WB);
+    be.download_later(p.pair_bytes.data(), pairs, sizeof(uint64_t) * (size_t)WA * (size_t)WB);
     be.free(pairs);
 
     // (5) copy descriptors and tile table
@@ -282,7 +307,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     int64_t* tb = be.template alloc<int64_t>(3 * n + 1);
     {
         CopyDesc* descs = p.descs;
-        be.for_each(3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
+        be.for_each(step::plan_copy_descs(), 3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
             if (i == 3 * n) { nt[i] = 0; return; }
             const int op = (int)(i / n);
             const int64_t k = i % n;
@@ -301,7 +326,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     p.tiles = be.template alloc<TileRef>(ntiles);
     {
         TileRef* tiles = p.tiles;
-        be.for_each(ntiles, [=] VPS_LAMBDA(int64_t t) {
+        be.for_each(step::plan_tile_table(), ntiles, [=] VPS_LAMBDA(int64_t t) {
             const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;
             TileRef r;
             r.desc = (uint32_t)d;
@@ -316,12 +341,12 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         vps_box* sorted = be.template alloc<vps_box>(n);
         uint32_t* inv = be.template alloc<uint32_t>(n);
         uint32_t* rperm = be.template alloc<uint32_t>(n);
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = boxes[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
-        be.for_each(n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
+        be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = boxes[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
+        be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
         p.boxes_send_order.resize((size_t)n);
         p.recv_perm.resize((size_t)n);
-        be.download(p.boxes_send_order.data(), sorted, sizeof(vps_box) * (size_t)n);
-        be.download(p.recv_perm.data(), rperm, sizeof(uint32_t) * (size_t)n);
+        be.download_later(p.boxes_send_order.data(), sorted, sizeof(vps_box) * (size_t)n);
+        be.download_later(p.recv_perm.data(), rperm, sizeof(uint32_t) * (size_t)n);
         be.free(sorted); be.free(inv); be.free(rperm);
     }
     be.free(ord_s); be.free(ord_r); be.free(boxes);

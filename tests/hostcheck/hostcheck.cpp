@@ -41,7 +41,7 @@ public:
     void free(void* p) { ::free(p); }
     void commit() {}
     void release_all() {}
-    template <class F> void for_each(int64_t n, F f) { for (int64_t i = 0; i < n; ++i) f(i); }
+    template <class Step, class F> void for_each(Step, int64_t n, F f) { for (int64_t i = 0; i < n; ++i) f(i); }
     void exclusive_scan(const int64_t* in, int64_t* out, int64_t n)
     {
         int64_t acc = 0;
@@ -60,8 +60,10 @@ public:
     }
     void upload(void* d, const void* h, size_t b) { if (b) memcpy(d, h, b); }
     void download(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
+    void download_later(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
     void zero(void* d, size_t b) { if (b) memset(d, 0, b); }
     void sync() {}
+    void quiesce() {}
     void set_ptr_table(void** table, void* const* host_ptrs, int n) { memcpy(table, host_ptrs, sizeof(void*) * (size_t)n); }
 
     // Same slot walk as the device kernel, one lane at a time, with bounds checks.

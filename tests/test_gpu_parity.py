@@ -43,4 +43,4 @@ def test_tile_size_does_not_change_results(lib, tile):
         w = cf.WORKLOADS["toy"]
         parity.run_single_rank(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], 1, seed=78)
     finally:
-        lib.set_tile_bytes(32768)
+        lib.set_tile_bytes(8192)

@@ -61,7 +61,7 @@ def test_tile_size_does_not_change_results(hlib, tile):
         w = cf.WORKLOADS["toy"]
         parity.run_single_rank(hlib, parity.HostMem(hlib), w["model"], w["src"], w["dst"], 1, seed=78)
     finally:
-        hlib.set_tile_bytes(32768)
+        hlib.set_tile_bytes(8192)
 
 
 def test_split_linear_range_properties(hlib):
