@@ -2,6 +2,7 @@
 // rocPRIM for the two generic primitives (exclusive scan, stable radix sort).
 #pragma once
 
+#include <cstdlib>
 #include <cstring>
 
 #include <hip/hip_runtime.h>
@@ -284,11 +285,21 @@ public:
     {
         if (ntiles <= 0) return;
         hipLaunchKernelGGL(k_copy_tiles, dim3((unsigned)ntiles), dim3(COPY_THREADS), 0, stream_, descs,
-                           tiles, (uint32_t)tile0, pa, alias);
+                           tiles, (uint32_t)tile0, pa, alias, xcd_chunk());
         VPS_HIP_CHECK(hipGetLastError());
     }
 
     hipStream_t stream() const { return stream_; }
+
+    // Tiles per XCD run (0 = plain round-robin); VPS_XCD_CHUNK overrides it for experiments.
+    static uint32_t xcd_chunk()
+    {
+        static const uint32_t v = [] {
+            const char* e = getenv("VPS_XCD_CHUNK");
+            return e ? (uint32_t)atoi(e) : 64u;
+        }();
+        return v;
+    }
 
 private:
     void recycle_dead()

@@ -34,7 +34,6 @@ typedef VPS_GLOBAL uint32_t* gdst4_t;
 
 constexpr int COPY_THREADS = 256;
 constexpr int COPY_WAVES = COPY_THREADS / 64;
-constexpr int COPY_UNROLL = 4;
 
 __device__ __forceinline__ uint32_t uniform32(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -51,30 +50,16 @@ __device__ __forceinline__ uint64_t slot_addr(const PtrArgs& pa, int32_t slot)
 }
 
 // Full vectors [wbeg, wend) of one run: vector w sits at dst `dvec + 16*w` (16-byte aligned)
-// and src `svec + 16*w`.  `lane` strides by `nlanes`.
+// and src `svec + 16*w`.  `lane` strides by `nlanes`.  One load in flight per lane: with eight
+// waves per SIMD resident this measured faster than unrolled batches of loads, whose stores
+// then arrive in bursts.
 __device__ __forceinline__ void copy_full_vectors(uint64_t svec, uint64_t dvec, uint32_t wbeg,
                                                   uint32_t wend, uint32_t lane, uint32_t nlanes)
 {
-    uint32_t w = wbeg + lane;
-    // all COPY_UNROLL loads are issued before the first store
-    for (; w + (COPY_UNROLL - 1) * nlanes < wend; w += COPY_UNROLL * nlanes) {
-        u32x4 v[COPY_UNROLL];
-#pragma unroll
-        for (int u = 0; u < COPY_UNROLL; ++u)
-            v[u] = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)(w + u * nlanes) * 16));
-#pragma unroll
-        for (int u = 0; u < COPY_UNROLL; ++u)
-            __builtin_nontemporal_store(v[u], (gdst16_t)(dvec + (uint64_t)(w + u * nlanes) * 16));
+    for (uint32_t w = wbeg + lane; w < wend; w += nlanes) {
+        const u32x4 v = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)w * 16));
+        __builtin_nontemporal_store(v, (gdst16_t)(dvec + (uint64_t)w * 16));
     }
-    u32x4 v[COPY_UNROLL - 1];
-#pragma unroll
-    for (int u = 0; u < COPY_UNROLL - 1; ++u)
-        if (w + u * nlanes < wend)
-            v[u] = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)(w + u * nlanes) * 16));
-#pragma unroll
-    for (int u = 0; u < COPY_UNROLL - 1; ++u)
-        if (w + u * nlanes < wend)
-            __builtin_nontemporal_store(v[u], (gdst16_t)(dvec + (uint64_t)(w + u * nlanes) * 16));
 }
 
 // Fewer than 16 bytes (a multiple of 2): lane t moves 2-byte unit t.
@@ -98,32 +83,43 @@ __device__ __forceinline__ void copy_run_window(uint64_t srow, uint64_t drow, ui
 __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __restrict__ descs,
                                                              const TileRef* __restrict__ tiles,
                                                              uint32_t tile0, PtrArgs pa,
-                                                             int alias_exchange)
+                                                             int alias_exchange, uint32_t xcd_chunk)
 {
-    const TileRef* tp = tiles + (tile0 + blockIdx.x);
-    const uint32_t di = uniform32(tp->desc);
-    const uint32_t q = uniform32(tp->q);
+    // Workgroups are dealt round-robin to the 8 XCDs.  Consecutive tiles are neighbours in
+    // memory, so hand each XCD runs of xcd_chunk consecutive tiles instead of every 8th one.
+    uint32_t b = blockIdx.x;
+    if (xcd_chunk) {
+        const uint32_t x = b & 7, j = b >> 3;
+        const uint32_t grp = j / xcd_chunk;
+        if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
+    }
+    const TileRef* tp = tiles + (tile0 + b);
+    const uint32_t tid = threadIdx.x;
+    const uint32_t flags = uniform32(tp->flags);
+    if (!(flags & TILE_INDIRECT)) {
+        // a contiguous piece of one long run
+        const uint32_t nbytes = uniform32(tp->nbytes);
+        if (!nbytes) return;
+        const uint64_t alt = tp->alt_src;
+        const uint64_t sa = uniform64((alias_exchange && alt != VPS_TILE_NO_ALT) ? alt : tp->src);
+        const uint64_t da = uniform64(tp->dst);
+        const uint64_t s = uniform64(slot_addr(pa, tile_slot(sa)) + tile_offset(sa));
+        const uint64_t t = uniform64(slot_addr(pa, tile_slot(da)) + tile_offset(da));
+        copy_run_window(s, t, nbytes, 0, (nbytes + 30) >> 4, tid, COPY_THREADS);
+        return;
+    }
+    const uint32_t di = uniform32((uint32_t)tp->alt_src);
+    const uint32_t q = uniform32((uint32_t)(tp->alt_src >> 32));
     const CopyDesc* __restrict__ d = descs + di;
     const bool alias = alias_exchange && d->alt_src_slot >= 0;
     const uint64_t sbase = uniform64(alias ? slot_addr(pa, d->alt_src_slot) + d->alt_src_byte
                                            : slot_addr(pa, d->src_slot) + d->src_byte);
     const uint64_t dbase = uniform64(slot_addr(pa, d->dst_slot) + d->dst_byte);
     const uint32_t es = d->es;
-    const uint32_t tid = threadIdx.x;
 
     if (d->mode == MODE_RUN) {
         const uint64_t run_bytes = (uint64_t)d->ext[3] * es;
-        const uint32_t cpr = d->chunks_per_row;
-        if (cpr) {
-            // a chunk of one long run: the whole workgroup walks its vectors
-            const uint32_t row = uniform32(q / cpr);
-            const uint32_t w0 = uniform32((q - row * cpr) * d->vec_window);
-            uint64_t so, to;
-            run_row_offsets(*d, row, so, to);
-            const uint64_t srow = uniform64(sbase + so);
-            const uint64_t drow = uniform64(dbase + to);
-            copy_run_window(srow, drow, run_bytes, w0, d->vec_window, tid, COPY_THREADS);
-        } else {
+        {
             // several short runs: one run per wavefront at a time
             const uint32_t rows = d->ext[0] * d->ext[1] * d->ext[2];
             const uint32_t rpt = d->rows_per_tile;

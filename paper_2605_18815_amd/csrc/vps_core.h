@@ -527,10 +527,24 @@ struct PtrArgs {
     char* const* tbl;      // all-ranks plans: table in device memory (nullptr otherwise)
 };
 
+// One tile of the copy engine (32 bytes, read by the workgroup with one scalar load).
+//   direct    a contiguous piece of one long run: everything the kernel needs is here, so a
+//             workgroup does no index arithmetic at all
+//   indirect  several short runs or an element-wise tile: tile q of descriptor `desc`
 struct TileRef {
-    uint32_t desc;
-    uint32_t q;  // tile index inside the descriptor
+    uint64_t src;      // direct: slot << 44 | byte offset in the slot's buffer
+    uint64_t dst;
+    uint64_t alt_src;  // direct: the sender's send buffer for in-place exchange (or TILE_NO_ALT)
+                       // indirect: q << 32 | desc
+    uint32_t nbytes;   // direct: bytes to move
+    uint32_t flags;    // TILE_INDIRECT
 };
+enum : uint32_t { TILE_INDIRECT = 1u };
+#define VPS_TILE_NO_ALT (~0ull)
+
+VPS_HD uint64_t tile_pack_addr(int32_t slot, uint64_t byte_off) { return ((uint64_t)slot << 44) | byte_off; }
+VPS_HD int32_t tile_slot(uint64_t a) { return (int32_t)(a >> 44); }
+VPS_HD uint64_t tile_offset(uint64_t a) { return a & ((1ull << 44) - 1); }
 
 // Geometry of tile q of a RUN descriptor: rows [row0, row0+nrows), and for each row the window
 // [w0, w0+nw) of aligned destination vectors.
@@ -592,6 +606,37 @@ VPS_HD void run_row_offsets(const CopyDesc& d, uint32_t row, uint64_t& so, uint6
     const uint32_t c0 = r1 / d.ext[1];
     so = (uint64_t)(((int64_t)c0 * d.sstr[0] + (int64_t)c1 * d.sstr[1] + (int64_t)c2 * d.sstr[2]) * (int64_t)d.es);
     to = (uint64_t)(((int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2]) * (int64_t)d.es);
+}
+
+// Tile q of descriptor `di`.  Chunks of a long run become direct tiles: chunk c covers the
+// destination vectors [c*vec_window, (c+1)*vec_window) counted from the 16-byte boundary at or
+// below the run's first destination byte (buffer bases are at least 16-byte aligned; with a
+// less aligned base the tiles are still disjoint and complete, only less evenly cut).
+VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
+{
+    TileRef t;
+    if (d.mode == MODE_RUN && d.chunks_per_row) {
+        const uint32_t row = q / d.chunks_per_row, c = q - row * d.chunks_per_row;
+        uint64_t so, to;
+        run_row_offsets(d, row, so, to);
+        const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
+        const uint64_t d0 = d.dst_byte + to, end = d0 + run_bytes, ab = d0 & ~15ull;
+        uint64_t lo = ab + 16ull * c * d.vec_window, hi = lo + 16ull * d.vec_window;
+        if (lo < d0) lo = d0;
+        if (hi > end) hi = end;
+        if (hi < lo) hi = lo;
+        t.src = tile_pack_addr(d.src_slot, d.src_byte + so + (lo - d0));
+        t.dst = tile_pack_addr(d.dst_slot, lo);
+        t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so + (lo - d0)) : VPS_TILE_NO_ALT;
+        t.nbytes = (uint32_t)(hi - lo);
+        t.flags = 0;
+    } else {
+        t.src = 0; t.dst = 0;
+        t.alt_src = ((uint64_t)q << 32) | di;
+        t.nbytes = 0;
+        t.flags = TILE_INDIRECT;
+    }
+    return t;
 }
 
 // Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.

@@ -326,12 +326,10 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     p.tiles = be.template alloc<TileRef>(ntiles);
     {
         TileRef* tiles = p.tiles;
+        const CopyDesc* descs = p.descs;
         be.for_each(step::plan_tile_table(), ntiles, [=] VPS_LAMBDA(int64_t t) {
             const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;
-            TileRef r;
-            r.desc = (uint32_t)d;
-            r.q = (uint32_t)(t - tb[d]);
-            tiles[t] = r;
+            tiles[t] = make_tile(descs[d], (uint32_t)d, (uint32_t)(t - tb[d]));
         });
     }
     be.free(nt); be.free(tb);
