@@ -128,8 +128,16 @@ def main():
 
     st = plan.stats()
     launches = 1 if rank >= 0 else 2
+    # HBM bytes per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this very
+    # workload and tile size (profiles/); null for any other configuration
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", f"k_copy_tiles_{args.workload}_rank{rank}_hbm_traffic.txt")
+    if os.path.exists(prof) and not args.tile_bytes:
+        for line in open(prof):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = int(line.split("=")[1])
     roofline = dict(bound="hbm", achieved=bytes_moved / (apply_avg * 1e-3) / 1e9, peak=HBM_PEAK_GBPS,
-                    unit="GB/s", frac=bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, traffic=None,
+                    unit="GB/s", frac=bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, traffic=traffic,
                     kernel="k_copy_tiles", launches_per_step=launches, kernel_ms_avg=apply_avg,
                     kernel_ms_median=apply_ms[len(apply_ms) // 2], algorithmic_bytes_per_step=bytes_moved)
 
@@ -161,7 +169,7 @@ def _avg(v):
     return sum(v) / len(v) if v else None
 
 
-def cpu_baseline(model, pa, pb, rank, seed, target_elems=48_000_000):
+def cpu_baseline(model, pa, pb, rank, seed, target_elems=192_000_000):
     """The per-element oracle on the host cores, on a bounded sample of the same rank's share:
     the first target_elems/num_buffers offsets of every destination buffer."""
     import oracle
