@@ -88,3 +88,8 @@ TINY_MOE = model(FAMILY_MOE, 4, 16, 8, 4, 4, 0, 32, experts=8, expert_ffn=8)
 # Odd sizes: local strides and flat edges are not multiples of any vector width.
 ODD_GPT = model(FAMILY_GPT, 3, 18, 6, 6, 3, 30, 42)
 ODD_MOE = model(FAMILY_MOE, 5, 12, 6, 2, 6, 0, 20, experts=6, expert_ffn=10)
+
+# Medium shapes: several 64-element blocks and ragged tails on every axis, still small enough for
+# the per-element oracle to verify every element in seconds.
+MID_MOE = model(FAMILY_MOE, 2, 136, 4, 2, 34, 0, 96, experts=4, expert_ffn=200)
+MID_GPT = model(FAMILY_GPT, 2, 192, 6, 6, 32, 516, 300)

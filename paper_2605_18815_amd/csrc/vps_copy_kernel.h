@@ -80,6 +80,68 @@ __device__ __forceinline__ void copy_run_window(uint64_t srow, uint64_t drow, ui
     if (g.tail_bytes) copy_units(g.svec + g.tail_off, g.dvec + g.tail_off, g.tail_bytes, nlanes - 1 - lane);
 }
 
+// A block of up to 64 x 64 elements whose contiguous axis differs between source and
+// destination (transposed expert storage): rows along the source's contiguous axis are read
+// with 16-byte loads into LDS, columns are gathered from LDS and written as 16-byte vectors
+// along the destination's contiguous axis.  The LDS pitch of 64+2 (2-byte) / 64+1 (4-byte)
+// elements keeps rows dword aligned and spreads a column over the banks.
+template <class E>
+__device__ __forceinline__ void copy_xpose_tile(const CopyDesc& d, uint32_t q, uint64_t sbase,
+                                                uint64_t dbase, uint32_t tid, uint32_t* lds_words)
+{
+    constexpr uint32_t T = XPOSE_T;
+    constexpr uint32_t V = 16 / sizeof(E);            // elements per 16-byte vector
+    constexpr uint32_t PITCH = T + 4 / sizeof(E);      // elements per LDS row
+    constexpr uint32_t NV = T / V;                     // vectors per full row
+    E* lds = reinterpret_cast<E*>(lds_words);
+    typedef const VPS_GLOBAL E* gsrc_t;
+    typedef VPS_GLOBAL E* gdst_t;
+
+    uint64_t so, to;
+    uint32_t ta, tb;
+    xpose_tile_geometry(d, q, so, to, ta, tb);
+    const uint64_t s0 = uniform64(sbase + so), t0 = uniform64(dbase + to);
+    const int64_t sb = d.sstr[3];      // source stride between consecutive b (elements)
+    const int64_t da = d.dstr[d.xa];   // destination stride between consecutive a (elements)
+
+    // phase 1: source rows (fixed b, a contiguous) -> lds[b][a]
+    for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
+        const uint32_t b = v / NV, a = (v % NV) * V;
+        if (b >= tb || a >= ta) continue;
+        const uint64_t g = s0 + (uint64_t)((int64_t)b * sb + a) * sizeof(E);
+        E* row = lds + b * PITCH + a;
+        if (a + V <= ta) {
+            const u32x4 x = __builtin_nontemporal_load((gsrc16_t)g);
+            uint32_t* r32 = reinterpret_cast<uint32_t*>(row);
+            r32[0] = x.x; r32[1] = x.y; r32[2] = x.z; r32[3] = x.w;
+        } else {
+            for (uint32_t k = 0; a + k < ta; ++k) row[k] = *(gsrc_t)(g + k * sizeof(E));
+        }
+    }
+    __syncthreads();
+    // phase 2: lds columns (fixed a, b contiguous) -> destination rows
+    for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
+        const uint32_t a = v / NV, b = (v % NV) * V;
+        if (a >= ta || b >= tb) continue;
+        const uint64_t g = t0 + (uint64_t)((int64_t)a * da + b) * sizeof(E);
+        const E* col = lds + b * PITCH + a;
+        if (b + V <= tb && (g & 15) == 0) {
+            u32x4 x;
+            if (sizeof(E) == 2) {
+                x.x = (uint32_t)col[0] | ((uint32_t)col[PITCH] << 16);
+                x.y = (uint32_t)col[2 * PITCH] | ((uint32_t)col[3 * PITCH] << 16);
+                x.z = (uint32_t)col[4 * PITCH] | ((uint32_t)col[5 * PITCH] << 16);
+                x.w = (uint32_t)col[6 * PITCH] | ((uint32_t)col[7 * PITCH] << 16);
+            } else {
+                x.x = col[0]; x.y = col[PITCH]; x.z = col[2 * PITCH]; x.w = col[3 * PITCH];
+            }
+            __builtin_nontemporal_store(x, (gdst16_t)g);
+        } else {
+            for (uint32_t k = 0; k < V && b + k < tb; ++k) *(gdst_t)(g + k * sizeof(E)) = col[k * PITCH];
+        }
+    }
+}
+
 __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __restrict__ descs,
                                                              const TileRef* __restrict__ tiles,
                                                              uint32_t tile0, PtrArgs pa,
@@ -134,6 +196,10 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
                 copy_run_window(srow, drow, run_bytes, 0, d->vec_window, lane, 64);
             }
         }
+    } else if (d->mode == MODE_XPOSE) {
+        __shared__ uint32_t lds_words[XPOSE_T * (XPOSE_T + 1)];
+        if (es == 2) copy_xpose_tile<uint16_t>(*d, q, sbase, dbase, tid, lds_words);
+        else copy_xpose_tile<uint32_t>(*d, q, sbase, dbase, tid, lds_words);
     } else {
         const uint64_t vol = (uint64_t)d->ext[0] * d->ext[1] * d->ext[2] * d->ext[3];
         const uint64_t k0 = (uint64_t)q * d->rows_per_tile;

@@ -371,6 +371,7 @@ VPS_HD uint64_t box_minor_key(const vps_box& b, const TensorRec& x)
 
 enum { OP_RETAIN = 0, OP_PACK = 1, OP_UNPACK = 2 };
 enum { MODE_RUN = 0, MODE_ELEM = 1, MODE_XPOSE = 2 };
+enum { XPOSE_T = 64 };  // edge of a transposed block, in elements
 
 // Pointer table slots of a single-rank plan.  All-ranks plans use
 // [src: rank*8+buf][dst: WA*8 + rank*8+buf][send: (WA+WB)*8 + rank][recv: (WA+WB)*8 + WA + rank].
@@ -392,7 +393,7 @@ struct CopyDesc {
     uint32_t vec_window;     // RUN: aligned 16-byte vectors per row handled by one tile
     uint32_t chunks_per_row; // RUN long rows: tiles per row (0 = short-row tiling)
     uint32_t ntiles;
-    uint32_t pad_;
+    uint32_t xa;             // XPOSE: the collapsed axis (0..2) that is contiguous in the source
 };
 
 struct PtrLayout {
@@ -513,6 +514,17 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             d.rows_per_tile = (uint32_t)k;
             d.ntiles = (uint32_t)((rows + k - 1) / k);
         }
+    } else if (d.dstr[3] == 1 && ((d.sstr[2] == 1 && d.ext[2] > 1) || (d.sstr[1] == 1 && d.ext[1] > 1) ||
+                                  (d.sstr[0] == 1 && d.ext[0] > 1))) {
+        // The destination is contiguous along axis 3, the source along another axis: 2-D
+        // transposes of XPOSE_T x XPOSE_T element blocks staged through LDS.
+        d.mode = MODE_XPOSE;
+        d.xa = (d.sstr[2] == 1 && d.ext[2] > 1) ? 2u : ((d.sstr[1] == 1 && d.ext[1] > 1) ? 1u : 0u);
+        const uint64_t na = (d.ext[d.xa] + XPOSE_T - 1) / XPOSE_T, nb = (d.ext[3] + XPOSE_T - 1) / XPOSE_T;
+        d.chunks_per_row = (uint32_t)na;
+        d.vec_window = (uint32_t)nb;
+        d.rows_per_tile = 0;
+        d.ntiles = (uint32_t)(vol / d.ext[d.xa] / d.ext[3] * na * nb);
     } else {
         d.mode = MODE_ELEM;
         uint64_t per = tile_bytes / (4 * d.es);
@@ -637,6 +649,35 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         t.flags = TILE_INDIRECT;
     }
     return t;
+}
+
+// Tile q of an XPOSE descriptor: a block of ta x tb elements in the plane of axis xa (contiguous
+// in the source) and axis 3 (contiguous in the destination), at fixed coordinates of the two
+// other axes.  so/to are the byte offsets of its first element; element (a, b) of the block
+// lies at so + (a + b*sstr[3])*es in the source and to + (a*dstr[xa] + b)*es in the destination.
+VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uint64_t& to,
+                                uint32_t& ta, uint32_t& tb)
+{
+    const uint32_t na = d.chunks_per_row, nb = d.vec_window;
+    const uint32_t ib = q % nb;
+    const uint32_t r = q / nb;
+    const uint32_t ia = r % na;
+    uint32_t o = r / na;
+    int64_t s = 0, t = 0;
+    for (int ax = 2; ax >= 0; --ax) {  // the two remaining axes, innermost first
+        if ((uint32_t)ax == d.xa) continue;
+        const uint32_t c = o % d.ext[ax];
+        o /= d.ext[ax];
+        s += (int64_t)c * d.sstr[ax];
+        t += (int64_t)c * d.dstr[ax];
+    }
+    const uint32_t a0 = ia * XPOSE_T, b0 = ib * XPOSE_T;
+    s += (int64_t)a0 * d.sstr[d.xa] + (int64_t)b0 * d.sstr[3];
+    t += (int64_t)a0 * d.dstr[d.xa] + (int64_t)b0 * d.dstr[3];
+    so = (uint64_t)(s * (int64_t)d.es);
+    to = (uint64_t)(t * (int64_t)d.es);
+    ta = d.ext[d.xa] - a0 < XPOSE_T ? d.ext[d.xa] - a0 : XPOSE_T;
+    tb = d.ext[3] - b0 < XPOSE_T ? d.ext[3] - b0 : XPOSE_T;
 }
 
 // Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.

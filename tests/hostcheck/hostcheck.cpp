@@ -112,6 +112,15 @@ public:
                     if (g.head_bytes) move((const char*)(uintptr_t)srow, (char*)(uintptr_t)drow, g.head_bytes);
                     if (g.tail_bytes) move((const char*)(uintptr_t)(g.svec + g.tail_off), (char*)(uintptr_t)(g.dvec + g.tail_off), g.tail_bytes);
                 }
+            } else if (d.mode == MODE_XPOSE) {
+                uint64_t so, to;
+                uint32_t ta, tb;
+                xpose_tile_geometry(d, tq, so, to, ta, tb);
+                if (ta == 0 || tb == 0 || ta > XPOSE_T || tb > XPOSE_T) ++g_violations;
+                for (uint32_t b = 0; b < tb; ++b)
+                    for (uint32_t a = 0; a < ta; ++a)
+                        move(sbase + so + ((int64_t)a + (int64_t)b * d.sstr[3]) * d.es,
+                             dbase + to + ((int64_t)a * d.dstr[d.xa] + (int64_t)b) * d.es, d.es);
             } else {
                 const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
                 const uint64_t k0 = (uint64_t)tq * d.rows_per_tile;

@@ -74,6 +74,13 @@ def test_moe235b_rank37_full_size(lib):
 
 
 @pytest.mark.timeout(900)
+def test_moe235b_rank37_destination_transposed_experts(lib):
+    """Variant: the destination stores experts transposed, so every expert box goes through the
+    LDS-staged transpose tiles."""
+    _run(lib, "moe235b", dst_over=dict(expert_layout=1))
+
+
+@pytest.mark.timeout(900)
 def test_gpt1p3b_all_ranks_full_size(lib):
     w = cf.WORKLOADS["gpt1p3b"]
     print("\ngpt1p3b all 32 ranks", flush=True)

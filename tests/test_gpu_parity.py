@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import SINGLE
+from test_hostcheck_parity import MEDIUM, SINGLE
 
 pytestmark = pytest.mark.gpu
 
@@ -19,6 +19,13 @@ def lib():
 @pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
 def test_all_ranks_resident(lib, name, m, pa, pb):
     out = parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0x5EED + len(name))
+    assert out["boxes"] > 0
+
+
+@pytest.mark.parametrize("name,m,pa,pb", MEDIUM, ids=[c[0] for c in MEDIUM])
+def test_medium_shapes_all_ranks(lib, name, m, pa, pb):
+    """Several 64-element blocks with ragged tails: LDS-staged transposes and short-run tiles."""
+    out = parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0xC0FFEE)
     assert out["boxes"] > 0
 
 

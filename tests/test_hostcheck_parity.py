@@ -31,6 +31,20 @@ def test_all_ranks_resident(hlib, name, m, pa, pb):
     assert out["boxes"] > 0
 
 
+MEDIUM = [
+    ("mid-moe-to-transposed", cf.MID_MOE, P(tp=2, pp=1, dp=1, ep=2), P(tp=1, pp=2, dp=2, ep=1, expert_layout=1)),
+    ("mid-moe-from-transposed", cf.MID_MOE, P(tp=1, pp=2, dp=1, ep=4, expert_layout=1), P(tp=2, pp=1, dp=2, ep=2)),
+    ("mid-moe-both-transposed", cf.MID_MOE, P(tp=2, pp=1, dp=2, ep=1, expert_layout=1), P(tp=1, pp=1, dp=2, ep=2, expert_layout=1, flat_order=1)),
+    ("mid-gpt-tp-blocked", cf.MID_GPT, P(tp=3, pp=1, dp=2), P(tp=2, pp=2, dp=1, qkv_layout=1)),
+]
+
+
+@pytest.mark.parametrize("name,m,pa,pb", MEDIUM, ids=[c[0] for c in MEDIUM])
+def test_medium_shapes_all_ranks(hlib, name, m, pa, pb):
+    out = parity.run_all_ranks(hlib, parity.HostMem(hlib), m, pa, pb, seed=0xC0FFEE)
+    assert out["boxes"] > 0
+
+
 SINGLE = [
     ("gpt-zero-to-replicated", 0), ("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-blocked-rev", 2),
     ("gpt-odd", 1), ("gpt-world-grows", 11), ("gpt-world-grows", 3), ("gqa", 6), ("moe-ep", 9),
