@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
+    ap.add_argument("--src", default="", help="override source layout fields, e.g. flat_order=1")
+    ap.add_argument("--dst", default="", help="override destination layout fields, e.g. expert_layout=1,qkv_layout=1")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="also run one plain device-to-device copy of MIB MiB (reference for HBM counters)")
     args = ap.parse_args()
@@ -48,7 +50,11 @@ def main():
     if args.tile_bytes:
         lib.set_tile_bytes(args.tile_bytes)
     w = cf.WORKLOADS[args.workload]
-    model, pa, pb = w["model"], w["src"], w["dst"]
+    model, pa, pb = w["model"], dict(w["src"]), dict(w["dst"])
+    for spec, par in ((args.src, pa), (args.dst, pb)):
+        for kv in filter(None, spec.split(",")):
+            k, v = kv.split("=")
+            par[k] = int(v)
     rank = args.rank if args.rank is not None else (w["rank"] if w["rank"] is not None else -1)
     stream = torch.cuda.current_stream().cuda_stream
 
@@ -132,7 +138,7 @@ def main():
     # workload and tile size (profiles/); null for any other configuration
     traffic = None
     prof = os.path.join(ROOT, "profiles", f"k_copy_tiles_{args.workload}_rank{rank}_hbm_traffic.txt")
-    if os.path.exists(prof) and not args.tile_bytes:
+    if os.path.exists(prof) and not (args.tile_bytes or args.src or args.dst):
         for line in open(prof):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = int(line.split("=")[1])

@@ -157,17 +157,27 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
     }
     const TileRef* tp = tiles + (tile0 + b);
     const uint32_t tid = threadIdx.x;
-    const uint32_t flags = uniform32(tp->flags);
-    if (!(flags & TILE_INDIRECT)) {
-        // a contiguous piece of one long run
+    const uint32_t nf = uniform32(tp->nruns_flags);
+    if (!(nf & TILE_INDIRECT)) {
+        const uint32_t nruns = nf >> 8;
+        if (!nruns) return;
         const uint32_t nbytes = uniform32(tp->nbytes);
-        if (!nbytes) return;
         const uint64_t alt = tp->alt_src;
         const uint64_t sa = uniform64((alias_exchange && alt != VPS_TILE_NO_ALT) ? alt : tp->src);
         const uint64_t da = uniform64(tp->dst);
         const uint64_t s = uniform64(slot_addr(pa, tile_slot(sa)) + tile_offset(sa));
         const uint64_t t = uniform64(slot_addr(pa, tile_slot(da)) + tile_offset(da));
-        copy_run_window(s, t, nbytes, 0, (nbytes + 30) >> 4, tid, COPY_THREADS);
+        const uint32_t nw = (nbytes + 30) >> 4;
+        if (nruns == 1) {
+            // a contiguous piece of one long run: the whole workgroup walks its vectors
+            copy_run_window(s, t, nbytes, 0, nw, tid, COPY_THREADS);
+        } else {
+            // short runs at a constant pitch: one run per wavefront at a time
+            const uint64_t sp = uniform64((uint64_t)tp->src_pitch), dp = uniform64((uint64_t)tp->dst_pitch);
+            const uint32_t wave = uniform32(tid >> 6), lane = tid & 63;
+            for (uint32_t r = wave; r < nruns; r += COPY_WAVES)
+                copy_run_window(s + r * sp, t + r * dp, nbytes, 0, nw, lane, 64);
+        }
         return;
     }
     const uint32_t di = uniform32((uint32_t)tp->alt_src);
@@ -179,24 +189,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
     const uint64_t dbase = uniform64(slot_addr(pa, d->dst_slot) + d->dst_byte);
     const uint32_t es = d->es;
 
-    if (d->mode == MODE_RUN) {
-        const uint64_t run_bytes = (uint64_t)d->ext[3] * es;
-        {
-            // several short runs: one run per wavefront at a time
-            const uint32_t rows = d->ext[0] * d->ext[1] * d->ext[2];
-            const uint32_t rpt = d->rows_per_tile;
-            const uint32_t row0 = q * rpt;
-            const uint32_t nrows = rows - row0 < rpt ? rows - row0 : rpt;
-            const uint32_t wave = uniform32(tid >> 6), lane = tid & 63;
-            for (uint32_t r = wave; r < nrows; r += COPY_WAVES) {
-                uint64_t so, to;
-                run_row_offsets(*d, row0 + r, so, to);
-                const uint64_t srow = uniform64(sbase + so);
-                const uint64_t drow = uniform64(dbase + to);
-                copy_run_window(srow, drow, run_bytes, 0, d->vec_window, lane, 64);
-            }
-        }
-    } else if (d->mode == MODE_XPOSE) {
+    if (d->mode == MODE_XPOSE) {
         __shared__ uint32_t lds_words[XPOSE_T * (XPOSE_T + 1)];
         if (es == 2) copy_xpose_tile<uint16_t>(*d, q, sbase, dbase, tid, lds_words);
         else copy_xpose_tile<uint32_t>(*d, q, sbase, dbase, tid, lds_words);

@@ -300,9 +300,21 @@ struct PlanCtx {
 VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t d, vps_box* out)
 {
     const vps_piece dp = c.DP[d];
-    const int64_t sa = c.sbase[map_group_item(c.A, dp.tensor, dp.kind)];
-    const int64_t sb = c.sbase[map_group_item(c.A, dp.tensor, dp.kind) + (int64_t)c.A.tp * c.A.ddp];
     const TensorRec x = c.T[dp.tensor];
+    const int64_t g0 = map_group_item(c.A, dp.tensor, dp.kind);
+    int64_t sa = c.sbase[g0];
+    int64_t sb = c.sbase[g0 + (int64_t)c.A.tp * c.A.ddp];
+    if (c.rank >= 0 && dp.rank != c.rank) {
+        // a piece of another destination rank can only pair with pieces of the planned rank,
+        // and those all belong to one mapper item of this (tensor, kind)
+        if (c.rank >= c.A.world) return 0;
+        const RankCoord rc = decode_rank(c.A, c.rank);
+        if (stage_of_layer(c.A, x.layer) != rc.pp) return 0;
+        if (x.group && x.expert / (c.A.experts / c.A.ep) != rc.ep) return 0;
+        const int64_t item = g0 + (int64_t)rc.tp * c.A.ddp + (x.group ? rc.edp : rc.ddp);
+        sa = c.sbase[item];
+        sb = c.sbase[item + 1];
+    }
     int n = 0;
     for (int64_t s = sa; s < sb; ++s) {
         const vps_piece sp = c.SP[s];
@@ -506,13 +518,16 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             d.rows_per_tile = 1;
             d.ntiles = (uint32_t)(rows * d.chunks_per_row);
         } else {
+            // short runs: k consecutive runs along axis 2 per tile, never across a slab
+            // (fixed coordinates on axes 0 and 1), so that run addresses are affine in a tile
             d.chunks_per_row = 0;
             d.vec_window = (uint32_t)nv_max;
             uint64_t k = vt / nv_max;
             if (k < 1) k = 1;
-            if (k > rows) k = rows;
+            if (k > d.ext[2]) k = d.ext[2];
             d.rows_per_tile = (uint32_t)k;
-            d.ntiles = (uint32_t)((rows + k - 1) / k);
+            const uint64_t tps = (d.ext[2] + k - 1) / k;
+            d.ntiles = (uint32_t)((uint64_t)d.ext[0] * d.ext[1] * tps);
         }
     } else if (d.dstr[3] == 1 && ((d.sstr[2] == 1 && d.ext[2] > 1) || (d.sstr[1] == 1 && d.ext[1] > 1) ||
                                   (d.sstr[0] == 1 && d.ext[0] > 1))) {
@@ -539,17 +554,19 @@ struct PtrArgs {
     char* const* tbl;      // all-ranks plans: table in device memory (nullptr otherwise)
 };
 
-// One tile of the copy engine (32 bytes, read by the workgroup with one scalar load).
-//   direct    a contiguous piece of one long run: everything the kernel needs is here, so a
-//             workgroup does no index arithmetic at all
+// One tile of the copy engine (48 bytes, read by the workgroup with scalar loads).
+//   direct    a contiguous piece of one long run, or several short runs at a constant pitch:
+//             everything the kernel needs is here, so a workgroup does no index arithmetic
 //   indirect  several short runs or an element-wise tile: tile q of descriptor `desc`
 struct TileRef {
-    uint64_t src;      // direct: slot << 44 | byte offset in the slot's buffer
+    uint64_t src;      // direct: slot << 44 | byte offset in the slot's buffer (first run)
     uint64_t dst;
     uint64_t alt_src;  // direct: the sender's send buffer for in-place exchange (or TILE_NO_ALT)
                        // indirect: q << 32 | desc
-    uint32_t nbytes;   // direct: bytes to move
-    uint32_t flags;    // TILE_INDIRECT
+    int64_t src_pitch; // direct, several runs: bytes between consecutive runs
+    int64_t dst_pitch;
+    uint32_t nbytes;   // direct: bytes of one run (piece)
+    uint32_t nruns_flags;  // bits 0..7 flags, bits 8..31 number of runs
 };
 enum : uint32_t { TILE_INDIRECT = 1u };
 #define VPS_TILE_NO_ALT (~0ull)
@@ -557,24 +574,6 @@ enum : uint32_t { TILE_INDIRECT = 1u };
 VPS_HD uint64_t tile_pack_addr(int32_t slot, uint64_t byte_off) { return ((uint64_t)slot << 44) | byte_off; }
 VPS_HD int32_t tile_slot(uint64_t a) { return (int32_t)(a >> 44); }
 VPS_HD uint64_t tile_offset(uint64_t a) { return a & ((1ull << 44) - 1); }
-
-// Geometry of tile q of a RUN descriptor: rows [row0, row0+nrows), and for each row the window
-// [w0, w0+nw) of aligned destination vectors.
-VPS_HD void run_tile_geometry(const CopyDesc& d, uint32_t q, uint32_t& row0, uint32_t& nrows,
-                              uint32_t& w0, uint32_t& nw)
-{
-    nw = d.vec_window;
-    if (d.chunks_per_row) {
-        row0 = q / d.chunks_per_row;
-        nrows = 1;
-        w0 = (q % d.chunks_per_row) * d.vec_window;
-    } else {
-        const uint32_t rows = d.ext[0] * d.ext[1] * d.ext[2];
-        row0 = q * d.rows_per_tile;
-        nrows = rows - row0 < d.rows_per_tile ? rows - row0 : d.rows_per_tile;
-        w0 = 0;
-    }
-}
 
 // How one run is moved by the caller responsible for the window [w0, w0 + nw) of its
 // destination-aligned 16-byte vectors.  The run covers dst bytes [drow, drow + run_bytes) and
@@ -627,6 +626,7 @@ VPS_HD void run_row_offsets(const CopyDesc& d, uint32_t row, uint64_t& so, uint6
 VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
 {
     TileRef t;
+    t.src_pitch = 0; t.dst_pitch = 0;
     if (d.mode == MODE_RUN && d.chunks_per_row) {
         const uint32_t row = q / d.chunks_per_row, c = q - row * d.chunks_per_row;
         uint64_t so, to;
@@ -641,12 +641,26 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         t.dst = tile_pack_addr(d.dst_slot, lo);
         t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so + (lo - d0)) : VPS_TILE_NO_ALT;
         t.nbytes = (uint32_t)(hi - lo);
-        t.flags = 0;
+        t.nruns_flags = (hi > lo ? 1u : 0u) << 8;
+    } else if (d.mode == MODE_RUN) {
+        const uint32_t k = d.rows_per_tile;
+        const uint32_t tps = (d.ext[2] + k - 1) / k;
+        const uint32_t slab = q / tps, r0 = (q - slab * tps) * k;
+        const uint32_t nruns = d.ext[2] - r0 < k ? d.ext[2] - r0 : k;
+        uint64_t so, to;
+        run_row_offsets(d, slab * d.ext[2] + r0, so, to);
+        t.src = tile_pack_addr(d.src_slot, d.src_byte + so);
+        t.dst = tile_pack_addr(d.dst_slot, d.dst_byte + to);
+        t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so) : VPS_TILE_NO_ALT;
+        t.src_pitch = d.sstr[2] * (int64_t)d.es;
+        t.dst_pitch = d.dstr[2] * (int64_t)d.es;
+        t.nbytes = d.ext[3] * d.es;
+        t.nruns_flags = nruns << 8;
     } else {
         t.src = 0; t.dst = 0;
         t.alt_src = ((uint64_t)q << 32) | di;
         t.nbytes = 0;
-        t.flags = TILE_INDIRECT;
+        t.nruns_flags = TILE_INDIRECT;
     }
     return t;
 }

@@ -77,34 +77,14 @@ public:
         };
         for (int64_t ti = 0; ti < ntiles; ++ti) {
             const TileRef tr = tiles[tile0 + ti];
-            if (!(tr.flags & TILE_INDIRECT)) {
-                if (!tr.nbytes) continue;
+            if (!(tr.nruns_flags & TILE_INDIRECT)) {
+                const uint32_t nruns = tr.nruns_flags >> 8;
                 const uint64_t sa = (alias_exchange && tr.alt_src != VPS_TILE_NO_ALT) ? tr.alt_src : tr.src;
-                const uint64_t srow = (uint64_t)(uintptr_t)slot_ptr(tile_slot(sa)) + tile_offset(sa);
-                const uint64_t drow = (uint64_t)(uintptr_t)slot_ptr(tile_slot(tr.dst)) + tile_offset(tr.dst);
-                const RunWindow g = run_window(srow, drow, tr.nbytes, 0, (tr.nbytes + 30) >> 4);
-                for (uint32_t w = g.wbeg; w < g.wend; ++w) {
-                    if ((g.dvec + 16ull * w) & 15) ++g_violations;
-                    move((const char*)(uintptr_t)(g.svec + 16ull * w), (char*)(uintptr_t)(g.dvec + 16ull * w), 16);
-                }
-                if (g.head_bytes) move((const char*)(uintptr_t)srow, (char*)(uintptr_t)drow, g.head_bytes);
-                if (g.tail_bytes) move((const char*)(uintptr_t)(g.svec + g.tail_off), (char*)(uintptr_t)(g.dvec + g.tail_off), g.tail_bytes);
-                continue;
-            }
-            const uint32_t tq = (uint32_t)(tr.alt_src >> 32);
-            const CopyDesc d = descs[(uint32_t)tr.alt_src];
-            const bool alias = alias_exchange && d.alt_src_slot >= 0;
-            const char* sbase = alias ? slot_ptr(d.alt_src_slot) + d.alt_src_byte : slot_ptr(d.src_slot) + d.src_byte;
-            char* dbase = slot_ptr(d.dst_slot) + d.dst_byte;
-            if (d.mode == MODE_RUN) {
-                uint32_t row0, nrows, w0, nw;
-                run_tile_geometry(d, tq, row0, nrows, w0, nw);
-                const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-                for (uint32_t r = 0; r < nrows; ++r) {
-                    uint64_t so, to;
-                    run_row_offsets(d, row0 + r, so, to);
-                    const uint64_t srow = (uint64_t)(uintptr_t)sbase + so, drow = (uint64_t)(uintptr_t)dbase + to;
-                    const RunWindow g = run_window(srow, drow, run_bytes, w0, nw);
+                const uint64_t s0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(sa)) + tile_offset(sa);
+                const uint64_t d0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(tr.dst)) + tile_offset(tr.dst);
+                for (uint32_t r = 0; r < nruns; ++r) {
+                    const uint64_t srow = s0 + r * (uint64_t)tr.src_pitch, drow = d0 + r * (uint64_t)tr.dst_pitch;
+                    const RunWindow g = run_window(srow, drow, tr.nbytes, 0, (tr.nbytes + 30) >> 4);
                     for (uint32_t w = g.wbeg; w < g.wend; ++w) {
                         if ((g.dvec + 16ull * w) & 15) ++g_violations;
                         move((const char*)(uintptr_t)(g.svec + 16ull * w), (char*)(uintptr_t)(g.dvec + 16ull * w), 16);
@@ -112,7 +92,14 @@ public:
                     if (g.head_bytes) move((const char*)(uintptr_t)srow, (char*)(uintptr_t)drow, g.head_bytes);
                     if (g.tail_bytes) move((const char*)(uintptr_t)(g.svec + g.tail_off), (char*)(uintptr_t)(g.dvec + g.tail_off), g.tail_bytes);
                 }
-            } else if (d.mode == MODE_XPOSE) {
+                continue;
+            }
+            const uint32_t tq = (uint32_t)(tr.alt_src >> 32);
+            const CopyDesc d = descs[(uint32_t)tr.alt_src];
+            const bool alias = alias_exchange && d.alt_src_slot >= 0;
+            const char* sbase = alias ? slot_ptr(d.alt_src_slot) + d.alt_src_byte : slot_ptr(d.src_slot) + d.src_byte;
+            char* dbase = slot_ptr(d.dst_slot) + d.dst_byte;
+            if (d.mode == MODE_XPOSE) {
                 uint64_t so, to;
                 uint32_t ta, tb;
                 xpose_tile_geometry(d, tq, so, to, ta, tb);
