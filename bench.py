@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
+    ap.add_argument("--staged-mib", type=int, default=0,
+                    help="all-ranks workloads: exchange in XOR step order under this per-rank buffer budget (MiB)")
     ap.add_argument("--src", default="", help="override source layout fields, e.g. flat_order=1")
     ap.add_argument("--dst", default="", help="override destination layout fields, e.g. expert_layout=1,qkv_layout=1")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
@@ -82,6 +84,14 @@ def main():
     if rank < 0:
         payload = 2 * info["send_total"] + info["retain_total"]   # every byte is packed and unpacked here
     bytes_moved = 2 * payload
+    stage = None
+    if args.staged_mib:
+        assert rank < 0, "--staged-mib needs a workload with all ranks resident"
+        stage = lib.stage_exchange(plan, args.staged_mib << 20, stream)
+        sinfo = stage.info()
+        scratch = alloc(sinfo["scratch_needed"], False)
+        # pack, exchange and unpack each read and write the exchanged bytes once
+        bytes_moved = 2 * (3 * info["send_total"] + info["retain_total"])
     torch.cuda.synchronize()
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -93,8 +103,16 @@ def main():
         else:
             a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
             p = lib.plan_intersections(a2, b2, rank, stream)
+        stg = None
+        if stage is not None:
+            stg = stage if args.apply_only else lib.stage_exchange(p, args.staged_mib << 20, stream)
         if k is not None:
             ev[k][0].record()
+        if stg is not None:
+            lib.apply_transition_staged(stg, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
+            if k is not None:
+                ev[k][1].record()
+            return (p, stg)
         lib.apply_transition(p, rank, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
         if k is not None:
             ev[k][1].record()
@@ -134,6 +152,8 @@ def main():
 
     st = plan.stats()
     launches = 1 if rank >= 0 else 2
+    if stage is not None:
+        launches = 1 + 3 * sinfo["num_stages"]
     # HBM bytes per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this very
     # workload and tile size (profiles/); null for any other configuration
     traffic = None
@@ -168,6 +188,8 @@ def main():
                                     "num_peers_out", "num_peers_in")},
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if stage is not None:
+        out["staged"] = dict(budget_mib=args.staged_mib, **sinfo, one_shot_scratch=info["scratch_needed"])
     print(json.dumps(out))
 
 

@@ -156,6 +156,33 @@ int vps_apply_transition(const vps_plan* plan, int32_t rank, const void* const* 
                          void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
                          void* stream);
 
+/* ---- staged exchange among resident ranks ----
+ * Algorithm 1 (MemoryAwareChunk and the step loop) and Section 4.3 "Asynchronous Deadlock-Free
+ * Communication", for an all-ranks plan.  Steps s = 1 .. 2^ceil(log2 N) - 1 (N = the larger
+ * world): in step s rank i is paired with rank i XOR s; the pair is skipped when the peer does
+ * not exist or no data flows.  cost(s) = max over ranks of the bytes the rank sends plus the
+ * bytes it receives in step s (alignment pad included).  Steps are taken in ascending order; a
+ * step joins the current stage unless the stage would then exceed budget_bytes_per_rank, in
+ * which case the stage is closed first.  Steps without traffic belong to no stage, no empty
+ * stage is emitted, and a step that alone exceeds the budget forms a stage of its own.
+ * Every stage is executed as pack -> exchange (each send segment is copied to the peer's
+ * receive segment) -> unpack, all stages reusing one scratch area of scratch_needed bytes;
+ * retained boxes are copied once, first.  The plan must outlive the stage plan. */
+typedef struct vps_stage_plan vps_stage_plan;
+int vps_stage_exchange(const vps_plan* plan, uint64_t budget_bytes_per_rank, void* stream,
+                       vps_stage_plan** out);
+int vps_stage_info(const vps_stage_plan* sp, int32_t* num_steps, int32_t* num_stages,
+                   uint64_t* scratch_needed);
+/* stage_of_step[s] (-1: no traffic) and step_cost[s] for s = 0 .. num_steps (entry 0 unused). */
+int vps_stage_steps(const vps_stage_plan* sp, int32_t* stage_of_step, uint64_t* step_cost,
+                    int32_t max_entries);
+/* src_bufs is [world_src][8], dst_bufs is [world_dst][8] (host arrays of device pointers).
+ * VPS_ERR_SCRATCH_TOO_SMALL if scratch_bytes < scratch_needed. */
+int vps_apply_transition_staged(const vps_stage_plan* sp, const void* const* src_bufs,
+                                void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
+                                void* stream);
+void vps_stage_plan_destroy(vps_stage_plan* sp);
+
 /* ---- queries (host side, no device work unless stated) ---- */
 int vps_config_world(const vps_config* cfg, int32_t* world);
 int vps_config_num_tensors(const vps_config* cfg, int32_t* n);

@@ -105,6 +105,10 @@ class Library:
             "plan_get_boxes": [vp, vp, i64],
             "plan_stats": [vp, P(PlanStats)],
             "set_tile_bytes": [u32],
+            "stage_exchange": [vp, u64, vp, P(vp)],
+            "stage_info": [vp, P(i32), P(i32), P(u64)],
+            "stage_steps": [vp, P(i32), P(u64), i32],
+            "apply_transition_staged": [vp, P(vp), P(vp), vp, u64, vp],
         }
         self._fn = {}
         for name, argtypes in sig.items():
@@ -112,7 +116,7 @@ class Library:
             f.argtypes = argtypes
             f.restype = C.c_int
             self._fn[name] = f
-        for name in ("config_destroy", "plan_destroy"):
+        for name in ("config_destroy", "plan_destroy", "stage_plan_destroy"):
             f = getattr(self._dll, prefix + name)
             f.argtypes = [vp]
             f.restype = None
@@ -126,7 +130,8 @@ class Library:
                "config_world", "config_num_tensors", "config_buffer_bytes", "config_num_pieces",
                "config_get_pieces", "plan_pair_bytes", "plan_peer_bytes", "plan_buffer_bytes",
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
-               "set_tile_bytes", "config_destroy", "plan_destroy", "last_error")
+               "set_tile_bytes", "config_destroy", "plan_destroy", "last_error", "stage_exchange",
+               "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy")
 
     def last_error(self):
         return self._fn["last_error"]().decode()
@@ -157,6 +162,16 @@ class Library:
         self._check(self._fn["apply_transition"](plan._h, rank, _ptr_array(src_bufs, len(src_bufs)),
                                                  _ptr_array(dst_bufs, len(dst_bufs)), scratch,
                                                  scratch_bytes, stream))
+
+    def stage_exchange(self, plan, budget_bytes_per_rank, stream=0):
+        out = C.c_void_p()
+        self._check(self._fn["stage_exchange"](plan._h, budget_bytes_per_rank, stream, C.byref(out)))
+        return StagePlan(self, out, plan)
+
+    def apply_transition_staged(self, sp, src_bufs, dst_bufs, scratch, scratch_bytes, stream=0):
+        self._check(self._fn["apply_transition_staged"](sp._h, _ptr_array(src_bufs, len(src_bufs)),
+                                                        _ptr_array(dst_bufs, len(dst_bufs)), scratch,
+                                                        scratch_bytes, stream))
 
     def set_tile_bytes(self, n):
         self._check(self._fn["set_tile_bytes"](n))
@@ -247,3 +262,25 @@ class Plan:
         st = PlanStats()
         self._lib._check(self._lib._fn["plan_stats"](self._h, C.byref(st)))
         return {n: getattr(st, n) for n, _ in PlanStats._fields_}
+
+
+class StagePlan:
+    def __init__(self, lib, handle, plan):
+        self._lib, self._h, self._plan = lib, handle, plan   # keeps the plan alive
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            self._lib._fn["stage_plan_destroy"](self._h)
+            self._h = None
+
+    def info(self):
+        a, b, c = C.c_int32(), C.c_int32(), C.c_uint64()
+        self._lib._check(self._lib._fn["stage_info"](self._h, C.byref(a), C.byref(b), C.byref(c)))
+        return dict(num_steps=a.value, num_stages=b.value, scratch_needed=c.value)
+
+    def steps(self):
+        n = self.info()["num_steps"] + 1
+        st = (C.c_int32 * n)()
+        cost = (C.c_uint64 * n)()
+        self._lib._check(self._lib._fn["stage_steps"](self._h, st, cost, n))
+        return list(st), list(cost)

@@ -56,6 +56,11 @@ struct vps_plan {
     std::vector<uint8_t> used[3];
 };
 
+struct vps_stage_plan {
+    vps::StageData d;
+    const vps_plan* plan;
+};
+
 #define VPS_TRY try {
 #define VPS_CATCH                                                            \
     }                                                                        \
@@ -423,6 +428,99 @@ int VPS_FN(plan_stats)(const vps_plan* plan, vps_plan_stats_t* out)
     if (!plan || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
     *out = plan->d.stats;
     return VPS_OK;
+}
+
+int VPS_FN(stage_exchange)(const vps_plan* plan, uint64_t budget, void* stream, vps_stage_plan** out)
+{
+    if (!plan || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    VPS_TRY
+    vps_stage_plan* sp = new vps_stage_plan();
+    sp->plan = plan;
+    VPS_BACKEND be(stream);
+    try {
+        vps::build_stage_plan(be, plan->d, budget, plan->d.tile_bytes, sp->d);
+    } catch (...) {
+        be.release_all();
+        delete sp;
+        throw;
+    }
+    be.commit();
+    *out = sp;
+    return VPS_OK;
+    VPS_CATCH
+}
+
+void VPS_FN(stage_plan_destroy)(vps_stage_plan* sp)
+{
+    if (!sp) return;
+    VPS_BACKEND be(nullptr);
+    be.quiesce();
+    vps::free_stage(be, sp->d);
+    delete sp;
+}
+
+int VPS_FN(stage_info)(const vps_stage_plan* sp, int32_t* num_steps, int32_t* num_stages, uint64_t* scratch_needed)
+{
+    if (!sp) return vps::fail(VPS_ERR_INVALID_ARG, "null stage plan");
+    if (num_steps) *num_steps = sp->d.nsteps;
+    if (num_stages) *num_stages = sp->d.nstages;
+    if (scratch_needed) *scratch_needed = sp->d.scratch_needed;
+    return VPS_OK;
+}
+
+int VPS_FN(stage_steps)(const vps_stage_plan* sp, int32_t* stage_of_step, uint64_t* step_cost, int32_t max_entries)
+{
+    if (!sp) return vps::fail(VPS_ERR_INVALID_ARG, "null stage plan");
+    for (int32_t s = 0; s <= sp->d.nsteps && s < max_entries; ++s) {
+        if (stage_of_step) stage_of_step[s] = sp->d.stage_of_step[(size_t)s];
+        if (step_cost) step_cost[s] = sp->d.step_cost[(size_t)s];
+    }
+    return VPS_OK;
+}
+
+int VPS_FN(apply_transition_staged)(const vps_stage_plan* sp, const void* const* src_bufs, void* const* dst_bufs,
+                                    void* scratch, uint64_t scratch_bytes, void* stream)
+{
+    if (!sp || !src_bufs || !dst_bufs) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    const vps::StageData& sd = sp->d;
+    const vps::PlanData& p = sp->plan->d;
+    if (scratch_bytes < sd.scratch_needed) return vps::fail(VPS_ERR_SCRATCH_TOO_SMALL, "scratch smaller than scratch_needed");
+    if (sd.scratch_needed && (!scratch || ((uintptr_t)scratch & 15))) return vps::fail(VPS_ERR_INVALID_ARG, "scratch must be a 16-byte aligned device pointer");
+    const vps::PtrLayout& L = p.layout;
+    std::vector<void*> ptrs((size_t)vps::num_slots(L), nullptr);
+    for (int32_t q = 0; q < p.A.world; ++q)
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_src(L, q, b)] = (void*)src_bufs[(size_t)q * 8 + b];
+    for (int32_t q = 0; q < p.B.world; ++q)
+        for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_dst(L, q, b)] = dst_bufs[(size_t)q * 8 + b];
+    for (int op = 0; op < 3; ++op) {
+        // send / receive slots are filled per stage below
+        std::vector<void*> chk = ptrs;
+        for (int32_t q = 0; q < p.A.world; ++q) chk[(size_t)vps::slot_send(L, q)] = scratch;
+        for (int32_t q = 0; q < p.B.world; ++q) chk[(size_t)vps::slot_recv(L, q)] = scratch;
+        if (int rc = vps::check_used(sp->plan, op, -1, chk, false)) return rc;
+    }
+    VPS_BACKEND be(stream);
+    vps::PtrArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.tbl = (char* const*)sd.ptr_table;
+    // retained boxes: old local -> new local, once
+    be.set_ptr_table(sd.ptr_table, ptrs.data(), (int)ptrs.size());
+    const int64_t n = p.nboxes;
+    be.launch_copy(p.descs, p.tiles, p.tile_base[0], p.tile_base[(size_t)n] - p.tile_base[0], pa, 0);
+    for (int32_t g = 0; g < sd.nstages; ++g) {
+        for (int32_t q = 0; q < p.A.world; ++q)
+            ptrs[(size_t)vps::slot_send(L, q)] = (char*)scratch + sd.send_base[(size_t)g * (size_t)p.A.world + (size_t)q];
+        for (int32_t q = 0; q < p.B.world; ++q)
+            ptrs[(size_t)vps::slot_recv(L, q)] = (char*)scratch + sd.recv_base[(size_t)g * (size_t)p.B.world + (size_t)q];
+        be.set_ptr_table(sd.ptr_table, ptrs.data(), (int)ptrs.size());
+        be.launch_copy(sd.descs, sd.tiles, sd.pack_begin[(size_t)g], sd.pack_begin[(size_t)g + 1] - sd.pack_begin[(size_t)g], pa, 0);
+        be.launch_copy(sd.descs, sd.tiles, sd.exch_begin[(size_t)g], sd.exch_begin[(size_t)g + 1] - sd.exch_begin[(size_t)g], pa, 0);
+        be.launch_copy(sd.descs, sd.tiles, sd.unpack_begin[(size_t)g], sd.unpack_begin[(size_t)g + 1] - sd.unpack_begin[(size_t)g], pa, 0);
+    }
+    return VPS_OK;
+    VPS_CATCH
 }
 
 }  // extern "C"

@@ -434,6 +434,10 @@ VPS_HD int32_t num_slots(const PtrLayout& L)
     return L.all_ranks ? (L.wa + L.wb) * 9 : PT_INLINE;
 }
 
+// A box that would need 2^31 tiles or more saturates the count; the planner then reports
+// VPS_ERR_OOM instead of building a wrapped-around table.
+VPS_HD uint32_t clamp_tiles(uint64_t n) { return n >= (1ull << 31) ? (1u << 31) : (uint32_t)n; }
+
 // Build the copy descriptor of one box for one operation.  resident(rank) tells whether the
 // rank's buffers exist on this GPU (planned rank, or every rank for all-ranks plans); boxes
 // whose operation does not apply get ntiles = 0.
@@ -516,7 +520,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             d.chunks_per_row = (uint32_t)((nv_max + vt - 1) / vt);
             d.vec_window = (uint32_t)vt;
             d.rows_per_tile = 1;
-            d.ntiles = (uint32_t)(rows * d.chunks_per_row);
+            d.ntiles = clamp_tiles(rows * d.chunks_per_row);
         } else {
             // short runs: k consecutive runs along axis 2 per tile, never across a slab
             // (fixed coordinates on axes 0 and 1), so that run addresses are affine in a tile
@@ -527,7 +531,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             if (k > d.ext[2]) k = d.ext[2];
             d.rows_per_tile = (uint32_t)k;
             const uint64_t tps = (d.ext[2] + k - 1) / k;
-            d.ntiles = (uint32_t)((uint64_t)d.ext[0] * d.ext[1] * tps);
+            d.ntiles = clamp_tiles((uint64_t)d.ext[0] * d.ext[1] * tps);
         }
     } else if (d.dstr[3] == 1 && ((d.sstr[2] == 1 && d.ext[2] > 1) || (d.sstr[1] == 1 && d.ext[1] > 1) ||
                                   (d.sstr[0] == 1 && d.ext[0] > 1))) {
@@ -539,13 +543,13 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         d.chunks_per_row = (uint32_t)na;
         d.vec_window = (uint32_t)nb;
         d.rows_per_tile = 0;
-        d.ntiles = (uint32_t)(vol / d.ext[d.xa] / d.ext[3] * na * nb);
+        d.ntiles = clamp_tiles(vol / d.ext[d.xa] / d.ext[3] * na * nb);
     } else {
         d.mode = MODE_ELEM;
         uint64_t per = tile_bytes / (4 * d.es);
         if (per < 256) per = 256;
         d.rows_per_tile = (uint32_t)per;
-        d.ntiles = (uint32_t)((vol + per - 1) / per);
+        d.ntiles = clamp_tiles((vol + per - 1) / per);
     }
 }
 
@@ -690,8 +694,8 @@ VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uin
     t += (int64_t)a0 * d.dstr[d.xa] + (int64_t)b0 * d.dstr[3];
     so = (uint64_t)(s * (int64_t)d.es);
     to = (uint64_t)(t * (int64_t)d.es);
-    ta = d.ext[d.xa] - a0 < XPOSE_T ? d.ext[d.xa] - a0 : XPOSE_T;
-    tb = d.ext[3] - b0 < XPOSE_T ? d.ext[3] - b0 : XPOSE_T;
+    ta = d.ext[d.xa] - a0 < (uint32_t)XPOSE_T ? d.ext[d.xa] - a0 : (uint32_t)XPOSE_T;
+    tb = d.ext[3] - b0 < (uint32_t)XPOSE_T ? d.ext[3] - b0 : (uint32_t)XPOSE_T;
 }
 
 // Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.

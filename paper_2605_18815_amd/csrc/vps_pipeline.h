@@ -15,6 +15,7 @@
 // contiguous buffers).
 #pragma once
 
+#include <algorithm>
 #include <chrono>
 #include <cstring>
 #include <vector>
@@ -53,6 +54,10 @@ struct plan_copy_descs {};
 struct plan_tile_table {};
 struct plan_sorted_boxes {};
 struct plan_recv_perm {};
+struct stage_tile_keys {};
+struct stage_tile_gather {};
+struct stage_descs {};
+struct stage_exchange_tiles {};
 }  // namespace step
 
 struct ConfigData {
@@ -377,6 +382,248 @@ inline void plan_tile_range(const PlanData& p, int op, int32_t rank, int64_t& be
     const int64_t k1 = rank < 0 ? n : first[(size_t)rank + 1];
     begin = p.tile_base[(size_t)(op * n + k0)];
     end = p.tile_base[(size_t)(op * n + k1)];
+}
+
+// ------------------------------------------------------------------- staged XOR exchange
+
+// DynaTrain Algorithm 1 (MemoryAwareChunk and the step loop) for resident virtual ranks: the
+// XOR steps are grouped into stages whose per-rank buffers fit a budget; every stage packs,
+// exchanges (send segment -> peer's receive segment, a device copy here) and unpacks, reusing
+// one scratch area.
+struct StageData {
+    int32_t nsteps = 0, nstages = 0;
+    std::vector<int32_t> stage_of_step;   // [nsteps + 1], -1 = no traffic in that step
+    std::vector<uint64_t> step_cost;      // [nsteps + 1], max over ranks of send + receive bytes
+    std::vector<uint64_t> send_base, recv_base;  // [stage][rank]: region offsets in scratch
+    std::vector<uint64_t> stage_scratch;  // [stage]
+    uint64_t scratch_needed = 0;
+    std::vector<int64_t> pack_begin, exch_begin, unpack_begin;  // [stage + 1] tile ranges
+    // backend memory
+    CopyDesc* descs = nullptr;   // 2n: pack and unpack descriptors with per-stage positions
+    TileRef* tiles = nullptr;    // [pack by stage | exchange by stage | unpack by stage]
+    void** ptr_table = nullptr;
+    int64_t n = 0;
+};
+
+template <class BE>
+void free_stage(BE& be, StageData& sd)
+{
+    be.free(sd.descs); be.free(sd.tiles); be.free(sd.ptr_table);
+    sd.descs = nullptr; sd.tiles = nullptr; sd.ptr_table = nullptr;
+}
+
+// The greedy of Algorithm 1 (MemoryAwareChunk) over steps 1..nsteps: a step joins the current
+// stage unless that would exceed the budget; steps without traffic belong to no stage, and no
+// empty stage is emitted (a step that alone exceeds the budget becomes a stage of its own).
+inline int32_t chunk_steps(const std::vector<uint64_t>& cost, uint64_t budget, std::vector<int32_t>& stage_of_step)
+{
+    const int32_t nsteps = (int32_t)cost.size() - 1;
+    stage_of_step.assign(cost.size(), -1);
+    int32_t nstages = 0;
+    uint64_t cur = 0;
+    bool open = false;
+    for (int32_t s = 1; s <= nsteps; ++s) {
+        if (cost[(size_t)s] == 0) continue;
+        if (open && cur + cost[(size_t)s] > budget) { ++nstages; cur = 0; open = false; }
+        stage_of_step[(size_t)s] = nstages;
+        cur += cost[(size_t)s];
+        open = true;
+    }
+    if (open) ++nstages;
+    return nstages;
+}
+
+template <class BE>
+void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_bytes, StageData& sd)
+{
+    if (!p.layout.all_ranks) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange needs an all-ranks plan" };
+    const int32_t WA = p.A.world, WB = p.B.world, W = WA > WB ? WA : WB;
+    const int64_t n = p.nboxes;
+    sd.n = n;
+    const size_t npair = (size_t)WA * (size_t)WB;
+    // (1) peer segments from the host copy of the boxes (sorted by source, destination)
+    std::vector<uint64_t> seg_bytes(npair, 0), seg_send(npair, 0), seg_recv(npair, 0);
+    for (const vps_box& b : p.boxes_send_order) {
+        if (b.src_rank == b.dst_rank) continue;
+        const size_t pr = (size_t)b.src_rank * (size_t)WB + (size_t)b.dst_rank;
+        if (seg_bytes[pr] == 0) { seg_send[pr] = b.send_pos; seg_recv[pr] = b.recv_pos; }
+        seg_bytes[pr] = b.send_pos + box_slot_bytes(b) - seg_send[pr];
+    }
+    // (2) XOR steps: in step s rank i is paired with i ^ s
+    int32_t pow2 = 1;
+    while (pow2 < W) pow2 <<= 1;
+    sd.nsteps = pow2 - 1;
+    sd.step_cost.assign((size_t)sd.nsteps + 1, 0);
+    auto seg = [&](int32_t i, int32_t j) -> uint64_t { return (i < WA && j < WB) ? seg_bytes[(size_t)i * (size_t)WB + (size_t)j] : 0; };
+    for (int32_t s = 1; s <= sd.nsteps; ++s)
+        for (int32_t r = 0; r < W; ++r) {
+            const uint64_t c = seg(r, r ^ s) + seg(r ^ s, r);
+            if (c > sd.step_cost[(size_t)s]) sd.step_cost[(size_t)s] = c;
+        }
+    sd.nstages = chunk_steps(sd.step_cost, budget, sd.stage_of_step);
+    const int32_t G = sd.nstages;
+    // (3) per stage: regions of every rank and positions of every segment inside them
+    std::vector<int32_t> stage_of_pair(npair, -1);
+    std::vector<int64_t> delta_send(npair, 0), delta_recv(npair, 0);
+    std::vector<uint64_t> st_send_off(npair, 0), st_recv_off(npair, 0);
+    sd.send_base.assign((size_t)G * (size_t)WA, 0);
+    sd.recv_base.assign((size_t)G * (size_t)WB, 0);
+    sd.stage_scratch.assign((size_t)G, 0);
+    for (int32_t g = 0; g < G; ++g) {
+        uint64_t off = 0;
+        for (int32_t i = 0; i < WA; ++i) {   // send regions, peers ascending inside
+            sd.send_base[(size_t)g * (size_t)WA + (size_t)i] = off;
+            uint64_t in = 0;
+            for (int32_t j = 0; j < WB; ++j) {
+                const int32_t s = i ^ j;
+                const size_t pr = (size_t)i * (size_t)WB + (size_t)j;
+                if (s == 0 || s > sd.nsteps || sd.stage_of_step[(size_t)s] != g || !seg_bytes[pr]) continue;
+                stage_of_pair[pr] = g;
+                st_send_off[pr] = in;
+                delta_send[pr] = (int64_t)in - (int64_t)seg_send[pr];
+                in += seg_bytes[pr];
+            }
+            off += (in + 255) & ~255ull;
+        }
+        for (int32_t j = 0; j < WB; ++j) {   // receive regions, sources ascending inside
+            sd.recv_base[(size_t)g * (size_t)WB + (size_t)j] = off;
+            uint64_t in = 0;
+            for (int32_t i = 0; i < WA; ++i) {
+                const size_t pr = (size_t)i * (size_t)WB + (size_t)j;
+                if (stage_of_pair[pr] != g) continue;
+                st_recv_off[pr] = in;
+                delta_recv[pr] = (int64_t)in - (int64_t)seg_recv[pr];
+                in += seg_bytes[pr];
+            }
+            off += (in + 255) & ~255ull;
+        }
+        sd.stage_scratch[(size_t)g] = off;
+        if (off > sd.scratch_needed) sd.scratch_needed = off;
+    }
+    // (4) device: descriptors with stage positions, tiles regrouped by stage
+    std::vector<int32_t> pair_send((size_t)n), pair_recv((size_t)n);
+    for (int64_t k = 0; k < n; ++k) {
+        const vps_box& b = p.boxes_send_order[(size_t)k];
+        pair_send[(size_t)k] = b.src_rank * WB + b.dst_rank;
+    }
+    for (int64_t k = 0; k < n; ++k) pair_recv[(size_t)k] = pair_send[(size_t)p.recv_perm[(size_t)k]];
+    int32_t* d_pair = be.template alloc<int32_t>(2 * n);       // pair of pack desc k, unpack desc k
+    int32_t* d_stage = be.template alloc<int32_t>((int64_t)npair);
+    int64_t* d_dsend = be.template alloc<int64_t>((int64_t)npair);
+    int64_t* d_drecv = be.template alloc<int64_t>((int64_t)npair);
+    be.upload(d_pair, pair_send.data(), sizeof(int32_t) * (size_t)n);
+    be.upload(d_pair + n, pair_recv.data(), sizeof(int32_t) * (size_t)n);
+    be.upload(d_stage, stage_of_pair.data(), sizeof(int32_t) * npair);
+    be.upload(d_dsend, delta_send.data(), sizeof(int64_t) * npair);
+    be.upload(d_drecv, delta_recv.data(), sizeof(int64_t) * npair);
+    sd.descs = be.template alloc<CopyDesc>(2 * n);
+    {
+        CopyDesc* out = sd.descs;
+        const CopyDesc* in = p.descs + n;   // the plan's pack and unpack descriptors
+        be.for_each(step::stage_descs(), 2 * n, [=] VPS_LAMBDA(int64_t i) {
+            CopyDesc d = in[i];
+            if (d.ntiles) {
+                const int32_t pr = d_pair[i];
+                if (i < n) d.dst_byte = (uint64_t)((int64_t)d.dst_byte + d_dsend[pr]);
+                else { d.src_byte = (uint64_t)((int64_t)d.src_byte + d_drecv[pr]); d.alt_src_slot = -1; }
+            }
+            out[i] = d;
+        });
+    }
+    // pack and unpack tiles of the plan, keyed by stage (stable sort keeps their order)
+    const int64_t t_pack0 = p.tile_base[(size_t)n], t_unpack0 = p.tile_base[(size_t)(2 * n)], t_end = p.tile_base[(size_t)(3 * n)];
+    const int64_t nmove = t_end - t_pack0;
+    int64_t* tb = be.template alloc<int64_t>(3 * n + 1);
+    be.upload(tb, p.tile_base.data(), sizeof(int64_t) * (size_t)(3 * n + 1));
+    uint64_t* key = be.template alloc<uint64_t>(nmove);
+    uint32_t* idx = be.template alloc<uint32_t>(nmove);
+    be.for_each(step::stage_tile_keys(), nmove, [=] VPS_LAMBDA(int64_t k) {
+        const int64_t t = t_pack0 + k;
+        const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;   // descriptor index in [n, 3n)
+        const uint64_t op = d < 2 * n ? 0 : 1;
+        key[k] = op << 32 | (uint32_t)d_stage[d_pair[d - n]];
+        idx[k] = (uint32_t)k;
+    });
+    be.sort_pairs(key, idx, nmove);
+    // exchange tiles: every segment cut into tile_bytes pieces, stages ascending
+    std::vector<int64_t> seg_tile_base;
+    std::vector<uint64_t> seg_src, seg_dst, seg_len;
+    sd.exch_begin.assign((size_t)G + 1, 0);
+    int64_t nexch = 0;
+    for (int32_t g = 0; g < G; ++g) {
+        sd.exch_begin[(size_t)g] = nexch;
+        for (int32_t i = 0; i < WA; ++i)
+            for (int32_t j = 0; j < WB; ++j) {
+                const size_t pr = (size_t)i * (size_t)WB + (size_t)j;
+                if (stage_of_pair[pr] != g) continue;
+                seg_tile_base.push_back(nexch);
+                seg_src.push_back(tile_pack_addr(slot_send(p.layout, i), st_send_off[pr]));
+                seg_dst.push_back(tile_pack_addr(slot_recv(p.layout, j), st_recv_off[pr]));
+                seg_len.push_back(seg_bytes[pr]);
+                nexch += (int64_t)((seg_bytes[pr] + tile_bytes - 1) / tile_bytes);
+            }
+    }
+    sd.exch_begin[(size_t)G] = nexch;
+    seg_tile_base.push_back(nexch);
+    const int64_t nseg = (int64_t)seg_len.size();
+    int64_t* d_stb = be.template alloc<int64_t>(nseg + 1);
+    uint64_t* d_ssrc = be.template alloc<uint64_t>(nseg);
+    uint64_t* d_sdst = be.template alloc<uint64_t>(nseg);
+    uint64_t* d_slen = be.template alloc<uint64_t>(nseg);
+    be.upload(d_stb, seg_tile_base.data(), sizeof(int64_t) * (size_t)(nseg + 1));
+    be.upload(d_ssrc, seg_src.data(), sizeof(uint64_t) * (size_t)nseg);
+    be.upload(d_sdst, seg_dst.data(), sizeof(uint64_t) * (size_t)nseg);
+    be.upload(d_slen, seg_len.data(), sizeof(uint64_t) * (size_t)nseg);
+    if (nmove + nexch >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 tiles" };
+    sd.tiles = be.template alloc<TileRef>(nmove + nexch);
+    {
+        // layout of the new table: [pack tiles by stage | exchange tiles by stage | unpack tiles by stage]
+        const int64_t npack = t_unpack0 - t_pack0;
+        TileRef* out = sd.tiles;
+        const TileRef* in = p.tiles;
+        const CopyDesc* sdescs = sd.descs;
+        be.for_each(step::stage_tile_gather(), nmove, [=] VPS_LAMBDA(int64_t k) {
+            const int64_t t = t_pack0 + idx[k];
+            const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;
+            // rebuilt from the stage descriptor: same geometry, stage positions
+            TileRef r = make_tile(sdescs[d - n], (uint32_t)(d - n), (uint32_t)(t - tb[d]));
+            (void)in;
+            out[k < npack ? k : k + nexch] = r;
+        });
+        be.for_each(step::stage_exchange_tiles(), nexch, [=] VPS_LAMBDA(int64_t t) {
+            const int64_t sg = upper_bound_idx(d_stb, nseg + 1, t) - 1;
+            const uint64_t o = (uint64_t)(t - d_stb[sg]) * tile_bytes;
+            TileRef r;
+            r.src = d_ssrc[sg] + o;
+            r.dst = d_sdst[sg] + o;
+            r.alt_src = VPS_TILE_NO_ALT;
+            r.src_pitch = 0; r.dst_pitch = 0;
+            r.nbytes = (uint32_t)(d_slen[sg] - o < tile_bytes ? d_slen[sg] - o : tile_bytes);
+            r.nruns_flags = 1u << 8;
+            out[npack + t] = r;
+        });
+    }
+    // per-stage tile ranges of pack and unpack from the sorted keys
+    std::vector<uint64_t> hkey((size_t)nmove);
+    be.download(hkey.data(), key, sizeof(uint64_t) * (size_t)nmove);
+    sd.pack_begin.assign((size_t)G + 1, 0);
+    sd.unpack_begin.assign((size_t)G + 1, 0);
+    {
+        const int64_t npack = t_unpack0 - t_pack0;
+        for (int32_t g = 0; g <= G; ++g) {
+            sd.pack_begin[(size_t)g] = std::lower_bound(hkey.begin(), hkey.end(), (uint64_t)g) - hkey.begin();
+            sd.unpack_begin[(size_t)g] = std::lower_bound(hkey.begin(), hkey.end(), (1ull << 32) | (uint64_t)g) - hkey.begin();
+        }
+        if (sd.pack_begin[(size_t)G] > npack) sd.pack_begin[(size_t)G] = npack;
+        for (int32_t g = 0; g <= G; ++g) {
+            sd.exch_begin[(size_t)g] += npack;
+            sd.unpack_begin[(size_t)g] += nexch;
+        }
+    }
+    sd.ptr_table = be.template alloc<void*>(num_slots(p.layout));
+    be.free(d_pair); be.free(d_stage); be.free(d_dsend); be.free(d_drecv); be.free(tb); be.free(key); be.free(idx);
+    be.free(d_stb); be.free(d_ssrc); be.free(d_sdst); be.free(d_slen);
+    be.sync();
 }
 
 }  // namespace vps

@@ -502,3 +502,88 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
                 checked += m
     log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
+
+
+# ----------------------------------------------------------------------------- staged exchange
+
+def memory_aware_chunk(cost, budget):
+    """Algorithm 1, MemoryAwareChunk, written out step by step (steps 1..len(cost)-1), with the
+    two declared readings: steps without traffic are skipped and no empty stage is emitted."""
+    stages, current, current_mem = [], [], 0
+    for s in range(1, len(cost)):
+        if cost[s] == 0:
+            continue
+        if current and current_mem + cost[s] > budget:
+            stages.append(current)
+            current, current_mem = [s], cost[s]
+        else:
+            current.append(s)
+            current_mem += cost[s]
+    if current:
+        stages.append(current)
+    return stages
+
+
+def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
+    """All ranks resident, exchange in XOR step order under a per-rank buffer budget."""
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plan = lib.plan_intersections(ca, cb, -1)
+    sp = lib.stage_exchange(plan, budget)
+    info = sp.info()
+    stage_of_step, step_cost = sp.steps()
+    W = max(a.world, b.world)
+    assert info["num_steps"] == (1 << max(W - 1, 0).bit_length()) - 1
+
+    # the schedule against Algorithm 1 written out in Python
+    seg = np.zeros((W, W), dtype=np.int64)
+    for i in range(a.world):
+        rb = None
+        for j in range(b.world):
+            if i != j:
+                seg[i, j] = plan.peer_segment(i, j)["bytes"]
+    cost = [0] * (info["num_steps"] + 1)
+    for s in range(1, info["num_steps"] + 1):
+        cost[s] = max(int(seg[r, r ^ s] if (r ^ s) < W else 0) + int(seg[r ^ s, r] if (r ^ s) < W else 0) for r in range(W))
+    assert cost == [int(c) for c in step_cost]
+    stages = memory_aware_chunk(cost, budget)
+    assert len(stages) == info["num_stages"]
+    for g, steps in enumerate(stages):
+        for s in steps:
+            assert stage_of_step[s] == g
+    assert all(stage_of_step[s] == -1 for s in range(1, len(cost)) if cost[s] == 0)
+    # XOR pairing: an involution, and every pair with traffic is met in exactly one step
+    for i in range(W):
+        for j in range(W):
+            if i != j and seg[i, j]:
+                s = i ^ j
+                assert 1 <= s <= info["num_steps"] and (j ^ s) == i and stage_of_step[s] >= 0
+    # payload never exceeds the aligned segments, and the budget holds when it can
+    for j in range(b.world):
+        rb = oracle.route_bytes(a, b, j)
+        for i in range(a.world):
+            if i != j:
+                assert rb[i] <= seg[i, j] <= rb[i] + 16 * plan.num_boxes
+    if budget >= max(cost):
+        for steps in stages:
+            assert sum(cost[s] for s in steps) <= budget
+
+    src_host = {(r, buf): a.fill(r, buf, seed, rank_salt, pad_word=0x3C3C3C3C) for r in range(a.world) for buf in range(8)}
+    src = {k: mem.alloc(v.nbytes) for k, v in src_host.items()}
+    for k, v in src_host.items():
+        mem.upload(src[k], v)
+    dst = {(j, buf): mem.alloc(b.buffer_elems(j, buf) * oracle.KIND_BYTES[buf % 4]) for j in range(b.world) for buf in range(8)}
+    scratch = mem.alloc(info["scratch_needed"])
+    mem.register_bounds()
+    lib.apply_transition_staged(sp, [mem.ptr(src[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                                [mem.ptr(dst[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                                mem.ptr(scratch), info["scratch_needed"])
+    mem.sync()
+    assert mem.violations() == 0
+    for (j, buf), d in dst.items():
+        want = oracle.expected(a, b, j, buf, seed, rank_salt, pad_word=SENT32)
+        got = mem.download(d).view(want.dtype)
+        assert np.array_equal(got, want), ("staged", j, buf)
+    one_shot = plan.buffer_bytes(-1)["scratch_needed"]
+    return dict(stages=info["num_stages"], steps=info["num_steps"], scratch=info["scratch_needed"], one_shot=one_shot,
+                max_cost=max(cost))

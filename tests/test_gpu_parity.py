@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import MEDIUM, SINGLE
+from test_hostcheck_parity import MEDIUM, SINGLE, STAGED
 
 pytestmark = pytest.mark.gpu
 
@@ -51,3 +51,19 @@ def test_tile_size_does_not_change_results(lib, tile):
         parity.run_single_rank(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], 1, seed=78)
     finally:
         lib.set_tile_bytes(8192)
+
+
+@pytest.mark.parametrize("name,budget_kind", [(n, k) for n, _ in STAGED for k in ("tiny", "mid")],
+                         ids=[f"{n}-{k}" for n, _ in STAGED for k in ("tiny", "mid")])
+def test_staged_xor_exchange(lib, name, budget_kind):
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    probe = parity.run_staged(lib, parity.GpuMem(), m, pa, pb, seed=5, budget=1 << 60)
+    budget = {"tiny": 1, "mid": max(probe["max_cost"] * 2, 1)}[budget_kind]
+    out = parity.run_staged(lib, parity.GpuMem(), m, pa, pb, seed=6, budget=budget)
+    assert out["stages"] >= 1
+
+
+def test_staged_exchange_toy_workload(lib):
+    w = cf.WORKLOADS["toy"]
+    out = parity.run_staged(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], seed=cf.seed_of("toy"), budget=8 << 20)
+    assert out["stages"] >= 2

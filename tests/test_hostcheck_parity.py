@@ -45,6 +45,24 @@ def test_medium_shapes_all_ranks(hlib, name, m, pa, pb):
     assert out["boxes"] > 0
 
 
+STAGED = [("gpt-zero-to-replicated", 0), ("gpt-blocked-rev", 1), ("gpt-world-grows", 2), ("moe-transposed", 3), ("moe-odd", 4)]
+
+
+@pytest.mark.parametrize("name,budget_kind", [(n, k) for n, _ in STAGED for k in ("tiny", "mid", "huge")],
+                         ids=[f"{n}-{k}" for n, _ in STAGED for k in ("tiny", "mid", "huge")])
+def test_staged_xor_exchange(hlib, name, budget_kind):
+    """Memory-aware stages and the XOR step order (Algorithm 1) give the same final state."""
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    probe = parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=5, budget=1 << 60)
+    assert probe["stages"] == 1
+    budget = {"tiny": 1, "mid": max(probe["max_cost"] * 2, 1), "huge": 1 << 60}[budget_kind]
+    out = parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=6, budget=budget)
+    if budget_kind == "tiny":
+        assert out["stages"] >= 2 and out["scratch"] < out["one_shot"] * 2
+    if budget_kind == "mid":
+        assert 1 <= out["stages"] <= probe["steps"]
+
+
 SINGLE = [
     ("gpt-zero-to-replicated", 0), ("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-blocked-rev", 2),
     ("gpt-odd", 1), ("gpt-world-grows", 11), ("gpt-world-grows", 3), ("gqa", 6), ("moe-ep", 9),
