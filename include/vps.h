@@ -126,6 +126,14 @@ int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* pa
 int vps_plan_intersections(const vps_config* src, const vps_config* dst, int32_t rank,
                            void* stream, vps_plan** out);
 
+/* Same, with flags.  VPS_PLAN_ROUTES_ONLY builds the routed boxes, their order and the byte counts
+ * but no copy descriptors and no tile table: for planning many ranks whose buffers are not
+ * resident (queries work; vps_pack / vps_unpack / vps_apply_transition return
+ * VPS_ERR_INVALID_ARG). */
+enum { VPS_PLAN_ROUTES_ONLY = 1 };
+int vps_plan_intersections_ex(const vps_config* src, const vps_config* dst, int32_t rank,
+                              uint32_t flags, void* stream, vps_plan** out);
+
 /* Algorithm 1 line 8 (PackData): copy every outgoing sub-box of `rank` from its old local
  * buffers into its send buffer.  src_bufs: host array of 8 device pointers (entries of empty
  * buffers may be NULL).  send_buf: device, >= send_total bytes (vps_plan_buffer_bytes), 16-byte
@@ -182,6 +190,21 @@ int vps_apply_transition_staged(const vps_stage_plan* sp, const void* const* src
                                 void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
                                 void* stream);
 void vps_stage_plan_destroy(vps_stage_plan* sp);
+
+/* ---- collective intent ----
+ * Algorithm 1 (OptimizePrimitives) and Section 4.3 "Communication Primitive Optimization": group
+ * the routed boxes that leave their rank by logical tensor and state kind and infer which
+ * collective the group amounts to from the number of distinct sources and destinations and from
+ * the slices: identical slices from one source to several destinations are a broadcast; slices
+ * from one source to several destinations that tile one contiguous range of the flattened
+ * tensor are a scatter; such slices from several sources to one destination a gather; all else
+ * stays point-to-point.  A slice is one routed box; it is contiguous when it is a single range of
+ * the row-major flattening of the unsharded tensor.  classes[tensor*4 + kind] receives the code;
+ * src must be the source configuration the plan was made from.  Runs on the device, synchronises
+ * the stream. */
+enum { VPS_COLL_NONE = 0, VPS_COLL_P2P = 1, VPS_COLL_BROADCAST = 2, VPS_COLL_SCATTER = 3, VPS_COLL_GATHER = 4 };
+int vps_plan_classify_collectives(const vps_plan* plan, const vps_config* src, void* stream,
+                                  int32_t* classes, int64_t max_entries);
 
 /* ---- queries (host side, no device work unless stated) ---- */
 int vps_config_world(const vps_config* cfg, int32_t* world);

@@ -16,6 +16,8 @@ ERR_INVALID_ARG, ERR_INDIVISIBLE, ERR_RANK_RANGE, ERR_MODEL_MISMATCH = -1, -2, -
 ERR_SCRATCH_TOO_SMALL, ERR_OOM, ERR_HIP = -5, -6, -7
 NUM_BUFFERS = 8
 NO_POS = (1 << 64) - 1
+PLAN_ROUTES_ONLY = 1
+COLL_NONE, COLL_P2P, COLL_BROADCAST, COLL_SCATTER, COLL_GATHER = range(5)
 
 MODEL_FIELDS = ("family", "layers", "hidden", "q_heads", "kv_heads", "head_dim", "ffn", "vocab",
                 "experts", "expert_ffn")
@@ -89,6 +91,7 @@ class Library:
         sig = {
             "describe_config": [P(ModelDesc), P(ParallelDesc), i32, P(vp)],
             "plan_intersections": [vp, vp, i32, vp, P(vp)],
+            "plan_intersections_ex": [vp, vp, i32, u32, vp, P(vp)],
             "pack": [vp, i32, P(vp), vp, vp],
             "unpack": [vp, i32, vp, P(vp), vp],
             "apply_transition": [vp, i32, P(vp), P(vp), vp, u64, vp],
@@ -106,6 +109,7 @@ class Library:
             "plan_stats": [vp, P(PlanStats)],
             "set_tile_bytes": [u32],
             "stage_exchange": [vp, u64, vp, P(vp)],
+            "plan_classify_collectives": [vp, vp, vp, P(i32), i64],
             "stage_info": [vp, P(i32), P(i32), P(u64)],
             "stage_steps": [vp, P(i32), P(u64), i32],
             "apply_transition_staged": [vp, P(vp), P(vp), vp, u64, vp],
@@ -130,7 +134,7 @@ class Library:
                "config_world", "config_num_tensors", "config_buffer_bytes", "config_num_pieces",
                "config_get_pieces", "plan_pair_bytes", "plan_peer_bytes", "plan_buffer_bytes",
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
-               "set_tile_bytes", "config_destroy", "plan_destroy", "last_error", "stage_exchange",
+               "set_tile_bytes", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
                "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy")
 
     def last_error(self):
@@ -150,6 +154,11 @@ class Library:
     def plan_intersections(self, src, dst, rank=-1, stream=0):
         out = C.c_void_p()
         self._check(self._fn["plan_intersections"](src._h, dst._h, rank, stream, C.byref(out)))
+        return Plan(self, out)
+
+    def plan_intersections_ex(self, src, dst, rank=-1, flags=0, stream=0):
+        out = C.c_void_p()
+        self._check(self._fn["plan_intersections_ex"](src._h, dst._h, rank, flags, stream, C.byref(out)))
         return Plan(self, out)
 
     def pack(self, plan, rank, src_bufs, send_buf, stream=0):
@@ -256,6 +265,14 @@ class Plan:
         n = self.num_boxes
         out = np.zeros(n, dtype=BOX_DTYPE)
         self._lib._check(self._lib._fn["plan_get_boxes"](self._h, out.ctypes.data, n))
+        return out
+
+    def classify_collectives(self, src_config, stream=0):
+        """int32 array [num_tensors*4]: COLL code per (tensor, kind)."""
+        n = src_config.num_tensors * 4
+        out = np.zeros(n, dtype=np.int32)
+        self._lib._check(self._lib._fn["plan_classify_collectives"](
+            self._h, src_config._h, stream, out.ctypes.data_as(C.POINTER(C.c_int32)), n))
         return out
 
     def stats(self):

@@ -109,8 +109,17 @@ void VPS_FN(config_destroy)(vps_config* c)
     delete c;
 }
 
+int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, int32_t rank, uint32_t flags,
+                                  void* stream, vps_plan** out);
+
 int VPS_FN(plan_intersections)(const vps_config* src, const vps_config* dst, int32_t rank, void* stream,
                                vps_plan** out)
+{
+    return VPS_FN(plan_intersections_ex)(src, dst, rank, 0, stream, out);
+}
+
+int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, int32_t rank, uint32_t flags,
+                                  void* stream, vps_plan** out)
 {
     if (!src || !dst || !out) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
     *out = nullptr;
@@ -118,7 +127,8 @@ int VPS_FN(plan_intersections)(const vps_config* src, const vps_config* dst, int
     vps_plan* p = new vps_plan();
     VPS_BACKEND be(stream);
     try {
-        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, p->d);
+        if (flags & ~(uint32_t)VPS_PLAN_ROUTES_ONLY) throw vps::Error{ VPS_ERR_INVALID_ARG, "unknown plan flag" };
+        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, (flags & VPS_PLAN_ROUTES_ONLY) != 0, p->d);
         vps::mark_used_slots(p->d, p->used);
     } catch (...) {
         be.release_all();
@@ -149,8 +159,9 @@ template <class BE>
 int launch_ops(BE& be, const vps_plan* plan, int64_t t0, int64_t t1, const std::vector<void*>& ptrs,
                int alias)
 {
-    if (t1 <= t0) return VPS_OK;
     const PlanData& p = plan->d;
+    if (p.routes_only) return fail(VPS_ERR_INVALID_ARG, "the plan was made with VPS_PLAN_ROUTES_ONLY and has no copy tables");
+    if (t1 <= t0) return VPS_OK;
     PtrArgs pa;
     memset(&pa, 0, sizeof(pa));
     if (p.layout.all_ranks) {
@@ -519,6 +530,27 @@ int VPS_FN(apply_transition_staged)(const vps_stage_plan* sp, const void* const*
         be.launch_copy(sd.descs, sd.tiles, sd.exch_begin[(size_t)g], sd.exch_begin[(size_t)g + 1] - sd.exch_begin[(size_t)g], pa, 0);
         be.launch_copy(sd.descs, sd.tiles, sd.unpack_begin[(size_t)g], sd.unpack_begin[(size_t)g + 1] - sd.unpack_begin[(size_t)g], pa, 0);
     }
+    return VPS_OK;
+    VPS_CATCH
+}
+
+int VPS_FN(plan_classify_collectives)(const vps_plan* plan, const vps_config* src, void* stream, int32_t* classes,
+                                      int64_t max_entries)
+{
+    if (!plan || !src || !classes) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    VPS_TRY
+    if (memcmp(&src->d.P, &plan->d.A, sizeof(vps::ParConst)) != 0)
+        return vps::fail(VPS_ERR_MODEL_MISMATCH, "src must be the source configuration of the plan");
+    std::vector<int32_t> cls;
+    VPS_BACKEND be(stream);
+    try {
+        vps::classify_collectives(be, plan->d, src->d, cls);
+    } catch (...) {
+        be.release_all();
+        throw;
+    }
+    be.commit();
+    for (size_t i = 0; i < cls.size() && (int64_t)i < max_entries; ++i) classes[i] = cls[i];
     return VPS_OK;
     VPS_CATCH
 }

@@ -721,6 +721,44 @@ VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
 #endif
 }
 
+VPS_HD void be_atomic_or(uint32_t* p, uint32_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    atomicOr(p, v);
+#else
+    *p |= v;
+#endif
+}
+
+// ------------------------------------------------------------------------------------------
+// Collective intent (Algorithm 1, OptimizePrimitives): per logical tensor and state kind, look
+// at the routed boxes ("slices") that leave their rank.
+// ------------------------------------------------------------------------------------------
+
+enum { COLL_NONE = 0, COLL_P2P = 1, COLL_BROADCAST = 2, COLL_SCATTER = 3, COLL_GATHER = 4 };
+enum : uint32_t { CF_ANY = 1, CF_MULTI_SRC = 2, CF_MULTI_DST = 4, CF_DIFFERENT = 8, CF_NONLINEAR = 16, CF_GAP = 32 };
+
+// Is the box one contiguous range of the row-major flattening of its unsharded tensor?
+VPS_HD bool box_is_linear_range(const vps_box& b, const TensorRec& x)
+{
+    int a = 0;
+    while (a < 4 && b.ext[a] == 1) ++a;   // outermost axis that the box really spans
+    for (int i = a + 1; i < 4; ++i)
+        if (b.lo[i] != 0 || b.ext[i] != x.shape[i]) return false;
+    return true;
+}
+
+VPS_HD int32_t classify_flags(uint32_t f)
+{
+    if (!(f & CF_ANY)) return COLL_NONE;
+    const bool one_src = !(f & CF_MULTI_SRC), one_dst = !(f & CF_MULTI_DST);
+    const bool identical = !(f & CF_DIFFERENT), cont = !(f & (CF_NONLINEAR | CF_GAP));
+    if (one_src && !one_dst && identical) return COLL_BROADCAST;
+    if (one_src && !one_dst && cont) return COLL_SCATTER;
+    if (!one_src && one_dst && cont) return COLL_GATHER;
+    return COLL_P2P;
+}
+
 template <class T>
 VPS_HD int64_t upper_bound_idx(const T* a, int64_t n, T v)
 {

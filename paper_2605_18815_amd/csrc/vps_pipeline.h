@@ -54,6 +54,10 @@ struct plan_copy_descs {};
 struct plan_tile_table {};
 struct plan_sorted_boxes {};
 struct plan_recv_perm {};
+struct coll_keys {};
+struct coll_group_key {};
+struct coll_flags {};
+struct coll_classes {};
 struct stage_tile_keys {};
 struct stage_tile_gather {};
 struct stage_descs {};
@@ -80,6 +84,7 @@ struct PlanData {
     ParConst A, B;
     int32_t rank = -1;
     uint32_t tile_bytes = 0;
+    bool routes_only = false;  // no copy descriptors and no tile table: queries only
     PtrLayout layout;
     int64_t nboxes = 0;
     // backend memory
@@ -211,7 +216,7 @@ inline uint64_t config_buffer_elems(const ConfigData& c, int32_t rank, int32_t b
 
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
-                uint32_t tile_bytes, PlanData& p)
+                uint32_t tile_bytes, bool routes_only, PlanData& p)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -221,7 +226,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     const ParConst A = ca.P, B = cb.P;
     const int32_t WA = A.world, WB = B.world, W = WA > WB ? WA : WB;
     if (rank < -1 || rank >= W) throw Error{ VPS_ERR_RANK_RANGE, "rank outside both worlds" };
-    p.A = A; p.B = B; p.rank = rank; p.tile_bytes = tile_bytes;
+    p.A = A; p.B = B; p.rank = rank; p.tile_bytes = tile_bytes; p.routes_only = routes_only;
     p.layout.all_ranks = rank < 0; p.layout.wa = WA; p.layout.wb = WB;
     const PtrLayout layout = p.layout;
 
@@ -307,6 +312,8 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     be.free(pairs);
 
     // (5) copy descriptors and tile table
+    p.tile_base.assign((size_t)(3 * n + 1), 0);
+    if (!routes_only) {
     p.descs = be.template alloc<CopyDesc>(3 * n);
     int64_t* nt = be.template alloc<int64_t>(3 * n + 1);
     int64_t* tb = be.template alloc<int64_t>(3 * n + 1);
@@ -338,6 +345,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         });
     }
     be.free(nt); be.free(tb);
+    }
 
     // (6) host copies for queries
     {
@@ -437,6 +445,7 @@ template <class BE>
 void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_bytes, StageData& sd)
 {
     if (!p.layout.all_ranks) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange needs an all-ranks plan" };
+    if (p.routes_only) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange needs a plan with copy tables" };
     const int32_t WA = p.A.world, WB = p.B.world, W = WA > WB ? WA : WB;
     const int64_t n = p.nboxes;
     sd.n = n;
@@ -623,6 +632,61 @@ void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_
     sd.ptr_table = be.template alloc<void*>(num_slots(p.layout));
     be.free(d_pair); be.free(d_stage); be.free(d_dsend); be.free(d_drecv); be.free(tb); be.free(key); be.free(idx);
     be.free(d_stb); be.free(d_ssrc); be.free(d_sdst); be.free(d_slen);
+    be.sync();
+}
+
+// --------------------------------------------------------------------- collective intent
+
+// Algorithm 1 (OptimizePrimitives, GroupByLogicalTensor ... Broadcast / Scatter / Gather): the
+// boxes that leave their rank are grouped by (tensor, kind); a group with one source, several
+// destinations and identical slices is a broadcast; with one source, several destinations and
+// slices that tile one contiguous range of the flattened tensor a scatter; with several
+// sources, one destination and such slices a gather; anything else stays point-to-point.
+// classes[tensor*4 + kind] receives the COLL_* code.
+template <class BE>
+void classify_collectives(BE& be, const PlanData& p, const ConfigData& ca, std::vector<int32_t>& classes)
+{
+    const int64_t n = p.nboxes;
+    const int32_t ngroups = p.A.nt * 4;
+    classes.assign((size_t)ngroups, COLL_NONE);
+    vps_box* boxes = be.template alloc<vps_box>(n);
+    be.upload(boxes, p.boxes_send_order.data(), sizeof(vps_box) * (size_t)n);
+    uint64_t* key = be.template alloc<uint64_t>(n);
+    uint64_t* gk = be.template alloc<uint64_t>(n);
+    uint32_t* ord = be.template alloc<uint32_t>(n);
+    uint32_t* flags = be.template alloc<uint32_t>(ngroups);
+    int32_t* out = be.template alloc<int32_t>(ngroups);
+    be.zero(flags, sizeof(uint32_t) * (size_t)ngroups);
+    const TensorRec* T = ca.T;
+    // order: group, then first element of the slice
+    be.for_each(step::coll_keys(), n, [=] VPS_LAMBDA(int64_t k) { key[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); ord[k] = (uint32_t)k; });
+    be.sort_pairs(key, ord, n);
+    be.for_each(step::coll_group_key(), n, [=] VPS_LAMBDA(int64_t k) {
+        const vps_box& b = boxes[ord[k]];
+        gk[k] = b.src_rank == b.dst_rank ? ~0ull : (uint64_t)(b.tensor * 4 + b.kind);   // retained boxes last
+    });
+    be.sort_pairs(gk, ord, n);
+    be.for_each(step::coll_flags(), n, [=] VPS_LAMBDA(int64_t k) {
+        if (gk[k] == ~0ull) return;
+        const vps_box& b = boxes[ord[k]];
+        const TensorRec x = T[b.tensor];
+        const int64_t g0 = lower_bound_idx(gk, n, gk[k]);
+        const vps_box& f = boxes[ord[g0]];
+        uint32_t fl = CF_ANY;
+        if (b.src_rank != f.src_rank) fl |= CF_MULTI_SRC;
+        if (b.dst_rank != f.dst_rank) fl |= CF_MULTI_DST;
+        for (int a = 0; a < 4; ++a)
+            if (b.lo[a] != f.lo[a] || b.ext[a] != f.ext[a]) fl |= CF_DIFFERENT;
+        if (!box_is_linear_range(b, x)) fl |= CF_NONLINEAR;
+        if (k > g0) {
+            const vps_box& pv = boxes[ord[k - 1]];
+            if (box_minor_key(pv, x) + box_volume(pv) != box_minor_key(b, x)) fl |= CF_GAP;
+        }
+        be_atomic_or(&flags[gk[k]], fl);
+    });
+    be.for_each(step::coll_classes(), ngroups, [=] VPS_LAMBDA(int64_t g) { out[g] = classify_flags(flags[g]); });
+    be.download(classes.data(), out, sizeof(int32_t) * (size_t)ngroups);
+    be.free(boxes); be.free(key); be.free(gk); be.free(ord); be.free(flags); be.free(out);
     be.sync();
 }
 

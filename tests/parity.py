@@ -587,3 +587,53 @@ def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
     one_shot = plan.buffer_bytes(-1)["scratch_needed"]
     return dict(stages=info["num_stages"], steps=info["num_steps"], scratch=info["scratch_needed"], one_shot=one_shot,
                 max_cost=max(cost))
+
+
+# ----------------------------------------------------------------------------- collective intent
+
+def classify_bruteforce(boxes, shapes):
+    """Algorithm 1 (OptimizePrimitives) over a box list, written with plain sets and lists.
+    Returns {(tensor, kind): code}; codes as in include/vps.h."""
+    NONE, P2P, BROADCAST, SCATTER, GATHER = range(5)
+    groups = {}
+    for bx in boxes:
+        if bx["src_rank"] != bx["dst_rank"]:
+            groups.setdefault((int(bx["tensor"]), int(bx["kind"])), []).append(bx)
+    out = {}
+    for (t, kind), bl in groups.items():
+        shape = shapes[t]
+        srcs = {int(b["src_rank"]) for b in bl}
+        dsts = {int(b["dst_rank"]) for b in bl}
+        slices = [(tuple(int(x) for x in b["lo"]), tuple(int(x) for x in b["ext"])) for b in bl]
+        identical = len(set(slices)) == 1
+
+        def as_range(lo, ext):
+            # the set of linear indices of the slice, and whether it is one range
+            idx = np.ravel_multi_index(np.meshgrid(*[np.arange(l, l + e) for l, e in zip(lo, ext)], indexing="ij"), shape).ravel()
+            idx.sort()
+            return int(idx[0]), int(idx[-1]) + 1, bool((np.diff(idx) == 1).all())
+
+        ranges = sorted(as_range(lo, ext) for lo, ext in slices)
+        cont = all(r[2] for r in ranges) and all(ranges[k][1] == ranges[k + 1][0] for k in range(len(ranges) - 1))
+        if len(srcs) == 1 and len(dsts) > 1 and identical:
+            out[(t, kind)] = BROADCAST
+        elif len(srcs) == 1 and len(dsts) > 1 and cont:
+            out[(t, kind)] = SCATTER
+        elif len(srcs) > 1 and len(dsts) == 1 and cont:
+            out[(t, kind)] = GATHER
+        else:
+            out[(t, kind)] = P2P
+    return out
+
+
+def run_classify(lib, model, pa, pb):
+    a = oracle.Config(model, pa)
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plan = lib.plan_intersections_ex(ca, cb, -1, flags=1)
+    got = plan.classify_collectives(ca)
+    shapes = [a.tensor_info(t)["shape"] for t in range(a.num_tensors)]
+    want = classify_bruteforce(plan.get_boxes(), shapes)
+    for t in range(a.num_tensors):
+        for kind in range(4):
+            assert got[t * 4 + kind] == want.get((t, kind), 0), (t, kind, got[t * 4 + kind], want.get((t, kind), 0))
+    return np.bincount(got, minlength=5)

@@ -88,3 +88,34 @@ def test_gpt1p3b_all_ranks_full_size(lib):
                                         seed=cf.seed_of("gpt1p3b"), fraction=FRACTION,
                                         log=lambda s: print(s, flush=True))
     assert out["checked"] > 0
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["gqa70b", "moe235b"])
+def test_all_ranks_planning_at_scale(lib, name):
+    """Routes of all 128 ranks at once (no copy tables): every box validated by the oracle on its
+    corners and random interior points, destination coverage exact for every rank."""
+    import time
+    import numpy as np
+    import oracle
+    from paper_2605_18815_amd import binding as B
+    w = cf.WORKLOADS[name]
+    a, b = oracle.Config(w["model"], w["src"]), oracle.Config(w["model"], w["dst"])
+    t0 = time.time()
+    ca, cb = lib.describe_config(w["model"], w["src"]), lib.describe_config(w["model"], w["dst"])
+    t1 = time.time()
+    plan = lib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
+    t2 = time.time()
+    boxes = plan.get_boxes()
+    print(f"\n{name}: {ca.num_pieces} + {cb.num_pieces} pieces in {t1 - t0:.3f}s, {len(boxes)} boxes in {t2 - t1:.3f}s "
+          f"({len(boxes) / (t2 - t1) / 1e6:.2f} M boxes/s)", flush=True)
+    parity.validate_boxes(a, b, boxes, -1, samples=8)
+    # one rank's plan is the restriction of the all-ranks plan
+    r = w["rank"]
+    one = lib.plan_intersections_ex(ca, cb, r, flags=B.PLAN_ROUTES_ONLY).get_boxes()
+    sel = boxes[(boxes["src_rank"] == r) | (boxes["dst_rank"] == r)]
+    keys = ["tensor", "kind", "src_rank", "dst_rank", "src_off", "dst_off"]
+    assert len(one) == len(sel)
+    assert np.array_equal(np.sort(one[keys], order=keys), np.sort(sel[keys], order=keys))
+    cls = plan.classify_collectives(ca)
+    print("  collective intent per (tensor, kind) [none, p2p, broadcast, scatter, gather]:", np.bincount(cls, minlength=5), flush=True)

@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import MEDIUM, SINGLE, STAGED
+from test_hostcheck_parity import COLLECTIVE_CASES, MEDIUM, SINGLE, STAGED
 
 pytestmark = pytest.mark.gpu
 
@@ -67,3 +67,15 @@ def test_staged_exchange_toy_workload(lib):
     w = cf.WORKLOADS["toy"]
     out = parity.run_staged(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], seed=cf.seed_of("toy"), budget=8 << 20)
     assert out["stages"] >= 2
+
+
+@pytest.mark.parametrize("name,m,pa,pb,expect", COLLECTIVE_CASES, ids=[c[0] for c in COLLECTIVE_CASES])
+def test_collective_intent_cases(lib, name, m, pa, pb, expect):
+    counts = parity.run_classify(lib, m, pa, pb)
+    assert counts[expect] > 0, counts
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS + [c[:4] for c in MEDIUM], ids=[c[0] for c in TRANSITIONS + MEDIUM])
+def test_collective_intent_matches_bruteforce(lib, name, m, pa, pb):
+    counts = parity.run_classify(lib, m, pa, pb)
+    assert counts.sum() > 0

@@ -63,6 +63,45 @@ def test_staged_xor_exchange(hlib, name, budget_kind):
         assert 1 <= out["stages"] <= probe["steps"]
 
 
+COLLECTIVE_CASES = [
+    ("broadcast-dp-grows", cf.TINY_GPT, P(dp=1, zero=0), P(dp=4, zero=0), 2),
+    ("scatter-tp-grows", cf.TINY_GPT, P(tp=1, zero=0), P(tp=4, zero=0), 3),
+    ("scatter-zero-on", cf.TINY_GPT, P(dp=1, zero=0), P(dp=4, zero=1), 3),
+    ("gather-tp-shrinks", cf.TINY_GPT, P(tp=4, zero=0), P(tp=1, zero=0), 4),
+    ("p2p-tp-pp", cf.TINY_GPT, P(tp=4, pp=2, dp=1), P(tp=2, pp=4, dp=1), 1),
+]
+
+
+@pytest.mark.parametrize("name,m,pa,pb,expect", COLLECTIVE_CASES, ids=[c[0] for c in COLLECTIVE_CASES])
+def test_collective_intent_cases(hlib, name, m, pa, pb, expect):
+    """Algorithm 1, OptimizePrimitives: the device classification against plain Python sets."""
+    counts = parity.run_classify(hlib, m, pa, pb)
+    assert counts[expect] > 0, counts
+
+
+@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+def test_collective_intent_matches_bruteforce(hlib, name, m, pa, pb):
+    counts = parity.run_classify(hlib, m, pa, pb)
+    assert counts.sum() == 4 * len(__import__("textbook").inventory(m))
+
+
+def test_routes_only_plan_refuses_copies(hlib):
+    from paper_2605_18815_amd import binding as B
+    ca = hlib.describe_config(cf.TINY_GPT, P(tp=2, dp=2))
+    cb = hlib.describe_config(cf.TINY_GPT, P(tp=1, dp=4, zero=0))
+    plan = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
+    full = hlib.plan_intersections(ca, cb, -1)
+    assert plan.num_boxes == full.num_boxes and np.array_equal(plan.get_boxes(), full.get_boxes())
+    assert plan.stats()["num_pack_tiles"] == 0
+    mem = parity.HostMem(hlib)
+    bufs = [mem.ptr(mem.alloc(max(ca.buffer_bytes(r % 4, b), cb.buffer_bytes(r % 4, b)))) for r in range(4) for b in range(8)]
+    with pytest.raises(VpsError) as e:
+        hlib.apply_transition(plan, -1, bufs, bufs, mem.ptr(mem.alloc(1 << 20)), 1 << 20)
+    assert e.value.code == B.ERR_INVALID_ARG
+    with pytest.raises(VpsError):
+        hlib.plan_intersections_ex(ca, cb, -1, flags=8)
+
+
 SINGLE = [
     ("gpt-zero-to-replicated", 0), ("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-blocked-rev", 2),
     ("gpt-odd", 1), ("gpt-world-grows", 11), ("gpt-world-grows", 3), ("gqa", 6), ("moe-ep", 9),
