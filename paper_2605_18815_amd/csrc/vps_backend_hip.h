@@ -209,8 +209,10 @@ public:
         free(tmp);
     }
 
-    // Stable ascending sort of (key, value) pairs, result back in the input arrays.
-    void sort_pairs(uint64_t* keys, uint32_t* vals, int64_t n)
+    // Stable ascending sort of (key, value) pairs.  The arrays are passed by reference: after the
+    // call they point at the sorted data (the sort ping-pongs between the inputs and two
+    // scratch arrays instead of copying back).
+    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n)
     {
         if (n <= 1) return;
         uint64_t* k2 = alloc<uint64_t>(n);
@@ -219,9 +221,8 @@ public:
         VPS_HIP_CHECK(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, 64, stream_));
         void* tmp = alloc<char>((int64_t)tmp_bytes);
         VPS_HIP_CHECK(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, 64, stream_));
-        VPS_HIP_CHECK(hipMemcpyAsync(keys, k2, sizeof(uint64_t) * (size_t)n, hipMemcpyDeviceToDevice, stream_));
-        VPS_HIP_CHECK(hipMemcpyAsync(vals, v2, sizeof(uint32_t) * (size_t)n, hipMemcpyDeviceToDevice, stream_));
-        free(tmp); free(k2); free(v2);
+        free(tmp); free(keys); free(vals);
+        keys = k2; vals = v2;
     }
 
     // The host array must stay valid until the next sync(); builders keep it alive.

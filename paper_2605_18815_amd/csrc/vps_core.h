@@ -243,8 +243,7 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
 }
 
 // ------------------------------------------------------------------------------------------
-// Planner: one item per destination piece; it walks the source pieces of the same
-// (tensor, kind).
+// Planner: one item per (destination piece, source rank slot) of the same (tensor, kind).
 // ------------------------------------------------------------------------------------------
 
 // The source rank selected for destination rank j among the ranks that hold the same data as
@@ -297,24 +296,28 @@ struct PlanCtx {
     int32_t rank;              // planned rank or -1
 };
 
-VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t d, vps_box* out)
+// One item per (destination piece, source mapper slot): slot u of the piece's (tensor, kind)
+// is the source item of tp index u / DDP and data-parallel index u % DDP, i.e. the pieces of one
+// source rank.  Items are ordered destination-piece major, so emitted boxes keep the order
+// (destination piece, source piece).
+VPS_HD int64_t plan_slots(const ParConst& A) { return (int64_t)A.tp * A.ddp; }
+
+VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t item, vps_box* out)
 {
-    const vps_piece dp = c.DP[d];
-    const TensorRec x = c.T[dp.tensor];
-    const int64_t g0 = map_group_item(c.A, dp.tensor, dp.kind);
-    int64_t sa = c.sbase[g0];
-    int64_t sb = c.sbase[g0 + (int64_t)c.A.tp * c.A.ddp];
-    if (c.rank >= 0 && dp.rank != c.rank) {
-        // a piece of another destination rank can only pair with pieces of the planned rank,
-        // and those all belong to one mapper item of this (tensor, kind)
+    const int64_t U = plan_slots(c.A);
+    const int64_t d = item / U, u = item - d * U;
+    const int32_t drank = c.DP[d].rank;
+    if (c.rank >= 0 && drank != c.rank) {
+        // a piece of another destination rank can only pair with pieces of the planned rank
         if (c.rank >= c.A.world) return 0;
         const RankCoord rc = decode_rank(c.A, c.rank);
-        if (stage_of_layer(c.A, x.layer) != rc.pp) return 0;
-        if (x.group && x.expert / (c.A.experts / c.A.ep) != rc.ep) return 0;
-        const int64_t item = g0 + (int64_t)rc.tp * c.A.ddp + (x.group ? rc.edp : rc.ddp);
-        sa = c.sbase[item];
-        sb = c.sbase[item + 1];
+        const int64_t slot_tp = u / c.A.ddp, slot_d = u - slot_tp * c.A.ddp;
+        if (slot_tp != rc.tp || (slot_d != rc.ddp && slot_d != rc.edp)) return 0;
     }
+    const vps_piece dp = c.DP[d];
+    const TensorRec x = c.T[dp.tensor];
+    const int64_t it = map_group_item(c.A, dp.tensor, dp.kind) + u;
+    const int64_t sa = c.sbase[it], sb = c.sbase[it + 1];
     int n = 0;
     for (int64_t s = sa; s < sb; ++s) {
         const vps_piece sp = c.SP[s];

@@ -230,11 +230,11 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     p.layout.all_ranks = rank < 0; p.layout.wa = WA; p.layout.wb = WB;
     const PtrLayout layout = p.layout;
 
-    // (1) intersections: one item per destination piece
+    // (1) intersections: one item per (destination piece, source rank slot)
     PlanCtx pc;
     pc.A = A; pc.B = B; pc.T = ca.T; pc.SP = ca.pieces; pc.DP = cb.pieces; pc.sbase = ca.piece_base;
     pc.rank = rank;
-    const int64_t nd = cb.npieces;
+    const int64_t nd = cb.npieces * plan_slots(A);
     int64_t* cnt = be.template alloc<int64_t>(nd + 1);
     int64_t* bbase = be.template alloc<int64_t>(nd + 1);
     be.for_each(step::plan_count_boxes(), nd + 1, [=] VPS_LAMBDA(int64_t d) { cnt[d] = d < nd ? plan_item_boxes(pc, d, nullptr) : 0; });

@@ -47,7 +47,7 @@ public:
         int64_t acc = 0;
         for (int64_t i = 0; i <= n; ++i) { out[i] = acc; acc += in[i]; }
     }
-    void sort_pairs(uint64_t* keys, uint32_t* vals, int64_t n)
+    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n)
     {
         std::vector<int64_t> idx((size_t)n);
         std::iota(idx.begin(), idx.end(), 0);

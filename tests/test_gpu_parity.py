@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import COLLECTIVE_CASES, MEDIUM, SINGLE, STAGED
+from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED
 
 pytestmark = pytest.mark.gpu
 
@@ -79,3 +79,14 @@ def test_collective_intent_cases(lib, name, m, pa, pb, expect):
 def test_collective_intent_matches_bruteforce(lib, name, m, pa, pb):
     counts = parity.run_classify(lib, m, pa, pb)
     assert counts.sum() > 0
+
+
+@pytest.mark.parametrize("name,m,pa,pb", EDGE_TRANSITIONS, ids=[c[0] for c in EDGE_TRANSITIONS])
+def test_edge_transitions(lib, name, m, pa, pb):
+    out = parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=3)
+    if name == "identity":
+        assert out["moved"] == 0
+    import oracle
+    wa, wb = oracle.Config(m, pa).world, oracle.Config(m, pb).world
+    for r in sorted({0, wa - 1, wb - 1, max(wa, wb) - 1}):
+        parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, r, seed=4)

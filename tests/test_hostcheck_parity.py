@@ -164,6 +164,61 @@ def test_split_linear_range_properties(hlib):
         assert cur == v1
 
 
+def test_library_exports_every_declared_symbol():
+    """The C ABI library loads without a GPU and exports every function include/vps.h declares."""
+    import os
+    import re
+    import ctypes
+    from paper_2605_18815_amd import build as lib_build
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "vps.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(vps_[a-z_]+)\s*\(", header))
+    assert {"vps_describe_config", "vps_plan_intersections", "vps_pack", "vps_unpack", "vps_apply_transition"} <= names
+    dll = ctypes.CDLL(lib_build.library_path())
+    for n in sorted(names):
+        assert hasattr(dll, n), f"{n} is declared in include/vps.h but not exported"
+    # and the binding wraps all of them
+    from paper_2605_18815_amd.binding import Library
+    assert {"vps_" + e for e in Library.EXPORTS} == names
+
+
+def test_product_calls_fail_loudly_without_a_gpu(gpu_available):
+    """No CPU fallback: on a machine without a GPU every compute entry point reports VPS_ERR_HIP."""
+    if gpu_available:
+        pytest.skip("a GPU is present")
+    import paper_2605_18815_amd as vps
+    from paper_2605_18815_amd import binding as B
+    lib = vps.load()
+    with pytest.raises(VpsError) as e:
+        lib.describe_config(cf.TINY_GPT, P(tp=2))
+    assert e.value.code == B.ERR_HIP
+    with pytest.raises(VpsError) as e:   # argument errors are still reported first
+        lib.describe_config(cf.TINY_GPT, P(tp=3))
+    assert e.value.code == B.ERR_INDIVISIBLE
+
+
+EDGE_TRANSITIONS = [
+    ("identity", cf.TINY_GPT, P(tp=2, pp=2, dp=2), P(tp=2, pp=2, dp=2)),
+    ("world-shrinks", cf.TINY_GPT, P(tp=4, pp=2, dp=2), P(tp=2, pp=1, dp=2)),
+    ("zero-off-to-on", cf.TINY_GQA, P(tp=2, dp=3, zero=0), P(tp=2, dp=3, zero=1)),
+    ("single-rank-worlds", cf.TINY_GPT, P(), P(zero=0)),
+    ("moe-dense-only-change", cf.TINY_MOE, P(tp=1, pp=2, dp=2, ep=2), P(tp=1, pp=2, dp=1, ep=4)),
+]
+
+
+@pytest.mark.parametrize("name,m,pa,pb", EDGE_TRANSITIONS, ids=[c[0] for c in EDGE_TRANSITIONS])
+def test_edge_transitions(hlib, name, m, pa, pb):
+    """Degenerate cases: nothing moves, ranks that exist on one side only, empty peer buffers."""
+    out = parity.run_all_ranks(hlib, parity.HostMem(hlib), m, pa, pb, seed=3)
+    if name == "identity":
+        assert out["moved"] == 0 and out["stats"]["num_send_boxes"] == 0
+    import oracle
+    wa, wb = oracle.Config(m, pa).world, oracle.Config(m, pb).world
+    for r in sorted({0, wa - 1, wb - 1, max(wa, wb) - 1}):
+        parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, r, seed=4)
+
+
 def test_error_codes(hlib):
     from paper_2605_18815_amd import binding as B
     with pytest.raises(VpsError) as e:
