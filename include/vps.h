@@ -159,7 +159,10 @@ int vps_unpack(const vps_plan* plan, int32_t rank, const void* recv_buf, void* c
  *   all-ranks plan: rank = -1; src_bufs is [world_src][8], dst_bufs is [world_dst][8]; scratch
  *     holds every rank's send buffer and the exchange is done by reading the peer's segment
  *     in place.
- * VPS_ERR_SCRATCH_TOO_SMALL if scratch_bytes < scratch_needed. */
+ * VPS_ERR_SCRATCH_TOO_SMALL if scratch_bytes < scratch_needed.  A source buffer must not be
+ * passed as a destination buffer as well (checked for equal pointers only: VPS_ERR_INVALID_ARG).
+ * Calls on a single-rank plan are re-entrant; calls on an all-ranks plan share one device-side
+ * pointer table, so they must not overlap on different streams. */
 int vps_apply_transition(const vps_plan* plan, int32_t rank, const void* const* src_bufs,
                          void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
                          void* stream);
@@ -208,6 +211,7 @@ int vps_plan_classify_collectives(const vps_plan* plan, const vps_config* src, v
 
 /* ---- queries (host side, no device work unless stated) ---- */
 int vps_config_world(const vps_config* cfg, int32_t* world);
+int vps_config_num_buffers(const vps_config* cfg, int32_t rank, int32_t* n); /* always VPS_NUM_BUFFERS */
 int vps_config_num_tensors(const vps_config* cfg, int32_t* n);
 int vps_config_buffer_bytes(const vps_config* cfg, int32_t rank, int32_t buf, uint64_t* bytes);
 int vps_config_num_pieces(const vps_config* cfg, int64_t* n);

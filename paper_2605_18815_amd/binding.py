@@ -97,6 +97,7 @@ class Library:
             "apply_transition": [vp, i32, P(vp), P(vp), vp, u64, vp],
             "config_world": [vp, P(i32)],
             "config_num_tensors": [vp, P(i32)],
+            "config_num_buffers": [vp, i32, P(i32)],
             "config_buffer_bytes": [vp, i32, i32, P(u64)],
             "config_num_pieces": [vp, P(i64)],
             "config_get_pieces": [vp, vp, i64],
@@ -131,7 +132,7 @@ class Library:
         self._fn["last_error"] = f
 
     EXPORTS = ("describe_config", "plan_intersections", "pack", "unpack", "apply_transition",
-               "config_world", "config_num_tensors", "config_buffer_bytes", "config_num_pieces",
+               "config_world", "config_num_tensors", "config_num_buffers", "config_buffer_bytes", "config_num_pieces",
                "config_get_pieces", "plan_pair_bytes", "plan_peer_bytes", "plan_buffer_bytes",
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
                "set_tile_bytes", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
@@ -205,6 +206,11 @@ class Config:
     def num_tensors(self):
         v = C.c_int32()
         self._lib._check(self._lib._fn["config_num_tensors"](self._h, C.byref(v)))
+        return v.value
+
+    def num_buffers(self, rank):
+        v = C.c_int32()
+        self._lib._check(self._lib._fn["config_num_buffers"](self._h, rank, C.byref(v)))
         return v.value
 
     def buffer_bytes(self, rank, buf):

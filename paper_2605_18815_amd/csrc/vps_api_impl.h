@@ -296,6 +296,13 @@ int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* con
     const vps::PtrLayout& L = p.layout;
     std::vector<void*> ptrs((size_t)vps::num_slots(L), nullptr);
     const int64_t n = p.nboxes;
+    {
+        const size_t ns = (size_t)(p.rank >= 0 ? 1 : p.A.world) * 8, nd = (size_t)(p.rank >= 0 ? 1 : p.B.world) * 8;
+        for (size_t i = 0; i < ns; ++i)
+            for (size_t j = 0; j < nd; ++j)
+                if (src_bufs[i] && src_bufs[i] == dst_bufs[j])
+                    return vps::fail(VPS_ERR_INVALID_ARG, "a source buffer is also passed as a destination buffer");
+    }
     VPS_BACKEND be(stream);
     if (p.rank >= 0) {
         for (int b = 0; b < 8; ++b) {
@@ -327,6 +334,14 @@ int VPS_FN(config_world)(const vps_config* c, int32_t* world)
 {
     if (!c || !world) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
     *world = c->d.P.world;
+    return VPS_OK;
+}
+
+int VPS_FN(config_num_buffers)(const vps_config* c, int32_t rank, int32_t* n)
+{
+    if (!c || !n) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    if (rank < 0 || rank >= c->d.P.world) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
+    *n = VPS_NUM_BUFFERS;
     return VPS_OK;
 }
 

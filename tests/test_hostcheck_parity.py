@@ -257,6 +257,11 @@ def test_error_codes(hlib):
     with pytest.raises(VpsError) as e:
         hlib.apply_transition(plan, 2, bufs, bufs, 0, 0)
     assert e.value.code == B.ERR_RANK_RANGE
+    big = mem.alloc(info["scratch_needed"])
+    with pytest.raises(VpsError) as e:   # source passed as destination as well
+        hlib.apply_transition(plan, 1, bufs, bufs, mem.ptr(big), info["scratch_needed"])
+    assert e.value.code == B.ERR_INVALID_ARG
+    assert ca.num_buffers(0) == 8
     with pytest.raises(VpsError) as e:
         hlib.pack(plan, 1, [0] * 8, mem.ptr(mem.alloc(info["send_total"])))
     assert e.value.code == B.ERR_INVALID_ARG
