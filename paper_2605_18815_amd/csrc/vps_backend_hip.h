@@ -212,15 +212,16 @@ public:
     // Stable ascending sort of (key, value) pairs.  The arrays are passed by reference: after the
     // call they point at the sorted data (the sort ping-pongs between the inputs and two
     // scratch arrays instead of copying back).
-    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n)
+    // Only the low `bits` bits of the keys are significant.
+    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n, int bits = 64)
     {
         if (n <= 1) return;
         uint64_t* k2 = alloc<uint64_t>(n);
         uint32_t* v2 = alloc<uint32_t>(n);
         size_t tmp_bytes = 0;
-        VPS_HIP_CHECK(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, 64, stream_));
+        VPS_HIP_CHECK(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, (unsigned)bits, stream_));
         void* tmp = alloc<char>((int64_t)tmp_bytes);
-        VPS_HIP_CHECK(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, 64, stream_));
+        VPS_HIP_CHECK(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, (unsigned)bits, stream_));
         free(tmp); free(keys); free(vals);
         keys = k2; vals = v2;
     }

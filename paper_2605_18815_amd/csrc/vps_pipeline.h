@@ -78,7 +78,15 @@ struct ConfigData {
     int64_t npieces = 0;
     // host copies
     std::vector<ClassRec> hC;
+    std::vector<uint64_t> tensor_numel_max;  // one entry: elements of the largest logical tensor
 };
+
+inline int bits_for(uint64_t max_value_exclusive)
+{
+    int b = 1;
+    while (b < 64 && (1ull << b) < max_value_exclusive) ++b;
+    return b;
+}
 
 struct PlanData {
     ParConst A, B;
@@ -135,6 +143,11 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     c.TL = be.template alloc<TensorLayout>(nt);
     c.C = be.template alloc<ClassRec>(P.ncls);
     be.upload(c.T, inv.data(), sizeof(TensorRec) * (size_t)nt);
+    {
+        uint64_t mx = 1;
+        for (const TensorRec& x : inv) mx = numel4(x.shape) > mx ? numel4(x.shape) : mx;
+        c.tensor_numel_max.assign(1, mx);
+    }
 
     // (1) class and shard length of every tensor; sort keys in flat-buffer order
     uint64_t* key = be.template alloc<uint64_t>(nt);
@@ -157,7 +170,7 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
         });
     }
     // (2) group the tensors by class, keeping flat order inside a class
-    be.sort_pairs(key, val, nt);
+    be.sort_pairs(key, val, nt, bits_for((uint64_t)P.ncls));
     {
         const TensorLayout* TL = c.TL;
         be.for_each(step::map_shard_lengths(), nt + 1, [=] VPS_LAMBDA(int64_t k) { len[k] = k < nt ? (int64_t)TL[val[k]].shard_len : 0; });
@@ -255,14 +268,18 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     uint32_t* by_lo = be.template alloc<uint32_t>(n);
     uint32_t* ord_s = be.template alloc<uint32_t>(n);
     uint32_t* ord_r = be.template alloc<uint32_t>(n);
+    // bits of the largest lo-corner key: the largest tensor of the model
+    uint64_t max_numel = 1;
+    for (const uint64_t v : ca.tensor_numel_max) max_numel = v > max_numel ? v : max_numel;
+    const int lo_bits = bits_for(max_numel);
     {
         const TensorRec* T = ca.T;
         be.for_each(step::plan_key_lo(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); by_lo[k] = (uint32_t)k; });
-        be.sort_pairs(kmin, by_lo, n);
+        be.sort_pairs(kmin, by_lo, n, lo_bits);
         be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], false); });
-        be.sort_pairs(kmaj, ord_s, n);
+        be.sort_pairs(kmaj, ord_s, n, 58);
         be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], true); });
-        be.sort_pairs(kmaj, ord_r, n);
+        be.sort_pairs(kmaj, ord_r, n, 58);
     }
     be.free(kmin); be.free(kmaj); be.free(by_lo);
 
@@ -553,7 +570,7 @@ void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_
         key[k] = op << 32 | (uint32_t)d_stage[d_pair[d - n]];
         idx[k] = (uint32_t)k;
     });
-    be.sort_pairs(key, idx, nmove);
+    be.sort_pairs(key, idx, nmove, 33);
     // exchange tiles: every segment cut into tile_bytes pieces, stages ascending
     std::vector<int64_t> seg_tile_base;
     std::vector<uint64_t> seg_src, seg_dst, seg_len;

@@ -47,8 +47,10 @@ public:
         int64_t acc = 0;
         for (int64_t i = 0; i <= n; ++i) { out[i] = acc; acc += in[i]; }
     }
-    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n)
+    void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n, int bits = 64)
     {
+        for (int64_t i = 0; bits < 64 && i < n; ++i)
+            if (keys[i] >> bits) { fprintf(stderr, "sort key wider than %d bits\n", bits); abort(); }
         std::vector<int64_t> idx((size_t)n);
         std::iota(idx.begin(), idx.end(), 0);
         std::stable_sort(idx.begin(), idx.end(), [&](int64_t a, int64_t b) { return keys[a] < keys[b]; });
