@@ -404,9 +404,11 @@ struct CopyDesc {
     uint32_t es;          // element bytes
     uint64_t alt_src_byte;
     uint32_t mode;
-    uint32_t rows_per_tile;  // RUN short rows: rows per tile.  ELEM: elements per tile
-    uint32_t vec_window;     // RUN: aligned 16-byte vectors per row handled by one tile
-    uint32_t chunks_per_row; // RUN long rows: tiles per row (0 = short-row tiling)
+    uint32_t rows_per_tile;  // RUN, short runs: runs per tile.  ELEM: elements per tile
+    uint32_t vec_window;     // RUN: 16-byte destination vectors of a run that one tile covers.
+                             // XPOSE: number of blocks along axis 3
+    uint32_t chunks_per_row; // RUN, long runs: tiles per run (0 = short-run tiling).
+                             // XPOSE: number of blocks along axis xa
     uint32_t ntiles;
     uint32_t xa;             // XPOSE: the collapsed axis (0..2) that is contiguous in the source
 };
@@ -517,6 +519,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         d.mode = MODE_RUN;
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
         const uint64_t rows = vol / d.ext[3];
+        if (rows >= (1ull << 31)) { d.ntiles = clamp_tiles(rows); return; }  // run index is 32-bit
         const uint64_t nv_max = (run_bytes + 30) / 16;  // aligned vectors a run can touch
         const uint64_t vt = tile_bytes / 16;
         if (nv_max > vt) {
