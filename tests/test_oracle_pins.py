@@ -47,6 +47,20 @@ TRANSITIONS = [
 ]
 
 
+def _golden():
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = [x.strip() for x in line.split("=")]
+            vals[k] = float(v)
+    return vals
+
+
+GOLD = _golden()
+
+
 # ----------------------------------------------------------------------------- inventory
 
 def _closed_form_params(m):
@@ -78,7 +92,7 @@ def test_70b_replica_state_is_about_1p26_tb():
     # (2 B param + 4 B grad + 4 B master + 4 B m + 4 B v per parameter).
     w = cf.WORKLOADS["gqa70b"]
     n = oracle.Config(w["model"], w["src"]).total_params
-    assert abs(n * 18 / 1.26e12 - 1) < 0.01
+    assert abs(n * GOLD["replica_state_bytes_per_param"] / (GOLD["replica_state_70b_tb"] * 1e12) - 1) < 0.01
     # Without gradients (collected before a switch) the migrated state is 14 B per parameter:
     a = oracle.Config(w["model"], w["src"])
     tot = 0
@@ -371,10 +385,13 @@ def test_figure4_worked_example_rank3():
     of stage 1, sends the third quarter of stage 1 to rank 2 and receives the last quarter of
     stage 0 from rank 1."""
     m = cf.model(cf.FAMILY_GPT, 4, 8, 4, 4, 2, 16, 16)
-    a, b = oracle.Config(m, P(tp=2, pp=2, zero=0)), oracle.Config(m, P(tp=4, pp=1, zero=0))
+    g = {k[8:]: int(v) for k, v in GOLD.items() if k.startswith("figure4_")}
+    a = oracle.Config(m, P(tp=g["src_tp"], pp=g["src_pp"], zero=0))
+    b = oracle.Config(m, P(tp=g["dst_tp"], pp=g["dst_pp"], zero=0))
+    assert g["rank"] == 3
     sharded = lambda t: a.tensor_info(t)["tp_axis"] >= 0
-    srcs, dsts = _peers(a, b, 3, sharded)
-    assert srcs == {1, 3} and dsts == {2, 3}
+    srcs, dsts = _peers(a, b, g["rank"], sharded)
+    assert srcs == {g["receives_from"], g["rank"]} and dsts == {g["sends_to"], g["rank"]}
     rb = oracle.route_bytes(a, b, 3)
     assert rb[3] > 0 and rb[1] > 0 and oracle.send_bytes(a, b, 3)[2] > 0
     # the retained sharded part is exactly the stage-1 share of rank 3's new quarter
