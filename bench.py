@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
+    ap.add_argument("--only", choices=["pack", "unpack"], default=None,
+                    help="time vps_pack or vps_unpack alone (implies --apply-only)")
     ap.add_argument("--staged-mib", type=int, default=0,
                     help="all-ranks workloads: exchange in XOR step order under this per-rank buffer budget (MiB)")
     ap.add_argument("--src", default="", help="override source layout fields, e.g. flat_order=1")
@@ -84,6 +86,10 @@ def main():
     if rank < 0:
         payload = 2 * info["send_total"] + info["retain_total"]   # every byte is packed and unpacked here
     bytes_moved = 2 * payload
+    if args.only:
+        assert rank >= 0, "--only needs a single-rank workload"
+        args.apply_only = True
+        bytes_moved = 2 * (info["send_total"] if args.only == "pack" else info["recv_total"])
     stage = None
     if args.staged_mib:
         assert rank < 0, "--staged-mib needs a workload with all ranks resident"
@@ -113,7 +119,12 @@ def main():
             if k is not None:
                 ev[k][1].record()
             return (p, stg)
-        lib.apply_transition(p, rank, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
+        if args.only == "pack":
+            lib.pack(p, rank, sp, scratch.data_ptr(), stream)
+        elif args.only == "unpack":
+            lib.unpack(p, rank, scratch.data_ptr() + info["recv_offset"], dp, stream)
+        else:
+            lib.apply_transition(p, rank, sp, dp, scratch.data_ptr(), scratch.numel(), stream)
         if k is not None:
             ev[k][1].record()
         return p
@@ -177,7 +188,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u16+u32", "data": "synthetic",
         "config": {"workload": f"{args.workload} rank {rank}" if rank >= 0 else f"{args.workload} all ranks",
-                   "src": pa, "dst": pb, "step": "apply only" if args.apply_only else "describe x2 + plan + apply",
+                   "src": pa, "dst": pb, "step": (args.only + " only") if args.only else ("apply only" if args.apply_only else "describe x2 + plan + apply"),
                    "tile_bytes": args.tile_bytes or 8192},
         "breakdown_ms": {"describe_x2": _avg(t_desc), "plan": _avg(t_plan), "apply_kernels": apply_avg},
         "apply_gbps": bytes_moved / (apply_avg * 1e-3) / 1e9,

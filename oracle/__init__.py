@@ -31,7 +31,8 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.build()
+    # ORACLE_LIB lets the mutation test of the pins load a deliberately broken build
+    path = os.environ.get("ORACLE_LIB") or _build.build()
     L = C.CDLL(path)
     vp, i32, u64, u32, i64 = C.c_void_p, C.c_int32, C.c_uint64, C.c_uint32, C.c_int64
     pi32, pu64, pi64 = C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_int64)
