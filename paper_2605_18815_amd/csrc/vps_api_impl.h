@@ -264,13 +264,13 @@ int VPS_FN(plan_buffer_bytes)(const vps_plan* plan, int32_t rank, uint64_t* send
     if (rank >= 0) {
         s = p.send_base[(size_t)rank + 1] - p.send_base[(size_t)rank];
         r = p.recv_base[(size_t)rank + 1] - p.recv_base[(size_t)rank];
-        if (rank < p.A.world && rank < p.B.world) k = p.pair_bytes[(size_t)rank * (size_t)p.B.world + (size_t)rank];
+        k = vps::plan_pair_bytes(p, rank, rank);
         roff = (s + 255) & ~255ull;
         need = roff + r;
     } else {
         s = p.send_base[(size_t)W];
         r = p.recv_base[(size_t)W];
-        for (int32_t q = 0; q < p.A.world && q < p.B.world; ++q) k += p.pair_bytes[(size_t)q * (size_t)p.B.world + (size_t)q];
+        for (int32_t q = 0; q < p.A.world && q < p.B.world; ++q) k += vps::plan_pair_bytes(p, q, q);
         need = s;
     }
     if (send_total) *send_total = s;
@@ -385,7 +385,7 @@ int VPS_FN(plan_pair_bytes)(const vps_plan* plan, int32_t src_rank, int32_t dst_
     const vps::PlanData& p = plan->d;
     if (src_rank < 0 || src_rank >= p.A.world || dst_rank < 0 || dst_rank >= p.B.world)
         return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
-    *bytes = p.pair_bytes[(size_t)src_rank * (size_t)p.B.world + (size_t)dst_rank];
+    *bytes = vps::plan_pair_bytes(p, src_rank, dst_rank);
     return VPS_OK;
 }
 
@@ -396,8 +396,8 @@ int VPS_FN(plan_peer_bytes)(const vps_plan* plan, int32_t rank, int32_t peer, ui
     const int32_t W = p.A.world > p.B.world ? p.A.world : p.B.world;
     if (rank < 0 || rank >= W || peer < 0 || peer >= W) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside both worlds");
     uint64_t s = 0, r = 0;
-    if (rank < p.A.world && peer < p.B.world) s = p.pair_bytes[(size_t)rank * (size_t)p.B.world + (size_t)peer];
-    if (peer < p.A.world && rank < p.B.world) r = p.pair_bytes[(size_t)peer * (size_t)p.B.world + (size_t)rank];
+    s = vps::plan_pair_bytes(p, rank, peer);
+    r = vps::plan_pair_bytes(p, peer, rank);
     if (send) *send = s;
     if (recv) *recv = r;
     return VPS_OK;

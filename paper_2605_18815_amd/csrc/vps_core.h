@@ -243,7 +243,7 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
 }
 
 // ------------------------------------------------------------------------------------------
-// Planner: one item per (destination piece, source rank slot) of the same (tensor, kind).
+// Planner: one item per (destination piece, distinct piece of source data).
 // ------------------------------------------------------------------------------------------
 
 // The source rank selected for destination rank j among the ranks that hold the same data as
@@ -252,6 +252,11 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
 // node if any, else all; in ascending rank order take index (data-parallel index of j under
 // the destination configuration) modulo count.  Section 4.3 asks for a proximity-based choice;
 // the tie-break is a convention of this library.
+VPS_HD int64_t floor_div(int64_t a, int64_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
+
+// Evaluated in closed form: the candidates form a grid (tp range x data-parallel range) whose
+// ranks are, for every data-parallel index, one run of consecutive integers; a node is an
+// interval of ranks, so only the few runs that can touch the node are looked at.
 VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const TensorRec& x,
                                   int32_t kind, int32_t i, int32_t j)
 {
@@ -261,30 +266,47 @@ VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const Te
     const int32_t di = x.group ? ci.edp : ci.ddp;
     const int32_t t0 = x.tp_axis < 0 ? 0 : ci.tp, t1 = x.tp_axis < 0 ? A.tp : ci.tp + 1;
     const int32_t d0 = sharded ? di : 0, d1 = sharded ? di + 1 : D;
-    const int32_t node = j / A.gpn;
-    int32_t n_all = 0, n_node = 0;
-    for (int32_t d = d0; d < d1; ++d) {
-        const int32_t ddp = x.group ? ci.ep + A.ep * d : d;
-        for (int32_t tp = t0; tp < t1; ++tp) {
-            const int32_t r = encode_rank(A, tp, ddp, ci.pp);
-            if (r == j) return j;
-            ++n_all;
-            if (r / A.gpn == node) ++n_node;
-        }
+    // (1) the destination rank itself, if it is one of the candidates
+    if (j < A.world) {
+        const RankCoord cj = decode_rank(A, j);
+        const int32_t dj = x.group ? cj.edp : cj.ddp;
+        if (cj.pp == ci.pp && cj.tp >= t0 && cj.tp < t1 && dj >= d0 && dj < d1 && (!x.group || cj.ep == ci.ep))
+            return j;
     }
-    const RankCoord cj = decode_rank(B, j);
-    const int32_t dpj = x.group ? cj.edp : cj.ddp;
-    const bool local = n_node > 0;
-    int32_t want = dpj % (local ? n_node : n_all);
-    for (int32_t d = d0; d < d1; ++d) {
-        const int32_t ddp = x.group ? ci.ep + A.ep * d : d;
-        for (int32_t tp = t0; tp < t1; ++tp) {
-            const int32_t r = encode_rank(A, tp, ddp, ci.pp);
-            if (local && r / A.gpn != node) continue;
-            if (want-- == 0) return r;
-        }
+    const RankCoord cb = decode_rank(B, j);
+    const int32_t dpj = x.group ? cb.edp : cb.ddp;
+    const int32_t nt = t1 - t0;
+    // (2) candidates on j's node.  Row q = ddp + DDP*pp holds the ranks TP*q + tp.
+    const int64_t n0 = (int64_t)(j / A.gpn) * A.gpn, n1 = n0 + A.gpn;
+    const int64_t step = x.group ? A.ep : 1;                       // rows of consecutive candidates
+    const int64_t qfirst = (x.group ? ci.ep + (int64_t)A.ep * d0 : d0) + (int64_t)A.ddp * ci.pp;
+    const int64_t qlast = qfirst + step * (d1 - d0 - 1);
+    int64_t qlo = floor_div(n0 - t1, A.tp) + 1, qhi = floor_div(n1 - t0 - 1, A.tp);
+    if (qlo < qfirst) qlo = qfirst;
+    if (qhi > qlast) qhi = qlast;
+    // align qlo up to a candidate row
+    if (qlo > qfirst) qlo = qfirst + (qlo - qfirst + step - 1) / step * step;
+    int64_t n_node = 0;
+    for (int64_t q = qlo; q <= qhi; q += step) {
+        const int64_t lo = A.tp * q + t0 > n0 ? A.tp * q + t0 : n0;
+        const int64_t hi = A.tp * q + t1 < n1 ? A.tp * q + t1 : n1;
+        if (hi > lo) n_node += hi - lo;
     }
-    return -1;
+    if (n_node > 0) {
+        int64_t want = dpj % n_node;
+        for (int64_t q = qlo; q <= qhi; q += step) {
+            const int64_t lo = A.tp * q + t0 > n0 ? A.tp * q + t0 : n0;
+            const int64_t hi = A.tp * q + t1 < n1 ? A.tp * q + t1 : n1;
+            if (hi <= lo) continue;
+            if (want < hi - lo) return (int32_t)(lo + want);
+            want -= hi - lo;
+        }
+        return -1;
+    }
+    // (3) no candidate on the node: index into all of them, ascending
+    const int64_t want = dpj % ((int64_t)nt * (d1 - d0));
+    const int64_t q = qfirst + step * (want / nt);
+    return (int32_t)(A.tp * q + t0 + want % nt);
 }
 
 struct PlanCtx {
@@ -296,32 +318,35 @@ struct PlanCtx {
     int32_t rank;              // planned rank or -1
 };
 
-// One item per (destination piece, source mapper slot): slot u of the piece's (tensor, kind)
-// is the source item of tp index u / DDP and data-parallel index u % DDP, i.e. the pieces of one
-// source rank.  Items are ordered destination-piece major, so emitted boxes keep the order
-// (destination piece, source piece).
-VPS_HD int64_t plan_slots(const ParConst& A) { return (int64_t)A.tp * A.ddp; }
-
-VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t item, vps_box* out)
+// Destination piece d is paired with every distinct piece of source data of its (tensor, kind):
+// one slot per source tp index if the tensor is TP-sharded, times one slot per source
+// data-parallel index if the kind is ZeRO-sharded.  Replicas are not enumerated: the rank that
+// serves a slot is computed from the selection rule.
+VPS_HD int32_t plan_piece_slots(const ParConst& A, const TensorRec& x, int32_t kind)
 {
-    const int64_t U = plan_slots(c.A);
-    const int64_t d = item / U, u = item - d * U;
-    const int32_t drank = c.DP[d].rank;
-    if (c.rank >= 0 && drank != c.rank) {
-        // a piece of another destination rank can only pair with pieces of the planned rank
-        if (c.rank >= c.A.world) return 0;
-        const RankCoord rc = decode_rank(c.A, c.rank);
-        const int64_t slot_tp = u / c.A.ddp, slot_d = u - slot_tp * c.A.ddp;
-        if (slot_tp != rc.tp || (slot_d != rc.ddp && slot_d != rc.edp)) return 0;
-    }
+    const int32_t nt = x.tp_axis < 0 ? 1 : A.tp;
+    const int32_t nd = (A.zero == 1 && kind != 0) ? (x.group ? A.dp : A.ddp) : 1;
+    return nt * nd;
+}
+
+VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t d, int32_t u, vps_box* out)
+{
     const vps_piece dp = c.DP[d];
     const TensorRec x = c.T[dp.tensor];
-    const int64_t it = map_group_item(c.A, dp.tensor, dp.kind) + u;
+    const ParConst& A = c.A;
+    const int32_t nd = (A.zero == 1 && dp.kind != 0) ? (x.group ? A.dp : A.ddp) : 1;
+    const int32_t tp_rep = x.tp_axis < 0 ? 0 : u / nd, d_rep = u % nd;
+    const int32_t pp = stage_of_layer(A, x.layer);
+    const int32_t ddp_rep = x.group ? x.expert / (A.experts / A.ep) + A.ep * d_rep : d_rep;
+    const int32_t src = select_source_rank(A, c.B, x, dp.kind, encode_rank(A, tp_rep, ddp_rep, pp), dp.rank);
+    if (c.rank >= 0 && dp.rank != c.rank && src != c.rank) return 0;
+    // the pieces of the serving rank are those of one mapper item
+    const RankCoord cs = decode_rank(A, src);
+    const int64_t it = map_group_item(A, dp.tensor, dp.kind) + (int64_t)cs.tp * A.ddp + (x.group ? cs.edp : cs.ddp);
     const int64_t sa = c.sbase[it], sb = c.sbase[it + 1];
     int n = 0;
     for (int64_t s = sa; s < sb; ++s) {
         const vps_piece sp = c.SP[s];
-        if (c.rank >= 0 && sp.rank != c.rank && dp.rank != c.rank) continue;
         int32_t lo[4], ext[4];
         bool empty = false;
         for (int a = 0; a < 4; ++a) {
@@ -332,7 +357,6 @@ VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t item, vps_box* out)
             lo[a] = l; ext[a] = h - l;
         }
         if (empty) continue;
-        if (select_source_rank(c.A, c.B, x, dp.kind, sp.rank, dp.rank) != sp.rank) continue;
         if (out) {
             vps_box& b = out[n];
             b.tensor = dp.tensor; b.kind = dp.kind;

@@ -40,6 +40,7 @@ struct map_class_lengths {};
 struct map_tensor_offsets {};
 struct map_count_pieces {};
 struct map_emit_pieces {};
+struct plan_piece_slots {};
 struct plan_count_boxes {};
 struct plan_emit_boxes {};
 struct plan_key_lo {};
@@ -105,7 +106,8 @@ struct PlanData {
     std::vector<int64_t> tile_base;          // 3*nboxes + 1
     std::vector<int64_t> first_send, first_recv;  // per rank: first box index, W+1 long
     std::vector<uint64_t> send_base, recv_base;   // per rank: offset of its buffer, W+1 long
-    std::vector<uint64_t> pair_bytes;             // [src*WB + dst]
+    std::vector<uint64_t> pair_bytes;             // all ranks: [src*WB + dst]; one rank r:
+                                                  // [src] = src -> r for src < WA, [WA + dst] = r -> dst
     std::vector<void*> host_ptrs;                 // staging for the pointer table
     vps_plan_stats_t stats;
 };
@@ -243,24 +245,43 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     p.layout.all_ranks = rank < 0; p.layout.wa = WA; p.layout.wb = WB;
     const PtrLayout layout = p.layout;
 
-    // (1) intersections: one item per (destination piece, source rank slot)
+    // (1) intersections: one item per (destination piece, distinct piece of source data)
     PlanCtx pc;
     pc.A = A; pc.B = B; pc.T = ca.T; pc.SP = ca.pieces; pc.DP = cb.pieces; pc.sbase = ca.piece_base;
     pc.rank = rank;
-    const int64_t nd = cb.npieces * plan_slots(A);
+    const int64_t npb = cb.npieces;
+    int64_t* nslot = be.template alloc<int64_t>(npb + 1);
+    int64_t* slot0 = be.template alloc<int64_t>(npb + 1);
+    {
+        const vps_piece* DPp = cb.pieces; const TensorRec* T = ca.T;
+        be.for_each(step::plan_piece_slots(), npb + 1, [=] VPS_LAMBDA(int64_t d) {
+            nslot[d] = d < npb ? plan_piece_slots(A, T[DPp[d].tensor], DPp[d].kind) : 0;
+        });
+    }
+    be.exclusive_scan(nslot, slot0, npb);
+    int64_t nd = 0;
+    be.download(&nd, slot0 + npb, sizeof(int64_t));
+    if (nd >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 piece pairs to examine" };
     int64_t* cnt = be.template alloc<int64_t>(nd + 1);
     int64_t* bbase = be.template alloc<int64_t>(nd + 1);
-    be.for_each(step::plan_count_boxes(), nd + 1, [=] VPS_LAMBDA(int64_t d) { cnt[d] = d < nd ? plan_item_boxes(pc, d, nullptr) : 0; });
+    be.for_each(step::plan_count_boxes(), nd + 1, [=] VPS_LAMBDA(int64_t i) {
+        if (i == nd) { cnt[i] = 0; return; }
+        const int64_t d = upper_bound_idx(slot0, npb + 1, i) - 1;
+        cnt[i] = plan_item_boxes(pc, d, (int32_t)(i - slot0[d]), nullptr);
+    });
     be.exclusive_scan(cnt, bbase, nd);
     int64_t n = 0;
     be.download(&n, bbase + nd, sizeof(int64_t));
     if (n >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 boxes" };
     p.nboxes = n;
     vps_box* boxes = be.template alloc<vps_box>(n);
-    be.for_each(step::plan_emit_boxes(), nd, [=] VPS_LAMBDA(int64_t d) {
-        if (bbase[d + 1] > bbase[d]) plan_item_boxes(pc, d, boxes + bbase[d]);
+    be.for_each(step::plan_emit_boxes(), nd, [=] VPS_LAMBDA(int64_t i) {
+        if (bbase[i + 1] > bbase[i]) {
+            const int64_t d = upper_bound_idx(slot0, npb + 1, i) - 1;
+            plan_item_boxes(pc, d, (int32_t)(i - slot0[d]), boxes + bbase[i]);
+        }
     });
-    be.free(cnt); be.free(bbase);
+    be.free(cnt); be.free(bbase); be.free(nslot); be.free(slot0);
 
     // (2) order: by lo corner first, then stably by (owner rank, peer, kind order, tensor)
     uint64_t* kmin = be.template alloc<uint64_t>(n);
@@ -318,14 +339,21 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     be.free(sz); be.free(pos); be.free(owner); be.free(first); be.free(rbase);
 
     // (4) payload bytes per (source, destination) pair
-    uint64_t* pairs = be.template alloc<uint64_t>((int64_t)WA * WB);
-    be.zero(pairs, sizeof(uint64_t) * (size_t)WA * (size_t)WB);
+    // (a full matrix for all-ranks plans, one row and one column for single-rank plans)
+    if (rank < 0 && (int64_t)WA * WB > ((int64_t)1 << 26))
+        throw Error{ VPS_ERR_OOM, "an all-ranks plan of this many ranks needs a byte matrix above 512 MiB" };
+    const int64_t npairs = rank < 0 ? (int64_t)WA * WB : (int64_t)WA + WB;
+    uint64_t* pairs = be.template alloc<uint64_t>(npairs);
+    be.zero(pairs, sizeof(uint64_t) * (size_t)npairs);
     be.for_each(step::plan_pair_bytes(), n, [=] VPS_LAMBDA(int64_t k) {
         const vps_box& b = boxes[k];
-        be_atomic_add(&pairs[(int64_t)b.src_rank * WB + b.dst_rank], box_volume(b) * kind_bytes(b.kind));
+        const uint64_t bytes = box_volume(b) * kind_bytes(b.kind);
+        if (rank < 0) { be_atomic_add(&pairs[(int64_t)b.src_rank * WB + b.dst_rank], bytes); return; }
+        if (b.dst_rank == rank) be_atomic_add(&pairs[b.src_rank], bytes);
+        if (b.src_rank == rank) be_atomic_add(&pairs[WA + b.dst_rank], bytes);
     });
-    p.pair_bytes.resize((size_t)WA * (size_t)WB);
-    be.download_later(p.pair_bytes.data(), pairs, sizeof(uint64_t) * (size_t)WA * (size_t)WB);
+    p.pair_bytes.resize((size_t)npairs);
+    be.download_later(p.pair_bytes.data(), pairs, sizeof(uint64_t) * (size_t)npairs);
     be.free(pairs);
 
     // (5) copy descriptors and tile table
@@ -399,6 +427,16 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
 }
 
 // Tile range [begin, end) of operation `op` for `rank` (-1: every rank).
+// Payload bytes src -> dst known to the plan (0 for pairs outside a single-rank plan).
+inline uint64_t plan_pair_bytes(const PlanData& p, int32_t src, int32_t dst)
+{
+    if (src < 0 || dst < 0 || src >= p.A.world || dst >= p.B.world) return 0;
+    if (p.rank < 0) return p.pair_bytes[(size_t)src * (size_t)p.B.world + (size_t)dst];
+    if (dst == p.rank) return p.pair_bytes[(size_t)src];
+    if (src == p.rank) return p.pair_bytes[(size_t)p.A.world + (size_t)dst];
+    return 0;
+}
+
 inline void plan_tile_range(const PlanData& p, int op, int32_t rank, int64_t& begin, int64_t& end)
 {
     const int64_t n = p.nboxes;

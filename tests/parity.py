@@ -301,7 +301,7 @@ def synth_recv_buffer(a, boxes, rank, nbytes, seed, rank_salt):
 
 
 def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_samples=0,
-                    full_compare=True, chunk=1 << 24):
+                    full_compare=True, chunk=1 << 24, check_bytes=True):
     """One rank's share: retain + pack + unpack in one apply_transition call, peers' buffers
     synthesized from the seeded pattern."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
@@ -340,7 +340,9 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
                 if not np.array_equal(got[o:o + m], want):
                     bad = np.nonzero(got[o:o + m] != want)[0]
                     raise AssertionError(f"dst buf {buf}: {bad.size} wrong elements from offset {o + bad[0]}")
-    # byte counts seen from this rank
+    # byte counts seen from this rank (quadratic in the number of replicas: skipped for huge worlds)
+    if not check_bytes:
+        in_a = in_b = False
     if in_b:
         rb = oracle.route_bytes(a, b, rank)
         for i in range(a.world):

@@ -90,3 +90,10 @@ def test_edge_transitions(lib, name, m, pa, pb):
     wa, wb = oracle.Config(m, pa).world, oracle.Config(m, pb).world
     for r in sorted({0, wa - 1, wb - 1, max(wa, wb) - 1}):
         parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, r, seed=4)
+
+
+def test_largest_world(lib):
+    m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
+    pa, pb = cf.parallel(tp=4, pp=8, dp=1024, zero=1), cf.parallel(tp=8, pp=8, dp=512, zero=1)
+    for rank in (0, 32767, 12345):
+        parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False)

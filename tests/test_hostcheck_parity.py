@@ -219,6 +219,16 @@ def test_edge_transitions(hlib, name, m, pa, pb):
         parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, r, seed=4)
 
 
+def test_largest_world(hlib):
+    """32768 ranks on each side (the limit of the 16-bit rank fields in the sort keys)."""
+    m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
+    pa, pb = P(tp=4, pp=8, dp=1024, zero=1), P(tp=8, pp=8, dp=512, zero=1)
+    for rank in (32767, 12345):
+        parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False)
+    with pytest.raises(VpsError):
+        hlib.describe_config(m, P(tp=4, pp=8, dp=2048))
+
+
 def test_error_codes(hlib):
     from paper_2605_18815_amd import binding as B
     with pytest.raises(VpsError) as e:
