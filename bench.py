@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
     ap.add_argument("--only", choices=["pack", "unpack"], default=None,
                     help="time vps_pack or vps_unpack alone (implies --apply-only)")
+    ap.add_argument("--through-buffers", action="store_true",
+                    help="stress mode: the rank is its own peer, so the whole share is packed and unpacked")
     ap.add_argument("--staged-mib", type=int, default=0,
                     help="all-ranks workloads: exchange in XOR step order under this per-rank buffer budget (MiB)")
     ap.add_argument("--src", default="", help="override source layout fields, e.g. flat_order=1")
@@ -64,7 +66,8 @@ def main():
 
     # ---- resident state: source buffers (seeded random bytes), destination buffers, scratch
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
-    plan = lib.plan_intersections(ca, cb, rank, stream)
+    plan_flags = vps.binding.PLAN_THROUGH_BUFFERS if args.through_buffers else 0
+    plan = lib.plan_intersections_ex(ca, cb, rank, plan_flags, stream)
     info = plan.buffer_bytes(rank)
     gen = torch.Generator(device=dev)
     gen.manual_seed(cf.seed_of(args.workload))
@@ -108,7 +111,7 @@ def main():
             p = plan
         else:
             a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
-            p = lib.plan_intersections(a2, b2, rank, stream)
+            p = lib.plan_intersections_ex(a2, b2, rank, plan_flags, stream)
         stg = None
         if stage is not None:
             stg = stage if args.apply_only else lib.stage_exchange(p, args.staged_mib << 20, stream)
@@ -146,7 +149,7 @@ def main():
         ta = time.perf_counter()
         a2, b2 = lib.describe_config(model, pa), lib.describe_config(model, pb)
         tb = time.perf_counter()
-        p2 = lib.plan_intersections(a2, b2, rank, stream)
+        p2 = lib.plan_intersections_ex(a2, b2, rank, plan_flags, stream)
         tc = time.perf_counter()
         t_desc.append((tb - ta) * 1e3)
         t_plan.append((tc - tb) * 1e3)
@@ -162,14 +165,14 @@ def main():
     apply_avg = sum(apply_ms) / len(apply_ms)
 
     st = plan.stats()
-    launches = 1 if rank >= 0 else 2
+    launches = 1 if rank >= 0 and not args.through_buffers else 2
     if stage is not None:
         launches = 1 + 3 * sinfo["num_stages"]
     # HBM bytes per launch as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for this very
     # workload and tile size (profiles/); null for any other configuration
     traffic = None
     prof = os.path.join(ROOT, "profiles", f"k_copy_tiles_{args.workload}_rank{rank}_hbm_traffic.txt")
-    if os.path.exists(prof) and not (args.tile_bytes or args.src or args.dst):
+    if os.path.exists(prof) and not (args.tile_bytes or args.src or args.dst or args.through_buffers or args.only or args.staged_mib):
         for line in open(prof):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = int(line.split("=")[1])
@@ -189,6 +192,7 @@ def main():
         "dtype": "u16+u32", "data": "synthetic",
         "config": {"workload": f"{args.workload} rank {rank}" if rank >= 0 else f"{args.workload} all ranks",
                    "src": pa, "dst": pb, "step": (args.only + " only") if args.only else ("apply only" if args.apply_only else "describe x2 + plan + apply"),
+                   "through_buffers": bool(args.through_buffers),
                    "tile_bytes": args.tile_bytes or 8192},
         "breakdown_ms": {"describe_x2": _avg(t_desc), "plan": _avg(t_plan), "apply_kernels": apply_avg},
         "apply_gbps": bytes_moved / (apply_avg * 1e-3) / 1e9,

@@ -126,11 +126,19 @@ int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* pa
 int vps_plan_intersections(const vps_config* src, const vps_config* dst, int32_t rank,
                            void* stream, vps_plan** out);
 
-/* Same, with flags.  VPS_PLAN_ROUTES_ONLY builds the routed boxes, their order and the byte counts
- * but no copy descriptors and no tile table: for planning many ranks whose buffers are not
- * resident (queries work; vps_pack / vps_unpack / vps_apply_transition return
- * VPS_ERR_INVALID_ARG). */
-enum { VPS_PLAN_ROUTES_ONLY = 1 };
+/* Same, with flags.
+ * VPS_PLAN_ROUTES_ONLY builds the routed boxes, their order and the byte counts but no copy
+ * descriptors and no tile table: for planning many ranks whose buffers are not resident (queries
+ * work; vps_pack / vps_unpack / vps_apply_transition return VPS_ERR_INVALID_ARG).
+ * VPS_PLAN_THROUGH_BUFFERS treats a rank as its own peer: the data that stays on a rank (T_retain
+ * of Section 4.2.1) is packed into the rank's own segment of the send buffer and unpacked from
+ * there instead of being copied directly, so that pack and unpack each run over the whole share
+ * (a measurement mode; the destination bits are the same).  retain_total is then 0 and the
+ * rank's own segment counts in send_total / recv_total and in vps_plan_peer_segment.
+ * vps_apply_transition on a single-rank plan reads the rank's own segment out of the send region
+ * (two launches); with vps_pack / vps_unpack the caller moves that segment from the send buffer
+ * to the receive buffer like any peer's.  vps_stage_exchange refuses such a plan. */
+enum { VPS_PLAN_ROUTES_ONLY = 1, VPS_PLAN_THROUGH_BUFFERS = 2 };
 int vps_plan_intersections_ex(const vps_config* src, const vps_config* dst, int32_t rank,
                               uint32_t flags, void* stream, vps_plan** out);
 

@@ -17,6 +17,7 @@ ERR_SCRATCH_TOO_SMALL, ERR_OOM, ERR_HIP = -5, -6, -7
 NUM_BUFFERS = 8
 NO_POS = (1 << 64) - 1
 PLAN_ROUTES_ONLY = 1
+PLAN_THROUGH_BUFFERS = 2
 COLL_NONE, COLL_P2P, COLL_BROADCAST, COLL_SCATTER, COLL_GATHER = range(5)
 
 MODEL_FIELDS = ("family", "layers", "hidden", "q_heads", "kv_heads", "head_dim", "ffn", "vocab",

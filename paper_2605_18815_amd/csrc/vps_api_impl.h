@@ -27,7 +27,7 @@ inline void mark_used_slots(const PlanData& p, std::vector<uint8_t> used[3])
     const int ns = num_slots(p.layout);
     for (int op = 0; op < 3; ++op) used[op].assign((size_t)ns, 0);
     for (const vps_box& b : p.boxes_send_order) {
-        const bool retained = b.src_rank == b.dst_rank;
+        const bool retained = box_retained(b, p.through_buffers);
         const bool src_res = p.rank < 0 || b.src_rank == p.rank;
         const bool dst_res = p.rank < 0 || b.dst_rank == p.rank;
         if (retained && src_res) {
@@ -127,8 +127,10 @@ int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, 
     vps_plan* p = new vps_plan();
     VPS_BACKEND be(stream);
     try {
-        if (flags & ~(uint32_t)VPS_PLAN_ROUTES_ONLY) throw vps::Error{ VPS_ERR_INVALID_ARG, "unknown plan flag" };
-        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, (flags & VPS_PLAN_ROUTES_ONLY) != 0, p->d);
+        if (flags & ~(uint32_t)(VPS_PLAN_ROUTES_ONLY | VPS_PLAN_THROUGH_BUFFERS))
+            throw vps::Error{ VPS_ERR_INVALID_ARG, "unknown plan flag" };
+        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, (flags & VPS_PLAN_ROUTES_ONLY) != 0,
+                        (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, p->d);
         vps::mark_used_slots(p->d, p->used);
     } catch (...) {
         be.release_all();
@@ -264,13 +266,13 @@ int VPS_FN(plan_buffer_bytes)(const vps_plan* plan, int32_t rank, uint64_t* send
     if (rank >= 0) {
         s = p.send_base[(size_t)rank + 1] - p.send_base[(size_t)rank];
         r = p.recv_base[(size_t)rank + 1] - p.recv_base[(size_t)rank];
-        k = vps::plan_pair_bytes(p, rank, rank);
+        k = p.through_buffers ? 0 : vps::plan_pair_bytes(p, rank, rank);
         roff = (s + 255) & ~255ull;
         need = roff + r;
     } else {
         s = p.send_base[(size_t)W];
         r = p.recv_base[(size_t)W];
-        for (int32_t q = 0; q < p.A.world && q < p.B.world; ++q) k += vps::plan_pair_bytes(p, q, q);
+        for (int32_t q = 0; q < p.A.world && q < p.B.world && !p.through_buffers; ++q) k += vps::plan_pair_bytes(p, q, q);
         need = s;
     }
     if (send_total) *send_total = s;
@@ -314,7 +316,12 @@ int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* con
         for (int op = 0; op < 3; ++op)
             if (int rc = vps::check_used(plan, op, rank, ptrs, false)) return rc;
         // the three operations touch disjoint destinations: one launch over every tile
-        return vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(3 * n)], ptrs, 0);
+        if (!p.through_buffers)
+            return vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(3 * n)], ptrs, 0);
+        // the rank is its own peer: its segment is unpacked straight out of the send buffer, after
+        // the pack launch has written it
+        if (int rc = vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(2 * n)], ptrs, 0)) return rc;
+        return vps::launch_ops(be, plan, p.tile_base[(size_t)(2 * n)], p.tile_base[(size_t)(3 * n)], ptrs, 1);
     }
     for (int32_t q = 0; q < p.A.world; ++q) {
         for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_src(L, q, b)] = (void*)src_bufs[(size_t)q * 8 + b];
@@ -411,7 +418,7 @@ int VPS_FN(plan_peer_segment)(const vps_plan* plan, int32_t src_rank, int32_t ds
     if (src_rank < 0 || src_rank >= p.A.world || dst_rank < 0 || dst_rank >= p.B.world)
         return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
     uint64_t so = UINT64_MAX, ro = UINT64_MAX, nb = 0;
-    if (src_rank != dst_rank) {
+    if (src_rank != dst_rank || p.through_buffers) {
         // boxes are sorted by (src, dst, ...): binary search the pair's range
         const std::vector<vps_box>& bx = p.boxes_send_order;
         auto key = [](const vps_box& b) { return ((uint64_t)b.src_rank << 32) | (uint32_t)b.dst_rank; };

@@ -467,13 +467,21 @@ VPS_HD int32_t num_slots(const PtrLayout& L)
 // VPS_ERR_OOM instead of building a wrapped-around table.
 VPS_HD uint32_t clamp_tiles(uint64_t n) { return n >= (1ull << 31) ? (1u << 31) : (uint32_t)n; }
 
+// A box whose source and destination rank coincide is copied directly old-local -> new-local
+// (T_retain of Section 4.2.1), unless the plan sends everything through the peer buffers: then
+// a rank is its own peer and the box is packed and unpacked like any other.
+VPS_HD bool box_retained(const vps_box& b, bool through_buffers)
+{
+    return !through_buffers && b.src_rank == b.dst_rank;
+}
+
 // Build the copy descriptor of one box for one operation.  resident(rank) tells whether the
 // rank's buffers exist on this GPU (planned rank, or every rank for all-ranks plans); boxes
 // whose operation does not apply get ntiles = 0.
 VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t planned_rank,
-                           uint32_t tile_bytes, CopyDesc& d)
+                           bool through_buffers, uint32_t tile_bytes, CopyDesc& d)
 {
-    const bool retained = b.src_rank == b.dst_rank;
+    const bool retained = box_retained(b, through_buffers);
     const bool src_res = planned_rank < 0 || b.src_rank == planned_rank;
     const bool dst_res = planned_rank < 0 || b.dst_rank == planned_rank;
     d = CopyDesc();
@@ -502,7 +510,9 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
     } else {
         active = !retained && dst_res;
         d.src_slot = slot_recv(L, b.dst_rank);
-        d.alt_src_slot = slot_send(L, b.src_rank);
+        // the sender's segment is on this GPU when every rank is, or when the sender is the
+        // planned rank itself
+        if (L.all_ranks || b.src_rank == b.dst_rank) d.alt_src_slot = slot_send(L, b.src_rank);
         d.dst_slot = slot_dst(L, b.dst_rank, b.dst_buf);
         d.src_byte = b.recv_pos;
         d.alt_src_byte = b.send_pos;

@@ -94,6 +94,7 @@ struct PlanData {
     int32_t rank = -1;
     uint32_t tile_bytes = 0;
     bool routes_only = false;  // no copy descriptors and no tile table: queries only
+    bool through_buffers = false;  // a rank is its own peer: nothing is copied directly
     PtrLayout layout;
     int64_t nboxes = 0;
     // backend memory
@@ -231,7 +232,8 @@ inline uint64_t config_buffer_elems(const ConfigData& c, int32_t rank, int32_t b
 
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
-                uint32_t tile_bytes, bool routes_only, PlanData& p)
+                uint32_t tile_bytes, bool routes_only, bool through_buffers,
+                PlanData& p)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -242,6 +244,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     const int32_t WA = A.world, WB = B.world, W = WA > WB ? WA : WB;
     if (rank < -1 || rank >= W) throw Error{ VPS_ERR_RANK_RANGE, "rank outside both worlds" };
     p.A = A; p.B = B; p.rank = rank; p.tile_bytes = tile_bytes; p.routes_only = routes_only;
+    p.through_buffers = through_buffers;
     p.layout.all_ranks = rank < 0; p.layout.wa = WA; p.layout.wb = WB;
     const PtrLayout layout = p.layout;
 
@@ -320,7 +323,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
             owner[k] = own;
             const bool resident = rank < 0 || own == rank;
-            sz[k] = (b.src_rank != b.dst_rank && resident) ? (int64_t)box_slot_bytes(b) : 0;
+            sz[k] = (!box_retained(b, through_buffers) && resident) ? (int64_t)box_slot_bytes(b) : 0;
         });
         be.exclusive_scan(sz, pos, n);
         be.for_each(step::plan_rank_bounds(), W + 1, [=] VPS_LAMBDA(int64_t r) { first[r] = lower_bound_idx(owner, n, (int32_t)r); });
@@ -370,7 +373,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             const int64_t k = i % n;
             const vps_box& b = boxes[op == OP_UNPACK ? ord_r[k] : ord_s[k]];
             CopyDesc d;
-            make_copy_desc(b, op, layout, rank, tile_bytes, d);
+            make_copy_desc(b, op, layout, rank, through_buffers, tile_bytes, d);
             descs[i] = d;
             nt[i] = d.ntiles;
         });
@@ -415,7 +418,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     st.num_boxes = n;
     std::vector<char> peer_out((size_t)W, 0), peer_in((size_t)W, 0);
     for (const vps_box& b : p.boxes_send_order) {
-        if (b.src_rank == b.dst_rank) { st.num_retain_boxes++; continue; }
+        if (box_retained(b, through_buffers)) { st.num_retain_boxes++; continue; }
         if (rank < 0 || b.src_rank == rank) { st.num_send_boxes++; if (rank >= 0) peer_out[(size_t)b.dst_rank] = 1; }
         if (rank < 0 || b.dst_rank == rank) { st.num_recv_boxes++; if (rank >= 0) peer_in[(size_t)b.src_rank] = 1; }
     }
@@ -501,6 +504,7 @@ void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_
 {
     if (!p.layout.all_ranks) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange needs an all-ranks plan" };
     if (p.routes_only) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange needs a plan with copy tables" };
+    if (p.through_buffers) throw Error{ VPS_ERR_INVALID_ARG, "staged exchange does not take a plan in which a rank is its own peer" };
     const int32_t WA = p.A.world, WB = p.B.world, W = WA > WB ? WA : WB;
     const int64_t n = p.nboxes;
     sd.n = n;

@@ -13,6 +13,7 @@ import oracle
 from datagen import boxfill, pattern
 
 SENTINEL = 0xA5
+PLAN_THROUGH_BUFFERS = 2   # vps.h
 SENT16, SENT32 = 0xA5A5, 0xA5A5A5A5
 
 
@@ -162,7 +163,7 @@ def gather_box(buf_words, off, strides, ext):
     return buf_words[idx.ravel()]
 
 
-def validate_boxes(a, b, boxes, planned_rank, samples=0):
+def validate_boxes(a, b, boxes, planned_rank, samples=0, through=False):
     """Per-element validation of the plan by the oracle, plus exact coverage counts."""
     ints, offs = boxes_to_oracle_arrays(boxes)
     bad, first = oracle.check_boxes(a, b, ints, offs, samples=samples)
@@ -177,7 +178,11 @@ def validate_boxes(a, b, boxes, planned_rank, samples=0):
         assert got == want, f"dst rank {j}: boxes cover {got} bytes, payload is {want}"
     # inside a peer buffer boxes are 16-byte aligned, disjoint and dense in their order
     for key, pos_key in (("src_rank", "send_pos"), ("dst_rank", "recv_pos")):
-        moving = boxes[(boxes["src_rank"] != boxes["dst_rank"]) & (boxes[pos_key] != np.uint64(2**64 - 1))]
+        travels = (boxes["src_rank"] != boxes["dst_rank"]) | through
+        if not through:
+            stay = boxes[boxes["src_rank"] == boxes["dst_rank"]]
+            assert (stay[pos_key] == np.uint64(2**64 - 1)).all(), "a retained box has a buffer position"
+        moving = boxes[travels & (boxes[pos_key] != np.uint64(2**64 - 1))]
         for r in np.unique(moving[key]):
             bx = moving[moving[key] == r]
             order = np.argsort(bx[pos_key], kind="stable")
@@ -191,16 +196,17 @@ def validate_boxes(a, b, boxes, planned_rank, samples=0):
 
 # ----------------------------------------------------------------------------- all ranks resident
 
-def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_payload=True):
+def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_payload=True, through=False):
     """Every virtual rank resident: apply_transition(rank=-1), then per-rank pack / exchange /
     unpack; dst buffers, per-pair byte counts and send payloads against the oracle."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
     check_config_against_oracle(ca, a)
     check_config_against_oracle(cb, b)
-    plan = lib.plan_intersections(ca, cb, -1)
+    plan = lib.plan_intersections_ex(ca, cb, -1, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, -1)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, -1)
+    validate_boxes(a, b, boxes, -1, through=through)
+    travels = (boxes["src_rank"] != boxes["dst_rank"]) | through
 
     src_host = {(r, buf): a.fill(r, buf, seed, rank_salt, pad_word=0x3C3C3C3C) for r in range(a.world) for buf in range(8)}
     src = {k: mem.alloc(v.nbytes) for k, v in src_host.items()}
@@ -226,6 +232,10 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
 
     # (1) one call for everything
     info = plan.buffer_bytes(-1)
+    if through:
+        assert info["retain_total"] == 0
+        assert info["send_total"] >= sum(b.payload_elems(j, buf) * oracle.KIND_BYTES[buf % 4]
+                                         for j in range(b.world) for buf in range(8))
     scratch = mem.alloc(info["scratch_needed"])
     dst = fresh_dst()
     mem.register_bounds()
@@ -262,12 +272,12 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
     # pack/unpack do not perform; compare the received part box by box instead
     for j in range(b.world):
         got = {buf: mem.download(dst2[(j, buf)]).view(kind_dtype(buf)) for buf in range(8)}
-        for bx in boxes[(boxes["dst_rank"] == j) & (boxes["src_rank"] != j)]:
+        for bx in boxes[(boxes["dst_rank"] == j) & travels]:
             buf = int(bx["dst_buf"])
             g = gather_box(got[buf], bx["dst_off"], bx["dst_stride"], bx["ext"])
             w = gather_box(want[(j, buf)], bx["dst_off"], bx["dst_stride"], bx["ext"])
             assert np.array_equal(g, w), ("unpack", j, bx)
-        for bx in boxes[(boxes["dst_rank"] == j) & (boxes["src_rank"] == j)]:
+        for bx in boxes[(boxes["dst_rank"] == j) & ~travels]:
             buf = int(bx["dst_buf"])
             g = gather_box(got[buf], bx["dst_off"], bx["dst_stride"], bx["ext"])
             assert (g == (SENT16 if buf % 4 == 0 else SENT32)).all(), "unpack wrote a retained box"
@@ -276,7 +286,7 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
     if check_send_payload:
         for i in range(a.world):
             sb = mem.download(sends[i])
-            for bx in boxes[(boxes["src_rank"] == i) & (boxes["dst_rank"] != i)]:
+            for bx in boxes[(boxes["src_rank"] == i) & travels]:
                 buf = int(bx["src_buf"])
                 w = gather_box(src_host[(i, buf)], bx["src_off"], bx["src_stride"], bx["ext"])
                 pos = int(bx["send_pos"])
@@ -301,15 +311,17 @@ def synth_recv_buffer(a, boxes, rank, nbytes, seed, rank_salt):
 
 
 def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_samples=0,
-                    full_compare=True, chunk=1 << 24, check_bytes=True):
+                    full_compare=True, chunk=1 << 24, check_bytes=True, through=False):
     """One rank's share: retain + pack + unpack in one apply_transition call, peers' buffers
     synthesized from the seeded pattern."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
-    plan = lib.plan_intersections(ca, cb, rank)
+    plan = lib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
     info = plan.buffer_bytes(rank)
+    if through:
+        assert info["retain_total"] == 0 and plan.stats()["num_retain_tiles"] == 0
 
     in_a, in_b = rank < a.world, rank < b.world
     src_host, src, dst = {}, {}, {}
@@ -353,7 +365,7 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
             assert plan.pair_bytes(rank, j) == sbytes[j], (rank, j)
     # send payload
     sb = mem.download(scratch)[:info["send_total"]]
-    for bx in boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]:
+    for bx in boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]:
         buf = int(bx["src_buf"])
         w = gather_box(src_host[buf], bx["src_off"], bx["src_stride"], bx["ext"])
         pos = int(bx["send_pos"])

@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED
+from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH
 
 pytestmark = pytest.mark.gpu
 
@@ -33,6 +33,16 @@ def test_medium_shapes_all_ranks(lib, name, m, pa, pb):
 def test_single_rank_share(lib, name, rank):
     _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
     parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=0xBEEF + rank)
+
+
+@pytest.mark.parametrize("name,rank", THROUGH, ids=[f"{n}-r{r}" for n, r in THROUGH])
+def test_rank_as_its_own_peer(lib, name, rank):
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    mem = parity.GpuMem()
+    if rank < 0:
+        parity.run_all_ranks(lib, mem, m, pa, pb, seed=0xD00D, through=True)
+    else:
+        parity.run_single_rank(lib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
 
 
 def test_toy_workload_all_ranks(lib):

@@ -100,6 +100,10 @@ def test_routes_only_plan_refuses_copies(hlib):
     assert e.value.code == B.ERR_INVALID_ARG
     with pytest.raises(VpsError):
         hlib.plan_intersections_ex(ca, cb, -1, flags=8)
+    own_peer = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_THROUGH_BUFFERS)
+    with pytest.raises(VpsError) as e:
+        hlib.stage_exchange(own_peer, 1 << 20)
+    assert e.value.code == B.ERR_INVALID_ARG
 
 
 SINGLE = [
@@ -114,6 +118,22 @@ def test_single_rank_share(hlib, name, rank):
     _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
     mem = parity.HostMem(hlib)
     parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xBEEF + rank)
+
+
+THROUGH = [("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-world-grows", 3), ("moe-transposed", 3), ("moe-odd", -1),
+           ("gpt-blocked-rev", -1)]
+
+
+@pytest.mark.parametrize("name,rank", THROUGH, ids=[f"{n}-r{r}" for n, r in THROUGH])
+def test_rank_as_its_own_peer(hlib, name, rank):
+    """VPS_PLAN_THROUGH_BUFFERS: retained data travels through the rank's own segment; the
+    destination bits and the payload in the send buffer stay those of the oracle."""
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    mem = parity.HostMem(hlib)
+    if rank < 0:
+        parity.run_all_ranks(hlib, mem, m, pa, pb, seed=0xD00D, through=True)
+    else:
+        parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
 
 
 def test_toy_workload_all_ranks(hlib):
