@@ -226,7 +226,19 @@ def cpu_baseline(model, pa, pb, rank, seed, target_elems=192_000_000):
         oracle.expected(a, b, rank, buf, seed, n=n)
         nbytes += n * oracle.KIND_BYTES[buf % 4]
     dt = time.perf_counter() - t0
-    return dict(value=2 * nbytes / dt / 1e9, unit="GB/s", cores=oracle.num_threads(), kind="oracle",
+    # the same on one core, on a sixteenth of the sample
+    cores = oracle.num_threads()
+    oracle.set_num_threads(1)
+    nb1 = 0
+    t1 = time.perf_counter()
+    for buf in bufs:
+        n = min(per // 16, b.buffer_elems(rank, buf))
+        oracle.expected(a, b, rank, buf, seed, n=n)
+        nb1 += n * oracle.KIND_BYTES[buf % 4]
+    dt1 = time.perf_counter() - t1
+    oracle.set_num_threads(cores)
+    return dict(value=2 * nbytes / dt / 1e9, unit="GB/s", cores=cores, kind="oracle",
+                value_one_core=2 * nb1 / dt1 / 1e9,
                 sample=f"first {per} elements of each of the {len(bufs)} destination buffers of rank {rank} "
                        f"({nbytes} bytes) through the per-element oracle (coordinate, owners, source rule, word)",
                 seconds=dt)

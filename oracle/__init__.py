@@ -74,6 +74,8 @@ def lib():
     L.orc_check_boxes.restype = i64
     L.orc_check_boxes.argtypes = [vp, vp, pi32, pi64, i64, i32, pi64]
     L.orc_num_threads.restype = C.c_int
+    L.orc_set_num_threads.argtypes = [C.c_int]
+    L.orc_set_num_threads.restype = None
     _lib = L
     return L
 
@@ -229,3 +231,7 @@ def check_boxes(a, b, ints, offs, samples=0):
 
 def num_threads():
     return lib().orc_num_threads()
+
+
+def set_num_threads(n):
+    lib().orc_set_num_threads(int(n))

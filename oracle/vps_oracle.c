@@ -707,3 +707,13 @@ int orc_num_threads(void)
     return 1;
 #endif
 }
+
+/* Number of OpenMP threads for the calls that follow (timing with one core and with all). */
+void orc_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}

@@ -128,6 +128,7 @@ int64_t orc_check_boxes(const orc_config* a, const orc_config* b, const int32_t*
                         const int64_t* offs, int64_t nboxes, int32_t samples, int64_t* first_bad);
 
 int orc_num_threads(void);
+void orc_set_num_threads(int n);
 
 #ifdef __cplusplus
 }
