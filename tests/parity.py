@@ -48,6 +48,12 @@ class HostMem:
     def sync(self):
         pass
 
+    def equal(self, x, y):
+        return bool(np.array_equal(x, y))
+
+    def all_bytes(self, x, value):
+        return bool((x == value).all())
+
     def register_bounds(self):
         if self.lib is None:
             return
@@ -95,6 +101,12 @@ class GpuMem:
 
     def sync(self):
         self.torch.cuda.synchronize()
+
+    def equal(self, x, y):
+        return bool(self.torch.equal(x, y))
+
+    def all_bytes(self, x, value):
+        return bool((x == value).all()) if x.numel() else True
 
     def register_bounds(self):
         pass
@@ -245,6 +257,25 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
     mem.sync()
     assert mem.violations() == 0
     compare(dst, "apply_transition(all)")
+
+    # (1b) and back again: the destination state just verified is the source of the reverse
+    # transition; expected values from the oracle's element-by-element copy of that state
+    rplan = lib.plan_intersections_ex(cb, ca, -1, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(cb, ca, -1)
+    rinfo = rplan.buffer_bytes(-1)
+    rscratch = mem.alloc(rinfo["scratch_needed"])
+    back = {k: mem.alloc(v.nbytes) for k, v in src_host.items()}
+    mem.register_bounds()
+    lib.apply_transition(rplan, -1, [mem.ptr(dst[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                         [mem.ptr(back[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                         mem.ptr(rscratch), rinfo["scratch_needed"])
+    mem.sync()
+    assert mem.violations() == 0
+    for (r, buf), h in src_host.items():
+        exp = np.full(h.size, SENT16 if buf % 4 == 0 else SENT32, dtype=h.dtype)
+        oracle.transition(b, a, r, buf, want, exp)
+        got = mem.download(back[(r, buf)]).view(h.dtype)
+        assert np.array_equal(got, exp), ("reverse transition", r, buf)
+    del back, rscratch, rplan
 
     # (2) per rank: pack, exchange segment by segment, unpack
     sends = {}
@@ -467,7 +498,8 @@ def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05,
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
-def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 << 22, box_samples=16, log=print):
+def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 << 22, box_samples=16, log=print,
+                           round_trip=True):
     """Every virtual rank resident at full size: one vps_apply_transition(rank=-1) call, all
     destination buffers against the oracle (layout-B fill of the same coordinate hash)."""
     import time
@@ -515,6 +547,25 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
                     raise AssertionError(f"dst ({j},{buf}): {bad.size} wrong elements in chunk at {o}, first {o + bad[0]}")
                 checked += m
     log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
+    if round_trip:
+        # A -> B -> A gives back every payload element of every source buffer (replicas hold the
+        # same bits under the seeded pattern, so the choice of source does not show)
+        del scratch
+        rplan = lib.plan_intersections(cb, ca, -1)
+        rinfo = rplan.buffer_bytes(-1)
+        rscratch = mem.alloc(rinfo["scratch_needed"])
+        back = {k: mem.alloc(len(v)) for k, v in src.items()}
+        lib.apply_transition(rplan, -1, [mem.ptr(dst[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                             [mem.ptr(back[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                             mem.ptr(rscratch), rinfo["scratch_needed"])
+        mem.sync()
+        same = 0
+        for (r, buf), t in src.items():
+            n = a.payload_elems(r, buf) * oracle.KIND_BYTES[buf % 4]
+            assert mem.equal(back[(r, buf)][:n], t[:n]), f"round trip changed source buffer ({r},{buf})"
+            assert mem.all_bytes(back[(r, buf)][n:], SENTINEL), f"round trip wrote the padding of ({r},{buf})"
+            same += n
+        log(f"  round trip: {same} bytes identical to the source state ({time.time() - t0:.1f}s)")
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
