@@ -51,6 +51,7 @@ public:
     {
         for (int64_t i = 0; bits < 64 && i < n; ++i)
             if (keys[i] >> bits) { fprintf(stderr, "sort key wider than %d bits\n", bits); abort(); }
+        if (n <= 1) return;
         std::vector<int64_t> idx((size_t)n);
         std::iota(idx.begin(), idx.end(), 0);
         std::stable_sort(idx.begin(), idx.end(), [&](int64_t a, int64_t b) { return keys[a] < keys[b]; });

@@ -102,6 +102,12 @@ def test_edge_transitions(lib, name, m, pa, pb):
         parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, r, seed=4)
 
 
+def test_random_transitions(lib):
+    import random_cases
+    ran = sum(random_cases.run_case(lib, parity.GpuMem, c) for c in random_cases.cases(20260000, 150))
+    assert ran >= 40
+
+
 def test_largest_world(lib):
     m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
     pa, pb = cf.parallel(tp=4, pp=8, dp=1024, zero=1), cf.parallel(tp=8, pp=8, dp=512, zero=1)

@@ -239,6 +239,12 @@ def test_edge_transitions(hlib, name, m, pa, pb):
         parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, r, seed=4)
 
 
+def test_random_transitions(hlib):
+    import random_cases
+    ran = sum(random_cases.run_case(hlib, lambda: parity.HostMem(hlib), c) for c in random_cases.cases(20260000, 150))
+    assert ran >= 40   # the rest drew a degree that does not divide the model
+
+
 def test_largest_world(hlib):
     """32768 ranks on each side (the limit of the 16-bit rank fields in the sort keys)."""
     m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
