@@ -12,6 +12,10 @@
  * All mapping, planning and copying runs in HIP kernels on the current device.  The library
  * never allocates payload memory: state buffers, send/receive buffers and scratch are owned
  * by the caller (device memory), and must stay alive until the stream has executed the work.
+ * Its own tables (piece, box, descriptor and tile tables) come from a process-wide pool of
+ * device blocks on the device that is current at the call; a process uses the library with
+ * one device current throughout (handles made on one device are not usable on another).
+ * Calls are thread-safe on distinct handles; a plan may be used by one thread at a time.
  *
  * Conventions
  *   state kinds     0 = bf16 parameters (2-byte words), 1 = fp32 master weights,
