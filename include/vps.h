@@ -174,7 +174,9 @@ int vps_unpack(const vps_plan* plan, int32_t rank, const void* recv_buf, void* c
  * VPS_ERR_SCRATCH_TOO_SMALL if scratch_bytes < scratch_needed.  A source buffer must not be
  * passed as a destination buffer as well (checked for equal pointers only: VPS_ERR_INVALID_ARG).
  * Calls on a single-rank plan are re-entrant; calls on an all-ranks plan share one device-side
- * pointer table, so they must not overlap on different streams. */
+ * pointer table, so they must not overlap on different streams.  The call enqueues kernels only
+ * (no allocation, no memset, no copy engine, no synchronisation), so it may be captured into a
+ * HIP graph; the same holds for vps_pack and vps_unpack. */
 int vps_apply_transition(const vps_plan* plan, int32_t rank, const void* const* src_bufs,
                          void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
                          void* stream);

@@ -113,3 +113,53 @@ def test_largest_world(lib):
     pa, pb = cf.parallel(tp=4, pp=8, dp=1024, zero=1), cf.parallel(tp=8, pp=8, dp=512, zero=1)
     for rank in (0, 32767, 12345):
         parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False)
+
+
+@pytest.mark.parametrize("rank", [-1, 1])
+def test_apply_transition_replayed_from_a_hip_graph(lib, rank):
+    """vps_apply_transition enqueues kernels only, so it can be captured into a HIP graph.  The
+    graph is replayed several times with eager work between the replays (new source data, cleared
+    destinations); every replay must equal an eager call on the same data."""
+    import torch
+    w = cf.WORKLOADS["toy"]
+    ca, cb = lib.describe_config(w["model"], w["src"]), lib.describe_config(w["model"], w["dst"])
+    plan = lib.plan_intersections(ca, cb, rank)
+    info = plan.buffer_bytes(rank)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    ra = range(ca.world) if rank < 0 else [rank]
+    rb = range(cb.world) if rank < 0 else [rank]
+    src = [torch.empty(ca.buffer_bytes(r, b), dtype=torch.uint8, device=dev) for r in ra for b in range(8)]
+    dst = [torch.empty(cb.buffer_bytes(r, b), dtype=torch.uint8, device=dev) for r in rb for b in range(8)]
+    ref = [torch.empty_like(t) for t in dst]
+    scratch = torch.empty(info["scratch_needed"], dtype=torch.uint8, device=dev)
+    scratch_ref = torch.empty_like(scratch)
+    ptrs = lambda ts: [t.data_ptr() if t.numel() else 0 for t in ts]
+
+    def new_inputs():
+        for t in src:
+            if t.numel():
+                t.random_(0, 256, generator=gen)
+        if scratch.numel():
+            scratch.random_(0, 256, generator=gen)   # the receive part stands in for the peers' data
+            scratch_ref.copy_(scratch)
+        for t in dst + ref:
+            t.fill_(0xA5)
+
+    side = torch.cuda.Stream()
+    new_inputs()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        lib.apply_transition(plan, rank, ptrs(src), ptrs(dst), scratch.data_ptr(), scratch.numel(), side.cuda_stream)
+    for replay in range(4):
+        new_inputs()
+        torch.cuda.synchronize()
+        graph.replay()
+        lib.apply_transition(plan, rank, ptrs(src), ptrs(ref), scratch_ref.data_ptr(), scratch_ref.numel(),
+                             torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        for got, want in zip(dst, ref):
+            assert torch.equal(got, want), f"replay {replay} differs from the eager call"
+        assert any(bool((t != 0xA5).any()) for t in dst if t.numel())
