@@ -176,10 +176,28 @@ def main():
         for line in open(prof):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = int(line.split("=")[1])
+    # the practical ceiling in the same process: a plain contiguous copy in the same launch shape
+    ceil_bytes = min(bytes_moved // 2, 8 << 30) // 16 * 16
+    plain_gbps = None
+    if ceil_bytes >= (64 << 20):
+        x, y = alloc(ceil_bytes, True), alloc(ceil_bytes, False)
+        cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for k in range(-2, 10):
+            if k >= 0:
+                cev[k][0].record()
+            lib.plain_copy(y.data_ptr(), x.data_ptr(), ceil_bytes, stream)
+            if k >= 0:
+                cev[k][1].record()
+        torch.cuda.synchronize()
+        plain_ms = sum(a.elapsed_time(b) for a, b in cev) / len(cev)
+        plain_gbps = 2 * ceil_bytes / (plain_ms * 1e-3) / 1e9
+        del x, y
     roofline = dict(bound="hbm", achieved=bytes_moved / (apply_avg * 1e-3) / 1e9, peak=HBM_PEAK_GBPS,
                     unit="GB/s", frac=bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, traffic=traffic,
                     kernel="k_copy_tiles", launches_per_step=launches, kernel_ms_avg=apply_avg,
-                    kernel_ms_median=apply_ms[len(apply_ms) // 2], algorithmic_bytes_per_step=bytes_moved)
+                    kernel_ms_median=apply_ms[len(apply_ms) // 2], algorithmic_bytes_per_step=bytes_moved,
+                    plain_copy_gbps=plain_gbps,
+                    frac_of_plain_copy=(bytes_moved / (apply_avg * 1e-3) / 1e9 / plain_gbps) if plain_gbps else None)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -212,13 +230,22 @@ def _avg(v):
     return sum(v) / len(v) if v else None
 
 
-def cpu_baseline(model, pa, pb, rank, seed, target_elems=192_000_000):
+def cpu_baseline(model, pa, pb, rank, seed, target_seconds=12.0):
     """The per-element oracle on the host cores, on a bounded sample of the same rank's share:
-    the first target_elems/num_buffers offsets of every destination buffer."""
+    the first `per` offsets of every destination buffer, `per` sized from a short pilot so that
+    the sample takes about target_seconds."""
     import oracle
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     bufs = [buf for buf in range(8) if b.buffer_elems(rank, buf)]
-    per = target_elems // max(len(bufs), 1)
+    pilot = 4_000_000
+    t0 = time.perf_counter()
+    done = 0
+    for buf in bufs:
+        n = min(pilot, b.buffer_elems(rank, buf))
+        oracle.expected(a, b, rank, buf, seed, n=n)
+        done += n
+    rate = done / (time.perf_counter() - t0)
+    per = max(pilot, int(rate * target_seconds) // max(len(bufs), 1))
     nbytes = 0
     t0 = time.perf_counter()
     for buf in bufs:
@@ -239,7 +266,7 @@ def cpu_baseline(model, pa, pb, rank, seed, target_elems=192_000_000):
     oracle.set_num_threads(cores)
     return dict(value=2 * nbytes / dt / 1e9, unit="GB/s", cores=cores, kind="oracle",
                 value_one_core=2 * nb1 / dt1 / 1e9,
-                sample=f"first {per} elements of each of the {len(bufs)} destination buffers of rank {rank} "
+                sample=f"first {per} elements (or all) of each of the {len(bufs)} destination buffers of rank {rank} "
                        f"({nbytes} bytes) through the per-element oracle (coordinate, owners, source rule, word)",
                 seconds=dt)
 

@@ -260,6 +260,14 @@ const char* vps_last_error(void);
  * 4 KiB and 1 MiB; default 8 KiB).  Applies to plans created afterwards. */
 int vps_set_tile_bytes(uint32_t bytes);
 
+/* Measurement aid, not part of the paper's method: a plain contiguous device-to-device copy of
+ * `bytes` bytes in the copy engine's launch shape (one workgroup per 8 KiB, the same XCD-aware
+ * block order, 16-byte nontemporal loads and stores) without any table.  Its rate is the
+ * practical ceiling the descriptor-driven copies are compared with.  dst, src: device, 16-byte
+ * aligned, not overlapping; bytes a multiple of 16 (VPS_ERR_INVALID_ARG otherwise).
+ * Asynchronous on `stream`. */
+int vps_plain_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -110,6 +110,7 @@ class Library:
             "plan_get_boxes": [vp, vp, i64],
             "plan_stats": [vp, P(PlanStats)],
             "set_tile_bytes": [u32],
+            "plain_copy": [vp, vp, u64, vp],
             "stage_exchange": [vp, u64, vp, P(vp)],
             "plan_classify_collectives": [vp, vp, vp, P(i32), i64],
             "stage_info": [vp, P(i32), P(i32), P(u64)],
@@ -136,7 +137,7 @@ class Library:
                "config_world", "config_num_tensors", "config_num_buffers", "config_buffer_bytes", "config_num_pieces",
                "config_get_pieces", "plan_pair_bytes", "plan_peer_bytes", "plan_buffer_bytes",
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
-               "set_tile_bytes", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
+               "set_tile_bytes", "plain_copy", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
                "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy")
 
     def last_error(self):
@@ -183,6 +184,9 @@ class Library:
         self._check(self._fn["apply_transition_staged"](sp._h, _ptr_array(src_bufs, len(src_bufs)),
                                                         _ptr_array(dst_bufs, len(dst_bufs)), scratch,
                                                         scratch_bytes, stream))
+
+    def plain_copy(self, dst, src, nbytes, stream=0):
+        self._check(self._fn["plain_copy"](dst, src, nbytes, stream))
 
     def set_tile_bytes(self, n):
         self._check(self._fn["set_tile_bytes"](n))

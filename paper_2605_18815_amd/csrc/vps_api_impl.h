@@ -80,6 +80,22 @@ int VPS_FN(set_tile_bytes)(uint32_t bytes)
     return VPS_OK;
 }
 
+int VPS_FN(plain_copy)(void* dst, const void* src, uint64_t bytes, void* stream)
+{
+    if (!bytes) return VPS_OK;
+    if (!dst || !src) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t)dst | (uintptr_t)src | bytes) & 15)
+        return vps::fail(VPS_ERR_INVALID_ARG, "plain copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+    const char* s = (const char*)src;
+    const char* d = (const char*)dst;
+    if (s < d + bytes && d < s + bytes) return vps::fail(VPS_ERR_INVALID_ARG, "plain copy ranges overlap");
+    VPS_TRY
+    VPS_BACKEND be(stream);
+    be.launch_plain_copy(dst, src, bytes);
+    return VPS_OK;
+    VPS_CATCH
+}
+
 int VPS_FN(describe_config)(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
                             vps_config** out)
 {

@@ -291,6 +291,17 @@ public:
         VPS_HIP_CHECK(hipGetLastError());
     }
 
+    void launch_plain_copy(void* dst, const void* src, uint64_t bytes)
+    {
+        const uint64_t nvec = bytes / 16;
+        const uint64_t blocks = (nvec + PLAIN_TILE_VECS - 1) / PLAIN_TILE_VECS;
+        if (!blocks) return;
+        if (blocks > 0x7fffffffULL) throw Error{ VPS_ERR_INVALID_ARG, "plain copy larger than 2^31 tiles" };
+        hipLaunchKernelGGL(k_plain_copy, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
+                           (const char*)src, (char*)dst, nvec, xcd_chunk());
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
     hipStream_t stream() const { return stream_; }
 
     // Tiles per XCD run (0 = plain round-robin); VPS_XCD_CHUNK overrides it for experiments.

@@ -208,4 +208,25 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
     }
 }
 
+// A plain contiguous copy in the copy engine's launch shape (one workgroup per 8 KiB, the same
+// block -> tile remap, the same 16-byte nontemporal accesses) but with no tables at all: the
+// practical ceiling on this GPU that k_copy_tiles is measured against.  nvec 16-byte vectors.
+constexpr uint32_t PLAIN_TILE_VECS = 512;
+
+__global__ __launch_bounds__(COPY_THREADS) void k_plain_copy(const char* __restrict__ src,
+                                                             char* __restrict__ dst, uint64_t nvec,
+                                                             uint32_t xcd_chunk)
+{
+    uint32_t b = blockIdx.x;
+    if (xcd_chunk) {
+        const uint32_t x = b & 7, j = b >> 3;
+        const uint32_t grp = j / xcd_chunk;
+        if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
+    }
+    const uint64_t v0 = (uint64_t)b * PLAIN_TILE_VECS;
+    const uint32_t n = (uint32_t)(nvec - v0 < PLAIN_TILE_VECS ? nvec - v0 : PLAIN_TILE_VECS);
+    const uint64_t s = (uint64_t)(uintptr_t)src + v0 * 16, t = (uint64_t)(uintptr_t)dst + v0 * 16;
+    copy_full_vectors(s, t, 0, n, threadIdx.x, COPY_THREADS);
+}
+
 }  // namespace vps

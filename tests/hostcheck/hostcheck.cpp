@@ -69,6 +69,12 @@ public:
     void quiesce() {}
     void set_ptr_table(void** table, void* const* host_ptrs, int n) { memcpy(table, host_ptrs, sizeof(void*) * (size_t)n); }
 
+    void launch_plain_copy(void* dst, const void* src, uint64_t bytes)
+    {
+        if (!in_bounds((const char*)src, bytes) || !in_bounds((char*)dst, bytes)) { ++g_violations; return; }
+        memcpy(dst, src, bytes);
+    }
+
     // Same slot walk as the device kernel, one lane at a time, with bounds checks.
     void launch_copy(const CopyDesc* descs, const TileRef* tiles, int64_t tile0, int64_t ntiles,
                      const PtrArgs& pa, int alias_exchange)

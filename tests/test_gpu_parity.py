@@ -163,3 +163,13 @@ def test_apply_transition_replayed_from_a_hip_graph(lib, rank):
         for got, want in zip(dst, ref):
             assert torch.equal(got, want), f"replay {replay} differs from the eager call"
         assert any(bool((t != 0xA5).any()) for t in dst if t.numel())
+
+
+def test_plain_copy_reference(lib):
+    import torch
+    n = 8192 * 1000 + 4096 + 16
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.full((n + 32,), 0xA5, dtype=torch.uint8, device="cuda:0")
+    lib.plain_copy(dst.data_ptr(), src.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:n], src) and bool((dst[n:] == 0xA5).all())

@@ -255,6 +255,22 @@ def test_largest_world(hlib):
         hlib.describe_config(m, P(tp=4, pp=8, dp=2048))
 
 
+def test_plain_copy_reference(hlib):
+    from paper_2605_18815_amd import binding as B
+    mem = parity.HostMem(hlib)
+    n = 8192 * 3 + 4096 + 16       # three full tiles and a ragged one
+    src, dst = mem.alloc(n), mem.alloc(n + 32)
+    src[:] = np.random.default_rng(5).integers(0, 256, n, dtype=np.uint8)
+    mem.register_bounds()
+    hlib.plain_copy(mem.ptr(dst), mem.ptr(src), n)
+    assert mem.violations() == 0
+    assert np.array_equal(dst[:n], src) and (dst[n:] == parity.SENTINEL).all()
+    for bad in ((mem.ptr(dst) + 8, mem.ptr(src), 64), (mem.ptr(dst), mem.ptr(src), 40), (mem.ptr(src) + 16, mem.ptr(src), 64)):
+        with pytest.raises(VpsError) as e:
+            hlib.plain_copy(*bad)
+        assert e.value.code == B.ERR_INVALID_ARG
+
+
 def test_error_codes(hlib):
     from paper_2605_18815_amd import binding as B
     with pytest.raises(VpsError) as e:
