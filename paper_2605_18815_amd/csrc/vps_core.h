@@ -246,14 +246,15 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
 // Planner: one item per (destination piece, distinct piece of source data).
 // ------------------------------------------------------------------------------------------
 
+VPS_HD int64_t floor_div(int64_t a, int64_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
+
 // The source rank selected for destination rank j among the ranks that hold the same data as
 // source rank i (i's TP replicas when the tensor is TP-replicated, i's data-parallel replicas
 // when the kind is not ZeRO-sharded).  Rule: j itself if it is among them; else those on j's
 // node if any, else all; in ascending rank order take index (data-parallel index of j under
 // the destination configuration) modulo count.  Section 4.3 asks for a proximity-based choice;
 // the tie-break is a convention of this library.
-VPS_HD int64_t floor_div(int64_t a, int64_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
-
+//
 // Evaluated in closed form: the candidates form a grid (tp range x data-parallel range) whose
 // ranks are, for every data-parallel index, one run of consecutive integers; a node is an
 // interval of ranks, so only the few runs that can touch the node are looked at.
