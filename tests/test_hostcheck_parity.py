@@ -255,6 +255,62 @@ def test_largest_world(hlib):
         hlib.describe_config(m, P(tp=4, pp=8, dp=2048))
 
 
+def test_box_checker_detects_planted_mistakes(hlib):
+    """The oracle's per-element check of a box list must notice a shifted source offset, a
+    shifted destination offset, a wrong stride, a box moved in the coordinate space, and a source
+    rank that holds the data but is not the one the selection rule names."""
+    import oracle
+    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == "gpt-zero-to-replicated"][0]
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    ca, cb = hlib.describe_config(m, pa), hlib.describe_config(m, pb)
+    boxes = hlib.plan_intersections(ca, cb, -1).get_boxes()
+    assert oracle.check_boxes(a, b, *parity.boxes_to_oracle_arrays(boxes))[0] == 0
+    big = int(np.argmax(np.prod(boxes["ext"].astype(np.int64), axis=1)))
+
+    def planted(edit):
+        bad = boxes.copy()
+        edit(bad)
+        return oracle.check_boxes(a, b, *parity.boxes_to_oracle_arrays(bad))
+
+    def shift(field, k=big, by=1):
+        def edit(bx):
+            bx[field][k] += by
+        return edit
+
+    for edit in (shift("src_off"), shift("dst_off"), shift("src_off", by=-1)):
+        nbad, first = planted(edit)
+        assert nbad > 0 and first == big
+
+    def wrong_stride(bx):
+        ax = int(np.argmax(bx["ext"][big]))
+        bx["dst_stride"][big][ax] += 1
+    assert planted(wrong_stride)[0] > 0
+
+    def moved_box(bx):
+        ax = int(np.argmax(bx["ext"][big]))
+        bx["lo"][big][ax] += 1
+    assert planted(moved_box)[0] > 0
+
+    # another replica of the same data: the bits would be right, the route is not the rule's
+    moving = np.nonzero(boxes["src_rank"] != boxes["dst_rank"])[0]
+    hits = 0
+    for k in moving:
+        if hits >= 5:
+            break
+        t, kind, lo = int(boxes["tensor"][k]), int(boxes["kind"][k]), tuple(int(v) for v in boxes["lo"][k])
+        others = [o for o in a.owners(kind, t, lo) if o[0] != int(boxes["src_rank"][k])]
+        if not others:
+            continue
+        r, buf, off = others[0]
+
+        def other_replica(bx, k=k, r=r, buf=buf, off=off):
+            bx["src_rank"][k], bx["src_buf"][k], bx["src_off"][k] = r, buf, off
+        nbad, first = planted(other_replica)
+        assert nbad > 0 and first == k
+        hits += 1
+    assert hits > 0
+
+
 def test_plain_copy_reference(hlib):
     from paper_2605_18815_amd import binding as B
     mem = parity.HostMem(hlib)
