@@ -43,7 +43,7 @@ def cases(first_seed, count):
         rng = random.Random(s)
         m = rng.choice(MODELS)
         pa, pb = random_parallel(rng, m), random_parallel(rng, m)
-        mode = rng.choice(["all", "all", "single", "through"])
+        mode = rng.choice(["all", "all", "single", "through", "staged", "classify"])
         rank = rng.randrange(max(cf.world(pa), cf.world(pb)))
         if cf.world(pa) <= MAX_WORLD and cf.world(pb) <= MAX_WORLD:
             out.append((s, m, pa, pb, mode, rank))
@@ -57,6 +57,12 @@ def run_case(lib, mem_factory, case):
         return False
     if mode == "single":
         parity.run_single_rank(lib, mem_factory(), m, pa, pb, rank, seed=s)
+    elif mode == "staged":
+        # budget drawn from the seed: from "every step its own stage" to "one stage"
+        budget = [1, 1 << 12, 1 << 16, 1 << 60][s % 4]
+        parity.run_staged(lib, mem_factory(), m, pa, pb, seed=s, budget=budget)
+    elif mode == "classify":
+        parity.run_classify(lib, m, pa, pb)
     else:
         parity.run_all_ranks(lib, mem_factory(), m, pa, pb, seed=s, through=(mode == "through"))
     return True
