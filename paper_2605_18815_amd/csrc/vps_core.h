@@ -537,7 +537,8 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         }
     int m = 0;
     for (int i = 0; i < n; ++i) {
-        if (m > 0 && s2[m - 1] == s2[i] * e[i] && d2[m - 1] == d2[i] * e[i]) {
+        // (extents stay below 2^31: a longer contiguous stretch is kept as rows of a 2-D box)
+        if (m > 0 && s2[m - 1] == s2[i] * e[i] && d2[m - 1] == d2[i] * e[i] && e[m - 1] * e[i] < ((int64_t)1 << 31)) {
             e[m - 1] *= e[i]; s2[m - 1] = s2[i]; d2[m - 1] = d2[i];
         } else {
             e[m] = e[i]; s2[m] = s2[i]; d2[m] = d2[i]; ++m;

@@ -26,6 +26,15 @@ struct Bounds {
 static std::vector<Bounds> g_bounds;
 static long g_violations = 0;
 
+// Dry run: the copy step checks bounds and records every destination write as an interval, but
+// moves nothing, so that shares far larger than host memory can be walked with made-up buffer
+// addresses.
+struct Interval {
+    uint64_t lo, hi;
+};
+static bool g_dry_run = false;
+static std::vector<Interval> g_dry_writes;
+
 static bool in_bounds(const void* p, size_t n)
 {
     const char* c = (const char*)p;
@@ -82,6 +91,12 @@ public:
         auto slot_ptr = [&](int32_t s) { return pa.tbl ? pa.tbl[s] : pa.inl[s]; };
         auto move = [&](const char* s, char* t, size_t n) {
             if (!in_bounds(s, n) || !in_bounds(t, n)) { ++g_violations; return; }
+            if (g_dry_run) {
+                const uint64_t lo = (uint64_t)(uintptr_t)t;
+                if (!g_dry_writes.empty() && g_dry_writes.back().hi == lo) g_dry_writes.back().hi = lo + n;
+                else g_dry_writes.push_back({ lo, lo + n });
+                return;
+            }
             memcpy(t, s, n);
         };
         for (int64_t ti = 0; ti < ntiles; ++ti) {
@@ -94,11 +109,13 @@ public:
                 for (uint32_t r = 0; r < nruns; ++r) {
                     const uint64_t srow = s0 + r * (uint64_t)tr.src_pitch, drow = d0 + r * (uint64_t)tr.dst_pitch;
                     const RunWindow g = run_window(srow, drow, tr.nbytes, 0, (tr.nbytes + 30) >> 4);
-                    for (uint32_t w = g.wbeg; w < g.wend; ++w) {
-                        if ((g.dvec + 16ull * w) & 15) ++g_violations;
-                        move((const char*)(uintptr_t)(g.svec + 16ull * w), (char*)(uintptr_t)(g.dvec + 16ull * w), 16);
-                    }
                     if (g.head_bytes) move((const char*)(uintptr_t)srow, (char*)(uintptr_t)drow, g.head_bytes);
+                    if (g.dvec & 15) ++g_violations;
+                    if (g_dry_run && g.wbeg < g.wend)
+                        move((const char*)(uintptr_t)(g.svec + 16ull * g.wbeg), (char*)(uintptr_t)(g.dvec + 16ull * g.wbeg),
+                             16ull * (g.wend - g.wbeg));
+                    for (uint32_t w = g.wbeg; w < g.wend && !g_dry_run; ++w)
+                        move((const char*)(uintptr_t)(g.svec + 16ull * w), (char*)(uintptr_t)(g.dvec + 16ull * w), 16);
                     if (g.tail_bytes) move((const char*)(uintptr_t)(g.svec + g.tail_off), (char*)(uintptr_t)(g.dvec + g.tail_off), g.tail_bytes);
                 }
                 continue;
@@ -148,6 +165,30 @@ void vpsh_set_bounds(const void* const* lo_hi, int n)
 }
 
 long vpsh_bounds_violations(void) { return vps::g_violations; }
+
+// Dry-run mode of the copy step (see g_dry_run).  Switching it on clears the recorded writes.
+void vpsh_set_dry_run(int on)
+{
+    vps::g_dry_run = on != 0;
+    vps::g_dry_writes.clear();
+}
+
+// Total bytes written since the dry run was switched on; *overlaps = number of recorded writes
+// that share a byte with an earlier one.
+uint64_t vpsh_dry_run_written(int64_t* overlaps)
+{
+    std::vector<vps::Interval>& w = vps::g_dry_writes;
+    std::sort(w.begin(), w.end(), [](const vps::Interval& a, const vps::Interval& b) { return a.lo < b.lo; });
+    uint64_t total = 0, reach = 0;
+    int64_t bad = 0;
+    for (const vps::Interval& i : w) {
+        total += i.hi - i.lo;
+        if (i.lo < reach) ++bad;
+        if (i.hi > reach) reach = i.hi;
+    }
+    if (overlaps) *overlaps = bad;
+    return total;
+}
 
 // Split a linear range of a row-major array: writes (start, axis, count) triples, returns n.
 int vpsh_split_linear_range(const int64_t* dims, uint64_t v0, uint64_t v1, int64_t* out, int max)

@@ -569,6 +569,56 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
+def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16):
+    """CPU build only: walk the tile table of one rank's apply_transition at full size without
+    memory behind it.  The buffers get made-up addresses; the copy step checks every access
+    against the buffer extents (destination extents end at the padding), records every write and
+    moves nothing.  The writes must be disjoint and add up to the whole destination payload plus
+    the outgoing payload: every destination byte is written exactly once."""
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
+    plan = hlib.plan_intersections(ca, cb, rank)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    info = plan.buffer_bytes(rank)
+    window = 1 << 40
+    base = lambda k: (16 + k) * window
+    src = [base(k) if rank < a.world and a.buffer_elems(rank, k) else 0 for k in range(8)]
+    dst = [base(8 + k) if rank < b.world and b.buffer_elems(rank, k) else 0 for k in range(8)]
+    scratch = base(16)
+    ranges = []
+    dst_payload = 0
+    for k in range(8):
+        if src[k]:
+            ranges.append((src[k], src[k] + a.buffer_elems(rank, k) * oracle.KIND_BYTES[k % 4]))
+        if dst[k]:
+            n = b.payload_elems(rank, k) * oracle.KIND_BYTES[k % 4]
+            ranges.append((dst[k], dst[k] + n))
+            dst_payload += n
+    ranges.append((scratch, scratch + info["scratch_needed"]))
+    arr = (C.c_void_p * (2 * len(ranges)))()
+    for i, (lo, hi) in enumerate(ranges):
+        arr[2 * i], arr[2 * i + 1] = lo, hi
+    dll = hlib._dll
+    dll.vpsh_set_bounds(arr, len(ranges))
+    dll.vpsh_set_dry_run(1)
+    try:
+        hlib.apply_transition(plan, rank, src, dst, scratch, info["scratch_needed"])
+        overlaps = C.c_int64(0)
+        dll.vpsh_dry_run_written.restype = C.c_uint64
+        written = dll.vpsh_dry_run_written(C.byref(overlaps))
+        dll.vpsh_bounds_violations.restype = C.c_long
+        violations = dll.vpsh_bounds_violations()
+    finally:
+        dll.vpsh_set_dry_run(0)
+    out = boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]
+    sent = int((np.prod(out["ext"].astype(np.int64), axis=1) * np.where(out["kind"] == 0, 2, 4)).sum())
+    assert violations == 0, f"{violations} accesses outside the buffers"
+    assert overlaps.value == 0, f"{overlaps.value} destination ranges written twice"
+    assert written == dst_payload + sent, (written, dst_payload, sent)
+    return dict(written=written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info)
+
+
 # ----------------------------------------------------------------------------- staged exchange
 
 def memory_aware_chunk(cost, budget):

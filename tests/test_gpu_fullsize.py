@@ -121,3 +121,71 @@ def test_all_ranks_planning_at_scale(lib, name):
     assert np.array_equal(np.sort(one[keys], order=keys), np.sort(sel[keys], order=keys))
     cls = plan.classify_collectives(ca)
     print("  collective intent per (tensor, kind) [none, p2p, broadcast, scatter, gather]:", np.bincount(cls, minlength=5), flush=True)
+
+
+@pytest.mark.timeout(900)
+def test_contiguous_run_beyond_32_bit_extent(lib):
+    """Regression: an embedding shard of 4.4e9 elements is one contiguous stretch whose element
+    count does not fit 32 bits.  Rank 0 of a two-stage pipeline keeps its state but reverses the
+    flat order, so every tensor moves to a new offset (124 GB resident).  Expected placement from
+    the oracle's per-element maps: whole tensors compared on the device, plus sampled elements."""
+    import numpy as np
+    import torch
+    import oracle
+    m = cf.model(cf.FAMILY_GQA, 2, 8192, 64, 8, 128, 1024, 540_000)
+    pa, pb = cf.parallel(tp=1, pp=2, dp=1), cf.parallel(tp=1, pp=2, dp=1, flat_order=1)
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    rank = 0
+    ca, cb = lib.describe_config(m, pa), lib.describe_config(m, pb)
+    plan = lib.plan_intersections(ca, cb, rank)
+    boxes = plan.get_boxes()
+    parity.validate_boxes(a, b, boxes, rank, samples=16)
+    info = plan.buffer_bytes(rank)
+    assert info["send_total"] == 0 and info["recv_total"] == 0
+    assert int(np.prod(boxes["ext"].astype(np.int64), axis=1).max()) > 1 << 32
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    dts = {2: torch.int16, 4: torch.int32}
+    src, dst = [], []
+    for buf in range(8):
+        es = oracle.KIND_BYTES[buf % 4]
+        s = torch.empty(a.buffer_elems(rank, buf), dtype=dts[es], device=dev)
+        if s.numel():
+            s.random_(generator=gen)
+        src.append(s)
+        dst.append(torch.full((b.buffer_elems(rank, buf),), -1, dtype=dts[es], device=dev))
+    print(f"\n{sum(t.numel() * t.element_size() for t in src + dst) / 1e9:.1f} GB resident", flush=True)
+    ptr = lambda ts: [t.data_ptr() if t.numel() else 0 for t in ts]
+    lib.apply_transition(plan, rank, ptr(src), ptr(dst), 0, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    # whole tensors: under both configurations rank 0 stores a tensor's shard row-major in one piece
+    step = 1 << 28
+    compared = 0
+    for t in range(a.num_tensors):
+        for kind in range(4):
+            own_a = [o for o in a.owners(kind, t, (0, 0, 0, 0)) if o[0] == rank]
+            own_b = [o for o in b.owners(kind, t, (0, 0, 0, 0)) if o[0] == rank]
+            assert len(own_a) == len(own_b)
+            if not own_a:
+                continue
+            (_, buf_a, off_a), (_, buf_b, off_b) = own_a[0], own_b[0]
+            n = int(np.prod(a.tensor_info(t)["shape"], dtype=np.int64))
+            for o in range(0, n, step):
+                k = min(step, n - o)
+                assert torch.equal(dst[buf_b][off_b + o:off_b + o + k], src[buf_a][off_a + o:off_a + o + k]), (t, kind, o)
+            compared += n
+    assert compared == sum(b.payload_elems(rank, buf) for buf in range(8))
+    # sampled elements through the per-element maps, and the padding is untouched
+    rng = np.random.default_rng(3)
+    for buf in range(8):
+        n, pay = b.buffer_elems(rank, buf), b.payload_elems(rank, buf)
+        if not n:
+            continue
+        offs = np.unique(np.concatenate([rng.integers(0, pay, 64), [0, pay - 1, (1 << 32) - 1, 1 << 32, (1 << 32) + 1]]))
+        for off in offs[offs < pay]:
+            t, cd = b.coord(rank, buf, int(off))
+            r, sb, so = [o for o in a.owners(buf % 4, t, cd) if o[0] == rank][0]
+            assert int(dst[buf][int(off)]) == int(src[sb][so]), (buf, off)
+        assert bool((dst[buf][pay:] == -1).all())
+    print(f"{compared} elements compared", flush=True)

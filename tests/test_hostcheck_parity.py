@@ -239,6 +239,43 @@ def test_edge_transitions(hlib, name, m, pa, pb):
         parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, r, seed=4)
 
 
+def test_tensors_beyond_32_bit_sizes(hlib):
+    """A 162 B-parameter model whose embedding has 6.5e10 elements and whose rank shares reach
+    100 GB: offsets, strides and tile counts beyond 32 bits (the CPU build runs under UBSan).
+    Planning only; every box is validated by the oracle on corners and random interior points."""
+    import oracle
+    from paper_2605_18815_amd import binding as B
+    m = cf.model(cf.FAMILY_GQA, 2, 32768, 256, 32, 128, 131072, 2_000_000)
+    pa, pb = P(tp=8, pp=1, dp=4), P(tp=4, pp=2, dp=4, qkv_layout=1)
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    assert a.total_params > 1.6e11
+    ca, cb = hlib.describe_config(m, pa), hlib.describe_config(m, pb)
+    routes = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
+    parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=16)
+    # rank 0 with copy descriptors and the tile table: its embedding shard is one contiguous
+    # stretch of 8.2e9 elements, more than a 32-bit extent holds
+    out = parity.dry_run_single_rank(hlib, m, pa, pb, 0)
+    assert out["info"]["retain_total"] > 8e10 and out["sent"] > 2e10
+
+
+FULL_SIZE_SHARES = [("gqa8b", 5, {}), ("gqa70b", 11, {}), ("gqa70b", 43, {}), ("gqa70b", 11, {"flat_order": 1}),
+                    ("moe235b", 37, {}), ("gpt1p3b", 29, {})]
+
+
+@pytest.mark.parametrize("name,rank,dst_over", FULL_SIZE_SHARES, ids=[f"{n}-r{r}{'-var' if o else ''}" for n, r, o in FULL_SIZE_SHARES])
+def test_full_size_shares_dry_run(hlib, name, rank, dst_over):
+    """The benchmark's rank shares at full size on the CPU build: the whole tile table is walked
+    without memory behind it; accesses stay inside the buffers and the writes cover every
+    destination payload byte and every outgoing byte exactly once."""
+    w = cf.WORKLOADS[name]
+    pa, pb = dict(w["src"]), dict(w["dst"])
+    if dst_over:
+        pa.update(dst_over)
+        pb.update(dst_over)
+    out = parity.dry_run_single_rank(hlib, w["model"], pa, pb, rank, box_samples=4)
+    assert out["written"] > 0
+
+
 def test_random_transitions(hlib):
     import random_cases
     ran = sum(random_cases.run_case(hlib, lambda: parity.HostMem(hlib), c) for c in random_cases.cases(20260000, 150))
