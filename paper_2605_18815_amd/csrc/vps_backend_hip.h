@@ -282,24 +282,33 @@ public:
         }
     }
 
+    // A dispatch holds fewer than 2^32 work-items per dimension, i.e. fewer than 2^24 workgroups
+    // of 256 lanes: larger tile ranges go out as several launches (a multiple of every XCD run
+    // length per launch, so the block -> tile order is the same as in one launch).
+    static constexpr int64_t MAX_GROUPS_PER_LAUNCH = (int64_t)1 << 23;
+
     void launch_copy(const CopyDesc* descs, const TileRef* tiles, int64_t tile0, int64_t ntiles,
                      const PtrArgs& pa, int alias)
     {
-        if (ntiles <= 0) return;
-        hipLaunchKernelGGL(k_copy_tiles, dim3((unsigned)ntiles), dim3(COPY_THREADS), 0, stream_, descs,
-                           tiles, (uint32_t)tile0, pa, alias, xcd_chunk());
-        VPS_HIP_CHECK(hipGetLastError());
+        for (int64_t off = 0; off < ntiles; off += MAX_GROUPS_PER_LAUNCH) {
+            const int64_t n = ntiles - off < MAX_GROUPS_PER_LAUNCH ? ntiles - off : MAX_GROUPS_PER_LAUNCH;
+            hipLaunchKernelGGL(k_copy_tiles, dim3((unsigned)n), dim3(COPY_THREADS), 0, stream_, descs,
+                               tiles, (uint32_t)(tile0 + off), pa, alias, xcd_chunk());
+            VPS_HIP_CHECK(hipGetLastError());
+        }
     }
 
     void launch_plain_copy(void* dst, const void* src, uint64_t bytes)
     {
         const uint64_t nvec = bytes / 16;
-        const uint64_t blocks = (nvec + PLAIN_TILE_VECS - 1) / PLAIN_TILE_VECS;
-        if (!blocks) return;
-        if (blocks > 0x7fffffffULL) throw Error{ VPS_ERR_INVALID_ARG, "plain copy larger than 2^31 tiles" };
-        hipLaunchKernelGGL(k_plain_copy, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
-                           (const char*)src, (char*)dst, nvec, xcd_chunk());
-        VPS_HIP_CHECK(hipGetLastError());
+        const uint64_t per_launch = (uint64_t)MAX_GROUPS_PER_LAUNCH * PLAIN_TILE_VECS;
+        for (uint64_t v0 = 0; v0 < nvec; v0 += per_launch) {
+            const uint64_t n = nvec - v0 < per_launch ? nvec - v0 : per_launch;
+            const uint64_t blocks = (n + PLAIN_TILE_VECS - 1) / PLAIN_TILE_VECS;
+            hipLaunchKernelGGL(k_plain_copy, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
+                               (const char*)src + v0 * 16, (char*)dst + v0 * 16, n, xcd_chunk());
+            VPS_HIP_CHECK(hipGetLastError());
+        }
     }
 
     hipStream_t stream() const { return stream_; }

@@ -83,6 +83,19 @@ def test_moe235b_rank37_destination_transposed_experts(lib):
 
 
 @pytest.mark.timeout(900)
+def test_moe235b_rank37_more_tiles_than_one_dispatch_holds(lib):
+    """With 4 KiB tiles the share has 13.8 M tiles; a dispatch of 256-lane workgroups holds fewer
+    than 2^24 of them, and the library cuts the tile range into launches of 2^23."""
+    lib.set_tile_bytes(4096)
+    try:
+        out = _run(lib, "moe235b", fraction=min(FRACTION, 0.1))
+    finally:
+        lib.set_tile_bytes(8192)
+    st = out["stats"]
+    assert st["num_retain_tiles"] + st["num_pack_tiles"] + st["num_unpack_tiles"] > 1 << 23
+
+
+@pytest.mark.timeout(900)
 def test_gpt1p3b_all_ranks_full_size(lib):
     w = cf.WORKLOADS["gpt1p3b"]
     print("\ngpt1p3b all 32 ranks", flush=True)
