@@ -5,7 +5,7 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import TRANSITIONS
-from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH
+from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH, check_error_codes
 
 pytestmark = pytest.mark.gpu
 
@@ -173,3 +173,7 @@ def test_plain_copy_reference(lib):
     lib.plain_copy(dst.data_ptr(), src.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert torch.equal(dst[:n], src) and bool((dst[n:] == 0xA5).all())
+
+
+def test_error_codes(lib):
+    check_error_codes(lib, parity.GpuMem())

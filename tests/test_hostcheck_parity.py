@@ -365,6 +365,12 @@ def test_plain_copy_reference(hlib):
 
 
 def test_error_codes(hlib):
+    check_error_codes(hlib, parity.HostMem(hlib))
+
+
+def check_error_codes(hlib, mem):
+    """Every documented error is reported with its code, before any device work is enqueued
+    (also run against the HIP library by the GPU tests)."""
     from paper_2605_18815_amd import binding as B
     with pytest.raises(VpsError) as e:
         hlib.describe_config(cf.TINY_GPT, P(tp=3))
@@ -394,7 +400,6 @@ def test_error_codes(hlib):
     assert e.value.code == B.ERR_RANK_RANGE
     plan = hlib.plan_intersections(ca, cb, 1)
     info = plan.buffer_bytes(1)
-    mem = parity.HostMem(hlib)
     bufs = [mem.ptr(mem.alloc(max(ca.buffer_bytes(1, b), cb.buffer_bytes(1, b)))) for b in range(8)]
     with pytest.raises(VpsError) as e:
         hlib.apply_transition(plan, 1, bufs, bufs, mem.ptr(mem.alloc(16)), 16)
