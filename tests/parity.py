@@ -569,7 +569,7 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
-def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16):
+def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16, through=False):
     """CPU build only: walk the tile table of one rank's apply_transition at full size without
     memory behind it.  The buffers get made-up addresses; the copy step checks every access
     against the buffer extents (destination extents end at the padding), records every write and
@@ -577,9 +577,9 @@ def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16):
     the outgoing payload: every destination byte is written exactly once."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
-    plan = hlib.plan_intersections(ca, cb, rank)
+    plan = hlib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else hlib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
     info = plan.buffer_bytes(rank)
     window = 1 << 40
     base = lambda k: (16 + k) * window
@@ -611,7 +611,7 @@ def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16):
         violations = dll.vpsh_bounds_violations()
     finally:
         dll.vpsh_set_dry_run(0)
-    out = boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]
+    out = boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]
     sent = int((np.prod(out["ext"].astype(np.int64), axis=1) * np.where(out["kind"] == 0, 2, 4)).sum())
     assert violations == 0, f"{violations} accesses outside the buffers"
     assert overlaps.value == 0, f"{overlaps.value} destination ranges written twice"

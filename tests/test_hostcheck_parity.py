@@ -258,21 +258,28 @@ def test_tensors_beyond_32_bit_sizes(hlib):
     assert out["info"]["retain_total"] > 8e10 and out["sent"] > 2e10
 
 
-FULL_SIZE_SHARES = [("gqa8b", 5, {}), ("gqa70b", 11, {}), ("gqa70b", 43, {}), ("gqa70b", 11, {"flat_order": 1}),
-                    ("moe235b", 37, {}), ("gpt1p3b", 29, {})]
+# (workload, rank, layout fields changed on both sides, plan through the buffers, tile bytes)
+FULL_SIZE_SHARES = [("gqa8b", 5, {}, False, 8192), ("gqa70b", 11, {}, False, 8192), ("gqa70b", 43, {}, False, 8192),
+                    ("gqa70b", 11, {"flat_order": 1}, False, 8192), ("moe235b", 37, {}, False, 8192),
+                    ("gpt1p3b", 29, {}, False, 8192), ("gqa70b", 11, {}, True, 8192), ("moe235b", 37, {}, True, 8192),
+                    ("gqa70b", 11, {}, False, 4096), ("gqa8b", 5, {"qkv_layout": 1}, False, 1 << 20)]
 
 
-@pytest.mark.parametrize("name,rank,dst_over", FULL_SIZE_SHARES, ids=[f"{n}-r{r}{'-var' if o else ''}" for n, r, o in FULL_SIZE_SHARES])
-def test_full_size_shares_dry_run(hlib, name, rank, dst_over):
+@pytest.mark.parametrize("name,rank,over,through,tile", FULL_SIZE_SHARES,
+                         ids=[f"{n}-r{r}{'-var' if o else ''}{'-through' if t else ''}-{tb}" for n, r, o, t, tb in FULL_SIZE_SHARES])
+def test_full_size_shares_dry_run(hlib, name, rank, over, through, tile):
     """The benchmark's rank shares at full size on the CPU build: the whole tile table is walked
     without memory behind it; accesses stay inside the buffers and the writes cover every
     destination payload byte and every outgoing byte exactly once."""
     w = cf.WORKLOADS[name]
     pa, pb = dict(w["src"]), dict(w["dst"])
-    if dst_over:
-        pa.update(dst_over)
-        pb.update(dst_over)
-    out = parity.dry_run_single_rank(hlib, w["model"], pa, pb, rank, box_samples=4)
+    pa.update(over)
+    pb.update(over)
+    hlib.set_tile_bytes(tile)
+    try:
+        out = parity.dry_run_single_rank(hlib, w["model"], pa, pb, rank, box_samples=4, through=through)
+    finally:
+        hlib.set_tile_bytes(8192)
     assert out["written"] > 0
 
 
