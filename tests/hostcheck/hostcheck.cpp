@@ -173,11 +173,13 @@ void vpsh_set_dry_run(int on)
     vps::g_dry_writes.clear();
 }
 
-// Total bytes written since the dry run was switched on; *overlaps = number of recorded writes
-// that share a byte with an earlier one.
-uint64_t vpsh_dry_run_written(int64_t* overlaps)
+// Bytes written into the address window [lo, hi) since the dry run was switched on; *overlaps =
+// number of recorded writes in the window that share a byte with an earlier one.
+uint64_t vpsh_dry_run_written(uint64_t lo, uint64_t hi, int64_t* overlaps)
 {
-    std::vector<vps::Interval>& w = vps::g_dry_writes;
+    std::vector<vps::Interval> w;
+    for (const vps::Interval& i : vps::g_dry_writes)
+        if (i.lo >= lo && i.hi <= hi) w.push_back(i);
     std::sort(w.begin(), w.end(), [](const vps::Interval& a, const vps::Interval& b) { return a.lo < b.lo; });
     uint64_t total = 0, reach = 0;
     int64_t bad = 0;

@@ -569,54 +569,112 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
+class DryRun:
+    """CPU build only: made-up buffer addresses for a walk of the tile table without memory.
+    Sources, destinations and scratch live in three separate address windows; the copy step
+    checks every access against the registered extents, records every write and moves nothing."""
+    SRC, DST, SCRATCH, END = 1 << 44, 1 << 45, 1 << 46, 1 << 47
+
+    def __init__(self, hlib):
+        self.dll = hlib._dll
+        self.ranges = []
+        self.next = {self.SRC: self.SRC, self.DST: self.DST, self.SCRATCH: self.SCRATCH}
+        self.dll.vpsh_dry_run_written.restype = C.c_uint64
+        self.dll.vpsh_dry_run_written.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(C.c_int64)]
+        self.dll.vpsh_bounds_violations.restype = C.c_long
+
+    def buffer(self, window, nbytes, extent=None):
+        """Address of a buffer of nbytes in `window`; accesses are legal in its first `extent` bytes."""
+        if not nbytes:
+            return 0
+        p = self.next[window]
+        self.next[window] = p + (int(nbytes) + 4095) // 4096 * 4096 + 4096
+        self.ranges.append((p, p + int(nbytes if extent is None else extent)))
+        return p
+
+    def __enter__(self):
+        arr = (C.c_void_p * (2 * len(self.ranges)))()
+        for i, (lo, hi) in enumerate(self.ranges):
+            arr[2 * i], arr[2 * i + 1] = lo, hi
+        self.dll.vpsh_set_bounds(arr, len(self.ranges))
+        self.dll.vpsh_set_dry_run(1)
+        return self
+
+    def __exit__(self, *exc):
+        self.violations = self.dll.vpsh_bounds_violations()
+        ov = C.c_int64(0)
+        self.dst_written = self.dll.vpsh_dry_run_written(self.DST, self.SCRATCH, C.byref(ov))
+        self.dst_overlaps = ov.value
+        self.scratch_written = self.dll.vpsh_dry_run_written(self.SCRATCH, self.END, C.byref(ov))
+        self.scratch_overlaps = ov.value
+        self.dll.vpsh_set_dry_run(0)
+        return False
+
+
 def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16, through=False):
     """CPU build only: walk the tile table of one rank's apply_transition at full size without
-    memory behind it.  The buffers get made-up addresses; the copy step checks every access
-    against the buffer extents (destination extents end at the padding), records every write and
-    moves nothing.  The writes must be disjoint and add up to the whole destination payload plus
-    the outgoing payload: every destination byte is written exactly once."""
+    memory behind it (see DryRun; destination extents end at the padding).  The writes must be
+    disjoint and add up to the whole destination payload and the outgoing payload: every
+    destination byte and every byte of the send buffer's boxes is written exactly once."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
     plan = hlib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else hlib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
     validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
     info = plan.buffer_bytes(rank)
-    window = 1 << 40
-    base = lambda k: (16 + k) * window
-    src = [base(k) if rank < a.world and a.buffer_elems(rank, k) else 0 for k in range(8)]
-    dst = [base(8 + k) if rank < b.world and b.buffer_elems(rank, k) else 0 for k in range(8)]
-    scratch = base(16)
-    ranges = []
-    dst_payload = 0
-    for k in range(8):
-        if src[k]:
-            ranges.append((src[k], src[k] + a.buffer_elems(rank, k) * oracle.KIND_BYTES[k % 4]))
-        if dst[k]:
-            n = b.payload_elems(rank, k) * oracle.KIND_BYTES[k % 4]
-            ranges.append((dst[k], dst[k] + n))
-            dst_payload += n
-    ranges.append((scratch, scratch + info["scratch_needed"]))
-    arr = (C.c_void_p * (2 * len(ranges)))()
-    for i, (lo, hi) in enumerate(ranges):
-        arr[2 * i], arr[2 * i + 1] = lo, hi
-    dll = hlib._dll
-    dll.vpsh_set_bounds(arr, len(ranges))
-    dll.vpsh_set_dry_run(1)
-    try:
+    dry = DryRun(hlib)
+    es = oracle.KIND_BYTES
+    src = [dry.buffer(dry.SRC, a.buffer_elems(rank, k) * es[k % 4] if rank < a.world else 0) for k in range(8)]
+    dst = [dry.buffer(dry.DST, b.buffer_elems(rank, k) * es[k % 4] if rank < b.world else 0,
+                      b.payload_elems(rank, k) * es[k % 4] if rank < b.world else 0) for k in range(8)]
+    dst_payload = sum(b.payload_elems(rank, k) * es[k % 4] for k in range(8)) if rank < b.world else 0
+    scratch = dry.buffer(dry.SCRATCH, info["scratch_needed"])
+    with dry:
         hlib.apply_transition(plan, rank, src, dst, scratch, info["scratch_needed"])
-        overlaps = C.c_int64(0)
-        dll.vpsh_dry_run_written.restype = C.c_uint64
-        written = dll.vpsh_dry_run_written(C.byref(overlaps))
-        dll.vpsh_bounds_violations.restype = C.c_long
-        violations = dll.vpsh_bounds_violations()
-    finally:
-        dll.vpsh_set_dry_run(0)
     out = boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]
     sent = int((np.prod(out["ext"].astype(np.int64), axis=1) * np.where(out["kind"] == 0, 2, 4)).sum())
-    assert violations == 0, f"{violations} accesses outside the buffers"
-    assert overlaps.value == 0, f"{overlaps.value} destination ranges written twice"
-    assert written == dst_payload + sent, (written, dst_payload, sent)
-    return dict(written=written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info)
+    assert dry.violations == 0, f"{dry.violations} accesses outside the buffers"
+    assert dry.dst_overlaps == 0 and dry.scratch_overlaps == 0, "a byte is written twice"
+    assert dry.dst_written == dst_payload and dry.scratch_written == sent, (dry.dst_written, dst_payload, dry.scratch_written, sent)
+    return dict(written=dry.dst_written + dry.scratch_written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info)
+
+
+def dry_run_all_ranks(hlib, model, pa, pb, staged_budget=None, box_samples=4):
+    """CPU build only: every virtual rank resident, at full size without memory: the one-shot
+    apply_transition(rank=-1), or the staged exchange under a per-rank budget (its scratch regions
+    are reused from stage to stage, so only the destination writes must be disjoint)."""
+    a, b = oracle.Config(model, pa), oracle.Config(model, pb)
+    ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
+    plan = hlib.plan_intersections(ca, cb, -1)
+    boxes = plan.get_boxes()
+    validate_boxes(a, b, boxes, -1, samples=box_samples)
+    es = oracle.KIND_BYTES
+    dry = DryRun(hlib)
+    src = [dry.buffer(dry.SRC, a.buffer_elems(r, k) * es[k % 4]) for r in range(a.world) for k in range(8)]
+    dst = [dry.buffer(dry.DST, b.buffer_elems(j, k) * es[k % 4], b.payload_elems(j, k) * es[k % 4])
+           for j in range(b.world) for k in range(8)]
+    dst_payload = sum(b.payload_elems(j, k) * es[k % 4] for j in range(b.world) for k in range(8))
+    moving = boxes[boxes["src_rank"] != boxes["dst_rank"]]
+    sent = int((np.prod(moving["ext"].astype(np.int64), axis=1) * np.where(moving["kind"] == 0, 2, 4)).sum())
+    if staged_budget is None:
+        need = plan.buffer_bytes(-1)["scratch_needed"]
+        scratch = dry.buffer(dry.SCRATCH, need)
+        with dry:
+            hlib.apply_transition(plan, -1, src, dst, scratch, need)
+        assert dry.scratch_overlaps == 0 and dry.scratch_written == sent, (dry.scratch_written, sent)
+        stages = 0
+    else:
+        sp = hlib.stage_exchange(plan, staged_budget)
+        sinfo = sp.info()
+        need, stages = sinfo["scratch_needed"], sinfo["num_stages"]
+        scratch = dry.buffer(dry.SCRATCH, need)
+        with dry:
+            hlib.apply_transition_staged(sp, src, dst, scratch, need)
+        assert dry.scratch_written == 2 * sent, (dry.scratch_written, sent)   # packed once, exchanged once
+    assert dry.violations == 0, f"{dry.violations} accesses outside the buffers"
+    assert dry.dst_overlaps == 0, "a destination byte is written twice"
+    assert dry.dst_written == dst_payload, (dry.dst_written, dst_payload)
+    return dict(written=dry.dst_written, sent=sent, scratch=need, stages=stages)
 
 
 # ----------------------------------------------------------------------------- staged exchange

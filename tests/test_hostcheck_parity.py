@@ -283,6 +283,18 @@ def test_full_size_shares_dry_run(hlib, name, rank, over, through, tile):
     assert out["written"] > 0
 
 
+@pytest.mark.parametrize("name,budget", [("toy", None), ("toy", 1), ("toy", 1 << 60), ("gpt1p3b", None), ("gpt1p3b", 64 << 20)],
+                         ids=["toy-oneshot", "toy-tiny-budget", "toy-one-stage", "gpt1p3b-oneshot", "gpt1p3b-64MiB-stages"])
+def test_all_ranks_full_size_dry_run(hlib, name, budget):
+    """All virtual ranks resident at full size on the CPU build, one-shot and staged in XOR step
+    order: accesses inside the buffers, every destination payload byte written exactly once."""
+    w = cf.WORKLOADS[name]
+    out = parity.dry_run_all_ranks(hlib, w["model"], w["src"], w["dst"], staged_budget=budget)
+    assert out["written"] > 0 and (budget is None or out["stages"] >= 1)
+    if name == "gpt1p3b" and budget:
+        assert out["stages"] > 1 and out["scratch"] < out["sent"]
+
+
 def test_random_transitions(hlib):
     import random_cases
     ran = sum(random_cases.run_case(hlib, lambda: parity.HostMem(hlib), c) for c in random_cases.cases(20260000, 150))
