@@ -648,15 +648,12 @@ void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_
         // layout of the new table: [pack tiles by stage | exchange tiles by stage | unpack tiles by stage]
         const int64_t npack = t_unpack0 - t_pack0;
         TileRef* out = sd.tiles;
-        const TileRef* in = p.tiles;
         const CopyDesc* sdescs = sd.descs;
         be.for_each(step::stage_tile_gather(), nmove, [=] VPS_LAMBDA(int64_t k) {
             const int64_t t = t_pack0 + idx[k];
             const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;
             // rebuilt from the stage descriptor: same geometry, stage positions
-            TileRef r = make_tile(sdescs[d - n], (uint32_t)(d - n), (uint32_t)(t - tb[d]));
-            (void)in;
-            out[k < npack ? k : k + nexch] = r;
+            out[k < npack ? k : k + nexch] = make_tile(sdescs[d - n], (uint32_t)(d - n), (uint32_t)(t - tb[d]));
         });
         be.for_each(step::stage_exchange_tiles(), nexch, [=] VPS_LAMBDA(int64_t t) {
             const int64_t sg = upper_bound_idx(d_stb, nseg + 1, t) - 1;
