@@ -79,7 +79,7 @@ struct ConfigData {
     int64_t npieces = 0;
     // host copies
     std::vector<ClassRec> hC;
-    std::vector<uint64_t> tensor_numel_max;  // one entry: elements of the largest logical tensor
+    uint64_t tensor_numel_max = 1;  // elements of the largest logical tensor
 };
 
 inline int bits_for(uint64_t max_value_exclusive)
@@ -146,11 +146,9 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     c.TL = be.template alloc<TensorLayout>(nt);
     c.C = be.template alloc<ClassRec>(P.ncls);
     be.upload(c.T, inv.data(), sizeof(TensorRec) * (size_t)nt);
-    {
-        uint64_t mx = 1;
-        for (const TensorRec& x : inv) mx = numel4(x.shape) > mx ? numel4(x.shape) : mx;
-        c.tensor_numel_max.assign(1, mx);
-    }
+    c.tensor_numel_max = 1;
+    for (const TensorRec& x : inv)
+        if (numel4(x.shape) > c.tensor_numel_max) c.tensor_numel_max = numel4(x.shape);
 
     // (1) class and shard length of every tensor; sort keys in flat-buffer order
     uint64_t* key = be.template alloc<uint64_t>(nt);
@@ -293,9 +291,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     uint32_t* ord_s = be.template alloc<uint32_t>(n);
     uint32_t* ord_r = be.template alloc<uint32_t>(n);
     // bits of the largest lo-corner key: the largest tensor of the model
-    uint64_t max_numel = 1;
-    for (const uint64_t v : ca.tensor_numel_max) max_numel = v > max_numel ? v : max_numel;
-    const int lo_bits = bits_for(max_numel);
+    const int lo_bits = bits_for(ca.tensor_numel_max);
     {
         const TensorRec* T = ca.T;
         be.for_each(step::plan_key_lo(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); by_lo[k] = (uint32_t)k; });
