@@ -40,6 +40,10 @@ inline void check_descs(const vps_model_desc& m, const vps_parallel_desc& p)
     if (m.family == VPS_FAMILY_MOE && m.expert_ffn % p.tp) bad(VPS_ERR_INDIVISIBLE, "tp does not divide expert_ffn");
     if (m.family == VPS_FAMILY_MOE && m.experts % p.ep) bad(VPS_ERR_INDIVISIBLE, "ep does not divide experts");
     if (p.pp > m.layers) bad(VPS_ERR_INDIVISIBLE, "pp exceeds the number of layers");
+    // tensor ids take 24 bits of the planner's sort keys
+    const int64_t per_layer = 12 + (m.family == VPS_FAMILY_MOE ? 2 * (int64_t)m.experts : 0);
+    if ((int64_t)m.layers * per_layer + 4 >= ((int64_t)1 << 24)) bad(VPS_ERR_INVALID_ARG, "more than 2^24 logical tensors");
+    if ((int64_t)m.q_heads * m.head_dim >= ((int64_t)1 << 31)) bad(VPS_ERR_INVALID_ARG, "q_heads * head_dim does not fit 31 bits");
 }
 
 inline ParConst make_par_const(const vps_model_desc& m, const vps_parallel_desc& p, int32_t nt)

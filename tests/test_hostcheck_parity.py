@@ -403,6 +403,9 @@ def check_error_codes(hlib, mem):
     with pytest.raises(VpsError) as e:
         hlib.describe_config(cf.TINY_GPT, P(tp=2), rank=2)
     assert e.value.code == B.ERR_RANK_RANGE
+    with pytest.raises(VpsError) as e:   # 20 M logical tensors: ids would not fit the sort keys
+        hlib.describe_config(cf.model(cf.FAMILY_MOE, 1000, 16, 4, 4, 4, 0, 64, experts=10000, expert_ffn=8), P())
+    assert e.value.code == B.ERR_INVALID_ARG
     ca = hlib.describe_config(cf.TINY_GPT, P(tp=2, dp=2))
     cb = hlib.describe_config(cf.TINY_GQA, P(tp=2, dp=2))
     with pytest.raises(VpsError) as e:
