@@ -4,6 +4,8 @@
 // names of include/vps.h.
 #pragma once
 
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -14,6 +16,20 @@ namespace vps {
 
 static thread_local std::string g_last_error;
 static uint32_t g_tile_bytes = 8u << 10;
+
+// Super-block shape of transposed boxes: 0 = chosen per box from the pitches; VPS_XPOSE_SHAPE
+// = "sa,sb" (blocks along the source's / the destination's contiguous axis) fixes it for
+// experiments.
+inline uint32_t xpose_shape_override()
+{
+    static const uint32_t v = [] {
+        const char* e = getenv("VPS_XPOSE_SHAPE");
+        unsigned sa = 0, sb = 0;
+        if (!e || sscanf(e, "%u,%u", &sa, &sb) != 2 || sa < 1 || sb < 1 || sa > 1024 || sb > 1024) return 0u;
+        return (uint32_t)(sa | sb << 16);
+    }();
+    return v;
+}
 
 inline int fail(int code, const std::string& msg)
 {
@@ -145,7 +161,8 @@ int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, 
     try {
         if (flags & ~(uint32_t)(VPS_PLAN_ROUTES_ONLY | VPS_PLAN_THROUGH_BUFFERS))
             throw vps::Error{ VPS_ERR_INVALID_ARG, "unknown plan flag" };
-        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, (flags & VPS_PLAN_ROUTES_ONLY) != 0,
+        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, vps::xpose_shape_override(),
+                        (flags & VPS_PLAN_ROUTES_ONLY) != 0,
                         (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, p->d);
         vps::mark_used_slots(p->d, p->used);
     } catch (...) {

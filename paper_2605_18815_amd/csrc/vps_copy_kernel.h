@@ -2,15 +2,16 @@
 // of DynaTrain Algorithm 1, plus the direct old-local -> new-local copy of retained slices).
 //
 // One workgroup (4 wavefronts of 64 lanes) per tile of roughly tile_bytes payload.
-//   direct tiles    a self-contained record (addresses as slot|offset, byte count, run count,
+//   run tiles       a self-contained record (addresses as slot|offset, byte count, run count,
 //                   pitches): a chunk of one long run walked by the whole workgroup, or several
 //                   short runs at a constant pitch, one run per wavefront at a time.  Lanes own
 //                   16-byte destination-aligned vectors: aligned 16-byte stores, 16-byte loads
 //                   at whatever element alignment the source has; the (at most two) partial
 //                   vectors at the ends of a run are moved in 2-byte units by a few lanes.
-//   indirect tiles  refer to a descriptor: 64 x 64 element blocks transposed through LDS when
-//                   the contiguous axis differs between source and destination (XPOSE), or one
-//                   element per lane when no axis is contiguous on both sides (ELEM).
+//   transpose tiles a self-contained record as well: a block of up to 64 x 64 elements moved
+//                   through LDS when the contiguous axis differs between source and destination.
+//   indirect tiles  refer to a descriptor: one element per lane when no axis is contiguous on
+//                   both sides (ELEM, degenerate shapes only).
 // Per-tile and per-run quantities are wave-uniform and kept in scalar registers; the lane state
 // is a handful of addresses, so eight waves per SIMD stay resident and hide HBM latency.
 // HBM-bound: every payload byte is read once and written once; the tile table adds 48 bytes per
@@ -88,8 +89,9 @@ __device__ __forceinline__ void copy_run_window(uint64_t srow, uint64_t drow, ui
 // along the destination's contiguous axis.  The LDS pitch of 64+2 (2-byte) / 64+1 (4-byte)
 // elements keeps rows dword aligned and spreads a column over the banks.
 template <class E>
-__device__ __forceinline__ void copy_xpose_tile(const CopyDesc& d, uint32_t q, uint64_t sbase,
-                                                uint64_t dbase, uint32_t tid, uint32_t* lds_words)
+__device__ __forceinline__ void copy_xpose_tile(uint64_t s0, uint64_t t0, int64_t src_pitch,
+                                                int64_t dst_pitch, uint32_t ta, uint32_t tb,
+                                                uint32_t tid, uint32_t* lds_words)
 {
     constexpr uint32_t T = XPOSE_T;
     constexpr uint32_t V = 16 / sizeof(E);            // elements per 16-byte vector
@@ -99,18 +101,11 @@ __device__ __forceinline__ void copy_xpose_tile(const CopyDesc& d, uint32_t q, u
     typedef const VPS_GLOBAL E* gsrc_t;
     typedef VPS_GLOBAL E* gdst_t;
 
-    uint64_t so, to;
-    uint32_t ta, tb;
-    xpose_tile_geometry(d, q, so, to, ta, tb);
-    const uint64_t s0 = uniform64(sbase + so), t0 = uniform64(dbase + to);
-    const int64_t sb = d.sstr[3];      // source stride between consecutive b (elements)
-    const int64_t da = d.dstr[d.xa];   // destination stride between consecutive a (elements)
-
     // phase 1: source rows (fixed b, a contiguous) -> lds[b][a]
     for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
         const uint32_t b = v / NV, a = (v % NV) * V;
         if (b >= tb || a >= ta) continue;
-        const uint64_t g = s0 + (uint64_t)((int64_t)b * sb + a) * sizeof(E);
+        const uint64_t g = s0 + (uint64_t)((int64_t)b * src_pitch) + a * sizeof(E);
         E* row = lds + b * PITCH + a;
         if (a + V <= ta) {
             const u32x4 x = __builtin_nontemporal_load((gsrc16_t)g);
@@ -125,7 +120,7 @@ __device__ __forceinline__ void copy_xpose_tile(const CopyDesc& d, uint32_t q, u
     for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
         const uint32_t a = v / NV, b = (v % NV) * V;
         if (a >= ta || b >= tb) continue;
-        const uint64_t g = t0 + (uint64_t)((int64_t)a * da + b) * sizeof(E);
+        const uint64_t g = t0 + (uint64_t)((int64_t)a * dst_pitch) + b * sizeof(E);
         const E* col = lds + b * PITCH + a;
         if (b + V <= tb && (g & 15) == 0) {
             u32x4 x;
@@ -161,14 +156,22 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
     const uint32_t tid = threadIdx.x;
     const uint32_t nf = uniform32(tp->nruns_flags);
     if (!(nf & TILE_INDIRECT)) {
-        const uint32_t nruns = nf >> 8;
-        if (!nruns) return;
         const uint32_t nbytes = uniform32(tp->nbytes);
         const uint64_t alt = tp->alt_src;
         const uint64_t sa = uniform64((alias_exchange && alt != VPS_TILE_NO_ALT) ? alt : tp->src);
         const uint64_t da = uniform64(tp->dst);
         const uint64_t s = uniform64(slot_addr(pa, tile_slot(sa)) + tile_offset(sa));
         const uint64_t t = uniform64(slot_addr(pa, tile_slot(da)) + tile_offset(da));
+        if (nf & TILE_XPOSE) {
+            __shared__ uint32_t lds_words[XPOSE_T * (XPOSE_T + 1)];
+            const int64_t sp = (int64_t)uniform64((uint64_t)tp->src_pitch), dp = (int64_t)uniform64((uint64_t)tp->dst_pitch);
+            const uint32_t ta = nbytes & 0xffffu, tb = nbytes >> 16;
+            if (nf & TILE_ES2) copy_xpose_tile<uint16_t>(s, t, sp, dp, ta, tb, tid, lds_words);
+            else copy_xpose_tile<uint32_t>(s, t, sp, dp, ta, tb, tid, lds_words);
+            return;
+        }
+        const uint32_t nruns = nf >> 8;
+        if (!nruns) return;
         const uint32_t nw = (nbytes + 30) >> 4;
         if (nruns == 1) {
             // a contiguous piece of one long run: the whole workgroup walks its vectors
@@ -182,6 +185,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
         }
         return;
     }
+    // element-wise fallback: no axis is contiguous on both sides (degenerate shapes only)
     const uint32_t di = uniform32((uint32_t)tp->alt_src);
     const uint32_t q = uniform32((uint32_t)(tp->alt_src >> 32));
     const CopyDesc* __restrict__ d = descs + di;
@@ -190,21 +194,14 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
                                            : slot_addr(pa, d->src_slot) + d->src_byte);
     const uint64_t dbase = uniform64(slot_addr(pa, d->dst_slot) + d->dst_byte);
     const uint32_t es = d->es;
-
-    if (d->mode == MODE_XPOSE) {
-        __shared__ uint32_t lds_words[XPOSE_T * (XPOSE_T + 1)];
-        if (es == 2) copy_xpose_tile<uint16_t>(*d, q, sbase, dbase, tid, lds_words);
-        else copy_xpose_tile<uint32_t>(*d, q, sbase, dbase, tid, lds_words);
-    } else {
-        const uint64_t vol = (uint64_t)d->ext[0] * d->ext[1] * d->ext[2] * d->ext[3];
-        const uint64_t k0 = (uint64_t)q * d->rows_per_tile;
-        const uint64_t k1 = k0 + d->rows_per_tile < vol ? k0 + d->rows_per_tile : vol;
-        for (uint64_t k = k0 + tid; k < k1; k += COPY_THREADS) {
-            int64_t so, to;
-            elem_offsets(*d, k, so, to);
-            if (es == 2) *(gdst2_t)(dbase + to) = *(gsrc2_t)(sbase + so);
-            else *(gdst4_t)(dbase + to) = *(gsrc4_t)(sbase + so);
-        }
+    const uint64_t vol = (uint64_t)d->ext[0] * d->ext[1] * d->ext[2] * d->ext[3];
+    const uint64_t k0 = (uint64_t)q * d->rows_per_tile;
+    const uint64_t k1 = k0 + d->rows_per_tile < vol ? k0 + d->rows_per_tile : vol;
+    for (uint64_t k = k0 + tid; k < k1; k += COPY_THREADS) {
+        int64_t so, to;
+        elem_offsets(*d, k, so, to);
+        if (es == 2) *(gdst2_t)(dbase + to) = *(gsrc2_t)(sbase + so);
+        else *(gdst4_t)(dbase + to) = *(gsrc4_t)(sbase + so);
     }
 }
 

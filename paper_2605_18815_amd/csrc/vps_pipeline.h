@@ -230,8 +230,8 @@ inline uint64_t config_buffer_elems(const ConfigData& c, int32_t rank, int32_t b
 
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
-                uint32_t tile_bytes, bool routes_only, bool through_buffers,
-                PlanData& p)
+                uint32_t tile_bytes, uint32_t xpose_shape, bool routes_only,
+                bool through_buffers, PlanData& p)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -369,7 +369,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             const int64_t k = i % n;
             const vps_box& b = boxes[op == OP_UNPACK ? ord_r[k] : ord_s[k]];
             CopyDesc d;
-            make_copy_desc(b, op, layout, rank, through_buffers, tile_bytes, d);
+            make_copy_desc(b, op, layout, rank, through_buffers, tile_bytes, xpose_shape, d);
             descs[i] = d;
             nt[i] = d.ntiles;
         });

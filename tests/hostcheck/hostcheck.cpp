@@ -89,14 +89,14 @@ public:
                      const PtrArgs& pa, int alias_exchange)
     {
         auto slot_ptr = [&](int32_t s) { return pa.tbl ? pa.tbl[s] : pa.inl[s]; };
+        auto note_write = [&](const char* t, size_t n) {
+            const uint64_t lo = (uint64_t)(uintptr_t)t;
+            if (!g_dry_writes.empty() && g_dry_writes.back().hi == lo) g_dry_writes.back().hi = lo + n;
+            else g_dry_writes.push_back({ lo, lo + n });
+        };
         auto move = [&](const char* s, char* t, size_t n) {
             if (!in_bounds(s, n) || !in_bounds(t, n)) { ++g_violations; return; }
-            if (g_dry_run) {
-                const uint64_t lo = (uint64_t)(uintptr_t)t;
-                if (!g_dry_writes.empty() && g_dry_writes.back().hi == lo) g_dry_writes.back().hi = lo + n;
-                else g_dry_writes.push_back({ lo, lo + n });
-                return;
-            }
+            if (g_dry_run) { note_write(t, n); return; }
             memcpy(t, s, n);
         };
         for (int64_t ti = 0; ti < ntiles; ++ti) {
@@ -106,6 +106,25 @@ public:
                 const uint64_t sa = (alias_exchange && tr.alt_src != VPS_TILE_NO_ALT) ? tr.alt_src : tr.src;
                 const uint64_t s0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(sa)) + tile_offset(sa);
                 const uint64_t d0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(tr.dst)) + tile_offset(tr.dst);
+                if (tr.nruns_flags & TILE_XPOSE) {
+                    const uint32_t ta = tr.nbytes & 0xffffu, tb = tr.nbytes >> 16;
+                    const uint32_t es = (tr.nruns_flags & TILE_ES2) ? 2 : 4;
+                    if (ta == 0 || tb == 0 || ta > XPOSE_T || tb > XPOSE_T) ++g_violations;
+                    for (uint32_t a = 0; a < ta; ++a) {
+                        if (g_dry_run) {   // one destination row of the block per recorded write
+                            const char* trow = (const char*)(uintptr_t)(d0 + (uint64_t)((int64_t)a * tr.dst_pitch));
+                            if (!in_bounds(trow, (size_t)tb * es)) ++g_violations;
+                            else note_write(trow, (size_t)tb * es);
+                            for (uint32_t b = 0; b < tb; b += tb > 1 ? tb - 1 : 1)   // first and last source element of the row
+                                if (!in_bounds((const char*)(uintptr_t)(s0 + (uint64_t)a * es + (uint64_t)((int64_t)b * tr.src_pitch)), es)) ++g_violations;
+                            continue;
+                        }
+                        for (uint32_t b = 0; b < tb; ++b)
+                            move((const char*)(uintptr_t)(s0 + (uint64_t)a * es + (uint64_t)((int64_t)b * tr.src_pitch)),
+                                 (char*)(uintptr_t)(d0 + (uint64_t)((int64_t)a * tr.dst_pitch) + (uint64_t)b * es), es);
+                    }
+                    continue;
+                }
                 for (uint32_t r = 0; r < nruns; ++r) {
                     const uint64_t srow = s0 + r * (uint64_t)tr.src_pitch, drow = d0 + r * (uint64_t)tr.dst_pitch;
                     const RunWindow g = run_window(srow, drow, tr.nbytes, 0, (tr.nbytes + 30) >> 4);
@@ -125,16 +144,7 @@ public:
             const bool alias = alias_exchange && d.alt_src_slot >= 0;
             const char* sbase = alias ? slot_ptr(d.alt_src_slot) + d.alt_src_byte : slot_ptr(d.src_slot) + d.src_byte;
             char* dbase = slot_ptr(d.dst_slot) + d.dst_byte;
-            if (d.mode == MODE_XPOSE) {
-                uint64_t so, to;
-                uint32_t ta, tb;
-                xpose_tile_geometry(d, tq, so, to, ta, tb);
-                if (ta == 0 || tb == 0 || ta > XPOSE_T || tb > XPOSE_T) ++g_violations;
-                for (uint32_t b = 0; b < tb; ++b)
-                    for (uint32_t a = 0; a < ta; ++a)
-                        move(sbase + so + ((int64_t)a + (int64_t)b * d.sstr[3]) * d.es,
-                             dbase + to + ((int64_t)a * d.dstr[d.xa] + (int64_t)b) * d.es, d.es);
-            } else {
+            {
                 const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
                 const uint64_t k0 = (uint64_t)tq * d.rows_per_tile;
                 const uint64_t k1 = k0 + d.rows_per_tile < vol ? k0 + d.rows_per_tile : vol;
