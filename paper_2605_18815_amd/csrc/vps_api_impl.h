@@ -25,7 +25,7 @@ inline uint32_t xpose_shape_override()
     static const uint32_t v = [] {
         const char* e = getenv("VPS_XPOSE_SHAPE");
         unsigned sa = 0, sb = 0;
-        if (!e || sscanf(e, "%u,%u", &sa, &sb) != 2 || sa < 1 || sb < 1 || sa > 1024 || sb > 1024) return 0u;
+        if (!e || sscanf(e, "%u,%u", &sa, &sb) != 2 || sa < 1 || sb < 1 || sa > 64 || sb > 64) return 0u;
         return (uint32_t)(sa | sb << 16);
     }();
     return v;
