@@ -212,7 +212,7 @@ def main():
                    "src": pa, "dst": pb, "step": (args.only + " only") if args.only else ("apply only" if args.apply_only else "describe x2 + plan + apply"),
                    "through_buffers": bool(args.through_buffers),
                    "tile_bytes": args.tile_bytes or 8192},
-        "breakdown_ms": {"describe_x2": _avg(t_desc), "plan": _avg(t_plan), "apply_kernels": apply_avg},
+        "breakdown_ms": {"describe_x2": _median(t_desc), "plan": _median(t_plan), "apply_kernels": apply_avg},
         "apply_gbps": bytes_moved / (apply_avg * 1e-3) / 1e9,
         "pct_hbm_peak_apply": 100.0 * bytes_moved / (apply_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS,
         "bytes": {"send": info["send_total"], "recv": info["recv_total"], "retain": info["retain_total"],
@@ -226,8 +226,8 @@ def main():
     print(json.dumps(out))
 
 
-def _avg(v):
-    return sum(v) / len(v) if v else None
+def _median(v):
+    return sorted(v)[len(v) // 2] if v else None
 
 
 def cpu_baseline(model, pa, pb, rank, seed, target_seconds=12.0):
