@@ -63,6 +63,7 @@ struct stage_tile_keys {};
 struct stage_tile_gather {};
 struct stage_descs {};
 struct stage_exchange_tiles {};
+struct stage_bounds {};
 }  // namespace step
 
 struct ConfigData {
@@ -665,20 +666,22 @@ void build_stage_plan(BE& be, const PlanData& p, uint64_t budget, uint32_t tile_
         });
     }
     // per-stage tile ranges of pack and unpack from the sorted keys
-    std::vector<uint64_t> hkey((size_t)nmove);
-    be.download(hkey.data(), key, sizeof(uint64_t) * (size_t)nmove);
     sd.pack_begin.assign((size_t)G + 1, 0);
     sd.unpack_begin.assign((size_t)G + 1, 0);
     {
+        int64_t* bounds = be.template alloc<int64_t>(2 * ((int64_t)G + 1));
+        be.for_each(step::stage_bounds(), 2 * ((int64_t)G + 1), [=] VPS_LAMBDA(int64_t i) {
+            const uint64_t op = i > G ? 1 : 0, g = (uint64_t)(i > G ? i - (G + 1) : i);
+            bounds[i] = lower_bound_idx(key, nmove, op << 32 | g);
+        });
+        std::vector<int64_t> hb(2 * ((size_t)G + 1));
+        be.download(hb.data(), bounds, sizeof(int64_t) * hb.size());
+        be.free(bounds);
         const int64_t npack = t_unpack0 - t_pack0;
         for (int32_t g = 0; g <= G; ++g) {
-            sd.pack_begin[(size_t)g] = std::lower_bound(hkey.begin(), hkey.end(), (uint64_t)g) - hkey.begin();
-            sd.unpack_begin[(size_t)g] = std::lower_bound(hkey.begin(), hkey.end(), (1ull << 32) | (uint64_t)g) - hkey.begin();
-        }
-        if (sd.pack_begin[(size_t)G] > npack) sd.pack_begin[(size_t)G] = npack;
-        for (int32_t g = 0; g <= G; ++g) {
+            sd.pack_begin[(size_t)g] = hb[(size_t)g] < npack ? hb[(size_t)g] : npack;
+            sd.unpack_begin[(size_t)g] = hb[(size_t)G + 1 + (size_t)g] + nexch;
             sd.exch_begin[(size_t)g] += npack;
-            sd.unpack_begin[(size_t)g] += nexch;
         }
     }
     sd.ptr_table = be.template alloc<void*>(num_slots(p.layout));
