@@ -204,6 +204,14 @@ def validate_boxes(a, b, boxes, planned_rank, samples=0, through=False):
             assert pos[0] == 0 and (pos[1:] == pos[:-1] + size[:-1]).all()
             peer = bx["dst_rank" if key == "src_rank" else "src_rank"][order]
             assert (np.diff(peer) >= 0).all(), "peer segments must ascend"
+            # the documented order inside a segment: kinds 1, 2, 3, 0; tensor id; lo corner row-major
+            lin = np.zeros(len(bx), dtype=np.int64)
+            for i, o in enumerate(order):
+                shp = a.tensor_info(int(bx["tensor"][o]))["shape"]
+                lo = [int(v) for v in bx["lo"][o]]
+                lin[i] = ((lo[0] * shp[1] + lo[1]) * shp[2] + lo[2]) * shp[3] + lo[3]
+            keys = list(zip(peer.tolist(), ((bx["kind"][order] + 3) & 3).tolist(), bx["tensor"][order].tolist(), lin.tolist()))
+            assert keys == sorted(keys), "boxes of a peer segment are not in the documented order"
 
 
 # ----------------------------------------------------------------------------- all ranks resident
@@ -759,7 +767,7 @@ def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
         assert np.array_equal(got, want), ("staged", j, buf)
     one_shot = plan.buffer_bytes(-1)["scratch_needed"]
     return dict(stages=info["num_stages"], steps=info["num_steps"], scratch=info["scratch_needed"], one_shot=one_shot,
-                max_cost=max(cost))
+                max_cost=max(cost), costs=cost)
 
 
 # ----------------------------------------------------------------------------- collective intent

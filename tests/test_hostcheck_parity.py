@@ -21,7 +21,9 @@ P = cf.parallel
 
 @pytest.fixture(scope="module")
 def hlib():
-    return Library(hc_build.build(), prefix="vpsh_")
+    import os
+    # VPSH_LIB lets the mutation test of the parity suite load a deliberately broken CPU build
+    return Library(os.environ.get("VPSH_LIB") or hc_build.build(), prefix="vpsh_")
 
 
 @pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
@@ -48,14 +50,16 @@ def test_medium_shapes_all_ranks(hlib, name, m, pa, pb):
 STAGED = [("gpt-zero-to-replicated", 0), ("gpt-blocked-rev", 1), ("gpt-world-grows", 2), ("moe-transposed", 3), ("moe-odd", 4)]
 
 
-@pytest.mark.parametrize("name,budget_kind", [(n, k) for n, _ in STAGED for k in ("tiny", "mid", "huge")],
-                         ids=[f"{n}-{k}" for n, _ in STAGED for k in ("tiny", "mid", "huge")])
+@pytest.mark.parametrize("name,budget_kind", [(n, k) for n, _ in STAGED for k in ("tiny", "mid", "exact", "huge")],
+                         ids=[f"{n}-{k}" for n, _ in STAGED for k in ("tiny", "mid", "exact", "huge")])
 def test_staged_xor_exchange(hlib, name, budget_kind):
     """Memory-aware stages and the XOR step order (Algorithm 1) give the same final state."""
     _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
     probe = parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=5, budget=1 << 60)
     assert probe["stages"] == 1
-    budget = {"tiny": 1, "mid": max(probe["max_cost"] * 2, 1), "huge": 1 << 60}[budget_kind]
+    busy = [c for c in probe["costs"][1:] if c]
+    # "exact": the first two steps with traffic fill the budget to the byte and must share a stage
+    budget = {"tiny": 1, "mid": max(probe["max_cost"] * 2, 1), "exact": sum(busy[:2]) or 1, "huge": 1 << 60}[budget_kind]
     out = parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=6, budget=budget)
     if budget_kind == "tiny":
         assert out["stages"] >= 2 and out["scratch"] < out["one_shot"] * 2

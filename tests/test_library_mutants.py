@@ -1,0 +1,55 @@
+"""Is the parity suite sharp?  Plant one plausible mistake at a time in a copy of the library's
+per-item code, build the CPU variant of it (tests/hostcheck), and require that the parity
+procedures against the oracle notice.  Everything here runs on the CPU; the mistake is never
+compiled for, or run on, a GPU."""
+import os
+import shutil
+import subprocess
+import sys
+import tempfile
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+MUTANTS = [
+    ("V block of blocked QKV at K's place", "vps_core.h", "bo = b == 0 ? 0 : (b == 1 ? P.q_per_g : P.q_per_g + 1);",
+     "bo = b == 0 ? 0 : (b == 1 ? P.q_per_g + 1 : P.q_per_g);"),
+    ("source offset of a box with the destination's strides", "vps_core.h",
+     "b.src_off += (int64_t)(lo[a] - sp.lo[a]) * sp.stride[a];", "b.src_off += (int64_t)(lo[a] - sp.lo[a]) * dp.stride[a];"),
+    ("replica choice ignores the data-parallel index", "vps_core.h", "int64_t want = dpj % n_node;", "int64_t want = 0 % n_node;"),
+    ("partial last vector of a run dropped at a window end", "vps_core.h",
+     "const bool has_tail = tailb && !(wl == 0 && head) && wl >= w0 && wl < wend_win;",
+     "const bool has_tail = tailb && !(wl == 0 && head) && wl >= w0 && wl + 1 < wend_win;"),
+    ("retained boxes get buffer positions", "vps_pipeline.h",
+     "sz[k] = (!box_retained(b, through_buffers) && resident) ? (int64_t)box_slot_bytes(b) : 0;",
+     "sz[k] = resident ? (int64_t)box_slot_bytes(b) : 0;"),
+    ("kinds in plain order inside a peer segment", "vps_core.h", "const uint64_t korder = (uint64_t)((b.kind + 3) & 3);",
+     "const uint64_t korder = (uint64_t)b.kind;"),
+    ("unpack reads at the sender's position", "vps_core.h", "d.src_byte = b.recv_pos;", "d.src_byte = b.send_pos;"),
+    ("block extent of a transpose not clipped", "vps_core.h",
+     "ta = d.ext[d.xa] - a0 < (uint32_t)XPOSE_T ? d.ext[d.xa] - a0 : (uint32_t)XPOSE_T;", "ta = (uint32_t)XPOSE_T;"),
+]
+
+PARITY = "all_ranks_resident or single_rank_share or medium_shapes"
+
+
+@pytest.mark.parametrize("name,header,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_parity_suite_catches_planted_mistake(name, header, old, new):
+    with tempfile.TemporaryDirectory() as tmp:
+        shutil.copytree(os.path.join(ROOT, "paper_2605_18815_amd", "csrc"), os.path.join(tmp, "paper_2605_18815_amd", "csrc"))
+        shutil.copytree(os.path.join(ROOT, "include"), os.path.join(tmp, "include"))
+        os.makedirs(os.path.join(tmp, "tests", "hostcheck"))
+        shutil.copy(os.path.join(ROOT, "tests", "hostcheck", "hostcheck.cpp"), os.path.join(tmp, "tests", "hostcheck"))
+        path = os.path.join(tmp, "paper_2605_18815_amd", "csrc", header)
+        src = open(path).read()
+        assert src.count(old) == 1, f"mutation site for '{name}' not found exactly once"
+        open(path, "w").write(src.replace(old, new))
+        lib = os.path.join(tmp, "libmutant.so")
+        subprocess.run(["g++", "-std=c++17", "-O0", "-fPIC", "-shared", "-o", lib,
+                        os.path.join(tmp, "tests", "hostcheck", "hostcheck.cpp")], check=True)
+        res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_hostcheck_parity.py"), "-x", "-q",
+                              "-k", PARITY, "-p", "no:cacheprovider"], env=dict(os.environ, VPSH_LIB=lib), cwd=ROOT,
+                             capture_output=True, text=True)
+        assert res.returncode != 0, f"no parity test noticed the planted mistake '{name}'"
+        assert "failed" in res.stdout
