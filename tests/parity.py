@@ -252,6 +252,8 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
 
     # (1) one call for everything
     info = plan.buffer_bytes(-1)
+    kept = sum(plan.pair_bytes(q, q) for q in range(min(a.world, b.world)))    # checked against the oracle above
+    assert info["retain_total"] == (0 if through else kept)
     if through:
         assert info["retain_total"] == 0
         assert info["send_total"] >= sum(b.payload_elems(j, buf) * oracle.KIND_BYTES[buf % 4]
@@ -394,14 +396,21 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
     # byte counts seen from this rank (quadratic in the number of replicas: skipped for huge worlds)
     if not check_bytes:
         in_a = in_b = False
+    nb = len(boxes)
     if in_b:
         rb = oracle.route_bytes(a, b, rank)
         for i in range(a.world):
             assert plan.pair_bytes(i, rank) == rb[i], (i, rank)
+        own = int(rb[rank]) if rank < a.world else 0
+        assert info["retain_total"] == (0 if through else own)
+        incoming = int(rb.sum()) - (0 if through else own)
+        assert incoming <= info["recv_total"] <= incoming + 16 * nb      # payload plus alignment pad
     if in_a:
         sbytes = oracle.send_bytes(a, b, rank)
         for j in range(b.world):
             assert plan.pair_bytes(rank, j) == sbytes[j], (rank, j)
+        outgoing = int(sbytes.sum()) - (0 if through or rank >= b.world else int(sbytes[rank]))
+        assert outgoing <= info["send_total"] <= outgoing + 16 * nb
     # send payload
     sb = mem.download(scratch)[:info["send_total"]]
     for bx in boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]:
