@@ -207,6 +207,42 @@ def test_library_exports_every_declared_symbol():
     assert {"vps_" + e for e in Library.EXPORTS} == names
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/vps.h compiles as strict C99, the struct sizes are those the binding assumes, and a
+    C program linked against the library can call it (argument errors only: no GPU needed)."""
+    import os
+    import subprocess
+    from paper_2605_18815_amd import build as lib_build
+    from paper_2605_18815_amd.binding import BOX_DTYPE, PIECE_DTYPE
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = lib_build.library_path()
+    src = tmp_path / "use_vps.c"
+    src.write_text('''
+#include <stdio.h>
+#include <string.h>
+#include "vps.h"
+int main(void)
+{
+    vps_model_desc m;
+    vps_parallel_desc p;
+    vps_config* c = 0;
+    memset(&m, 0, sizeof m);
+    memset(&p, 0, sizeof p);
+    printf("%d %d ", (int)sizeof(vps_piece), (int)sizeof(vps_box));
+    printf("%d ", vps_describe_config(&m, &p, -1, &c));      /* all-zero descriptors: invalid argument */
+    printf("%d ", vps_describe_config(0, &p, -1, &c));
+    printf("%d ", vps_set_tile_bytes(1000));
+    printf("%d\\n", vps_last_error()[0] != 0);
+    return 0;
+}
+''')
+    exe = tmp_path / "use_vps"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe), lib, "-Wl,-rpath," + os.path.dirname(lib), "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()
+    assert [int(v) for v in out] == [PIECE_DTYPE.itemsize, BOX_DTYPE.itemsize, -1, -1, -1, 1]
+
+
 def test_product_calls_fail_loudly_without_a_gpu(gpu_available):
     """No CPU fallback: on a machine without a GPU every compute entry point reports VPS_ERR_HIP."""
     if gpu_available:
