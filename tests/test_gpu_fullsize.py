@@ -17,6 +17,16 @@ def lib():
     return vps.load()
 
 
+@pytest.fixture(autouse=True)
+def _release_cached_device_memory():
+    """These tests hold up to 130 GB each: give torch's cached blocks back between them."""
+    import gc
+    import torch
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+
+
 def _run(lib, name, rank=None, src_over=None, dst_over=None, fraction=None):
     w = cf.WORKLOADS[name]
     pa, pb = dict(w["src"]), dict(w["dst"])
