@@ -105,6 +105,28 @@ def test_moe235b_rank37_more_tiles_than_one_dispatch_holds(lib):
     assert st["num_retain_tiles"] + st["num_pack_tiles"] + st["num_unpack_tiles"] > 1 << 23
 
 
+PAPER_CASES = [("llama70b-64-to-128", False, 127), ("llama70b-64-to-128", False, 40),
+               ("llama70b-64-to-128", True, 100), ("llama13b-16-to-32", True, 5), ("llama7b-8-to-16", False, 15)]
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,reverse,rank", PAPER_CASES, ids=[f"{n}-{'back' if r else 'forward'}-r{k}" for n, r, k in PAPER_CASES])
+def test_paper_table_transition_one_rank_full_size(lib, name, reverse, rank):
+    """World-size-changing transitions of the paper's hybrid reconfiguration table at full model
+    size: ranks that exist on the destination side only (everything arrives through the buffers),
+    on the source side only (everything leaves), and on both."""
+    w = cf.PAPER_TRANSITIONS[name]
+    pa, pb = (w["dst"], w["src"]) if reverse else (w["src"], w["dst"])
+    print(f"\n{name} {'back' if reverse else 'forward'} rank {rank}", flush=True)
+    out = parity.run_single_rank_fullsize(lib, parity.GpuMem(), w["model"], pa, pb, rank, seed=0x7AB1E + rank,
+                                          fraction=FRACTION, log=lambda s: print(s, flush=True))
+    world_a, world_b = cf.world(pa), cf.world(pb)
+    if rank >= world_a:
+        assert out["info"]["retain_total"] == 0 and out["info"]["send_total"] == 0 and out["checked"] > 0
+    if rank >= world_b:
+        assert out["info"]["retain_total"] == 0 and out["info"]["recv_total"] == 0 and out["checked"] == 0
+
+
 @pytest.mark.timeout(900)
 def test_gpt1p3b_all_ranks_full_size(lib):
     w = cf.WORKLOADS["gpt1p3b"]
