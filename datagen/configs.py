@@ -77,14 +77,18 @@ WORKLOADS = {
 }
 
 
-# World-size-changing transitions of the paper's hybrid reconfiguration table (dense rows; tuples
-# there are (TP, PP, DP)), on the published LLaMA-2 shapes.  ZeRO-1 on both sides.  Planned at model
+# Transitions of the paper's evaluation on the published LLaMA-2 shapes: the world-size-changing
+# dense rows of its hybrid reconfiguration table and the pair of its ablation (tuples there are
+# (TP, PP, DP)).  ZeRO-1 on both sides.  Planned at model
 # scale (routes, dry runs); no state of this size is materialised.
 PAPER_TRANSITIONS = {
     "llama7b-8-to-16": dict(model=model(FAMILY_GQA, 32, 4096, 32, 32, 128, 11008, 32000),
                             src=parallel(tp=2, pp=2, dp=2), dst=parallel(tp=4, pp=4, dp=1)),
     "llama13b-16-to-32": dict(model=model(FAMILY_GQA, 40, 5120, 40, 40, 128, 13824, 32000),
                               src=parallel(tp=4, pp=4, dp=1), dst=parallel(tp=2, pp=8, dp=2)),
+    # the pair of the paper's ablation of its communication optimizations (16 GPUs on both sides)
+    "llama13b-ablation-pair": dict(model=model(FAMILY_GQA, 40, 5120, 40, 40, 128, 13824, 32000),
+                                   src=parallel(tp=2, pp=8, dp=1), dst=parallel(tp=2, pp=2, dp=4)),
     "llama70b-64-to-128": dict(model=model(FAMILY_GQA, 80, 8192, 64, 8, 128, 28672, 32000),
                                src=parallel(tp=4, pp=8, dp=2), dst=parallel(tp=8, pp=16, dp=1)),
 }

@@ -106,7 +106,8 @@ def test_moe235b_rank37_more_tiles_than_one_dispatch_holds(lib):
 
 
 PAPER_CASES = [("llama70b-64-to-128", False, 127), ("llama70b-64-to-128", False, 40),
-               ("llama70b-64-to-128", True, 100), ("llama13b-16-to-32", True, 5), ("llama7b-8-to-16", False, 15)]
+               ("llama70b-64-to-128", True, 100), ("llama13b-16-to-32", True, 5), ("llama7b-8-to-16", False, 15),
+               ("llama13b-ablation-pair", False, 9)]
 
 
 @pytest.mark.timeout(900)
