@@ -55,13 +55,15 @@ def main():
     lib = vps.load()
     if args.tile_bytes:
         lib.set_tile_bytes(args.tile_bytes)
-    w = cf.WORKLOADS[args.workload]
+    w = cf.workload(args.workload)
     model, pa, pb = w["model"], dict(w["src"]), dict(w["dst"])
     for spec, par in ((args.src, pa), (args.dst, pb)):
         for kv in filter(None, spec.split(",")):
             k, v = kv.split("=")
             par[k] = int(v)
     rank = args.rank if args.rank is not None else (w["rank"] if w["rank"] is not None else -1)
+    if args.workload in cf.PAPER_TRANSITIONS and rank < 0:
+        sys.exit("bench.py: the paper's transitions do not fit one GPU with every rank resident; pass --rank")
     stream = torch.cuda.current_stream().cuda_stream
 
     # ---- resident state: source buffers (seeded random bytes), destination buffers, scratch

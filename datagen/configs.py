@@ -94,8 +94,15 @@ PAPER_TRANSITIONS = {
 }
 
 
+def workload(name):
+    """A benchmark workload or one of the paper's transitions (those have no default rank)."""
+    if name in WORKLOADS:
+        return WORKLOADS[name]
+    return dict(PAPER_TRANSITIONS[name], rank=None, index=16 + sorted(PAPER_TRANSITIONS).index(name))
+
+
 def seed_of(name):
-    return SEED_BASE + WORKLOADS[name]["index"]
+    return SEED_BASE + workload(name)["index"]
 
 
 # Small shapes for brute-force tests: every axis is tiny but each sharding rule is exercised.
