@@ -177,11 +177,17 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
             // a contiguous piece of one long run: the whole workgroup walks its vectors
             copy_run_window(s, t, nbytes, 0, nw, tid, COPY_THREADS);
         } else {
-            // short runs at a constant pitch: one run per wavefront at a time
             const uint64_t sp = uniform64((uint64_t)tp->src_pitch), dp = uniform64((uint64_t)tp->dst_pitch);
-            const uint32_t wave = uniform32(tid >> 6), lane = tid & 63;
-            for (uint32_t r = wave; r < nruns; r += COPY_WAVES)
-                copy_run_window(s + r * sp, t + r * dp, nbytes, 0, nw, lane, 64);
+            if (nruns < COPY_WAVES) {
+                // two or three runs of a few KiB: the whole workgroup takes them one after the other
+                for (uint32_t r = 0; r < nruns; ++r)
+                    copy_run_window(s + r * sp, t + r * dp, nbytes, 0, nw, tid, COPY_THREADS);
+            } else {
+                // short runs at a constant pitch: one run per wavefront at a time
+                const uint32_t wave = uniform32(tid >> 6), lane = tid & 63;
+                for (uint32_t r = wave; r < nruns; r += COPY_WAVES)
+                    copy_run_window(s + r * sp, t + r * dp, nbytes, 0, nw, lane, 64);
+            }
         }
         return;
     }
