@@ -573,7 +573,12 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
         const uint64_t rows = vol / d.ext[3];
         if (rows >= (1ull << 31)) { d.ntiles = clamp_tiles(rows); return; }  // run index is 32-bit
-        const uint64_t nv_max = (run_bytes + 30) / 16;  // aligned vectors a run can touch
+        // 16-byte destination vectors a run can touch, counted from the 16-byte boundary at or
+        // below its first byte: exact when every run of the box starts on such a boundary
+        bool aligned = (d.dst_byte & 15) == 0;
+        for (int a = 0; a < 3; ++a)
+            if (d.ext[a] > 1 && ((d.dstr[a] * (int64_t)d.es) & 15)) aligned = false;
+        const uint64_t nv_max = (run_bytes + (aligned ? 15 : 30)) / 16;
         const uint64_t vt = tile_bytes / 16;
         if (nv_max > vt) {
             d.chunks_per_row = (uint32_t)((nv_max + vt - 1) / vt);
