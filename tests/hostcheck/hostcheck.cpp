@@ -33,6 +33,9 @@ struct Interval {
     uint64_t lo, hi;
 };
 static bool g_dry_run = false;
+// Tiles seen by the copy step since the last vpsh_tile_histogram call, by kind: count and bytes.
+enum { TK_FULL_RUN = 0, TK_PART_RUN = 1, TK_FEW_RUNS = 2, TK_MANY_RUNS = 3, TK_XPOSE = 4, TK_ELEM = 5, TK_EMPTY = 6, TK_KINDS = 7 };
+static uint64_t g_hist_count[TK_KINDS], g_hist_bytes[TK_KINDS];
 static std::vector<Interval> g_dry_writes;
 
 static bool in_bounds(const void* p, size_t n)
@@ -42,6 +45,8 @@ static bool in_bounds(const void* p, size_t n)
         if (c >= b.lo && c + n <= b.hi) return true;
     return false;
 }
+
+uint32_t g_tile_bytes_setting();
 
 class HostBackend {
 public:
@@ -103,6 +108,18 @@ public:
             const TileRef tr = tiles[tile0 + ti];
             if (!(tr.nruns_flags & TILE_INDIRECT)) {
                 const uint32_t nruns = tr.nruns_flags >> 8;
+                {
+                    int kind;
+                    uint64_t bytes = (uint64_t)nruns * tr.nbytes;
+                    if (tr.nruns_flags & TILE_XPOSE) {
+                        kind = TK_XPOSE;
+                        bytes = (uint64_t)(tr.nbytes & 0xffffu) * (tr.nbytes >> 16) * ((tr.nruns_flags & TILE_ES2) ? 2 : 4);
+                    } else if (nruns == 0) kind = TK_EMPTY;
+                    else if (nruns == 1) kind = 2 * tr.nbytes >= g_tile_bytes_setting() ? TK_FULL_RUN : TK_PART_RUN;
+                    else kind = nruns < 4 ? TK_FEW_RUNS : TK_MANY_RUNS;
+                    g_hist_count[kind]++;
+                    g_hist_bytes[kind] += bytes;
+                }
                 const uint64_t sa = (alias_exchange && tr.alt_src != VPS_TILE_NO_ALT) ? tr.alt_src : tr.src;
                 const uint64_t s0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(sa)) + tile_offset(sa);
                 const uint64_t d0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(tr.dst)) + tile_offset(tr.dst);
@@ -141,6 +158,8 @@ public:
             }
             const uint32_t tq = (uint32_t)(tr.alt_src >> 32);
             const CopyDesc d = descs[(uint32_t)tr.alt_src];
+            g_hist_count[TK_ELEM]++;
+            g_hist_bytes[TK_ELEM] += (uint64_t)d.rows_per_tile * d.es;
             const bool alias = alias_exchange && d.alt_src_slot >= 0;
             const char* sbase = alias ? slot_ptr(d.alt_src_slot) + d.alt_src_byte : slot_ptr(d.src_slot) + d.src_byte;
             char* dbase = slot_ptr(d.dst_slot) + d.dst_byte;
@@ -164,6 +183,10 @@ public:
 #define VPS_FN(name) vpsh_##name
 #include "../../paper_2605_18815_amd/csrc/vps_api_impl.h"
 
+namespace vps {
+uint32_t g_tile_bytes_setting() { return g_tile_bytes; }
+}
+
 extern "C" {
 
 // Register the address ranges the copy step may touch (pairs of lo, hi); clears the counter.
@@ -175,6 +198,18 @@ void vpsh_set_bounds(const void* const* lo_hi, int n)
 }
 
 long vpsh_bounds_violations(void) { return vps::g_violations; }
+
+// Tiles walked since the previous call, by kind (full single run: at least half a tile of
+// payload; partial single run; 2-3 runs; 4 or more runs; transpose; element-wise; empty):
+// counts and payload bytes, 7 entries each.  Resets the counters.
+void vpsh_tile_histogram(uint64_t* counts, uint64_t* bytes)
+{
+    for (int i = 0; i < vps::TK_KINDS; ++i) {
+        counts[i] = vps::g_hist_count[i];
+        bytes[i] = vps::g_hist_bytes[i];
+        vps::g_hist_count[i] = vps::g_hist_bytes[i] = 0;
+    }
+}
 
 // Dry-run mode of the copy step (see g_dry_run).  Switching it on clears the recorded writes.
 void vpsh_set_dry_run(int on)

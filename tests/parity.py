@@ -609,7 +609,11 @@ class DryRun:
         self.ranges.append((p, p + int(nbytes if extent is None else extent)))
         return p
 
+    TILE_KINDS = ("full_run", "partial_run", "few_runs", "many_runs", "transpose", "elementwise", "empty")
+
     def __enter__(self):
+        skip = (C.c_uint64 * 7)()
+        self.dll.vpsh_tile_histogram(skip, skip)    # reset
         arr = (C.c_void_p * (2 * len(self.ranges)))()
         for i, (lo, hi) in enumerate(self.ranges):
             arr[2 * i], arr[2 * i + 1] = lo, hi
@@ -625,6 +629,9 @@ class DryRun:
         self.scratch_written = self.dll.vpsh_dry_run_written(self.SCRATCH, self.END, C.byref(ov))
         self.scratch_overlaps = ov.value
         self.dll.vpsh_set_dry_run(0)
+        n, by = (C.c_uint64 * 7)(), (C.c_uint64 * 7)()
+        self.dll.vpsh_tile_histogram(n, by)
+        self.tiles = {k: (int(n[i]), int(by[i])) for i, k in enumerate(self.TILE_KINDS)}   # kind -> (count, bytes)
         return False
 
 
@@ -653,7 +660,8 @@ def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16, through=False
     assert dry.violations == 0, f"{dry.violations} accesses outside the buffers"
     assert dry.dst_overlaps == 0 and dry.scratch_overlaps == 0, "a byte is written twice"
     assert dry.dst_written == dst_payload and dry.scratch_written == sent, (dry.dst_written, dst_payload, dry.scratch_written, sent)
-    return dict(written=dry.dst_written + dry.scratch_written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info)
+    return dict(written=dry.dst_written + dry.scratch_written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info,
+                tiles=dry.tiles)
 
 
 def dry_run_all_ranks(hlib, model, pa, pb, staged_budget=None, box_samples=4):

@@ -321,6 +321,14 @@ def test_full_size_shares_dry_run(hlib, name, rank, over, through, tile):
     finally:
         hlib.set_tile_bytes(8192)
     assert out["written"] > 0
+    # tile quality: no workgroup without work, and the bulk of the bytes in tiles of at least half
+    # the tile size (small tiles cost a workgroup launch each)
+    tiles = out["tiles"]
+    assert tiles["empty"][0] == 0 and tiles["elementwise"][0] == 0
+    total = sum(b for _, b in tiles.values())
+    assert total == out["written"]
+    big = tiles["full_run"][1] + tiles["few_runs"][1] + tiles["many_runs"][1]
+    assert big >= 0.95 * total, tiles
 
 
 @pytest.mark.parametrize("name,budget", [("toy", None), ("toy", 1), ("toy", 1 << 60), ("gpt1p3b", None), ("gpt1p3b", 64 << 20)],
