@@ -27,6 +27,10 @@
  *                   (D = data-parallel group size).  Kind 0 holds the whole padded buffer;
  *                   kinds 1..3 hold the rank's 1/D range when zero_stage = 1.
  *   ranks           rank = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp, DDP = EP*DP.
+ *   limits          at most 32768 ranks per configuration and 2^24 logical tensors; fewer than
+ *                   2^31 pieces, boxes and tiles per table (VPS_ERR_OOM beyond); an all-ranks
+ *                   plan keeps a src x dst byte matrix and is refused above 2^26 rank pairs;
+ *                   tensor axes are 31-bit, offsets and strides 64-bit.
  *   return values   0 on success, a negative vps_status otherwise; vps_last_error() returns
  *                   a thread-local message.  Functions never throw and never synchronise the
  *                   stream, except where stated.  On error no device work has been enqueued.
