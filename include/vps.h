@@ -6,8 +6,8 @@
  * (F_P, Section 4.1); a switch from configuration A to B is the set of intersections between
  * source and destination regions (Section 4.2.1), including ZeRO flat-buffer shards mapped
  * back into the same space (Section 4.2.2); outgoing slices are packed into one contiguous
- * buffer per peer, exchanged, and unpacked into the new local layout (Algorithm 1, lines
- * 7-8 and 17; Section 4.3 "Memory-Aware Contiguous Buffer").
+ * buffer per peer, exchanged, and unpacked into the new local layout (Algorithm 1, PackData and
+ * UnpackData; Section 4.3 "Memory-Aware Contiguous Buffer").
  *
  * All mapping, planning and copying runs in HIP kernels on the current device.  The library
  * never allocates payload memory: state buffers, send/receive buffers and scratch are owned
@@ -150,7 +150,7 @@ enum { VPS_PLAN_ROUTES_ONLY = 1, VPS_PLAN_THROUGH_BUFFERS = 2 };
 int vps_plan_intersections_ex(const vps_config* src, const vps_config* dst, int32_t rank,
                               uint32_t flags, void* stream, vps_plan** out);
 
-/* Algorithm 1 line 8 (PackData): copy every outgoing sub-box of `rank` from its old local
+/* Algorithm 1, PackData: copy every outgoing sub-box of `rank` from its old local
  * buffers into its send buffer.  src_bufs: host array of 8 device pointers (entries of empty
  * buffers may be NULL).  send_buf: device, >= send_total bytes (vps_plan_buffer_bytes), 16-byte
  * aligned.  Peer segments are laid out in ascending peer order; inside a segment boxes are
@@ -160,14 +160,14 @@ int vps_plan_intersections_ex(const vps_config* src, const vps_config* dst, int3
 int vps_pack(const vps_plan* plan, int32_t rank, const void* const* src_bufs, void* send_buf,
              void* stream);
 
-/* Algorithm 1 line 17 (UnpackData): copy every incoming sub-box of `rank` from its receive
+/* Algorithm 1, UnpackData: copy every incoming sub-box of `rank` from its receive
  * buffer (same layout rules, segments in ascending source-rank order) into the new local
  * buffers.  dst_bufs: host array of 8 device pointers.  Padding elements of dst are never
  * written. */
 int vps_unpack(const vps_plan* plan, int32_t rank, const void* recv_buf, void* const* dst_bufs,
                void* stream);
 
-/* Algorithm 1 lines 6-19 for the resident ranks, in one call: retained boxes are copied
+/* Algorithm 1, the body of ExecuteSwitch for the resident ranks, in one call: retained boxes are copied
  * old-local -> new-local directly, outgoing boxes are packed, incoming ones unpacked.
  *   single-rank plan: rank = planned rank; src_bufs/dst_bufs are 8 pointers each; scratch holds
  *     [send buffer | receive buffer] at the offsets reported by vps_plan_buffer_bytes.  The
