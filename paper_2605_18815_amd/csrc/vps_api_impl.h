@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 
@@ -42,6 +43,7 @@ inline void mark_used_slots(const PlanData& p, std::vector<uint8_t> used[3])
 {
     const int ns = num_slots(p.layout);
     for (int op = 0; op < 3; ++op) used[op].assign((size_t)ns, 0);
+    if (p.routes_only) return;   // no copy tables: nothing is ever dereferenced
     for (const vps_box& b : p.boxes_send_order) {
         const bool retained = box_retained(b, p.through_buffers);
         const bool src_res = p.rank < 0 || b.src_rank == p.rank;
@@ -70,7 +72,24 @@ struct vps_config {
 struct vps_plan {
     vps::PlanData d;
     std::vector<uint8_t> used[3];
+    std::mutex host_copy;   // guards the on-demand host copy of the boxes
 };
+
+namespace vps {
+
+// Queries that read the boxes on the host fetch them first if the plan left them on the device.
+inline const PlanData& with_host_boxes(const vps_plan* plan)
+{
+    vps_plan* mp = const_cast<vps_plan*>(plan);
+    std::lock_guard<std::mutex> g(mp->host_copy);
+    if (!mp->d.host_boxes_ready) {
+        VPS_BACKEND be(nullptr);
+        ensure_host_boxes(be, mp->d);
+    }
+    return mp->d;
+}
+
+}  // namespace vps
 
 struct vps_stage_plan {
     vps::StageData d;
@@ -447,7 +466,8 @@ int VPS_FN(plan_peer_segment)(const vps_plan* plan, int32_t src_rank, int32_t ds
                               uint64_t* recv_off, uint64_t* bytes)
 {
     if (!plan) return vps::fail(VPS_ERR_INVALID_ARG, "null plan");
-    const vps::PlanData& p = plan->d;
+    VPS_TRY
+    const vps::PlanData& p = vps::with_host_boxes(plan);
     if (src_rank < 0 || src_rank >= p.A.world || dst_rank < 0 || dst_rank >= p.B.world)
         return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
     uint64_t so = UINT64_MAX, ro = UINT64_MAX, nb = 0;
@@ -472,6 +492,7 @@ int VPS_FN(plan_peer_segment)(const vps_plan* plan, int32_t src_rank, int32_t ds
     if (recv_off) *recv_off = ro;
     if (bytes) *bytes = nb;
     return VPS_OK;
+    VPS_CATCH
 }
 
 int VPS_FN(plan_num_boxes)(const vps_plan* plan, int64_t* n)
@@ -484,9 +505,12 @@ int VPS_FN(plan_num_boxes)(const vps_plan* plan, int64_t* n)
 int VPS_FN(plan_get_boxes)(const vps_plan* plan, vps_box* out, int64_t max)
 {
     if (!plan || (!out && max > 0)) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
-    const int64_t n = max < plan->d.nboxes ? max : plan->d.nboxes;
-    if (n > 0) memcpy(out, plan->d.boxes_send_order.data(), sizeof(vps_box) * (size_t)n);
+    VPS_TRY
+    const vps::PlanData& p = vps::with_host_boxes(plan);
+    const int64_t n = max < p.nboxes ? max : p.nboxes;
+    if (n > 0) memcpy(out, p.boxes_send_order.data(), sizeof(vps_box) * (size_t)n);
     return VPS_OK;
+    VPS_CATCH
 }
 
 int VPS_FN(plan_stats)(const vps_plan* plan, vps_plan_stats_t* out)

@@ -55,6 +55,7 @@ struct plan_copy_descs {};
 struct plan_tile_table {};
 struct plan_sorted_boxes {};
 struct plan_recv_perm {};
+struct plan_count_retained {};
 struct coll_keys {};
 struct coll_group_key {};
 struct coll_flags {};
@@ -102,7 +103,13 @@ struct PlanData {
     CopyDesc* descs = nullptr;  // 3*nboxes: retain | pack (send order), unpack (receive order)
     TileRef* tiles = nullptr;
     void** ptr_table = nullptr;  // all-ranks plans: device copy of the pointer table
+    vps_box* d_boxes = nullptr;      // the boxes in send order (device copy of boxes_send_order)
+    uint32_t* d_recv_perm = nullptr; // device copy of recv_perm
     // host copies
+    // An all-ranks plan without copy tables brings the two arrays below to the host only when a
+    // query asks for them (host_boxes_ready): for thousands of ranks they are tens of megabytes,
+    // several times the cost of planning itself.
+    bool host_boxes_ready = false;
     std::vector<vps_box> boxes_send_order;   // sorted by (src, dst, kind order, tensor, lo)
     std::vector<uint32_t> recv_perm;         // receive order -> index into boxes_send_order
     std::vector<int64_t> tile_base;          // 3*nboxes + 1
@@ -124,8 +131,8 @@ void free_config(BE& be, ConfigData& c)
 template <class BE>
 void free_plan(BE& be, PlanData& p)
 {
-    be.free(p.descs); be.free(p.tiles); be.free(p.ptr_table);
-    p.descs = nullptr; p.tiles = nullptr; p.ptr_table = nullptr;
+    be.free(p.descs); be.free(p.tiles); be.free(p.ptr_table); be.free(p.d_boxes); be.free(p.d_recv_perm);
+    p.descs = nullptr; p.tiles = nullptr; p.ptr_table = nullptr; p.d_boxes = nullptr; p.d_recv_perm = nullptr;
 }
 
 // ---------------------------------------------------------------------------------- mapper
@@ -392,19 +399,37 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     be.free(nt); be.free(tb);
     }
 
-    // (6) host copies for queries
+    // (6) boxes in send order and the receive permutation: kept on the device, copied to the host
+    // now, or on demand for an all-ranks plan without copy tables
+    const bool lazy = routes_only && rank < 0;
+    int64_t* counts = be.template alloc<int64_t>(2);
+    int64_t hcounts[2] = { 0, 0 };
     {
         vps_box* sorted = be.template alloc<vps_box>(n);
         uint32_t* inv = be.template alloc<uint32_t>(n);
         uint32_t* rperm = be.template alloc<uint32_t>(n);
         be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = boxes[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
         be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
-        p.boxes_send_order.resize((size_t)n);
-        p.recv_perm.resize((size_t)n);
-        be.download_later(p.boxes_send_order.data(), sorted, sizeof(vps_box) * (size_t)n);
-        be.download_later(p.recv_perm.data(), rperm, sizeof(uint32_t) * (size_t)n);
-        be.free(sorted); be.free(inv); be.free(rperm);
+        p.d_boxes = sorted;
+        p.d_recv_perm = rperm;
+        be.free(inv);
+        if (!lazy) {
+            p.boxes_send_order.resize((size_t)n);
+            p.recv_perm.resize((size_t)n);
+            be.download_later(p.boxes_send_order.data(), sorted, sizeof(vps_box) * (size_t)n);
+            be.download_later(p.recv_perm.data(), rperm, sizeof(uint32_t) * (size_t)n);
+            p.host_boxes_ready = true;
+        } else {
+            // the only statistic that needs the boxes: how many stay on their rank
+            be.zero(counts, sizeof(int64_t) * 2);
+            be.for_each(step::plan_count_retained(), n, [=] VPS_LAMBDA(int64_t k) {
+                if (box_retained(sorted[k], through_buffers)) be_atomic_add((uint64_t*)&counts[0], 1);
+            });
+            be.download_later(hcounts, counts, sizeof(int64_t) * 2);
+            p.host_boxes_ready = false;
+        }
     }
+    be.free(counts);
     be.free(ord_s); be.free(ord_r); be.free(boxes);
     if (layout.all_ranks) p.ptr_table = be.template alloc<void*>(num_slots(layout));
     p.host_ptrs.assign((size_t)num_slots(layout), nullptr);
@@ -413,17 +438,35 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     vps_plan_stats_t& st = p.stats;
     st = vps_plan_stats_t();
     st.num_boxes = n;
-    std::vector<char> peer_out((size_t)W, 0), peer_in((size_t)W, 0);
-    for (const vps_box& b : p.boxes_send_order) {
-        if (box_retained(b, through_buffers)) { st.num_retain_boxes++; continue; }
-        if (rank < 0 || b.src_rank == rank) { st.num_send_boxes++; if (rank >= 0) peer_out[(size_t)b.dst_rank] = 1; }
-        if (rank < 0 || b.dst_rank == rank) { st.num_recv_boxes++; if (rank >= 0) peer_in[(size_t)b.src_rank] = 1; }
+    if (lazy) {
+        st.num_retain_boxes = hcounts[0];
+        st.num_send_boxes = st.num_recv_boxes = n - hcounts[0];
+    } else {
+        std::vector<char> peer_out((size_t)W, 0), peer_in((size_t)W, 0);
+        for (const vps_box& b : p.boxes_send_order) {
+            if (box_retained(b, through_buffers)) { st.num_retain_boxes++; continue; }
+            if (rank < 0 || b.src_rank == rank) { st.num_send_boxes++; if (rank >= 0) peer_out[(size_t)b.dst_rank] = 1; }
+            if (rank < 0 || b.dst_rank == rank) { st.num_recv_boxes++; if (rank >= 0) peer_in[(size_t)b.src_rank] = 1; }
+        }
+        for (int r = 0; r < W; ++r) { st.num_peers_out += peer_out[(size_t)r]; st.num_peers_in += peer_in[(size_t)r]; }
     }
-    for (int r = 0; r < W; ++r) { st.num_peers_out += peer_out[(size_t)r]; st.num_peers_in += peer_in[(size_t)r]; }
     st.num_retain_tiles = p.tile_base[(size_t)n] - p.tile_base[0];
     st.num_pack_tiles = p.tile_base[(size_t)(2 * n)] - p.tile_base[(size_t)n];
     st.num_unpack_tiles = p.tile_base[(size_t)(3 * n)] - p.tile_base[(size_t)(2 * n)];
     st.plan_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count();
+}
+
+// The host copies of the boxes, fetched on first use for plans that did not bring them along.
+template <class BE>
+void ensure_host_boxes(BE& be, PlanData& p)
+{
+    if (p.host_boxes_ready) return;
+    p.boxes_send_order.resize((size_t)p.nboxes);
+    p.recv_perm.resize((size_t)p.nboxes);
+    be.download_later(p.boxes_send_order.data(), p.d_boxes, sizeof(vps_box) * (size_t)p.nboxes);
+    be.download_later(p.recv_perm.data(), p.d_recv_perm, sizeof(uint32_t) * (size_t)p.nboxes);
+    be.sync();
+    p.host_boxes_ready = true;
 }
 
 // Tile range [begin, end) of operation `op` for `rank` (-1: every rank).
@@ -704,8 +747,7 @@ void classify_collectives(BE& be, const PlanData& p, const ConfigData& ca, std::
     const int64_t n = p.nboxes;
     const int32_t ngroups = p.A.nt * 4;
     classes.assign((size_t)ngroups, COLL_NONE);
-    vps_box* boxes = be.template alloc<vps_box>(n);
-    be.upload(boxes, p.boxes_send_order.data(), sizeof(vps_box) * (size_t)n);
+    const vps_box* boxes = p.d_boxes;
     uint64_t* key = be.template alloc<uint64_t>(n);
     uint64_t* gk = be.template alloc<uint64_t>(n);
     uint32_t* ord = be.template alloc<uint32_t>(n);
@@ -741,7 +783,7 @@ void classify_collectives(BE& be, const PlanData& p, const ConfigData& ca, std::
     });
     be.for_each(step::coll_classes(), ngroups, [=] VPS_LAMBDA(int64_t g) { out[g] = classify_flags(flags[g]); });
     be.download(classes.data(), out, sizeof(int32_t) * (size_t)ngroups);
-    be.free(boxes); be.free(key); be.free(gk); be.free(ord); be.free(flags); be.free(out);
+    be.free(key); be.free(gk); be.free(ord); be.free(flags); be.free(out);
     be.sync();
 }
 
