@@ -71,17 +71,28 @@ class HostMem:
 
 
 class GpuMem:
-    """torch-backed device memory (torch is only the allocator and the copy engine here)."""
+    """torch-backed device memory (torch is only the allocator and the copy engine here).
+    Every allocation sits between two guard zones; violations() counts guard bytes that a kernel
+    overwrote (the CPU build checks every access instead)."""
+    GUARD = 4096
+    GUARD_BYTE = 0x5A
 
     def __init__(self):
         import torch
         self.torch = torch
         self.dev = torch.device("cuda:0")
+        self.guards = []
 
     def alloc(self, nbytes, fill=SENTINEL):
-        t = self.torch.empty(max(int(nbytes), 0), dtype=self.torch.uint8, device=self.dev)
-        if t.numel():
-            t.fill_(fill)
+        n = max(int(nbytes), 0)
+        if n == 0:
+            return self.torch.empty(0, dtype=self.torch.uint8, device=self.dev)
+        whole = self.torch.empty(n + 2 * self.GUARD, dtype=self.torch.uint8, device=self.dev)
+        whole[:self.GUARD].fill_(self.GUARD_BYTE)
+        whole[self.GUARD + n:].fill_(self.GUARD_BYTE)
+        t = whole[self.GUARD:self.GUARD + n]
+        t.fill_(fill)
+        self.guards.append((whole, n))
         return t
 
     def ptr(self, v):
@@ -112,7 +123,11 @@ class GpuMem:
         pass
 
     def violations(self):
-        return 0
+        self.torch.cuda.synchronize()
+        bad = 0
+        for whole, n in self.guards:
+            bad += int((whole[:self.GUARD] != self.GUARD_BYTE).sum()) + int((whole[self.GUARD + n:] != self.GUARD_BYTE).sum())
+        return bad
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -512,6 +527,7 @@ def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05,
             assert np.array_equal(sb[pos:pos + ext[3] * es].view(w.dtype), w), ("send payload", bx, r)
             nrows_checked += 1
     log(f"  {nrows_checked} rows of outgoing boxes compared with the send buffer ({time.time() - t0:.1f}s)")
+    assert mem.violations() == 0, "a kernel wrote outside its buffers"
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
@@ -583,6 +599,7 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
             assert mem.all_bytes(back[(r, buf)][n:], SENTINEL), f"round trip wrote the padding of ({r},{buf})"
             same += n
         log(f"  round trip: {same} bytes identical to the source state ({time.time() - t0:.1f}s)")
+    assert mem.violations() == 0, "a kernel wrote outside its buffers"
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 
 
