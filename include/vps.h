@@ -185,6 +185,25 @@ int vps_apply_transition(const vps_plan* plan, int32_t rank, const void* const* 
                          void* const* dst_bufs, void* scratch, uint64_t scratch_bytes,
                          void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): vps_apply_transition for an all-ranks plan with the
+ * staging area (every rank's send buffer) in a device array that is part of the library image
+ * instead of a caller-owned scratch.  The call allocates nothing on the device and frees nothing;
+ * it enqueues the same kernels as vps_apply_transition(plan, -1, ...).
+ *   plan       an all-ranks plan (VPS_ERR_INVALID_ARG for a single-rank plan: its receive buffer
+ *              is filled by the caller and cannot be library memory)
+ *   src_bufs   host array [world_src][8] of device pointers, dst_bufs [world_dst][8]
+ *   limit      scratch_needed of the plan (vps_plan_buffer_bytes, rank = -1) must not exceed
+ *              VPS_STATIC_SCRATCH_BYTES: VPS_ERR_SCRATCH_TOO_SMALL otherwise, nothing enqueued
+ * Every GPU that the library runs on holds its own copy of the array until the process ends.  All
+ * calls on one GPU share that GPU's array, which keeps the previous call's contents (nothing in it
+ * needs clearing: pack writes every byte that unpack reads): calls that overlap on one GPU, on any
+ * streams, race and must be serialised by the caller. */
+#define VPS_STATIC_SCRATCH_BYTES (128ull << 20)
+int vps_apply_transition_static(const vps_plan* plan, const void* const* src_bufs,
+                                void* const* dst_bufs, void* stream);
+uint64_t vps_static_scratch_bytes(void); /* VPS_STATIC_SCRATCH_BYTES of the loaded library */
+
 /* ---- staged exchange among resident ranks ----
  * Algorithm 1 (MemoryAwareChunk and the step loop) and Section 4.3 "Asynchronous Deadlock-Free
  * Communication", for an all-ranks plan.  Steps s = 1 .. 2^ceil(log2 N) - 1 (N = the larger

@@ -117,6 +117,10 @@ class Library:
             "stage_steps": [vp, P(i32), P(u64), i32],
             "apply_transition_staged": [vp, P(vp), P(vp), vp, u64, vp],
         }
+        if prefix == "vps_":
+            # product library only: the entry point that keeps its staging area in a device
+            # array of the library image
+            sig["apply_transition_static"] = [vp, P(vp), P(vp), vp]
         self._fn = {}
         for name, argtypes in sig.items():
             f = getattr(self._dll, prefix + name)
@@ -132,13 +136,19 @@ class Library:
         f.argtypes = []
         f.restype = C.c_char_p
         self._fn["last_error"] = f
+        if prefix == "vps_":
+            f = getattr(self._dll, prefix + "static_scratch_bytes")
+            f.argtypes = []
+            f.restype = C.c_uint64
+            self._fn["static_scratch_bytes"] = f
 
     EXPORTS = ("describe_config", "plan_intersections", "pack", "unpack", "apply_transition",
                "config_world", "config_num_tensors", "config_num_buffers", "config_buffer_bytes", "config_num_pieces",
                "config_get_pieces", "plan_pair_bytes", "plan_peer_bytes", "plan_buffer_bytes",
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
                "set_tile_bytes", "plain_copy", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
-               "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy")
+               "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy",
+               "apply_transition_static", "static_scratch_bytes")
 
     def last_error(self):
         return self._fn["last_error"]().decode()
@@ -174,6 +184,13 @@ class Library:
         self._check(self._fn["apply_transition"](plan._h, rank, _ptr_array(src_bufs, len(src_bufs)),
                                                  _ptr_array(dst_bufs, len(dst_bufs)), scratch,
                                                  scratch_bytes, stream))
+
+    def apply_transition_static(self, plan, src_bufs, dst_bufs, stream=0):
+        self._check(self._fn["apply_transition_static"](plan._h, _ptr_array(src_bufs, len(src_bufs)),
+                                                        _ptr_array(dst_bufs, len(dst_bufs)), stream))
+
+    def static_scratch_bytes(self):
+        return int(self._fn["static_scratch_bytes"]())
 
     def stage_exchange(self, plan, budget_bytes_per_rank, stream=0):
         out = C.c_void_p()
