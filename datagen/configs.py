@@ -12,6 +12,10 @@ parallel: tp, pp, dp, ep degrees.  World size is tp*pp*dp*ep.  ``dp`` is the dat
           qkv_layout 0 = interleaved per kv group, 1 = [all Q | all K | all V] blocks.
           expert_layout 0 = row-major, 1 = transposed storage.
           flat_order 0 = ascending tensor id in the flat buffer, 1 = descending.
+          ep_placement 0 = EP and expert-DP form a grid beside TP (world = tp*pp*dp*ep);
+          1 = EP is carved out of the tp*dp ranks of a pipeline stage (world = tp*pp*dp, experts
+          not TP-sharded, expert data-parallel degree tp*dp/ep), the form of the MoE tuples
+          (TP, PP, DP, EP) in the paper's hybrid reconfiguration table.
 """
 
 FAMILY_GPT = 0
@@ -25,12 +29,15 @@ def model(family, layers, hidden, q_heads, kv_heads, head_dim, ffn, vocab, exper
 
 
 def parallel(tp=1, pp=1, dp=1, ep=1, zero=1, gpus_per_node=8, qkv_layout=0, expert_layout=0,
-             flat_order=0):
+             flat_order=0, ep_placement=0):
     return dict(tp=tp, pp=pp, dp=dp, ep=ep, zero=zero, gpus_per_node=gpus_per_node,
-                qkv_layout=qkv_layout, expert_layout=expert_layout, flat_order=flat_order)
+                qkv_layout=qkv_layout, expert_layout=expert_layout, flat_order=flat_order,
+                ep_placement=ep_placement)
 
 
 def world(p):
+    if p.get("ep_placement", 0) == 1:
+        return p["tp"] * p["pp"] * p["dp"]
     return p["tp"] * p["pp"] * p["dp"] * p["ep"]
 
 

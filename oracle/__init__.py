@@ -21,7 +21,7 @@ class _Model(C.Structure):
 
 class _Parallel(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tp", "pp", "dp", "ep", "zero", "gpus_per_node",
-                                         "qkv_layout", "expert_layout", "flat_order")]
+                                         "qkv_layout", "expert_layout", "flat_order", "ep_placement")]
 
 
 _lib = None
@@ -73,6 +73,10 @@ def lib():
     L.orc_send_bytes.argtypes = [vp, vp, i32, u32, pu64]
     L.orc_check_boxes.restype = i64
     L.orc_check_boxes.argtypes = [vp, vp, pi32, pi64, i64, i32, pi64]
+    L.orc_piece_key.restype = C.c_int
+    L.orc_piece_key.argtypes = [vp, i32, i32, u64, pi64]
+    L.orc_recv_payload.restype = i64
+    L.orc_recv_payload.argtypes = [vp, vp, i32, C.c_int, u64, u64, C.c_uint8, vp, u64, pu64]
     L.orc_num_threads.restype = C.c_int
     L.orc_set_num_threads.argtypes = [C.c_int]
     L.orc_set_num_threads.restype = None
@@ -126,9 +130,9 @@ class Config:
         return dict(shape=tuple(shape), tp_axis=info[0], group=info[1], layer=info[2], expert=info[3])
 
     def rank_coords(self, rank):
-        o = (C.c_int32 * 5)()
+        o = (C.c_int32 * 6)()
         lib().orc_rank_coords(self._h, rank, o)
-        return dict(tp=o[0], ddp=o[1], pp=o[2], ep=o[3], edp=o[4])
+        return dict(tp=o[0], ddp=o[1], pp=o[2], ep=o[3], edp=o[4], etp=o[5])
 
     def buffer_elems(self, rank, buf):
         return lib().orc_buffer_elems(self._h, rank, buf)
@@ -152,6 +156,14 @@ class Config:
         o = (C.c_uint64 * max_owners)()
         n = lib().orc_owners(self._h, kind, tensor, cd, max_owners, r, b, o)
         return [(r[k], b[k], o[k]) for k in range(n)]
+
+    def piece_key(self, rank, buf, off):
+        """(storage block, level, parent unit) of the piece that holds a stored element, None for padding."""
+        o = (C.c_int64 * 3)()
+        r = lib().orc_piece_key(self._h, rank, buf, off, o)
+        if r < 0:
+            raise IndexError("offset outside buffer or element without a piece")
+        return tuple(o) if r == 1 else None
 
     def linear(self, tensor, coord):
         cd = (C.c_int32 * 4)(*coord)
@@ -199,6 +211,24 @@ def transition(a, b, j, buf, src_bufs, dst, off0=0):
     if rc:
         raise OracleError("transition(): missing source buffer or bad range")
     return dst
+
+
+def recv_payload(a, b, j, seed, rank_salt=0, through=False, pad_byte=0xA5):
+    """The receive buffer of destination rank j as its sources must have packed it (uint8 array)
+    and seg_off[world_A + 1]: segment of source i = bytes [seg_off[i], seg_off[i + 1])."""
+    cap = sum(b.buffer_elems(j, buf) * KIND_BYTES[buf % 4] + 16 * 0 for buf in range(NBUF))
+    cap = cap + 16 * (1 << 16)   # room for the alignment pad of up to 65536 boxes
+    seg = np.zeros(a.world + 1, dtype=np.uint64)
+    while True:
+        out = np.empty(int(cap), dtype=np.uint8)
+        n = lib().orc_recv_payload(a._h, b._h, j, int(bool(through)), seed, rank_salt, pad_byte, out.ctypes.data,
+                                   cap, seg.ctypes.data_as(C.POINTER(C.c_uint64)))
+        if n == -3:
+            cap *= 2
+            continue
+        if n < 0:
+            raise OracleError(f"recv_payload failed ({n})")
+        return out[:n].copy(), seg
 
 
 def route_bytes(a, b, j, buf_mask=0xFF):

@@ -7,7 +7,12 @@
  * ZeRO offsets are positions in the flattened parameter order of the data-parallel group.)
  *
  * Conventions where the paper is silent (each is a declared reading of this repository):
- *   rank order      g = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp, DDP = EP*DP
+ *   rank order      g = tp + TP*(ddp + DDP*pp); the expert group sees the same ranks as
+ *                   g = etp + ETP*(ep + EP*(edp + EDP*pp)) with ETP*EP*EDP = TP*DDP.
+ *                   ep_placement 0: EP and expert-DP form a grid beside TP (ETP = TP, EDP = DP,
+ *                   DDP = EP*DP, world = TP*PP*DP*EP); ep_placement 1: EP is carved out of the
+ *                   TP x DP ranks of a stage (ETP = 1, DDP = DP, EDP = TP*DP/EP, world =
+ *                   TP*PP*DP), as in the MoE rows of the paper's hybrid reconfiguration table
  *   pipeline split  stage p owns layers [floor(p*L/PP), floor((p+1)*L/PP)); embedding on the
  *                   first stage, final norm and output layer on the last, untied
  *   flat buffer     per rank one dense and one expert group; local shards concatenated in
@@ -16,6 +21,7 @@
  */
 #include "vps_oracle.h"
 
+#include <limits.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -54,7 +60,8 @@ struct orc_config {
     orc_parallel p;
     int32_t nt;
     tensor_t* t;
-    int32_t ddp;      /* dense data-parallel degree = dp*ep */
+    int32_t ddp;      /* dense data-parallel degree */
+    int32_t etp, edp; /* tensor- and data-parallel degree of the expert group */
     int32_t q_per_g;  /* query heads per kv group */
     int32_t ncls[2];  /* classes per group: dense pp, expert pp*ep */
     class_t* cls[2];
@@ -181,11 +188,18 @@ orc_config* orc_config_create(const orc_model* m, const orc_parallel* p, char* e
     if (m->kv_heads % p->tp) FAIL("tp %d does not divide kv groups %d", p->tp, m->kv_heads);
     if (m->vocab % p->tp) FAIL("tp %d does not divide vocab %d", p->tp, m->vocab);
     if (m->family != ORC_FAMILY_MOE && m->ffn % p->tp) FAIL("tp %d does not divide ffn %d", p->tp, m->ffn);
-    if (m->family == ORC_FAMILY_MOE && m->expert_ffn % p->tp) FAIL("tp %d does not divide expert_ffn %d", p->tp, m->expert_ffn);
+    if (m->family == ORC_FAMILY_MOE && p->ep_placement == 0 && m->expert_ffn % p->tp)
+        FAIL("tp %d does not divide expert_ffn %d", p->tp, m->expert_ffn);
     if (m->family == ORC_FAMILY_MOE && m->experts % p->ep) FAIL("ep %d does not divide experts %d", p->ep, m->experts);
     if (p->pp > m->layers) FAIL("pp %d exceeds layers %d", p->pp, m->layers);
     if (p->zero != 0 && p->zero != 1) FAIL("zero stage must be 0 or 1");
-    c->ddp = p->dp * p->ep;
+    if (p->ep_placement != 0 && p->ep_placement != 1) FAIL("ep_placement must be 0 or 1");
+    if (p->ep_placement == 0) {
+        c->ddp = p->dp * p->ep; c->etp = p->tp; c->edp = p->dp;
+    } else {
+        if ((p->tp * p->dp) % p->ep) FAIL("ep %d does not divide tp*dp = %d", p->ep, p->tp * p->dp);
+        c->ddp = p->dp; c->etp = 1; c->edp = p->tp * p->dp / p->ep;
+    }
     c->q_per_g = m->q_heads / m->kv_heads;
     build_inventory(c);
 
@@ -197,7 +211,7 @@ orc_config* orc_config_create(const orc_model* m, const orc_parallel* p, char* e
         tensor_t* x = &c->t[t];
         int pp = stage_of_layer(c, x->layer);
         x->cls = x->group == 0 ? pp : pp * p->ep + ep_of_expert(c, x->expert);
-        x->shard_len = numel4(x->shape) / (uint64_t)(x->tp_axis >= 0 ? p->tp : 1);
+        x->shard_len = numel4(x->shape) / (uint64_t)(x->tp_axis >= 0 ? (x->group ? c->etp : p->tp) : 1);
         c->cls[x->group][x->cls].n++;
     }
     for (int g = 0; g < 2; ++g)
@@ -221,7 +235,7 @@ orc_config* orc_config_create(const orc_model* m, const orc_parallel* p, char* e
         for (int k = 0; k < c->ncls[g]; ++k) {
             class_t* cl = &c->cls[g][k];
             cl->start[cl->n] = cl->len;
-            uint64_t q = 8ull * (uint64_t)(g == 0 ? c->ddp : p->dp);
+            uint64_t q = 8ull * (uint64_t)(g == 0 ? c->ddp : c->edp);
             cl->padded = (cl->len + q - 1) / q * q;
         }
     return c;
@@ -263,9 +277,11 @@ uint64_t orc_total_params(const orc_config* c)
 
 void orc_rank_coords(const orc_config* c, int32_t rank, int32_t* o)
 {
-    const int TP = c->p.tp, DDP = c->ddp, EP = c->p.ep;
+    const int TP = c->p.tp, DDP = c->ddp, EP = c->p.ep, ETP = c->etp;
     int tp = rank % TP, ddp = (rank / TP) % DDP, pp = rank / (TP * DDP);
-    o[0] = tp; o[1] = ddp; o[2] = pp; o[3] = ddp % EP; o[4] = ddp / EP;
+    int q = rank % (TP * DDP); /* position inside the pipeline stage */
+    o[0] = tp; o[1] = ddp; o[2] = pp;
+    o[5] = q % ETP; o[3] = (q / ETP) % EP; o[4] = q / (ETP * EP);
 }
 
 static int rank_of(const orc_config* c, int tp, int ddp, int pp)
@@ -273,17 +289,22 @@ static int rank_of(const orc_config* c, int tp, int ddp, int pp)
     return tp + c->p.tp * (ddp + c->ddp * pp);
 }
 
+static int rank_of_expert(const orc_config* c, int etp, int ep, int edp, int pp)
+{
+    return etp + c->etp * (ep + c->p.ep * (edp + c->edp * pp));
+}
+
 /* The flat buffer that (rank, group) sees, its data-parallel group size and the rank's index
  * in that group. */
 static const class_t* class_of_rank(const orc_config* c, int rank, int group, int* D, int* didx)
 {
-    int rc[5];
+    int rc[6];
     orc_rank_coords(c, rank, rc);
     if (group == 0) {
         *D = c->ddp; *didx = rc[1];
         return &c->cls[0][rc[2]];
     }
-    *D = c->p.dp; *didx = rc[4];
+    *D = c->edp; *didx = rc[4];
     return &c->cls[1][rc[2] * c->p.ep + rc[3]];
 }
 
@@ -320,7 +341,7 @@ static void shard_of(const orc_config* c, const tensor_t* x, int tp, shard_t* s)
 {
     for (int a = 0; a < 4; ++a) { s->lo[a] = 0; s->ext[a] = x->shape[a]; }
     if (x->tp_axis >= 0) {
-        s->ext[x->tp_axis] = x->shape[x->tp_axis] / c->p.tp;
+        s->ext[x->tp_axis] = x->shape[x->tp_axis] / (x->group ? c->etp : c->p.tp);
         s->lo[x->tp_axis] = tp * s->ext[x->tp_axis];
     }
     s->blk_axis = x->blk_axis;
@@ -342,23 +363,39 @@ static void shard_of(const orc_config* c, const tensor_t* x, int tp, shard_t* s)
     }
 }
 
-/* shard-local storage index of global coordinate cd (must lie inside the shard) */
-static uint64_t shard_index(const shard_t* s, const int32_t* cd)
+/* Where global coordinate cd (inside the shard) is stored: the storage block, the block's
+ * offset in the shard, the row-major index u inside the block and the block's dimensions n in
+ * storage order (outermost first). */
+static void shard_locate(const shard_t* s, const int32_t* cd, int* blk, uint64_t* base, uint64_t* u,
+                         uint64_t* n)
 {
     int32_t rel[4], e[4];
     for (int a = 0; a < 4; ++a) { rel[a] = cd[a] - s->lo[a]; e[a] = s->ext[a]; }
-    uint64_t base = 0;
+    *base = 0;
     int k = 0;
     for (; k < s->nblk; ++k) {
         if (rel[s->blk_axis] >= s->blo[k] && rel[s->blk_axis] < s->blo[k] + s->blen[k]) break;
         int32_t ee[4] = { e[0], e[1], e[2], e[3] };
         ee[s->blk_axis] = s->blen[k];
-        base += numel4(ee);
+        *base += numel4(ee);
     }
     rel[s->blk_axis] -= s->blo[k];
     e[s->blk_axis] = s->blen[k];
-    uint64_t u = 0;
-    for (int q = 0; q < 4; ++q) { int a = s->order[q]; u = u * (uint64_t)e[a] + (uint64_t)rel[a]; }
+    *u = 0;
+    for (int q = 0; q < 4; ++q) {
+        int a = s->order[q];
+        *u = *u * (uint64_t)e[a] + (uint64_t)rel[a];
+        n[q] = (uint64_t)e[a];
+    }
+    *blk = k;
+}
+
+/* shard-local storage index of global coordinate cd (must lie inside the shard) */
+static uint64_t shard_index(const shard_t* s, const int32_t* cd)
+{
+    int blk;
+    uint64_t base, u, n[4];
+    shard_locate(s, cd, &blk, &base, &u, n);
     return base + u;
 }
 
@@ -405,10 +442,10 @@ int orc_coord(const orc_config* c, int32_t rank, int32_t buf, uint64_t off, int3
         if (cl->start[mid] <= f) lo = mid; else hi = mid - 1;
     }
     const int t = cl->tid[lo];
-    int rc[5];
+    int rc[6];
     orc_rank_coords(c, rank, rc);
     shard_t s;
-    shard_of(c, &c->t[t], rc[0], &s);
+    shard_of(c, &c->t[t], group == 0 ? rc[0] : rc[5], &s);
     shard_coord(&s, f - cl->start[lo], coord);
     *tensor = t;
     return 1;
@@ -418,10 +455,10 @@ int orc_owners(const orc_config* c, int32_t kind, int32_t tensor, const int32_t*
                int32_t* ranks, int32_t* bufs, uint64_t* offs)
 {
     const tensor_t* x = &c->t[tensor];
-    const int TP = c->p.tp, EP = c->p.ep;
+    const int TP = x->group == 0 ? c->p.tp : c->etp;
     const int pp = stage_of_layer(c, x->layer);
     const class_t* cl = &c->cls[x->group][x->cls];
-    const int D = x->group == 0 ? c->ddp : c->p.dp;
+    const int D = x->group == 0 ? c->ddp : c->edp;
     int tp_lo = 0, tp_hi = TP;
     if (x->tp_axis >= 0) {
         tp_lo = coord[x->tp_axis] / (x->shape[x->tp_axis] / TP);
@@ -439,9 +476,9 @@ int orc_owners(const orc_config* c, int32_t kind, int32_t tensor, const int32_t*
                 if (f / per != (uint64_t)di) continue;
                 off = f - per * (uint64_t)di;
             }
-            int ddp = x->group == 0 ? di : ep_of_expert(c, x->expert) + EP * di;
             if (n < max) {
-                ranks[n] = rank_of(c, tp, ddp, pp);
+                ranks[n] = x->group == 0 ? rank_of(c, tp, di, pp)
+                                         : rank_of_expert(c, tp, ep_of_expert(c, x->expert), di, pp);
                 bufs[n] = x->group * 4 + kind;
                 offs[n] = off;
             }
@@ -481,7 +518,7 @@ int orc_select_source(const orc_config* a, const orc_config* b, int32_t j, int32
             if (r[k] / a->p.gpus_per_node == node) idx[m++] = k;
         if (m == 0)
             for (int k = 0; k < n; ++k) idx[m++] = k;
-        int rc[5];
+        int rc[6];
         orc_rank_coords(b, j, rc);
         const int dpi = b->t[tensor].group == 0 ? rc[1] : rc[4];
         pick = idx[dpi % m];
@@ -623,6 +660,260 @@ int orc_send_bytes(const orc_config* a, const orc_config* b, int32_t i, uint32_t
         }
     }
     return bad ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------ per-peer buffers */
+
+/* The order of data inside a per-peer buffer (Algorithm 1, PackData; Section 4.3 "Memory-Aware
+ * Contiguous Buffer") is a convention of this repository, the paper leaves it open:
+ *
+ *   A rank stores, per tensor and storage block, one contiguous stretch [v0, v1) of the block's
+ *   row-major storage (its flat range clipped to the block).  A stored element belongs to the
+ *   coarsest aligned unit of that storage (an element, a row, a plane, ...) that lies completely
+ *   inside [v0, v1); the units of one level under one parent unit form a *piece*, which is an
+ *   axis-aligned box of the logical tensor.  The elements that travel from rank i to rank j and
+ *   share a piece of i and a piece of j form a *routed box*.  Inside the segment i -> j the
+ *   routed boxes are ordered by (state kind 1, 2, 3, 0; tensor id; lo corner in row-major order
+ *   of the unsharded tensor); every box is serialised row-major in global axis order and starts
+ *   at a multiple of 16 bytes.  A rank's receive buffer is the concatenation of the segments of
+ *   its sources in ascending rank order, its send buffer that of its destinations. */
+
+typedef struct {
+    int32_t blk, level;
+    uint64_t parent;
+} piece_key_t;
+
+/* The piece of `rank` that holds element (kind, tensor, cd); 0 if the rank does not store it. */
+static int piece_of(const orc_config* c, int rank, int kind, int tensor, const int32_t* cd,
+                    piece_key_t* k)
+{
+    const tensor_t* x = &c->t[tensor];
+    int rc[6], D, didx;
+    orc_rank_coords(c, rank, rc);
+    shard_t s;
+    shard_of(c, x, x->group == 0 ? rc[0] : rc[5], &s);
+    for (int a = 0; a < 4; ++a)
+        if (cd[a] < s.lo[a] || cd[a] >= s.lo[a] + s.ext[a]) return 0;
+    int blk;
+    uint64_t base, u, n[4];
+    shard_locate(&s, cd, &blk, &base, &u, n);
+    const class_t* cl = class_of_rank(c, rank, x->group, &D, &didx);
+    if (cl != &c->cls[x->group][x->cls]) return 0; /* another pipeline stage or expert block */
+    uint64_t r0 = 0, r1 = cl->padded;
+    if (kind_sharded(c, kind)) {
+        const uint64_t per = cl->padded / (uint64_t)D;
+        r0 = per * (uint64_t)didx;
+        r1 = r0 + per;
+    }
+    /* the rank's flat range, clipped to this block and relative to it */
+    const uint64_t b0 = x->start + base, b1 = b0 + n[0] * n[1] * n[2] * n[3];
+    const uint64_t lo = r0 > b0 ? r0 : b0, hi = r1 < b1 ? r1 : b1;
+    if (lo >= hi) return 0;
+    const uint64_t v0 = lo - b0, v1 = hi - b0;
+    if (u < v0 || u >= v1) return 0;
+    uint64_t st[4];
+    st[3] = 1; st[2] = n[3]; st[1] = n[3] * n[2]; st[0] = n[3] * n[2] * n[1];
+    int q = 0;
+    for (; q < 3; ++q) {
+        const uint64_t unit = u / st[q] * st[q];
+        if (unit >= v0 && unit + st[q] <= v1) break;
+    }
+    k->blk = blk;
+    k->level = q;
+    k->parent = q == 0 ? 0 : u / st[q - 1];
+    return 1;
+}
+
+int orc_piece_key(const orc_config* c, int32_t rank, int32_t buf, uint64_t off, int64_t* out3)
+{
+    int32_t t, cd[4];
+    const int r = orc_coord(c, rank, buf, off, &t, cd);
+    if (r <= 0) return r;
+    piece_key_t k;
+    if (!piece_of(c, rank, buf % 4, t, cd, &k)) return -2;
+    out3[0] = k.blk; out3[1] = k.level; out3[2] = (int64_t)k.parent;
+    return 1;
+}
+
+typedef struct {
+    int32_t src, kind, tensor, ablk, alevel, bblk, blevel;
+    uint64_t aparent, bparent;
+} box_id_t;
+
+typedef struct {
+    box_id_t id;
+    int32_t used;
+    int32_t lo[4], hi[4]; /* componentwise smallest and largest coordinate seen */
+    uint64_t count;       /* elements seen */
+    uint64_t lin_lo;      /* row-major index of the lo corner in the unsharded tensor */
+    uint64_t pos;         /* byte position of the box in the receive buffer */
+} box_acc_t;
+
+typedef struct {
+    box_acc_t* e;
+    size_t cap, n;
+} box_table_t;
+
+static int box_id_equal(const box_id_t* a, const box_id_t* b)
+{
+    return a->src == b->src && a->kind == b->kind && a->tensor == b->tensor && a->ablk == b->ablk &&
+           a->alevel == b->alevel && a->bblk == b->bblk && a->blevel == b->blevel &&
+           a->aparent == b->aparent && a->bparent == b->bparent;
+}
+
+static uint64_t box_id_hash(const box_id_t* a)
+{
+    uint64_t h = vps_pattern_mix64((uint64_t)a->src, (uint32_t)a->kind, (uint32_t)a->tensor, a->aparent);
+    h = vps_pattern_mix64(h, (uint32_t)(a->ablk * 4 + a->alevel), (uint32_t)(a->bblk * 4 + a->blevel), a->bparent);
+    return h;
+}
+
+static box_acc_t* box_find(box_table_t* t, const box_id_t* id, int insert);
+
+static void box_grow(box_table_t* t)
+{
+    box_table_t old = *t;
+    t->cap = old.cap ? old.cap * 2 : 256;
+    t->e = (box_acc_t*)calloc(t->cap, sizeof(box_acc_t));
+    t->n = 0;
+    for (size_t i = 0; i < old.cap; ++i)
+        if (old.e[i].used) *box_find(t, &old.e[i].id, 1) = old.e[i];
+    free(old.e);
+}
+
+static box_acc_t* box_find(box_table_t* t, const box_id_t* id, int insert)
+{
+    if (insert && (t->n + 1) * 2 > t->cap) box_grow(t);
+    if (!t->cap) return NULL;
+    size_t i = (size_t)box_id_hash(id) & (t->cap - 1);
+    while (t->e[i].used) {
+        if (box_id_equal(&t->e[i].id, id)) return &t->e[i];
+        i = (i + 1) & (t->cap - 1);
+    }
+    if (!insert) return NULL;
+    box_acc_t* e = &t->e[i];
+    e->id = *id;
+    e->used = 1;
+    e->count = 0;
+    for (int a = 0; a < 4; ++a) { e->lo[a] = INT32_MAX; e->hi[a] = INT32_MIN; }
+    t->n++;
+    return e;
+}
+
+static void box_absorb(box_acc_t* e, const int32_t* lo, const int32_t* hi, uint64_t count)
+{
+    for (int a = 0; a < 4; ++a) {
+        if (lo[a] < e->lo[a]) e->lo[a] = lo[a];
+        if (hi[a] > e->hi[a]) e->hi[a] = hi[a];
+    }
+    e->count += count;
+}
+
+/* The routed box of destination slot (j, buf, off): 1 and id filled if the element travels
+ * (or stays, when `through` routes retained data through the buffers too), 0 otherwise. */
+static int routed_box_of(const orc_config* a, const orc_config* b, int j, int buf, uint64_t off,
+                         int through, box_id_t* id, int32_t* cd)
+{
+    int32_t t, sr, sb;
+    uint64_t so;
+    if (orc_coord(b, j, buf, off, &t, cd) != 1) return 0;
+    const int kind = buf % 4;
+    if (!orc_select_source(a, b, j, kind, t, cd, &sr, &sb, &so)) return -1;
+    if (sr == j && !through) return 0;
+    piece_key_t ka, kb;
+    if (!piece_of(a, sr, kind, t, cd, &ka) || !piece_of(b, j, kind, t, cd, &kb)) return -1;
+    id->src = sr; id->kind = kind; id->tensor = t;
+    id->ablk = ka.blk; id->alevel = ka.level; id->aparent = ka.parent;
+    id->bblk = kb.blk; id->blevel = kb.level; id->bparent = kb.parent;
+    return 1;
+}
+
+static int box_order(const void* pa, const void* pb)
+{
+    const box_acc_t* x = *(box_acc_t* const*)pa;
+    const box_acc_t* y = *(box_acc_t* const*)pb;
+    if (x->id.src != y->id.src) return x->id.src < y->id.src ? -1 : 1;
+    const int kx = (x->id.kind + 3) & 3, ky = (y->id.kind + 3) & 3; /* kinds 1, 2, 3, then 0 */
+    if (kx != ky) return kx < ky ? -1 : 1;
+    if (x->id.tensor != y->id.tensor) return x->id.tensor < y->id.tensor ? -1 : 1;
+    if (x->lin_lo != y->lin_lo) return x->lin_lo < y->lin_lo ? -1 : 1;
+    return 0;
+}
+
+int64_t orc_recv_payload(const orc_config* a, const orc_config* b, int32_t j, int through,
+                         uint64_t seed, uint64_t rank_salt, uint8_t pad_byte, void* out,
+                         uint64_t cap, uint64_t* seg_off)
+{
+    const int WA = orc_world(a);
+    box_table_t all = { NULL, 0, 0 };
+    int bad = 0;
+    /* pass 1: which routed boxes exist, their corners and element counts */
+#pragma omp parallel
+    {
+        box_table_t mine = { NULL, 0, 0 };
+        for (int buf = 0; buf < ORC_NBUF; ++buf) {
+            const int64_t n = (int64_t)orc_buffer_elems(b, j, buf);
+#pragma omp for schedule(static) reduction(| : bad)
+            for (int64_t k = 0; k < n; ++k) {
+                box_id_t id;
+                int32_t cd[4];
+                const int r = routed_box_of(a, b, j, buf, (uint64_t)k, through, &id, cd);
+                if (r < 0) bad = 1;
+                if (r <= 0) continue;
+                box_absorb(box_find(&mine, &id, 1), cd, cd, 1);
+            }
+        }
+#pragma omp critical
+        for (size_t i = 0; i < mine.cap; ++i)
+            if (mine.e[i].used) box_absorb(box_find(&all, &mine.e[i].id, 1), mine.e[i].lo, mine.e[i].hi, mine.e[i].count);
+        free(mine.e);
+    }
+    if (bad) { free(all.e); return -1; }
+    /* order and positions */
+    box_acc_t** ord = (box_acc_t**)malloc(sizeof(box_acc_t*) * (all.n ? all.n : 1));
+    size_t nb = 0;
+    for (size_t i = 0; i < all.cap; ++i) {
+        box_acc_t* e = &all.e[i];
+        if (!e->used) continue;
+        uint64_t vol = 1;
+        for (int ax = 0; ax < 4; ++ax) vol *= (uint64_t)(e->hi[ax] - e->lo[ax] + 1);
+        if (vol != e->count) bad = 1; /* the elements of a piece pair must fill their bounding box */
+        e->lin_lo = orc_linear(a, e->id.tensor, e->lo);
+        ord[nb++] = e;
+    }
+    qsort(ord, nb, sizeof(box_acc_t*), box_order);
+    uint64_t pos = 0;
+    size_t k = 0;
+    for (int i = 0; i <= WA; ++i) {
+        if (seg_off) seg_off[i] = pos;
+        for (; k < nb && ord[k]->id.src == i; ++k) {
+            ord[k]->pos = pos;
+            pos += (ord[k]->count * (ord[k]->id.kind == 0 ? 2u : 4u) + 15u) & ~(uint64_t)15;
+        }
+    }
+    free(ord);
+    if (bad || pos > cap) { free(all.e); return bad ? -2 : -3; }
+    memset(out, pad_byte, (size_t)pos);
+    /* pass 2: every travelling element to its place in its box */
+    for (int buf = 0; buf < ORC_NBUF; ++buf) {
+        const int64_t n = (int64_t)orc_buffer_elems(b, j, buf);
+#pragma omp parallel for schedule(static) reduction(| : bad)
+        for (int64_t q = 0; q < n; ++q) {
+            box_id_t id;
+            int32_t cd[4];
+            if (routed_box_of(a, b, j, buf, (uint64_t)q, through, &id, cd) <= 0) continue;
+            const box_acc_t* e = box_find(&all, &id, 0);
+            if (!e) { bad = 1; continue; }
+            uint64_t idx = 0; /* row-major index inside the box, global axis order */
+            for (int ax = 0; ax < 4; ++ax) idx = idx * (uint64_t)(e->hi[ax] - e->lo[ax] + 1) + (uint64_t)(cd[ax] - e->lo[ax]);
+            const uint64_t sd = vps_pattern_seed_for_rank(seed, rank_salt, (uint32_t)id.src);
+            const uint32_t w = vps_pattern_word(sd, (uint32_t)id.kind, (uint32_t)id.tensor, orc_linear(a, id.tensor, cd));
+            if (id.kind == 0) ((uint16_t*)((char*)out + e->pos))[idx] = (uint16_t)w;
+            else ((uint32_t*)((char*)out + e->pos))[idx] = w;
+        }
+    }
+    free(all.e);
+    return bad ? -1 : (int64_t)pos;
 }
 
 /* ------------------------------------------------------------------ box validation */

@@ -22,8 +22,9 @@
  * an independent assemble-then-slice reshard in numpy, identity and round-trip transitions,
  * closed-form byte counts, the Figure 4 worked example, parameter counts.
  * parity unpinned: the replica source rule (orc_select_source) and the order of elements
- * inside a per-peer buffer are conventions of this repository; the paper only says that the
- * source is chosen by proximity (Section 4.3) and that slices are packed per peer.
+ * inside a per-peer buffer (orc_piece_key, orc_recv_payload) are conventions of this repository;
+ * the paper only says that the source is chosen by proximity (Section 4.3) and that slices are
+ * packed per peer.  They are checked against a second, box-based formulation in numpy.
  */
 #ifndef VPS_ORACLE_H
 #define VPS_ORACLE_H
@@ -48,6 +49,9 @@ typedef struct {
     int32_t qkv_layout;    /* 0 interleaved, 1 blocked [Q|K|V] */
     int32_t expert_layout; /* 0 row-major, 1 transposed storage */
     int32_t flat_order;    /* 0 ascending tensor id, 1 descending */
+    int32_t ep_placement;  /* 0: world = tp*pp*dp*ep, experts TP-sharded, dp = expert data-parallel
+                              degree; 1: EP carved out of the tp*dp ranks of a stage (world =
+                              tp*pp*dp), experts not TP-sharded, expert dp = tp*dp/ep */
 } orc_parallel;
 
 typedef struct orc_config orc_config;
@@ -63,8 +67,8 @@ void orc_tensor_info(const orc_config* c, int32_t t, int32_t* shape, int32_t* in
 uint64_t orc_tensor_numel(const orc_config* c, int32_t t);
 uint64_t orc_total_params(const orc_config* c);
 
-/* rank -> {tp, dense dp index, pp, ep, expert dp index} */
-void orc_rank_coords(const orc_config* c, int32_t rank, int32_t* out5);
+/* rank -> {tp, dense dp index, pp, ep, expert dp index, expert tp index} */
+void orc_rank_coords(const orc_config* c, int32_t rank, int32_t* out6);
 
 /* Element counts of local buffer `buf` of `rank`: allocated size and non-padding part. */
 uint64_t orc_buffer_elems(const orc_config* c, int32_t rank, int32_t buf);
@@ -126,6 +130,22 @@ int orc_send_bytes(const orc_config* a, const orc_config* b, int32_t i, uint32_t
  * (0 = valid); first_bad receives the index of the first offending box or -1. */
 int64_t orc_check_boxes(const orc_config* a, const orc_config* b, const int32_t* ints,
                         const int64_t* offs, int64_t nboxes, int32_t samples, int64_t* first_bad);
+
+/* The piece (see vps_oracle.c, "per-peer buffers") of the element stored at (rank, buf, off):
+ * out3 = {storage block, level, parent unit}.  Two stored elements of one (rank, buffer, tensor)
+ * belong to the same piece iff the three numbers agree.  Returns 1, 0 for padding, < 0 on error. */
+int orc_piece_key(const orc_config* c, int32_t rank, int32_t buf, uint64_t off, int64_t* out3);
+
+/* Algorithm 1, PackData / Section 4.3: the receive buffer of destination rank j as its source
+ * ranks must have packed it, i.e. the segments i -> j in ascending i, which are also the
+ * pieces of the senders' send buffers.  Every element comes from the pattern of its selected
+ * source (orc_fill with the same seed and rank_salt); pad bytes between boxes are pad_byte.
+ * seg_off[0..world_A] receives the byte offset of every source's segment (seg_off[world_A] =
+ * total).  through != 0 also routes the data that stays on rank j through its own segment.
+ * Returns the number of bytes, or < 0 (-3: cap too small). */
+int64_t orc_recv_payload(const orc_config* a, const orc_config* b, int32_t j, int through,
+                         uint64_t seed, uint64_t rank_salt, uint8_t pad_byte, void* out,
+                         uint64_t cap, uint64_t* seg_off);
 
 int orc_num_threads(void);
 void orc_set_num_threads(int n);

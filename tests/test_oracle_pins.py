@@ -34,6 +34,14 @@ LAYOUT_CASES = [
     ("moe-odd-tp2ep2dp3-blocked-transposed", cf.ODD_MOE, P(tp=2, pp=3, dp=3, ep=2, zero=1, qkv_layout=1, expert_layout=1)),
 ]
 
+# EP carved out of the TP x DP ranks of a stage (the form of the paper's MoE strategy tuples)
+LAYOUT_CASES += [
+    ("moe-carved-tp2dp2ep4", cf.TINY_MOE, P(tp=2, pp=2, dp=2, ep=4, zero=1, ep_placement=1)),
+    ("moe-carved-tp4dp1ep2-transposed", cf.TINY_MOE, P(tp=4, pp=1, dp=1, ep=2, zero=1, expert_layout=1, ep_placement=1)),
+    ("moe-odd-carved-tp2dp3ep3-z0", cf.ODD_MOE, P(tp=2, pp=1, dp=3, ep=3, zero=0, ep_placement=1)),
+    ("moe-odd-carved-tp1dp6ep2-blocked-rev", cf.ODD_MOE, P(tp=1, pp=5, dp=6, ep=2, zero=1, qkv_layout=1, flat_order=1, ep_placement=1)),
+]
+
 TRANSITIONS = [
     ("gpt-zero-to-replicated", cf.TINY_GPT, P(tp=2, dp=2, zero=1), P(tp=1, dp=4, zero=0)),
     ("gpt-tp-pp", cf.TINY_GPT, P(tp=4, pp=2, dp=1), P(tp=2, pp=4, dp=1)),
@@ -45,6 +53,16 @@ TRANSITIONS = [
     ("moe-transposed", cf.TINY_MOE, P(tp=2, pp=2, dp=1, ep=2), P(tp=1, pp=2, dp=2, ep=2, expert_layout=1)),
     ("moe-odd", cf.ODD_MOE, P(tp=1, pp=2, dp=2, ep=3), P(tp=2, pp=1, dp=3, ep=2, expert_layout=1, flat_order=1)),
 ]
+
+
+# Transitions between configurations with EP carved out of TP x DP (and to / from the grid form)
+TRANSITIONS_CARVED = [
+    ("moe-carved-ep-shrinks", cf.TINY_MOE, P(tp=4, pp=2, dp=1, ep=4, ep_placement=1), P(tp=2, pp=1, dp=4, ep=2, ep_placement=1)),
+    ("moe-carved-ep-grows", cf.TINY_MOE, P(tp=2, pp=2, dp=2, ep=2, ep_placement=1), P(tp=4, pp=4, dp=1, ep=4, ep_placement=1, expert_layout=1)),
+    ("moe-grid-to-carved", cf.TINY_MOE, P(tp=2, pp=2, dp=1, ep=2), P(tp=2, pp=1, dp=4, ep=8, ep_placement=1)),
+    ("moe-odd-carved", cf.ODD_MOE, P(tp=2, pp=1, dp=3, ep=3, ep_placement=1), P(tp=1, pp=5, dp=2, ep=2, ep_placement=1, flat_order=1)),
+]
+ALL_TRANSITIONS = TRANSITIONS + TRANSITIONS_CARVED
 
 
 def _golden():
@@ -122,7 +140,7 @@ def test_fill_equals_textbook_layout(name, m, p):
     """coord_P against numpy slicing, every slot of every rank and buffer."""
     c = oracle.Config(m, p)
     layout = textbook.address_layout(m, p)
-    assert c.world == cf.world(p)
+    assert c.world == cf.world(p) == textbook.degrees(p)[6]
     seed = 0xABCDEF
     for rank in range(c.world):
         for buf in range(8):
@@ -148,14 +166,16 @@ def test_owners_is_inverse_of_coord_bruteforce(name, m, p):
     for (rank, buf), (tid, lin) in layout.items():
         for pos in np.nonzero(tid >= 0)[0]:
             slots.setdefault((buf % 4, int(tid[pos]), int(lin[pos])), []).append((rank, buf, int(pos)))
-    DDP = p["dp"] * p["ep"]
+    TP, PP, DDP, EP, ETP, EDP, world = textbook.degrees(p)
+    assert c.world == world
     total = 0
     for t in range(c.num_tensors):
         info = c.tensor_info(t)
         shape = info["shape"]
         for kind in range(4):
-            D = DDP if info["group"] == 0 else p["dp"]
-            replicas = (p["tp"] if info["tp_axis"] < 0 else 1) * (1 if (kind and p["zero"]) else D)
+            D = DDP if info["group"] == 0 else EDP
+            T = TP if info["group"] == 0 else ETP
+            replicas = (T if (info["tp_axis"] < 0 or T == 1) else 1) * (1 if (kind and p["zero"]) else D)
             step = 1 if kind in (0, 1) else 7  # kinds 2, 3 behave like kind 1: sample them
             for lin_idx in range(0, int(np.prod(shape)), step):
                 cd = np.unravel_index(lin_idx, shape)
@@ -195,7 +215,7 @@ def _oracle_transition_all(a, b, src):
     return out
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_transition_equals_assemble_then_slice(name, m, pa, pb):
     """The per-element transition against the textbook reshard: gather every logical tensor
     from the source shards, cut it again for the destination configuration."""
@@ -213,7 +233,7 @@ def test_transition_equals_assemble_then_slice(name, m, pa, pb):
         assert np.array_equal(got[key], want[key]), key
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_expected_is_layout_b_fill_and_roundtrip(name, m, pa, pb):
     """With coordinate-hash payloads: A->B gives the layout-B fill; A->B->A is the identity."""
     a, b = oracle.Config(m, pa), oracle.Config(m, pb)
@@ -248,7 +268,7 @@ def test_identity_transition_moves_nothing(name, m, p):
         assert sb[j] == pay and sb.sum() == pay
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_send_and_receive_byte_counts_agree(name, m, pa, pb):
     """Buffer byte counts match on both sides: what i sends to j is what j takes from i, the
     received plus retained volume is the destination payload."""
@@ -261,7 +281,7 @@ def test_send_and_receive_byte_counts_agree(name, m, pa, pb):
         assert recv[j].sum() == pay
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_region_algebra_and_selection_rule(name, m, pa, pb):
     """Section 4.2.1: per rank, T_retain = R_src & R_dst is exactly what is copied locally,
     T_recv = R_dst - R_src is exactly what arrives from peers, T_send = R_src - R_dst never
@@ -469,3 +489,156 @@ def test_boxfill_generator_matches_numpy_pattern():
         idx = np.arange(int(np.prod(shape)), dtype=np.uint64).reshape(shape)
         idx = idx[lo[0]:lo[0] + ext[0], lo[1]:lo[1] + ext[1], lo[2]:lo[2] + ext[2], lo[3]:lo[3] + ext[3]]
         assert np.array_equal(out, pattern.word(1234, kind, 17, idx.ravel()))
+
+
+# ----------------------------------------------------------------------------- declared readings, worked out by hand
+
+def _declared():
+    import os
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "declared_readings.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = [x.strip() for x in line.split("=")]
+            vals[k] = [int(x) for x in v.split(",")]
+    return vals
+
+
+@pytest.mark.parametrize("layers,pp", [(94, 8), (94, 4), (80, 8), (80, 4), (5, 3), (4, 4)])
+def test_pipeline_split_matches_the_hand_table(layers, pp):
+    """Layers per pipeline stage when the layer count is not a multiple of PP (a declared
+    reading: the paper does not say): read off from where the oracle puts every layer's first
+    tensor, against the table in tests/golden/declared_readings.txt."""
+    want = _declared()[f"stage_sizes_{layers}_layers_pp{pp}"]
+    assert len(want) == pp and sum(want) == layers
+    m = cf.model(cf.FAMILY_GQA, layers, 8, 2, 2, 4, 16, 16)
+    c = oracle.Config(m, P(pp=pp, zero=0))
+    got = [0] * pp
+    for l in range(layers):
+        t = 1 + 6 * l                       # embedding, then six tensors per layer
+        assert c.tensor_info(t)["layer"] == l and c.tensor_info(t - 1)["layer"] == l - 1
+        (rank, _, _), = c.owners(0, t, (0, 0, 0, 0))
+        got[c.rank_coords(rank)["pp"]] += 1
+    assert got == want
+    # embedding on the first stage, final norm and output layer on the last
+    assert c.rank_coords(c.owners(0, 0, (0, 0, 0, 0))[0][0])["pp"] == 0
+    for t in (c.num_tensors - 2, c.num_tensors - 1):
+        assert c.rank_coords(c.owners(0, t, (0, 0, 0, 0))[0][0])["pp"] == pp - 1
+
+
+@pytest.mark.parametrize("experts,ep", [(128, 8), (128, 16), (8, 4), (6, 3)])
+def test_expert_blocks_match_the_hand_table(experts, ep):
+    """Experts are cut over EP in contiguous blocks (declared reading): first expert of every
+    block against the table, both for the grid placement and for EP carved out of TP x DP."""
+    first = _declared()[f"first_expert_of_block_{experts}_experts_ep{ep}"]
+    assert len(first) == ep
+    m = cf.model(cf.FAMILY_MOE, 1, 8, 2, 2, 4, 0, 16, experts=experts, expert_ffn=4)
+    for par in (P(ep=ep, zero=0), P(tp=1, dp=ep, ep=ep, zero=0, ep_placement=1)):
+        c = oracle.Config(m, par)
+        got = {}
+        for e in range(experts):
+            t = 1 + 7 + 2 * e                # embedding, seven dense tensors of layer 0, two tensors per expert
+            assert c.tensor_info(t)["expert"] == e
+            (rank, _, _), = c.owners(0, t, (0, 0, 0, 0))
+            got.setdefault(c.rank_coords(rank)["ep"], []).append(e)
+        assert [min(got[k]) for k in range(ep)] == first
+        assert all(got[k] == list(range(first[k], first[k] + experts // ep)) for k in range(ep))
+
+
+def test_carved_expert_ranks_follow_the_hand_example():
+    """EP carved out of TP x DP, (TP, PP, DP, EP) = (2, 1, 4, 2) on 8 ranks: position q = tp + 2*dp
+    inside the stage, ep = q mod 2, expert data-parallel index = q div 2 (table in
+    tests/golden/declared_readings.txt)."""
+    d = _declared()
+    m = cf.model(cf.FAMILY_MOE, 1, 8, 2, 2, 4, 0, 16, experts=4, expert_ffn=4)
+    c = oracle.Config(m, P(tp=2, pp=1, dp=4, ep=2, ep_placement=1))
+    assert c.world == 8
+    assert [c.rank_coords(r)["ep"] for r in range(8)] == d["carved_tp2_dp4_ep2_ep_of_rank"]
+    assert [c.rank_coords(r)["edp"] for r in range(8)] == d["carved_tp2_dp4_ep2_edp_of_rank"]
+    assert [c.rank_coords(r)["tp"] for r in range(8)] == d["carved_tp2_dp4_ep2_tp_of_rank"]
+    assert [c.rank_coords(r)["ddp"] for r in range(8)] == d["carved_tp2_dp4_ep2_dp_of_rank"]
+
+
+# ----------------------------------------------------------------------------- per-peer buffers
+
+@pytest.mark.parametrize("name,m,p", LAYOUT_CASES, ids=[c[0] for c in LAYOUT_CASES])
+def test_pieces_match_the_box_decomposition(name, m, p):
+    """The oracle's per-element piece rule (coarsest aligned storage unit inside the rank's flat
+    range) against the numpy decomposition of every storage block's range into the fewest boxes:
+    the same partition of every buffer."""
+    c = oracle.Config(m, p)
+    pcs = textbook.pieces(m, p)
+    for rank in range(c.world):
+        for buf in range(8):
+            n = c.buffer_elems(rank, buf)
+            groups = {}
+            for off in range(n):
+                key = c.piece_key(rank, buf, off)
+                if key is not None:
+                    groups.setdefault((c.coord(rank, buf, off)[0],) + key, []).append(off)
+            got = sorted(tuple(v) for v in groups.values())
+            want = sorted(tuple(sorted(offs.tolist())) for _, offs, _ in pcs[(rank, buf)])
+            assert got == want, (rank, buf)
+            # and each piece is an axis-aligned box of its tensor
+            for t, offs, addr in pcs[(rank, buf)]:
+                shape = c.tensor_info(t)["shape"]
+                cd = np.stack(np.unravel_index(addr, shape))
+                assert int(np.prod(cd.max(axis=1) - cd.min(axis=1) + 1)) == addr.size
+
+
+def _box_based_recv_buffer(a, b, m, pa, pb, j, seed, salt, through, pad_byte=0xA5):
+    """The receive buffer of rank j built from boxes: every (source piece x destination piece)
+    intersection whose selected source is that source rank, ordered by (source, kind 1 2 3 0,
+    tensor, lo corner), serialised row-major, 16-byte aligned."""
+    pcs_a, pcs_b = textbook.pieces(m, pa), textbook.pieces(m, pb)
+    by_tensor = {}
+    for (i, buf), lst in pcs_a.items():
+        for t, _, addr in lst:
+            by_tensor.setdefault((buf % 4, t), []).append((i, np.sort(addr)))
+    routed = []
+    for buf in range(8):
+        kind = buf % 4
+        for t, _, addr_b in pcs_b[(j, buf)]:
+            shape = a.tensor_info(t)["shape"]
+            for i, addr_a in by_tensor.get((kind, t), []):
+                x = np.intersect1d(addr_a, addr_b, assume_unique=True)
+                if not x.size:
+                    continue
+                picks = {oracle.select_source(a, b, j, kind, t, [int(v) for v in np.unravel_index(int(e), shape)])[0]
+                         for e in (x[0], x[-1], x[x.size // 2])}
+                assert len(picks) == 1
+                if picks != {i} or (i == j and not through):
+                    continue
+                routed.append((i, (kind + 3) & 3, t, int(x[0]), kind, x))
+    routed.sort(key=lambda r: r[:4])
+    out, seg = [], np.zeros(a.world + 1, dtype=np.uint64)
+    pos = 0
+    for i, _, t, _, kind, x in routed:
+        words = pattern.word(pattern.seed_for_rank(seed, salt, i), kind, t, x.astype(np.uint64))
+        raw = words.astype(np.uint16 if kind == 0 else np.uint32).tobytes()
+        raw += bytes([pad_byte]) * ((-len(raw)) % 16)
+        out.append(raw)
+        pos += len(raw)
+        seg[i + 1:] = pos
+    return np.frombuffer(b"".join(out), dtype=np.uint8), seg
+
+
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
+def test_recv_payload_equals_the_box_based_formulation(name, m, pa, pb):
+    """Algorithm 1, PackData: the per-element construction of a receive buffer against the
+    box-based one; the order inside a buffer is a convention of this repository, stated twice."""
+    a, b = oracle.Config(m, pa), oracle.Config(m, pb)
+    for through in (False, True):
+        for j in range(b.world):
+            got, seg = oracle.recv_payload(a, b, j, seed=31, rank_salt=0x77, through=through)
+            want, wseg = _box_based_recv_buffer(a, b, m, pa, pb, j, 31, 0x77, through)
+            assert np.array_equal(seg, wseg), (j, through)
+            assert np.array_equal(got, want), (j, through)
+            if not through:
+                rb = oracle.route_bytes(a, b, j)
+                for i in range(a.world):
+                    nbytes = int(seg[i + 1] - seg[i])
+                    assert nbytes % 16 == 0
+                    if i != j:
+                        assert int(rb[i]) <= nbytes
+                        assert (nbytes == 0) == (rb[i] == 0)

@@ -6,8 +6,10 @@ addresses, cuts it with np.split / np.transpose / np.concatenate the way a train
 would shard it, and flattens the result into the rank-local buffers.  The two share no code.
 
 Layout conventions restated here (declared readings, the paper leaves them open):
-rank = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp; stage p owns layers
-[p*L//PP, (p+1)*L//PP); flat buffers are per (rank, group), tail padded to 8*D elements.
+rank = tp + TP*(ddp + DDP*pp); the expert group sees position q = rank mod (TP*DDP) of a stage
+as q = etp + ETP*(ep + EP*edp), with (ETP, EDP, DDP) = (TP, DP, DP*EP) when EP and expert-DP form
+a grid beside TP and (1, TP*DP/EP, DP) when EP is carved out of the TP x DP ranks; stage p owns
+layers [p*L//PP, (p+1)*L//PP); flat buffers are per (rank, group), tail padded to 8*D elements.
 """
 import numpy as np
 
@@ -53,60 +55,130 @@ def _stage(layer, L, PP):
     return [p for p in range(PP) if (p * L) // PP <= layer < ((p + 1) * L) // PP][0]
 
 
-def _stored(addr, tp_axis, tp, TP, role, p, q_per_g):
-    """Shard `addr` (array of linear indices in natural shape) and flatten in storage order."""
+def _stored_blocks(addr, tp_axis, tp, TP, role, p, q_per_g):
+    """Shard `addr` (array of linear indices in natural shape) the way a rank stores it: a list of
+    arrays (storage blocks), each to be flattened row-major, one after the other."""
     x = addr
     if tp_axis is not None:
         x = np.split(x, TP, axis=tp_axis)[tp]
     if role == "qkv" and p["qkv_layout"] == 1:
-        parts = [x[:, :q_per_g], x[:, q_per_g:q_per_g + 1], x[:, q_per_g + 1:]]
-        return np.concatenate([q.ravel() for q in parts])
+        return [x[:, :q_per_g], x[:, q_per_g:q_per_g + 1], x[:, q_per_g + 1:]]
     if role == "gate_up" and p["expert_layout"] == 1:
-        return np.transpose(x, (2, 0, 1)).ravel()
+        return [np.transpose(x, (2, 0, 1))]
     if role == "down" and p["expert_layout"] == 1:
-        return np.transpose(x, (1, 0)).ravel()
-    return x.ravel()
+        return [np.transpose(x, (1, 0))]
+    return [x]
+
+
+def degrees(p):
+    """(TP, PP, dense DP, EP, expert TP, expert DP, world) of a parallel description."""
+    TP, PP, DP, EP = p["tp"], p["pp"], p["dp"], p["ep"]
+    if p.get("ep_placement", 0) == 0:
+        return TP, PP, DP * EP, EP, TP, DP, TP * PP * DP * EP
+    return TP, PP, DP, EP, 1, TP * DP // EP, TP * PP * DP
+
+
+def rank_position(p, rank):
+    """tp, dense dp index, pipeline stage, expert tp, ep, expert dp index of a rank."""
+    TP, PP, DDP, EP, ETP, EDP, world = degrees(p)
+    tp, ddp, pp = rank % TP, (rank // TP) % DDP, rank // (TP * DDP)
+    q = rank % (TP * DDP)
+    return tp, ddp, pp, q % ETP, (q // ETP) % EP, q // (ETP * EP)
+
+
+def rank_blocks(m, p, rank, group):
+    """The storage blocks of (rank, group) in flat order: [(tensor, block array of addresses)],
+    the data-parallel group size and the rank's index in it."""
+    inv = inventory(m)
+    TP, PP, DDP, EP, ETP, EDP, world = degrees(p)
+    tp, ddp, pp, etp, ep, edp = rank_position(p, rank)
+    L = m["layers"]
+    q_per_g = m["q_heads"] // m["kv_heads"]
+    T, t_idx, D, didx = (TP, tp, DDP, ddp) if group == 0 else (ETP, etp, EDP, edp)
+    order = range(len(inv))
+    if p["flat_order"] == 1:
+        order = reversed(order)
+    blocks = []
+    for t in order:
+        shape, tp_axis, grp, layer, expert, role = inv[t]
+        if grp != group or _stage(layer, L, PP) != pp:
+            continue
+        if group == 1 and expert // (m["experts"] // EP) != ep:
+            continue
+        addr = np.arange(int(np.prod(shape)), dtype=np.int64).reshape(shape)
+        for blk in _stored_blocks(addr, tp_axis, t_idx, T, role, p, q_per_g):
+            blocks.append((t, blk))
+    return blocks, D, didx
 
 
 def address_layout(m, p):
     """{(rank, buf): (tensor ids int32, linear indices int64)}; padding slots have tensor -1."""
-    inv = inventory(m)
-    TP, PP, DP, EP = p["tp"], p["pp"], p["dp"], p["ep"]
-    DDP = DP * EP
-    L = m["layers"]
-    q_per_g = m["q_heads"] // m["kv_heads"]
+    world = degrees(p)[6]
     out = {}
-    for pp in range(PP):
-        for ddp in range(DDP):
-            ep, edp = ddp % EP, ddp // EP
-            for tp in range(TP):
-                rank = tp + TP * (ddp + DDP * pp)
-                for group in (0, 1):
-                    D, didx = (DDP, ddp) if group == 0 else (DP, edp)
-                    tids, lins = [np.zeros(0, np.int32)], [np.zeros(0, np.int64)]
-                    order = range(len(inv))
-                    if p["flat_order"] == 1:
-                        order = reversed(order)
-                    for t in order:
-                        shape, tp_axis, grp, layer, expert, role = inv[t]
-                        if grp != group or _stage(layer, L, PP) != pp:
-                            continue
-                        if group == 1 and expert // (m["experts"] // EP) != ep:
-                            continue
-                        addr = np.arange(int(np.prod(shape)), dtype=np.int64).reshape(shape)
-                        flat = _stored(addr, tp_axis, tp, TP, role, p, q_per_g)
-                        lins.append(flat)
-                        tids.append(np.full(flat.size, t, np.int32))
-                    tid, lin = np.concatenate(tids), np.concatenate(lins)
-                    quantum = 8 * D
-                    padn = (-tid.size) % quantum
-                    tid = np.concatenate([tid, np.full(padn, -1, np.int32)])
-                    lin = np.concatenate([lin, np.full(padn, -1, np.int64)])
-                    for kind in range(4):
-                        if kind != 0 and p["zero"] == 1:
-                            out[(rank, group * 4 + kind)] = (np.split(tid, D)[didx], np.split(lin, D)[didx])
-                        else:
-                            out[(rank, group * 4 + kind)] = (tid, lin)
+    for rank in range(world):
+        for group in (0, 1):
+            blocks, D, didx = rank_blocks(m, p, rank, group)
+            tid = np.concatenate([np.zeros(0, np.int32)] + [np.full(b.size, t, np.int32) for t, b in blocks])
+            lin = np.concatenate([np.zeros(0, np.int64)] + [b.ravel() for t, b in blocks])
+            padn = (-tid.size) % (8 * D)
+            tid = np.concatenate([tid, np.full(padn, -1, np.int32)])
+            lin = np.concatenate([lin, np.full(padn, -1, np.int64)])
+            for kind in range(4):
+                if kind != 0 and p["zero"] == 1:
+                    out[(rank, group * 4 + kind)] = (np.split(tid, D)[didx], np.split(lin, D)[didx])
+                else:
+                    out[(rank, group * 4 + kind)] = (tid, lin)
+    return out
+
+
+def range_boxes(shape, v0, v1):
+    """The linear range [v0, v1) of a row-major array of `shape` as the fewest boxes (tuples of
+    slices): whole slabs along the leading axis form one box, a partial first or last slab is cut
+    the same way one axis further in."""
+    if not shape:
+        return [()]
+    inner = int(np.prod(shape[1:], dtype=np.int64))
+    first, last = v0 // inner, (v1 - 1) // inner
+    if v0 == first * inner and v1 == (last + 1) * inner:
+        return [(slice(first, last + 1),) + tuple(slice(0, n) for n in shape[1:])]
+    if first == last:
+        return [(slice(first, first + 1),) + b for b in range_boxes(shape[1:], v0 - first * inner, v1 - first * inner)]
+    out, k0, k1 = [], first, last + 1
+    if v0 != first * inner:
+        out += [(slice(first, first + 1),) + b for b in range_boxes(shape[1:], v0 - first * inner, inner)]
+        k0 = first + 1
+    tail = []
+    if v1 != (last + 1) * inner:
+        tail = [(slice(last, last + 1),) + b for b in range_boxes(shape[1:], 0, v1 - last * inner)]
+        k1 = last
+    if k0 < k1:
+        out.append((slice(k0, k1),) + tuple(slice(0, n) for n in shape[1:]))
+    return out + tail
+
+
+def pieces(m, p):
+    """{(rank, buf): [(tensor, buffer offsets int64, addresses int64)]}: every rank's stored data cut
+    into boxes: per storage block the rank's flat range, split by range_boxes.  Offsets and
+    addresses (linear indices in the unsharded tensor) are in the box's storage order."""
+    world = degrees(p)[6]
+    out = {}
+    for rank in range(world):
+        for group in (0, 1):
+            blocks, D, didx = rank_blocks(m, p, rank, group)
+            total = sum(b.size for _, b in blocks)
+            padded = total + (-total) % (8 * D)
+            for kind in range(4):
+                sharded = kind != 0 and p["zero"] == 1
+                r0, r1 = (padded // D * didx, padded // D * (didx + 1)) if sharded else (0, padded)
+                lst, start = [], 0
+                for t, blk in blocks:
+                    v0, v1 = max(r0, start) - start, min(r1, start + blk.size) - start
+                    if v0 < v1:
+                        where = np.arange(blk.size, dtype=np.int64).reshape(blk.shape)
+                        for box in range_boxes(blk.shape, v0, v1):
+                            lst.append((t, where[box].ravel() + (start - r0), blk[box].ravel()))
+                    start += blk.size
+                out[(rank, group * 4 + kind)] = lst
     return out
 
 
