@@ -69,8 +69,8 @@ typedef struct vps_model_desc {
     int32_t family, layers, hidden, q_heads, kv_heads, head_dim, ffn, vocab, experts, expert_ffn;
 } vps_model_desc;
 
-/* Parallel configuration.  World size = tp*pp*dp*ep; dp is the data-parallel degree of the
- * expert group, dense tensors are replicated over dp*ep ranks. */
+/* Parallel configuration.  With ep_placement = 0 the world size is tp*pp*dp*ep, dp is the
+ * data-parallel degree of the expert group and dense tensors are replicated over dp*ep ranks. */
 typedef struct vps_parallel_desc {
     int32_t tp, pp, dp, ep;
     int32_t zero_stage;    /* 0 or 1 */
@@ -78,6 +78,13 @@ typedef struct vps_parallel_desc {
     int32_t qkv_layout;    /* 0 interleaved per kv group, 1 blocked [all Q | all K | all V] */
     int32_t expert_layout; /* 0 row-major, 1 transposed storage (gate_up as (h,2,f), down as (f,h)) */
     int32_t flat_order;    /* 0 ascending tensor id, 1 descending */
+    int32_t ep_placement;  /* 0: EP and expert-DP form a grid beside TP: world = tp*pp*dp*ep, experts
+                              are TP-sharded like the dense MLP, dp = expert data-parallel degree.
+                              1: EP is carved out of the tp*dp ranks of a pipeline stage (the form
+                              of the paper's (TP, PP, DP, EP) MoE tuples): world = tp*pp*dp, position
+                              q = tp + tp_degree*dp_index in the stage has ep = q mod EP and expert
+                              data-parallel index q div EP; experts are not TP-sharded; ep must
+                              divide tp*dp */
 } vps_parallel_desc;
 
 typedef struct vps_config vps_config; /* a configuration mapped onto the VPS (device tables) */
@@ -279,8 +286,17 @@ void vps_config_destroy(vps_config* cfg);
 void vps_plan_destroy(vps_plan* plan);
 const char* vps_last_error(void);
 
-/* Tuning knob for benchmarks: target payload bytes per workgroup tile (power of two between
- * 4 KiB and 1 MiB; default 8 KiB).  Applies to plans created afterwards. */
+/* Settings for benchmarks and tests; they apply to plans created afterwards (launch settings to
+ * launches made afterwards) and may be changed from any thread.
+ *   VPS_OPT_TILE_BYTES        target payload bytes per workgroup tile: a power of two between
+ *                             4 KiB and 1 MiB, default 8 KiB (vps_set_tile_bytes sets the same)
+ *   VPS_OPT_SMALL_PLAN_BOXES  plans with at most this many boxes (1 .. 65536, default 8192) are
+ *                             ordered by counting in one launch; larger ones by a radix sort
+ *   VPS_OPT_XPOSE_SHAPE       super-block shape of transposed boxes, sa | sb << 16 (1 .. 64 each);
+ *                             0 = chosen per box from the row pitches (default)
+ *   VPS_OPT_XCD_RUN           consecutive tiles handed to one XCD (0 = round-robin, default 64) */
+enum { VPS_OPT_TILE_BYTES = 0, VPS_OPT_SMALL_PLAN_BOXES = 1, VPS_OPT_XPOSE_SHAPE = 2, VPS_OPT_XCD_RUN = 3 };
+int vps_set_option(int32_t option, uint32_t value);
 int vps_set_tile_bytes(uint32_t bytes);
 
 /* Measurement aid, not part of the paper's method: a plain contiguous device-to-device copy of

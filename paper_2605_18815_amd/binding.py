@@ -16,6 +16,7 @@ ERR_INVALID_ARG, ERR_INDIVISIBLE, ERR_RANK_RANGE, ERR_MODEL_MISMATCH = -1, -2, -
 ERR_SCRATCH_TOO_SMALL, ERR_OOM, ERR_HIP = -5, -6, -7
 NUM_BUFFERS = 8
 NO_POS = (1 << 64) - 1
+OPT_TILE_BYTES, OPT_SMALL_PLAN_BOXES, OPT_XPOSE_SHAPE, OPT_XCD_RUN = range(4)
 PLAN_ROUTES_ONLY = 1
 PLAN_THROUGH_BUFFERS = 2
 COLL_NONE, COLL_P2P, COLL_BROADCAST, COLL_SCATTER, COLL_GATHER = range(5)
@@ -23,7 +24,7 @@ COLL_NONE, COLL_P2P, COLL_BROADCAST, COLL_SCATTER, COLL_GATHER = range(5)
 MODEL_FIELDS = ("family", "layers", "hidden", "q_heads", "kv_heads", "head_dim", "ffn", "vocab",
                 "experts", "expert_ffn")
 PARALLEL_FIELDS = ("tp", "pp", "dp", "ep", "zero_stage", "gpus_per_node", "qkv_layout",
-                   "expert_layout", "flat_order")
+                   "expert_layout", "flat_order", "ep_placement")
 
 
 class ModelDesc(C.Structure):
@@ -66,6 +67,7 @@ def parallel_desc(p):
     d = dict(p)
     if "zero" in d:
         d["zero_stage"] = d.pop("zero")
+    d.setdefault("ep_placement", 0)
     return ParallelDesc(**{k: int(d[k]) for k in PARALLEL_FIELDS})
 
 
@@ -110,6 +112,7 @@ class Library:
             "plan_get_boxes": [vp, vp, i64],
             "plan_stats": [vp, P(PlanStats)],
             "set_tile_bytes": [u32],
+            "set_option": [i32, u32],
             "plain_copy": [vp, vp, u64, vp],
             "stage_exchange": [vp, u64, vp, P(vp)],
             "plan_classify_collectives": [vp, vp, vp, P(i32), i64],
@@ -148,7 +151,7 @@ class Library:
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
                "set_tile_bytes", "plain_copy", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
                "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy",
-               "apply_transition_static", "static_scratch_bytes")
+               "apply_transition_static", "static_scratch_bytes", "set_option")
 
     def last_error(self):
         return self._fn["last_error"]().decode()
@@ -207,6 +210,9 @@ class Library:
 
     def set_tile_bytes(self, n):
         self._check(self._fn["set_tile_bytes"](n))
+
+    def set_option(self, option, value):
+        self._check(self._fn["set_option"](option, value))
 
 
 class Config:

@@ -7,30 +7,55 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <string>
+#include <unordered_map>
 
 #include "vps_pipeline.h"
 
 namespace vps {
 
 static thread_local std::string g_last_error;
-static uint32_t g_tile_bytes = 8u << 10;
 
-// Super-block shape of transposed boxes: 0 = chosen per box from the pitches; VPS_XPOSE_SHAPE
-// = "sa,sb" (blocks along the source's / the destination's contiguous axis) fixes it for
-// experiments.
-inline uint32_t xpose_shape_override()
-{
-    static const uint32_t v = [] {
-        const char* e = getenv("VPS_XPOSE_SHAPE");
-        unsigned sa = 0, sb = 0;
-        if (!e || sscanf(e, "%u,%u", &sa, &sb) != 2 || sa < 1 || sb < 1 || sa > 64 || sb > 64) return 0u;
-        return (uint32_t)(sa | sb << 16);
-    }();
-    return v;
-}
+// Settings that apply to plans created afterwards (vps_set_option).  Plain atomics: a plan reads
+// them once, when it is made.
+static std::atomic<uint32_t> g_tile_bytes{ 8u << 10 };
+static std::atomic<uint32_t> g_small_plan_boxes{ 8192u };   // boxes ordered by counting, without a sort
+static std::atomic<uint32_t> g_xpose_shape{ 0u };           // 0 = chosen per box from the pitches
+
+// Number of tiles of the plans made so far, by what determines it (model, both configurations,
+// rank, flags, tile size).  A repeated transition then sizes its tile table without waiting for
+// the device.  Only a size: every plan computes all of its tables anew.
+struct TileHints {
+    std::mutex m;
+    std::unordered_map<uint64_t, int64_t> tiles;
+    static uint64_t key(const vps_model_desc& model, const vps_parallel_desc& a, const vps_parallel_desc& b, int32_t rank,
+                        uint32_t flags, uint32_t tile_bytes, uint32_t xpose_shape)
+    {
+        uint64_t h = 0xcbf29ce484222325ull;
+        auto mix = [&](const void* p, size_t n) {
+            for (size_t i = 0; i < n; ++i) h = (h ^ ((const unsigned char*)p)[i]) * 0x100000001b3ull;   // FNV-1a
+        };
+        mix(&model, sizeof model); mix(&a, sizeof a); mix(&b, sizeof b); mix(&rank, sizeof rank);
+        mix(&flags, sizeof flags); mix(&tile_bytes, sizeof tile_bytes); mix(&xpose_shape, sizeof xpose_shape);
+        return h;
+    }
+    int64_t get(uint64_t k)
+    {
+        std::lock_guard<std::mutex> g(m);
+        auto it = tiles.find(k);
+        return it == tiles.end() ? 0 : it->second;
+    }
+    void put(uint64_t k, int64_t n)
+    {
+        std::lock_guard<std::mutex> g(m);
+        if (tiles.size() > 4096) tiles.clear();
+        tiles[k] = n;
+    }
+};
+static TileHints g_tile_hints;
 
 inline int fail(int code, const std::string& msg)
 {
@@ -38,44 +63,39 @@ inline int fail(int code, const std::string& msg)
     return code;
 }
 
-// Which pointer-table slots an operation dereferences, per plan.
-inline void mark_used_slots(const PlanData& p, std::vector<uint8_t> used[3])
-{
-    const int ns = num_slots(p.layout);
-    for (int op = 0; op < 3; ++op) used[op].assign((size_t)ns, 0);
-    if (p.routes_only) return;   // no copy tables: nothing is ever dereferenced
-    for (const vps_box& b : p.boxes_send_order) {
-        const bool retained = box_retained(b, p.through_buffers);
-        const bool src_res = p.rank < 0 || b.src_rank == p.rank;
-        const bool dst_res = p.rank < 0 || b.dst_rank == p.rank;
-        if (retained && src_res) {
-            used[OP_RETAIN][(size_t)slot_src(p.layout, b.src_rank, b.src_buf)] = 1;
-            used[OP_RETAIN][(size_t)slot_dst(p.layout, b.dst_rank, b.dst_buf)] = 1;
-        }
-        if (!retained && src_res) {
-            used[OP_PACK][(size_t)slot_src(p.layout, b.src_rank, b.src_buf)] = 1;
-            used[OP_PACK][(size_t)slot_send(p.layout, b.src_rank)] = 1;
-        }
-        if (!retained && dst_res) {
-            used[OP_UNPACK][(size_t)slot_recv(p.layout, b.dst_rank)] = 1;
-            used[OP_UNPACK][(size_t)slot_dst(p.layout, b.dst_rank, b.dst_buf)] = 1;
-        }
-    }
-}
-
 }  // namespace vps
 
 struct vps_config {
     vps::ConfigData d;
+    std::mutex host_copy;   // guards the on-demand host copies (class table, piece table)
 };
 
 struct vps_plan {
     vps::PlanData d;
-    std::vector<uint8_t> used[3];
-    std::mutex host_copy;   // guards the on-demand host copy of the boxes
+    std::mutex host_copy;   // guards the on-demand host copy of the boxes and the stream list
+    std::vector<void*> streams;   // streams that copy kernels of this plan were queued on
 };
 
 namespace vps {
+
+// Size queries need the class table on the host; piece queries need the piece table.
+inline vps::ConfigData& with_host_config(const vps_config* cfg, bool pieces)
+{
+    vps_config* mc = const_cast<vps_config*>(cfg);
+    std::lock_guard<std::mutex> g(mc->host_copy);
+    VPS_BACKEND be(nullptr);
+    try {
+        ensure_config_host(be, mc->d);
+        if (pieces) ensure_pieces(be, mc->d);
+    } catch (...) {
+        // the backend takes back what it allocated: the configuration must not keep pointers to it
+        mc->d.piece_base = nullptr; mc->d.pieces = nullptr; mc->d.npieces = -1;
+        be.release_all();
+        throw;
+    }
+    be.commit();   // the piece table now belongs to the configuration
+    return mc->d;
+}
 
 // Queries that read the boxes on the host fetch them first if the plan left them on the device.
 inline const PlanData& with_host_boxes(const vps_plan* plan)
@@ -94,6 +114,8 @@ inline const PlanData& with_host_boxes(const vps_plan* plan)
 struct vps_stage_plan {
     vps::StageData d;
     const vps_plan* plan;
+    std::mutex guard;
+    std::vector<void*> streams;   // streams that copy kernels of this stage plan were queued on
 };
 
 #define VPS_TRY try {
@@ -113,6 +135,28 @@ int VPS_FN(set_tile_bytes)(uint32_t bytes)
         return vps::fail(VPS_ERR_INVALID_ARG, "tile bytes must be a power of two in [4 KiB, 1 MiB]");
     vps::g_tile_bytes = bytes;
     return VPS_OK;
+}
+
+int VPS_FN(set_option)(int32_t option, uint32_t value)
+{
+    if (option == VPS_OPT_TILE_BYTES) return VPS_FN(set_tile_bytes)(value);
+    if (option == VPS_OPT_SMALL_PLAN_BOXES) {
+        if (value < 1 || value > (1u << 16)) return vps::fail(VPS_ERR_INVALID_ARG, "small-plan limit must be in [1, 65536]");
+        vps::g_small_plan_boxes = value;
+        return VPS_OK;
+    }
+    if (option == VPS_OPT_XPOSE_SHAPE) {
+        const uint32_t sa = value & 0xffffu, sb = value >> 16;
+        if (value && (sa < 1 || sb < 1 || sa > 64 || sb > 64)) return vps::fail(VPS_ERR_INVALID_ARG, "super-block edges must be in [1, 64]");
+        vps::g_xpose_shape = value;
+        return VPS_OK;
+    }
+    if (option == VPS_OPT_XCD_RUN) {
+        if (value > 4096) return vps::fail(VPS_ERR_INVALID_ARG, "XCD run length must be at most 4096 tiles");
+        VPS_BACKEND::set_xcd_chunk(value);
+        return VPS_OK;
+    }
+    return vps::fail(VPS_ERR_INVALID_ARG, "unknown option");
 }
 
 int VPS_FN(plain_copy)(void* dst, const void* src, uint64_t bytes, void* stream)
@@ -180,10 +224,13 @@ int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, 
     try {
         if (flags & ~(uint32_t)(VPS_PLAN_ROUTES_ONLY | VPS_PLAN_THROUGH_BUFFERS))
             throw vps::Error{ VPS_ERR_INVALID_ARG, "unknown plan flag" };
-        vps::build_plan(be, src->d, dst->d, rank, vps::g_tile_bytes, vps::xpose_shape_override(),
-                        (flags & VPS_PLAN_ROUTES_ONLY) != 0,
-                        (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, p->d);
-        vps::mark_used_slots(p->d, p->used);
+        const uint32_t tile_bytes = vps::g_tile_bytes.load(), xpose_shape = vps::g_xpose_shape.load();
+        const uint64_t hk = vps::TileHints::key(src->d.model, src->d.par, dst->d.par, rank, flags, tile_bytes, xpose_shape);
+        vps::build_plan(be, src->d, dst->d, rank, tile_bytes, xpose_shape,
+                        vps::g_small_plan_boxes.load(), (flags & VPS_PLAN_ROUTES_ONLY) != 0,
+                        (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, vps::g_tile_hints.get(hk), p->d);
+        const vps_plan_stats_t& st = p->d.stats;
+        vps::g_tile_hints.put(hk, st.num_retain_tiles + st.num_pack_tiles + st.num_unpack_tiles);
     } catch (...) {
         be.release_all();
         delete p;
@@ -199,7 +246,8 @@ void VPS_FN(plan_destroy)(vps_plan* p)
 {
     if (!p) return;
     VPS_BACKEND be(nullptr);
-    be.quiesce();  // queued copy kernels may still read the plan's tables
+    // copy kernels that are still queued read the plan's tables: wait for the streams they are on
+    for (void* s : p->streams) be.wait_stream(s);
     vps::free_plan(be, p->d);
     delete p;
 }
@@ -216,6 +264,12 @@ int launch_ops(BE& be, const vps_plan* plan, int64_t t0, int64_t t1, const std::
     const PlanData& p = plan->d;
     if (p.routes_only) return fail(VPS_ERR_INVALID_ARG, "the plan was made with VPS_PLAN_ROUTES_ONLY and has no copy tables");
     if (t1 <= t0) return VPS_OK;
+    {
+        vps_plan* mp = const_cast<vps_plan*>(plan);
+        std::lock_guard<std::mutex> g(mp->host_copy);
+        void* s = (void*)be.stream();
+        if (std::find(mp->streams.begin(), mp->streams.end(), s) == mp->streams.end()) mp->streams.push_back(s);
+    }
     PtrArgs pa;
     memset(&pa, 0, sizeof(pa));
     if (p.layout.all_ranks) {
@@ -232,7 +286,7 @@ inline int check_used(const vps_plan* plan, int op, int32_t rank, const std::vec
                       bool alias)
 {
     const PlanData& p = plan->d;
-    const std::vector<uint8_t>& u = plan->used[op];
+    const std::vector<uint8_t>& u = p.used[op];
     for (size_t s = 0; s < u.size(); ++s) {
         if (!u[s] || ptrs[s]) continue;
         // a slot of another rank does not matter when only `rank` is launched
@@ -349,7 +403,9 @@ int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* con
     if (need && (!scratch || ((uintptr_t)scratch & 15))) return vps::fail(VPS_ERR_INVALID_ARG, "scratch must be a 16-byte aligned device pointer");
     const vps::PtrLayout& L = p.layout;
     std::vector<void*> ptrs((size_t)vps::num_slots(L), nullptr);
-    const int64_t n = p.nboxes;
+    // the table holds the retain tiles, then the pack tiles, then the unpack tiles
+    const int64_t t_retain = p.op_tile[vps::OP_RETAIN].front(), t_unpack = p.op_tile[vps::OP_UNPACK].front();
+    const int64_t t_end = p.op_tile[vps::OP_UNPACK].back();
     {
         const size_t ns = (size_t)(p.rank >= 0 ? 1 : p.A.world) * 8, nd = (size_t)(p.rank >= 0 ? 1 : p.B.world) * 8;
         for (size_t i = 0; i < ns; ++i)
@@ -369,11 +425,11 @@ int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* con
             if (int rc = vps::check_used(plan, op, rank, ptrs, false)) return rc;
         // the three operations touch disjoint destinations: one launch over every tile
         if (!p.through_buffers)
-            return vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(3 * n)], ptrs, 0);
+            return vps::launch_ops(be, plan, t_retain, t_end, ptrs, 0);
         // the rank is its own peer: its segment is unpacked straight out of the send buffer, after
         // the pack launch has written it
-        if (int rc = vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(2 * n)], ptrs, 0)) return rc;
-        return vps::launch_ops(be, plan, p.tile_base[(size_t)(2 * n)], p.tile_base[(size_t)(3 * n)], ptrs, 1);
+        if (int rc = vps::launch_ops(be, plan, t_retain, t_unpack, ptrs, 0)) return rc;
+        return vps::launch_ops(be, plan, t_unpack, t_end, ptrs, 1);
     }
     for (int32_t q = 0; q < p.A.world; ++q) {
         for (int b = 0; b < 8; ++b) ptrs[(size_t)vps::slot_src(L, q, b)] = (void*)src_bufs[(size_t)q * 8 + b];
@@ -384,8 +440,8 @@ int VPS_FN(apply_transition)(const vps_plan* plan, int32_t rank, const void* con
     for (int op = 0; op < 3; ++op)
         if (int rc = vps::check_used(plan, op, -1, ptrs, true)) return rc;
     // retain + pack for every rank, then unpack straight out of the senders' segments
-    if (int rc = vps::launch_ops(be, plan, p.tile_base[0], p.tile_base[(size_t)(2 * n)], ptrs, 0)) return rc;
-    return vps::launch_ops(be, plan, p.tile_base[(size_t)(2 * n)], p.tile_base[(size_t)(3 * n)], ptrs, 1);
+    if (int rc = vps::launch_ops(be, plan, t_retain, t_unpack, ptrs, 0)) return rc;
+    return vps::launch_ops(be, plan, t_unpack, t_end, ptrs, 1);
     VPS_CATCH
 }
 
@@ -416,24 +472,30 @@ int VPS_FN(config_buffer_bytes)(const vps_config* c, int32_t rank, int32_t buf, 
     if (!c || !bytes) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
     if (rank < 0 || rank >= c->d.P.world) return vps::fail(VPS_ERR_RANK_RANGE, "rank outside the world");
     if (buf < 0 || buf >= 8) return vps::fail(VPS_ERR_INVALID_ARG, "buffer index must be 0..7");
-    *bytes = vps::config_buffer_elems(c->d, rank, buf) * vps::kind_bytes(buf % 4);
+    VPS_TRY
+    *bytes = vps::config_buffer_elems(vps::with_host_config(c, false), rank, buf) * vps::kind_bytes(buf % 4);
+    return VPS_OK;
+    VPS_CATCH
     return VPS_OK;
 }
 
 int VPS_FN(config_num_pieces)(const vps_config* c, int64_t* n)
 {
     if (!c || !n) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
-    *n = c->d.npieces;
+    VPS_TRY
+    *n = vps::with_host_config(c, true).npieces;
     return VPS_OK;
+    VPS_CATCH
 }
 
 int VPS_FN(config_get_pieces)(const vps_config* c, vps_piece* out, int64_t max)
 {
     if (!c || (!out && max > 0)) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
     VPS_TRY
+    const vps::ConfigData& d = vps::with_host_config(c, true);
     VPS_BACKEND be(nullptr);
-    const int64_t n = max < c->d.npieces ? max : c->d.npieces;
-    if (n > 0) be.download(out, c->d.pieces, sizeof(vps_piece) * (size_t)n);
+    const int64_t n = max < d.npieces ? max : d.npieces;
+    if (n > 0) be.download(out, d.pieces, sizeof(vps_piece) * (size_t)n);
     return VPS_OK;
     VPS_CATCH
 }
@@ -529,7 +591,7 @@ int VPS_FN(stage_exchange)(const vps_plan* plan, uint64_t budget, void* stream, 
     sp->plan = plan;
     VPS_BACKEND be(stream);
     try {
-        vps::build_stage_plan(be, plan->d, budget, plan->d.tile_bytes, sp->d);
+        vps::build_stage_plan(be, vps::with_host_boxes(plan), budget, plan->d.tile_bytes, sp->d);
     } catch (...) {
         be.release_all();
         delete sp;
@@ -545,7 +607,7 @@ void VPS_FN(stage_plan_destroy)(vps_stage_plan* sp)
 {
     if (!sp) return;
     VPS_BACKEND be(nullptr);
-    be.quiesce();
+    for (void* s : sp->streams) be.wait_stream(s);
     vps::free_stage(be, sp->d);
     delete sp;
 }
@@ -592,13 +654,21 @@ int VPS_FN(apply_transition_staged)(const vps_stage_plan* sp, const void* const*
         if (int rc = vps::check_used(sp->plan, op, -1, chk, false)) return rc;
     }
     VPS_BACKEND be(stream);
+    {
+        vps_stage_plan* msp = const_cast<vps_stage_plan*>(sp);
+        std::lock_guard<std::mutex> g(msp->guard);
+        if (std::find(msp->streams.begin(), msp->streams.end(), stream) == msp->streams.end()) msp->streams.push_back(stream);
+        vps_plan* mp = const_cast<vps_plan*>(sp->plan);
+        std::lock_guard<std::mutex> g2(mp->host_copy);
+        if (std::find(mp->streams.begin(), mp->streams.end(), stream) == mp->streams.end()) mp->streams.push_back(stream);
+    }
     vps::PtrArgs pa;
     memset(&pa, 0, sizeof(pa));
     pa.tbl = (char* const*)sd.ptr_table;
     // retained boxes: old local -> new local, once
     be.set_ptr_table(sd.ptr_table, ptrs.data(), (int)ptrs.size());
-    const int64_t n = p.nboxes;
-    be.launch_copy(p.descs, p.tiles, p.tile_base[0], p.tile_base[(size_t)n] - p.tile_base[0], pa, 0);
+    be.launch_copy(p.descs, p.tiles, p.op_tile[vps::OP_RETAIN].front(),
+                   p.op_tile[vps::OP_RETAIN].back() - p.op_tile[vps::OP_RETAIN].front(), pa, 0);
     for (int32_t g = 0; g < sd.nstages; ++g) {
         for (int32_t q = 0; q < p.A.world; ++q)
             ptrs[(size_t)vps::slot_send(L, q)] = (char*)scratch + sd.send_base[(size_t)g * (size_t)p.A.world + (size_t)q];

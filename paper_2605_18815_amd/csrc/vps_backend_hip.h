@@ -1,5 +1,6 @@
 // vps_backend_hip.h - device backend of the mapper/planner pipeline: one kernel lane per item,
-// rocPRIM for the two generic primitives (exclusive scan, stable radix sort).
+// wavefront prefix sums for compaction and scans, rocPRIM only for the radix sort of plans with
+// more boxes than the counting path takes.
 #pragma once
 
 #include <cstdlib>
@@ -9,6 +10,7 @@
 #include <rocprim/rocprim.hpp>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <unordered_map>
@@ -32,6 +34,230 @@ __global__ __launch_bounds__(256) void k_for_each(F f, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) f(i);
+}
+
+// ---- wavefront and workgroup prefix sums (all 64 lanes of a wavefront must call) ----
+
+template <class V>
+__device__ __forceinline__ V wave_exclusive_scan(V v, V& total)
+{
+    const unsigned lane = threadIdx.x & 63u;
+    V x = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const V y = __shfl_up(x, d, 64);
+        if (lane >= (unsigned)d) x += y;
+    }
+    total = __shfl(x, 63, 64);
+    return x - v;
+}
+
+// Exclusive prefix sum over the 256 lanes of a workgroup; `carry` (4 entries of LDS) is scratch.
+template <class V>
+__device__ __forceinline__ V group_exclusive_scan(V v, V& total, V* carry)
+{
+    V wtot;
+    const V in_wave = wave_exclusive_scan(v, wtot);
+    const unsigned wave = threadIdx.x >> 6;
+    __syncthreads();   // carry may still be read from the previous round
+    if ((threadIdx.x & 63u) == 63u) carry[wave] = wtot;
+    __syncthreads();
+    V before = 0;
+    total = 0;
+#pragma unroll
+    for (unsigned w = 0; w < 4; ++w) {
+        const V c = carry[w];
+        if (w < wave) before += c;
+        total += c;
+    }
+    return before + in_wave;
+}
+
+// F_P, flat offsets: workgroup `cls` walks the tensors of its pipeline stage in flat-buffer order
+// and gives every tensor of its class the running sum of the shard lengths before it (a
+// workgroup-wide prefix sum per 1024 tensors, four consecutive ones per lane); the class length
+// and its padded size fall out at the end.
+__global__ __launch_bounds__(256) void k_layout_classes(ParConst P, const TensorRec* __restrict__ T,
+                                                        TensorLayout* __restrict__ TL, ClassRec* __restrict__ C)
+{
+    __shared__ uint64_t carry[4];
+    const int32_t cls = (int32_t)blockIdx.x;
+    int32_t lo, hi;
+    stage_tensor_range(P, cls < P.pp ? cls : (cls - P.pp) / P.ep, lo, hi);
+    const int32_t count = hi - lo;
+    uint64_t running = 0;
+    for (int32_t q0 = 0; q0 < count; q0 += 1024) {
+        int32_t t[4];
+        uint64_t len[4], mine = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int32_t q = q0 + (int32_t)threadIdx.x * 4 + k;
+            t[k] = -1;
+            len[k] = 0;
+            if (q < count) {
+                const int32_t id = P.flat_order ? hi - 1 - q : lo + q;
+                const TensorRec x = T[id];
+                if (class_of_tensor(P, x) == cls) { t[k] = id; len[k] = shard_elems(P, x); }
+            }
+            mine += len[k];
+        }
+        uint64_t total;
+        uint64_t before = running + group_exclusive_scan(mine, total, carry);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (t[k] >= 0) {
+                TensorLayout tl;
+                tl.start = before; tl.shard_len = len[k]; tl.cls = cls; tl.pad_ = 0;
+                TL[t[k]] = tl;
+            }
+            before += len[k];
+        }
+        running += total;
+    }
+    if (threadIdx.x == 0) C[cls] = make_class_rec(P, cls, running);
+}
+
+// A slot of the box table for every lane that is emitting a box right now: a ballot names the
+// lanes, the first of them takes the wavefront's share with one atomic, and each lane's slot is
+// that base plus the number of emitting lanes below it.
+__device__ __forceinline__ uint64_t take_box_slot(unsigned long long* counter)
+{
+    const uint64_t mask = __ballot(1);
+    const unsigned lane = threadIdx.x & 63u;
+    const int leader = __ffsll((unsigned long long)mask) - 1;
+    const unsigned below = (unsigned)__popcll(mask & ((1ull << lane) - 1ull));
+    unsigned long long base = 0;
+    if ((int)lane == leader) base = atomicAdd(counter, (unsigned long long)__popcll(mask));
+    const unsigned lo = (unsigned)__shfl((int)(unsigned)base, leader, 64);
+    const unsigned hi = (unsigned)__shfl((int)(unsigned)(base >> 32), leader, 64);
+    return (((uint64_t)hi << 32) | lo) + below;
+}
+
+// Intersections with wavefront compaction: every lane walks the routed boxes of its item and
+// writes each into the next free slot of the box table, together with its ordering record.
+// Boxes beyond the table's capacity are counted but not written.
+__global__ __launch_bounds__(256) void k_plan_emit(PlanCtx pc, int mode, int through, int64_t lanes,
+                                                   vps_box* __restrict__ raw, OrderRec* __restrict__ recs,
+                                                   uint64_t cap, unsigned long long* counter)
+{
+    const int64_t lane = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (lane >= lanes) return;
+    plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
+        const uint64_t k = take_box_slot(counter);
+        if (k < cap) {
+            raw[k] = b;
+            recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
+        }
+    });
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
+{
+    const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, mask, 64);
+    const unsigned hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), mask, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+// Place of every box in the send and in the receive order by counting (order_by_counting).  A
+// group of 16 lanes shares one box: the ordering records are staged through LDS 256 at a time,
+// every lane of the group counts a sixteenth of them, and a butterfly over the group adds the
+// counts up.  f(k, place, part) continues with box k on the group's lanes part = 0 .. 15.
+constexpr unsigned ORDER_GROUP = 16;
+
+template <class Step, class F>
+__global__ __launch_bounds__(256) void k_order_by_counting(const OrderRec* __restrict__ recs, const uint64_t* __restrict__ nbox,
+                                                           uint32_t bound, F f)
+{
+    constexpr unsigned BOXES = 256 / ORDER_GROUP;
+    __shared__ OrderRec tile[256];
+    const uint64_t n64 = *nbox;
+    if (n64 > bound || (uint64_t)blockIdx.x * BOXES >= n64) return;   // uniform over the workgroup
+    const uint32_t n = (uint32_t)n64, part = threadIdx.x % ORDER_GROUP, k = blockIdx.x * BOXES + threadIdx.x / ORDER_GROUP;
+    const OrderRec me = recs[k < n ? k : n - 1];
+    const uint64_t floor_s = order_owner_floor(me.key_s), floor_r = order_owner_floor(me.key_r);
+    OrderPlace o = order_place_zero();
+    for (uint32_t q0 = 0; q0 < n; q0 += 256) {
+        __syncthreads();
+        if (q0 + threadIdx.x < n) tile[threadIdx.x] = recs[q0 + threadIdx.x];
+        __syncthreads();
+        const uint32_t m = n - q0 < 256u ? n - q0 : 256u;
+        for (uint32_t q = part; q < m; q += ORDER_GROUP) order_count_one(tile[q], me, floor_s, floor_r, o);
+    }
+#pragma unroll
+    for (int d = ORDER_GROUP / 2; d >= 1; d >>= 1) {
+        o.idx_s += (uint32_t)__shfl_xor((int)o.idx_s, d, 64);
+        o.idx_r += (uint32_t)__shfl_xor((int)o.idx_r, d, 64);
+        o.gpos_s += shfl_xor_u64(o.gpos_s, d);
+        o.gpos_r += shfl_xor_u64(o.gpos_r, d);
+        o.base_s += shfl_xor_u64(o.base_s, d);
+        o.base_r += shfl_xor_u64(o.base_r, d);
+    }
+    if (k < n) f(k, o, part);
+}
+
+// ---- exclusive prefix sum of n int64 values: out[i] = in[0] + ... + in[i-1] ----
+constexpr int SCAN_PER_LANE = 8;
+constexpr int SCAN_PER_GROUP = 256 * SCAN_PER_LANE;
+
+// One workgroup walks the whole array (small inputs, and the table of workgroup sums).
+__device__ __forceinline__ void scan_by_one_group(const int64_t* in, int64_t* out, int64_t n)
+{
+    __shared__ int64_t carry[4];
+    int64_t running = 0;
+    for (int64_t base = 0; base < n; base += SCAN_PER_GROUP) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * SCAN_PER_LANE;
+        int64_t v[SCAN_PER_LANE], mine = 0;
+#pragma unroll
+        for (int k = 0; k < SCAN_PER_LANE; ++k) { v[k] = i0 + k < n ? in[i0 + k] : 0; mine += v[k]; }
+        int64_t total;
+        int64_t acc = running + group_exclusive_scan(mine, total, carry);
+#pragma unroll
+        for (int k = 0; k < SCAN_PER_LANE; ++k) { if (i0 + k < n) out[i0 + k] = acc; acc += v[k]; }
+        running += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_scan_one_group(const int64_t* in, int64_t* out, int64_t n)
+{
+    scan_by_one_group(in, out, n);
+}
+
+// The same over the first mult * (*count) + 1 entries (at most n; nothing happens beyond), and
+// then, in the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.
+template <class Step, class F>
+__global__ __launch_bounds__(256) void k_scan_counted_then_each(const int64_t* in, int64_t* out, int64_t n,
+                                                                const uint64_t* count, int mult, int64_t m, F f)
+{
+    const int64_t len = (int64_t)*count * mult + 1;
+    if (len > n) return;
+    scan_by_one_group(in, out, len);
+    __syncthreads();   // the sums are in memory for every lane of the workgroup
+    for (int64_t i = threadIdx.x; i < m; i += 256) f(i);
+}
+
+__global__ __launch_bounds__(256) void k_scan_group_sums(const int64_t* in, int64_t* sums, int64_t n)
+{
+    __shared__ int64_t carry[4];
+    const int64_t i0 = (int64_t)blockIdx.x * SCAN_PER_GROUP + (int64_t)threadIdx.x * SCAN_PER_LANE;
+    int64_t mine = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER_LANE; ++k) mine += i0 + k < n ? in[i0 + k] : 0;
+    int64_t total;
+    group_exclusive_scan(mine, total, carry);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void k_scan_with_offsets(const int64_t* in, int64_t* out, const int64_t* offsets, int64_t n)
+{
+    __shared__ int64_t carry[4];
+    const int64_t i0 = (int64_t)blockIdx.x * SCAN_PER_GROUP + (int64_t)threadIdx.x * SCAN_PER_LANE;
+    int64_t v[SCAN_PER_LANE], mine = 0;
+#pragma unroll
+    for (int k = 0; k < SCAN_PER_LANE; ++k) { v[k] = i0 + k < n ? in[i0 + k] : 0; mine += v[k]; }
+    int64_t total;
+    int64_t acc = offsets[blockIdx.x] + group_exclusive_scan(mine, total, carry);
+#pragma unroll
+    for (int k = 0; k < SCAN_PER_LANE; ++k) { if (i0 + k < n) out[i0 + k] = acc; acc += v[k]; }
 }
 
 // Pointer tables travel as kernel arguments: the launch copies them, so the host array can be
@@ -182,9 +408,6 @@ public:
         recycle_dead();
     }
 
-    // Wait until nothing on the device can still use blocks that are about to be recycled.
-    void quiesce() { (void)hipDeviceSynchronize(); }
-
     template <class Step, class F>
     void for_each(Step, int64_t n, F f)
     {
@@ -196,18 +419,78 @@ public:
     }
 
     // out[i] = in[0] + ... + in[i-1] for i in [0, n]; both arrays hold n+1 entries and in[n]
-    // must be 0.
+    // must be 0.  Up to 64 Ki entries one workgroup walks the array; beyond, every workgroup sums
+    // its 2048 entries, one workgroup scans those sums, and a third launch finishes.
     void exclusive_scan(const int64_t* in, int64_t* out, int64_t n)
     {
-        size_t tmp_bytes = 0;
-        const size_t count = (size_t)n + 1;
-        VPS_HIP_CHECK(rocprim::exclusive_scan(nullptr, tmp_bytes, in, out, (int64_t)0, count,
-                                              rocprim::plus<int64_t>(), stream_));
-        void* tmp = alloc<char>((int64_t)tmp_bytes);
-        VPS_HIP_CHECK(rocprim::exclusive_scan(tmp, tmp_bytes, in, out, (int64_t)0, count,
-                                              rocprim::plus<int64_t>(), stream_));
-        free(tmp);
+        const int64_t count = n + 1;
+        if (count <= 32 * SCAN_PER_GROUP) {
+            hipLaunchKernelGGL(k_scan_one_group, dim3(1), dim3(256), 0, stream_, in, out, count);
+            VPS_HIP_CHECK(hipGetLastError());
+            return;
+        }
+        const int64_t groups = (count + SCAN_PER_GROUP - 1) / SCAN_PER_GROUP;
+        int64_t* sums = alloc<int64_t>(groups);
+        hipLaunchKernelGGL(k_scan_group_sums, dim3((unsigned)groups), dim3(256), 0, stream_, in, sums, count);
+        hipLaunchKernelGGL(k_scan_one_group, dim3(1), dim3(256), 0, stream_, (const int64_t*)sums, sums, groups);
+        hipLaunchKernelGGL(k_scan_with_offsets, dim3((unsigned)groups), dim3(256), 0, stream_, in, out, (const int64_t*)sums, count);
+        VPS_HIP_CHECK(hipGetLastError());
+        free(sums);
     }
+
+    // The same over the first mult * (*count) + 1 entries, *count read on the device (at most
+    // `bound` entries; nothing happens if there would be more), followed in the same launch by
+    // f(i) for i in [0, m).
+    template <class Step, class F>
+    void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
+                                          int mult, int64_t m, F f)
+    {
+        hipLaunchKernelGGL((k_scan_counted_then_each<Step, F>), dim3(1), dim3(256), 0, stream_, in, out, bound, count, mult, m, f);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
+    // f(k, place, part) for every box k < *nbox (at most `bound` boxes) and part = 0 .. 15,
+    // place = order_by_counting.
+    template <class Step, class F>
+    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, F f)
+    {
+        const int64_t per = 256 / ORDER_GROUP;
+        const int64_t blocks = (bound + per - 1) / per;
+        hipLaunchKernelGGL((k_order_by_counting<Step, F>), dim3((unsigned)blocks), dim3(256), 0, stream_, recs, nbox, (uint32_t)bound, f);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
+    void layout_classes(const ParConst& P, const TensorRec* T, TensorLayout* TL, ClassRec* C)
+    {
+        hipLaunchKernelGGL(k_layout_classes, dim3((unsigned)P.ncls), dim3(256), 0, stream_, P, T, TL, C);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
+    void plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter)
+    {
+        const int64_t lanes = plan_num_lanes(pc, mode);
+        if (lanes <= 0) return;
+        const int64_t blocks = (lanes + 255) / 256;
+        if (blocks > 0x7fffffffLL) throw Error{ VPS_ERR_OOM, "more than 2^39 piece pairs to examine" };
+        hipLaunchKernelGGL(k_plan_emit, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, through ? 1 : 0, lanes,
+                           raw, recs, cap, (unsigned long long*)counter);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
+    // Work queued on the null stream so far (the mapping kernels of vps_describe_config) comes
+    // before what this backend's stream runs next.  A blocking stream is ordered against the null
+    // stream by the runtime; any other stream waits for an event.
+    void after_null_stream()
+    {
+        if (!stream_) return;
+        unsigned flags = 0;
+        if (hipStreamGetFlags(stream_, &flags) == hipSuccess && !(flags & hipStreamNonBlocking)) return;
+        static thread_local hipEvent_t ev = nullptr;
+        if (!ev) VPS_HIP_CHECK(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        VPS_HIP_CHECK(hipEventRecord(ev, nullptr));
+        VPS_HIP_CHECK(hipStreamWaitEvent(stream_, ev, 0));
+    }
+
 
     // Stable ascending sort of (key, value) pairs.  The arrays are passed by reference: after the
     // call they point at the sorted data (the sort ping-pongs between the inputs and two
@@ -313,15 +596,18 @@ public:
 
     hipStream_t stream() const { return stream_; }
 
-    // Tiles per XCD run (0 = plain round-robin); VPS_XCD_CHUNK overrides it for experiments.
-    static uint32_t xcd_chunk()
+    // Tiles per XCD run (0 = plain round-robin).
+    static std::atomic<uint32_t>& xcd_chunk_setting()
     {
-        static const uint32_t v = [] {
-            const char* e = getenv("VPS_XCD_CHUNK");
-            return e ? (uint32_t)atoi(e) : 64u;
-        }();
+        static std::atomic<uint32_t> v{ 64u };
         return v;
     }
+    static uint32_t xcd_chunk() { return xcd_chunk_setting().load(); }
+    static void set_xcd_chunk(uint32_t v) { xcd_chunk_setting() = v; }
+
+    // Wait until the work queued on stream `s` has finished (errors, e.g. a stream that no longer
+    // exists, are ignored: nothing can be running on it then).
+    void wait_stream(void* s) { (void)hipStreamSynchronize((hipStream_t)s); }
 
 private:
     void recycle_dead()

@@ -41,11 +41,14 @@ struct TensorRec {
 // Constants of one parallel configuration, passed to kernels by value.
 struct ParConst {
     int32_t tp, pp, dp, ep, zero, gpn, qkv_layout, expert_layout, flat_order;
-    int32_t ddp;      // dense data-parallel degree = dp*ep
+    int32_t ddp;      // dense data-parallel degree
+    int32_t etp, edp; // tensor- and data-parallel degree of the expert group (etp*ep*edp = tp*ddp)
+    int32_t dmax;     // max(ddp, edp): data-parallel extent of the mapper's item grid
     int32_t world;    // tp*pp*ddp
     int32_t layers, experts, q_per_g;
     int32_t nt;       // logical tensors
     int32_t ncls;     // flat-buffer classes: pp dense + pp*ep expert
+    int32_t per_layer; // logical tensors per layer (ids 1 + l*per_layer .. of layer l)
 };
 
 // Where a tensor's local shard sits in the flat buffer of the ranks that hold it.
@@ -62,9 +65,13 @@ struct ClassRec {
 };
 
 struct RankCoord {
-    int32_t tp, ddp, pp, ep, edp;
+    int32_t tp, ddp, pp, ep, edp, etp;
 };
 
+// Dense tensors see a rank as tp + TP*(ddp + DDP*pp).  The expert group sees the rank's position
+// inside its pipeline stage as etp + ETP*(ep + EP*edp): with EP and expert-DP as a grid beside TP
+// (ETP = TP, EDP = DP, DDP = EP*DP) or with EP carved out of the TP x DP ranks (ETP = 1,
+// EDP = TP*DP/EP, DDP = DP).
 VPS_HD RankCoord decode_rank(const ParConst& P, int32_t r)
 {
     RankCoord c;
@@ -72,15 +79,22 @@ VPS_HD RankCoord decode_rank(const ParConst& P, int32_t r)
     const int32_t q = r / P.tp;
     c.ddp = q % P.ddp;
     c.pp = q / P.ddp;
-    c.ep = c.ddp % P.ep;
-    c.edp = c.ddp / P.ep;
+    const int32_t s = r % (P.tp * P.ddp);
+    c.etp = s % P.etp;
+    c.ep = (s / P.etp) % P.ep;
+    c.edp = s / (P.etp * P.ep);
     return c;
 }
 
-VPS_HD int32_t encode_rank(const ParConst& P, int32_t tp, int32_t ddp, int32_t pp)
+// Rank of group `group` (0 dense, 1 expert) with tensor-parallel index t, data-parallel index d
+// of that group, pipeline stage pp and (expert group only) expert-parallel index ep.
+VPS_HD int32_t encode_rank(const ParConst& P, int32_t group, int32_t t, int32_t d, int32_t pp, int32_t ep)
 {
-    return tp + P.tp * (ddp + P.ddp * pp);
+    return group ? t + P.etp * (ep + P.ep * (d + P.edp * pp)) : t + P.tp * (d + P.ddp * pp);
 }
+
+VPS_HD int32_t group_tp(const ParConst& P, int32_t group) { return group ? P.etp : P.tp; }
+VPS_HD int32_t group_dp(const ParConst& P, int32_t group) { return group ? P.edp : P.ddp; }
 
 // Pipeline stage of a layer when stage p owns layers [floor(p*L/PP), floor((p+1)*L/PP)):
 // the largest p with p*L/PP < layer+1.  The embedding (-1) is on the first stage, everything
@@ -92,11 +106,30 @@ VPS_HD int32_t stage_of_layer(const ParConst& P, int32_t layer)
     return (int32_t)((((int64_t)layer + 1) * P.pp + P.layers - 1) / P.layers) - 1;
 }
 
+// The tensor ids [lo, hi) that live on pipeline stage p: its layers, the embedding on the first
+// stage, everything after the last layer on the last one (ids ascend in forward order).
+VPS_HD void stage_tensor_range(const ParConst& P, int32_t p, int32_t& lo, int32_t& hi)
+{
+    const int32_t l0 = (int32_t)((int64_t)p * P.layers / P.pp), l1 = (int32_t)(((int64_t)p + 1) * P.layers / P.pp);
+    lo = p == 0 ? 0 : 1 + l0 * P.per_layer;
+    hi = p == P.pp - 1 ? P.nt : 1 + l1 * P.per_layer;
+}
+
 VPS_HD int32_t class_of_tensor(const ParConst& P, const TensorRec& x)
 {
     const int32_t pp = stage_of_layer(P, x.layer);
     if (x.group == 0) return pp;
     return P.pp + pp * P.ep + x.expert / (P.experts / P.ep);
+}
+
+// Length of a flat-buffer class and its size padded to 8 elements per data-parallel rank.
+VPS_HD ClassRec make_class_rec(const ParConst& P, int32_t cls, uint64_t len)
+{
+    ClassRec r;
+    r.len = len;
+    const uint64_t quantum = 8ull * (uint64_t)(cls < P.pp ? P.ddp : P.edp);
+    r.padded = (len + quantum - 1) / quantum * quantum;
+    return r;
 }
 
 VPS_HD uint64_t numel4(const int32_t* s)
@@ -106,7 +139,7 @@ VPS_HD uint64_t numel4(const int32_t* s)
 
 VPS_HD uint64_t shard_elems(const ParConst& P, const TensorRec& x)
 {
-    return numel4(x.shape) / (uint64_t)(x.tp_axis >= 0 ? P.tp : 1);
+    return numel4(x.shape) / (uint64_t)(x.tp_axis >= 0 ? group_tp(P, x.group) : 1);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -121,11 +154,11 @@ struct MapCtx {
     int32_t rank_filter;  // -1: all ranks
 };
 
-VPS_HD int64_t map_num_items(const ParConst& P) { return (int64_t)P.nt * 4 * P.tp * P.ddp; }
+VPS_HD int64_t map_num_items(const ParConst& P) { return (int64_t)P.nt * 4 * P.tp * P.dmax; }
 
 VPS_HD int64_t map_group_item(const ParConst& P, int32_t tensor, int32_t kind)
 {
-    return ((int64_t)tensor * 4 + kind) * P.tp * P.ddp;
+    return ((int64_t)tensor * 4 + kind) * P.tp * P.dmax;
 }
 
 // Cut the linear range [v0, v1) of a row-major array with dimensions n[0..3] into the
@@ -133,48 +166,53 @@ VPS_HD int64_t map_group_item(const ParConst& P, int32_t tensor, int32_t kind)
 // aligned and the unit still fits, descend again near the end.  Calls emit(start, axis, count)
 // for each box: it begins at linear position `start`, spans `count` units of `axis` and is
 // full on all finer axes.
-template <class Emit>
-VPS_HD int split_linear_range(const int64_t* n, uint64_t v0, uint64_t v1, Emit emit)
+template <class U, class Emit>
+VPS_HD int split_linear_range_t(const int64_t* n, U v0, U v1, Emit emit)
 {
-    uint64_t st[4];
+    U st[4];
     st[3] = 1;
-    st[2] = (uint64_t)n[3];
-    st[1] = st[2] * (uint64_t)n[2];
-    st[0] = st[1] * (uint64_t)n[1];
+    st[2] = (U)n[3];
+    st[1] = st[2] * (U)n[2];
+    st[0] = st[1] * (U)n[1];
     int count = 0;
-    uint64_t cur = v0;
+    U cur = v0;
     while (cur < v1) {
         int q = 3;
-        while (q > 0 && cur % st[q - 1] == 0 && cur + st[q - 1] <= v1) --q;
-        const uint64_t cq = (cur / st[q]) % (uint64_t)n[q];
-        uint64_t cnt = (uint64_t)n[q] - cq;
-        const uint64_t fit = (v1 - cur) / st[q];
+        while (q > 0 && cur % st[q - 1] == 0 && v1 - cur >= st[q - 1]) --q;
+        const U cq = (cur / st[q]) % (U)n[q];
+        U cnt = (U)n[q] - cq;
+        const U fit = (v1 - cur) / st[q];
         if (fit < cnt) cnt = fit;
-        emit(cur, q, cnt);
+        emit((uint64_t)cur, q, (uint64_t)cnt);
         cur += cnt * st[q];
         ++count;
     }
     return count;
 }
 
+template <class Emit>
+VPS_HD int split_linear_range(const int64_t* n, uint64_t v0, uint64_t v1, Emit emit)
+{
+    // the same in 32-bit arithmetic when the array has fewer than 2^32 elements (integer
+    // division is several times cheaper there)
+    const uint64_t vol = (uint64_t)n[0] * (uint64_t)n[1] * (uint64_t)n[2] * (uint64_t)n[3];
+    if (vol <= 0xffffffffull && v1 <= 0xffffffffull) return split_linear_range_t<uint32_t>(n, (uint32_t)v0, (uint32_t)v1, emit);
+    return split_linear_range_t<uint64_t>(n, v0, v1, emit);
+}
+
 // Pieces of one (tensor, kind, tp, dp-index) item: the part of the local shard that lies in
 // the rank's flat range, as boxes in global coordinates with local offsets and strides.
-// Returns the number of pieces; writes them when out != nullptr.
-VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
+// Calls f(piece) for each of them, in storage order; returns their number.
+template <class F>
+VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t tp, int32_t didx, F f)
 {
     const ParConst& P = c.P;
-    const int32_t didx = (int32_t)(item % P.ddp);
-    int64_t r = item / P.ddp;
-    const int32_t tp = (int32_t)(r % P.tp);
-    r /= P.tp;
-    const int32_t kind = (int32_t)(r % 4);
-    const int32_t t = (int32_t)(r / 4);
     const TensorRec x = c.T[t];
-    const int32_t D = x.group ? P.dp : P.ddp;
-    if (didx >= D) return 0;
+    const int32_t D = group_dp(P, x.group), TPg = group_tp(P, x.group);
+    if (didx >= D || tp >= TPg) return 0;
     const int32_t pp = stage_of_layer(P, x.layer);
-    const int32_t ddp = x.group ? x.expert / (P.experts / P.ep) + P.ep * didx : didx;
-    const int32_t rank = encode_rank(P, tp, ddp, pp);
+    const int32_t ep = x.group ? x.expert / (P.experts / P.ep) : 0;
+    const int32_t rank = encode_rank(P, x.group, tp, didx, pp, ep);
     if (c.rank_filter >= 0 && rank != c.rank_filter) return 0;
 
     const TensorLayout tl = c.TL[t];
@@ -193,7 +231,7 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
     int32_t slo[4], sext[4];
     for (int a = 0; a < 4; ++a) { slo[a] = 0; sext[a] = x.shape[a]; }
     if (x.tp_axis >= 0) {
-        sext[x.tp_axis] = x.shape[x.tp_axis] / P.tp;
+        sext[x.tp_axis] = x.shape[x.tp_axis] / TPg;
         slo[x.tp_axis] = tp * sext[x.tp_axis];
     }
     // storage order of the axes, outermost first
@@ -219,22 +257,22 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
         if (lo < hi) {
             int64_t st[4];
             st[3] = 1; st[2] = n[3]; st[1] = n[3] * n[2]; st[0] = n[3] * n[2] * n[1];
-            int k = npieces;
             npieces += split_linear_range(n, lo - bbase, hi - bbase,
                 [&](uint64_t start, int axis, uint64_t cnt) {
-                    if (!out) return;
-                    vps_piece& p = out[k++];
+                    vps_piece p;
                     p.tensor = t; p.rank = rank; p.kind = kind; p.buf = x.group * 4 + kind;
                     uint64_t rem = start;
                     for (int q = 0; q < 4; ++q) {
                         const int a = order[q];
-                        const int64_t cq = (int64_t)(rem / (uint64_t)st[q]);
+                        const int64_t cq = bvol <= 0xffffffffull ? (int64_t)((uint32_t)rem / (uint32_t)st[q])
+                                                                 : (int64_t)(rem / (uint64_t)st[q]);
                         rem -= (uint64_t)cq * (uint64_t)st[q];
                         p.lo[a] = slo[a] + ((blocked && a == x.blk_axis) ? bo : 0) + (int32_t)cq;
                         p.ext[a] = q < axis ? 1 : (q == axis ? (int32_t)cnt : (int32_t)n[q]);
                         p.stride[a] = st[q];
                     }
                     p.off = (int64_t)(tl.start + bbase + start - r0);
+                    f(p);
                 });
         }
         bbase += bvol;
@@ -242,8 +280,27 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
     return npieces;
 }
 
+VPS_HD void map_decode_item(const ParConst& P, int64_t item, int32_t& t, int32_t& kind, int32_t& tp, int32_t& didx)
+{
+    didx = (int32_t)(item % P.dmax);
+    int64_t r = item / P.dmax;
+    tp = (int32_t)(r % P.tp);
+    r /= P.tp;
+    kind = (int32_t)(r % 4);
+    t = (int32_t)(r / 4);
+}
+
+// The pieces of mapper item `item`; writes them when out != nullptr.  Returns their number.
+VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
+{
+    int32_t t, kind, tp, didx;
+    map_decode_item(c.P, item, t, kind, tp, didx);
+    int k = 0;
+    return map_item_each_piece(c, t, kind, tp, didx, [&](const vps_piece& p) { if (out) out[k++] = p; });
+}
+
 // ------------------------------------------------------------------------------------------
-// Planner: one item per (destination piece, distinct piece of source data).
+// Planner: one item per (destination mapper item, distinct piece of source data).
 // ------------------------------------------------------------------------------------------
 
 VPS_HD int64_t floor_div(int64_t a, int64_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
@@ -263,41 +320,43 @@ VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const Te
 {
     const RankCoord ci = decode_rank(A, i);
     const bool sharded = A.zero == 1 && kind != 0;
-    const int32_t D = x.group ? A.dp : A.ddp;
-    const int32_t di = x.group ? ci.edp : ci.ddp;
-    const int32_t t0 = x.tp_axis < 0 ? 0 : ci.tp, t1 = x.tp_axis < 0 ? A.tp : ci.tp + 1;
+    const int32_t D = group_dp(A, x.group), T = group_tp(A, x.group);
+    const int32_t di = x.group ? ci.edp : ci.ddp, ti = x.group ? ci.etp : ci.tp;
+    const int32_t t0 = x.tp_axis < 0 ? 0 : ti, t1 = x.tp_axis < 0 ? T : ti + 1;
     const int32_t d0 = sharded ? di : 0, d1 = sharded ? di + 1 : D;
     // (1) the destination rank itself, if it is one of the candidates
     if (j < A.world) {
         const RankCoord cj = decode_rank(A, j);
-        const int32_t dj = x.group ? cj.edp : cj.ddp;
-        if (cj.pp == ci.pp && cj.tp >= t0 && cj.tp < t1 && dj >= d0 && dj < d1 && (!x.group || cj.ep == ci.ep))
+        const int32_t dj = x.group ? cj.edp : cj.ddp, tj = x.group ? cj.etp : cj.tp;
+        if (cj.pp == ci.pp && tj >= t0 && tj < t1 && dj >= d0 && dj < d1 && (!x.group || cj.ep == ci.ep))
             return j;
     }
     const RankCoord cb = decode_rank(B, j);
     const int32_t dpj = x.group ? cb.edp : cb.ddp;
     const int32_t nt = t1 - t0;
-    // (2) candidates on j's node.  Row q = ddp + DDP*pp holds the ranks TP*q + tp.
+    // (2) candidates on j's node.  Row q holds the ranks T*q + t: q = d + DDP*pp for dense
+    // tensors, q = ep + EP*(d + EDP*pp) for experts.
     const int64_t n0 = (int64_t)(j / A.gpn) * A.gpn, n1 = n0 + A.gpn;
     const int64_t step = x.group ? A.ep : 1;                       // rows of consecutive candidates
-    const int64_t qfirst = (x.group ? ci.ep + (int64_t)A.ep * d0 : d0) + (int64_t)A.ddp * ci.pp;
+    const int64_t qfirst = x.group ? ci.ep + (int64_t)A.ep * (d0 + (int64_t)A.edp * ci.pp)
+                                   : d0 + (int64_t)A.ddp * ci.pp;
     const int64_t qlast = qfirst + step * (d1 - d0 - 1);
-    int64_t qlo = floor_div(n0 - t1, A.tp) + 1, qhi = floor_div(n1 - t0 - 1, A.tp);
+    int64_t qlo = floor_div(n0 - t1, T) + 1, qhi = floor_div(n1 - t0 - 1, T);
     if (qlo < qfirst) qlo = qfirst;
     if (qhi > qlast) qhi = qlast;
     // align qlo up to a candidate row
     if (qlo > qfirst) qlo = qfirst + (qlo - qfirst + step - 1) / step * step;
     int64_t n_node = 0;
     for (int64_t q = qlo; q <= qhi; q += step) {
-        const int64_t lo = A.tp * q + t0 > n0 ? A.tp * q + t0 : n0;
-        const int64_t hi = A.tp * q + t1 < n1 ? A.tp * q + t1 : n1;
+        const int64_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
+        const int64_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
         if (hi > lo) n_node += hi - lo;
     }
     if (n_node > 0) {
         int64_t want = dpj % n_node;
         for (int64_t q = qlo; q <= qhi; q += step) {
-            const int64_t lo = A.tp * q + t0 > n0 ? A.tp * q + t0 : n0;
-            const int64_t hi = A.tp * q + t1 < n1 ? A.tp * q + t1 : n1;
+            const int64_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
+            const int64_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
             if (hi <= lo) continue;
             if (want < hi - lo) return (int32_t)(lo + want);
             want -= hi - lo;
@@ -307,73 +366,143 @@ VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const Te
     // (3) no candidate on the node: index into all of them, ascending
     const int64_t want = dpj % ((int64_t)nt * (d1 - d0));
     const int64_t q = qfirst + step * (want / nt);
-    return (int32_t)(A.tp * q + t0 + want % nt);
+    return (int32_t)(T * q + t0 + want % nt);
 }
 
 struct PlanCtx {
     ParConst A, B;
-    const TensorRec* T;
-    const vps_piece* SP;       // source pieces, grouped by (tensor, kind)
-    const vps_piece* DP;       // destination pieces
-    const int64_t* sbase;      // source piece index of every mapper item (exclusive scan)
+    MapCtx ma, mb;             // the two configurations' layout tables (rank_filter = -1)
     int32_t rank;              // planned rank or -1
+    // single-rank plans: the tensor ids the rank can hold as a destination / as a source
+    int32_t recv_lo, recv_n, send_lo, send_n;
 };
 
-// Destination piece d is paired with every distinct piece of source data of its (tensor, kind):
+// Fill the tensor ranges of a single-rank plan from the rank's pipeline stages.
+VPS_HD void plan_set_rank_ranges(PlanCtx& c)
+{
+    c.recv_lo = c.recv_n = c.send_lo = c.send_n = 0;
+    if (c.rank < 0) return;
+    int32_t lo, hi;
+    if (c.rank < c.B.world) { stage_tensor_range(c.B, decode_rank(c.B, c.rank).pp, lo, hi); c.recv_lo = lo; c.recv_n = hi - lo; }
+    if (c.rank < c.A.world) { stage_tensor_range(c.A, decode_rank(c.A, c.rank).pp, lo, hi); c.send_lo = lo; c.send_n = hi - lo; }
+}
+
+// A destination item is paired with every distinct piece of source data of its (tensor, kind):
 // one slot per source tp index if the tensor is TP-sharded, times one slot per source
 // data-parallel index if the kind is ZeRO-sharded.  Replicas are not enumerated: the rank that
 // serves a slot is computed from the selection rule.
 VPS_HD int32_t plan_piece_slots(const ParConst& A, const TensorRec& x, int32_t kind)
 {
-    const int32_t nt = x.tp_axis < 0 ? 1 : A.tp;
-    const int32_t nd = (A.zero == 1 && kind != 0) ? (x.group ? A.dp : A.ddp) : 1;
+    const int32_t nt = x.tp_axis < 0 ? 1 : group_tp(A, x.group);
+    const int32_t nd = (A.zero == 1 && kind != 0) ? group_dp(A, x.group) : 1;
     return nt * nd;
 }
 
-VPS_HD int plan_item_boxes(const PlanCtx& c, int64_t d, int32_t u, vps_box* out)
+VPS_HD int32_t plan_max_slots(const ParConst& A) { return A.tp * A.dmax; }
+
+// Which lanes a planning launch enumerates.
+//   PLAN_ALL   every (tensor, kind, destination tp, destination dp index, slot)
+//   PLAN_RECV  destination items of the planned rank only: (tensor, kind, slot)
+//   PLAN_SEND  the slot that the planned rank serves: (tensor, kind, destination tp, dp index);
+//              boxes that stay on the rank are left to PLAN_RECV
+//   PLAN_RANK  the lanes of PLAN_RECV followed by those of PLAN_SEND: everything of one rank
+enum { PLAN_ALL = 0, PLAN_RECV = 1, PLAN_SEND = 2, PLAN_RANK = 3 };
+
+VPS_HD int64_t plan_num_lanes(const PlanCtx& c, int mode)
 {
-    const vps_piece dp = c.DP[d];
-    const TensorRec x = c.T[dp.tensor];
+    const int64_t tk = (int64_t)c.A.nt * 4;
+    if (mode == PLAN_RECV) return (int64_t)c.recv_n * 4 * plan_max_slots(c.A);
+    if (mode == PLAN_SEND) return (int64_t)c.send_n * 4 * c.B.tp * c.B.dmax;
+    if (mode == PLAN_RANK) return plan_num_lanes(c, PLAN_RECV) + plan_num_lanes(c, PLAN_SEND);
+    return tk * c.B.tp * c.B.dmax * plan_max_slots(c.A);
+}
+
+// The routed boxes of one lane: the pieces of one destination item intersected with the pieces
+// of the source rank that serves one slot of source data.  Calls f(box) for each non-empty
+// intersection (lo corners ascending within one pair of pieces only); returns their number.
+template <class F>
+VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
+{
     const ParConst& A = c.A;
-    const int32_t nd = (A.zero == 1 && dp.kind != 0) ? (x.group ? A.dp : A.ddp) : 1;
+    const ParConst& B = c.B;
+    int32_t t, kind, tpb, db, u;
+    if (mode == PLAN_RANK) {
+        const int64_t nrecv = plan_num_lanes(c, PLAN_RECV);
+        mode = lane < nrecv ? PLAN_RECV : PLAN_SEND;
+        if (mode == PLAN_SEND) lane -= nrecv;
+    }
+    if (mode == PLAN_ALL) {
+        const int32_t smax = plan_max_slots(A);
+        u = (int32_t)(lane % smax);
+        map_decode_item(B, lane / smax, t, kind, tpb, db);
+    } else if (mode == PLAN_RECV) {
+        const int32_t smax = plan_max_slots(A);
+        u = (int32_t)(lane % smax);
+        kind = (int32_t)((lane / smax) % 4);
+        t = c.recv_lo + (int32_t)(lane / smax / 4);
+        tpb = db = 0;
+    } else {
+        map_decode_item(B, lane, t, kind, tpb, db);
+        t += c.send_lo;
+        u = 0;
+    }
+    const TensorRec x = c.ma.T[t];
+    if (mode == PLAN_RECV) {
+        if (c.rank >= B.world) return 0;
+        const RankCoord cr = decode_rank(B, c.rank);
+        tpb = x.group ? cr.etp : cr.tp;
+        db = x.group ? cr.edp : cr.ddp;
+        // the rank holds the tensor only on its own stage (and expert block)
+        if (stage_of_layer(B, x.layer) != cr.pp || (x.group && x.expert / (B.experts / B.ep) != cr.ep)) return 0;
+    }
+    if (tpb >= group_tp(B, x.group) || db >= group_dp(B, x.group)) return 0;
+    const int32_t nd = (A.zero == 1 && kind != 0) ? group_dp(A, x.group) : 1;
+    if (mode == PLAN_SEND) {
+        if (c.rank >= A.world) return 0;
+        const RankCoord cs = decode_rank(A, c.rank);
+        if (stage_of_layer(A, x.layer) != cs.pp || (x.group && x.expert / (A.experts / A.ep) != cs.ep)) return 0;
+        u = (x.tp_axis < 0 ? 0 : (x.group ? cs.etp : cs.tp)) * nd + (nd > 1 ? (x.group ? cs.edp : cs.ddp) : 0);
+    }
+    if (u >= plan_piece_slots(A, x, kind)) return 0;
+    const int32_t ppb = stage_of_layer(B, x.layer), epb = x.group ? x.expert / (B.experts / B.ep) : 0;
+    const int32_t dst_rank = encode_rank(B, x.group, tpb, db, ppb, epb);
+    if (mode == PLAN_SEND && dst_rank == c.rank) return 0;
     const int32_t tp_rep = x.tp_axis < 0 ? 0 : u / nd, d_rep = u % nd;
-    const int32_t pp = stage_of_layer(A, x.layer);
-    const int32_t ddp_rep = x.group ? x.expert / (A.experts / A.ep) + A.ep * d_rep : d_rep;
-    const int32_t src = select_source_rank(A, c.B, x, dp.kind, encode_rank(A, tp_rep, ddp_rep, pp), dp.rank);
-    if (c.rank >= 0 && dp.rank != c.rank && src != c.rank) return 0;
-    // the pieces of the serving rank are those of one mapper item
+    if (x.tp_axis >= 0) {
+        // the two shards must overlap on the tensor-parallel axis
+        const int32_t ea = x.shape[x.tp_axis] / group_tp(A, x.group), eb = x.shape[x.tp_axis] / group_tp(B, x.group);
+        if (tp_rep * ea >= (tpb + 1) * eb || tpb * eb >= (tp_rep + 1) * ea) return 0;
+    }
+    const int32_t ppa = stage_of_layer(A, x.layer), epa = x.group ? x.expert / (A.experts / A.ep) : 0;
+    const int32_t src = select_source_rank(A, B, x, kind, encode_rank(A, x.group, tp_rep, d_rep, ppa, epa), dst_rank);
+    if (c.rank >= 0 && dst_rank != c.rank && src != c.rank) return 0;
     const RankCoord cs = decode_rank(A, src);
-    const int64_t it = map_group_item(A, dp.tensor, dp.kind) + (int64_t)cs.tp * A.ddp + (x.group ? cs.edp : cs.ddp);
-    const int64_t sa = c.sbase[it], sb = c.sbase[it + 1];
+    const int32_t tps = x.group ? cs.etp : cs.tp, ds = x.group ? cs.edp : cs.ddp;
     int n = 0;
-    for (int64_t s = sa; s < sb; ++s) {
-        const vps_piece sp = c.SP[s];
-        int32_t lo[4], ext[4];
-        bool empty = false;
-        for (int a = 0; a < 4; ++a) {
-            const int32_t l = sp.lo[a] > dp.lo[a] ? sp.lo[a] : dp.lo[a];
-            const int32_t hs = sp.lo[a] + sp.ext[a], hd = dp.lo[a] + dp.ext[a];
-            const int32_t h = hs < hd ? hs : hd;
-            if (l >= h) empty = true;
-            lo[a] = l; ext[a] = h - l;
-        }
-        if (empty) continue;
-        if (out) {
-            vps_box& b = out[n];
-            b.tensor = dp.tensor; b.kind = dp.kind;
+    map_item_each_piece(c.mb, t, kind, tpb, db, [&](const vps_piece& dp) {
+        map_item_each_piece(c.ma, t, kind, tps, ds, [&](const vps_piece& sp) {
+            vps_box b;
+            for (int a = 0; a < 4; ++a) {
+                const int32_t l = sp.lo[a] > dp.lo[a] ? sp.lo[a] : dp.lo[a];
+                const int32_t hs = sp.lo[a] + sp.ext[a], hd = dp.lo[a] + dp.ext[a];
+                const int32_t h = hs < hd ? hs : hd;
+                if (l >= h) return;
+                b.lo[a] = l; b.ext[a] = h - l;
+            }
+            b.tensor = t; b.kind = kind;
             b.src_rank = sp.rank; b.dst_rank = dp.rank;
             b.src_buf = sp.buf; b.dst_buf = dp.buf;
             b.src_off = sp.off; b.dst_off = dp.off;
             for (int a = 0; a < 4; ++a) {
-                b.lo[a] = lo[a]; b.ext[a] = ext[a];
                 b.src_stride[a] = sp.stride[a]; b.dst_stride[a] = dp.stride[a];
-                b.src_off += (int64_t)(lo[a] - sp.lo[a]) * sp.stride[a];
-                b.dst_off += (int64_t)(lo[a] - dp.lo[a]) * dp.stride[a];
+                b.src_off += (int64_t)(b.lo[a] - sp.lo[a]) * sp.stride[a];
+                b.dst_off += (int64_t)(b.lo[a] - dp.lo[a]) * dp.stride[a];
             }
             b.send_pos = UINT64_MAX; b.recv_pos = UINT64_MAX;
-        }
-        ++n;
-    }
+            f(b);
+            ++n;
+        });
+    });
     return n;
 }
 
@@ -390,6 +519,14 @@ VPS_HD uint64_t box_slot_bytes(const vps_box& b)
     return (box_volume(b) * kind_bytes(b.kind) + 15ull) & ~15ull;
 }
 
+// A box whose source and destination rank coincide is copied directly old-local -> new-local
+// (T_retain of Section 4.2.1), unless the plan sends everything through the peer buffers: then
+// a rank is its own peer and the box is packed and unpacked like any other.
+VPS_HD bool box_retained(const vps_box& b, bool through_buffers)
+{
+    return !through_buffers && b.src_rank == b.dst_rank;
+}
+
 // Order inside a peer buffer: kinds 1,2,3 then 0; tensor id; lo corner in row-major order.
 VPS_HD uint64_t box_major_key(const vps_box& b, bool by_dst)
 {
@@ -398,11 +535,102 @@ VPS_HD uint64_t box_major_key(const vps_box& b, bool by_dst)
     const uint64_t korder = (uint64_t)((b.kind + 3) & 3);
     return (((first << 16 | second) << 2 | korder) << 24) | (uint64_t)b.tensor;
 }
+enum { MAJOR_KEY_OWNER_SHIFT = 42 };  // key >> 42 = the rank that owns the buffer
 
 VPS_HD uint64_t box_minor_key(const vps_box& b, const TensorRec& x)
 {
     return (((uint64_t)b.lo[0] * (uint64_t)x.shape[1] + (uint64_t)b.lo[1]) * (uint64_t)x.shape[2] +
             (uint64_t)b.lo[2]) * (uint64_t)x.shape[3] + (uint64_t)b.lo[3];
+}
+
+// What the ordering passes need of a box: its keys in the send and in the receive order and the
+// bytes it takes in a peer buffer (a multiple of 16; the low bits say whether it counts in its
+// source's send buffer and in its destination's receive buffer: it travels and that rank's
+// buffers are on this GPU).
+struct OrderRec {
+    uint64_t key_s, key_r, klo, bytes_flags;
+};
+enum : uint64_t { ORD_SENDS = 1, ORD_RECEIVES = 2 };
+
+VPS_HD OrderRec make_order_rec(const vps_box& b, const TensorRec& x, int32_t planned_rank, bool through_buffers)
+{
+    OrderRec r;
+    r.key_s = box_major_key(b, false);
+    r.key_r = box_major_key(b, true);
+    r.klo = box_minor_key(b, x);
+    r.bytes_flags = box_slot_bytes(b);
+    if (!box_retained(b, through_buffers)) {
+        if (planned_rank < 0 || b.src_rank == planned_rank) r.bytes_flags |= ORD_SENDS;
+        if (planned_rank < 0 || b.dst_rank == planned_rank) r.bytes_flags |= ORD_RECEIVES;
+    }
+    return r;
+}
+
+// Place of a box in both orders by counting over all n boxes: its index is the number of boxes
+// with a smaller key, its cumulative buffer position the bytes of the counted ones among them;
+// base_* are the bytes that belong to ranks before the box's owner.  Keys are unique (boxes of
+// one tensor and kind between two ranks are disjoint), so the indices are a permutation.
+struct OrderPlace {
+    uint32_t idx_s, idx_r;
+    uint64_t gpos_s, gpos_r, base_s, base_r;
+};
+
+VPS_HD OrderPlace order_place_zero()
+{
+    OrderPlace o;
+    o.idx_s = o.idx_r = 0;
+    o.gpos_s = o.gpos_r = o.base_s = o.base_r = 0;
+    return o;
+}
+
+VPS_HD uint64_t order_send_bytes(const OrderRec& r) { return (r.bytes_flags & ORD_SENDS) ? r.bytes_flags & ~(uint64_t)15 : 0; }
+VPS_HD uint64_t order_recv_bytes(const OrderRec& r) { return (r.bytes_flags & ORD_RECEIVES) ? r.bytes_flags & ~(uint64_t)15 : 0; }
+
+// One more box r for the place of box `me`; floor_* is the smallest key of me's owner rank.
+VPS_HD void order_count_one(const OrderRec& r, const OrderRec& me, uint64_t floor_s, uint64_t floor_r, OrderPlace& o)
+{
+    const uint64_t sb = order_send_bytes(r), rb = order_recv_bytes(r);
+    const bool less_s = r.key_s < me.key_s || (r.key_s == me.key_s && r.klo < me.klo);
+    const bool less_r = r.key_r < me.key_r || (r.key_r == me.key_r && r.klo < me.klo);
+    o.idx_s += less_s ? 1u : 0u;
+    o.idx_r += less_r ? 1u : 0u;
+    o.gpos_s += less_s ? sb : 0;
+    o.gpos_r += less_r ? rb : 0;
+    o.base_s += r.key_s < floor_s ? sb : 0;
+    o.base_r += r.key_r < floor_r ? rb : 0;
+}
+
+VPS_HD uint64_t order_owner_floor(uint64_t key) { return key >> MAJOR_KEY_OWNER_SHIFT << MAJOR_KEY_OWNER_SHIFT; }
+
+VPS_HD OrderPlace order_by_counting(const OrderRec* recs, uint32_t n, uint32_t k)
+{
+    const OrderRec me = recs[k];
+    const uint64_t floor_s = order_owner_floor(me.key_s), floor_r = order_owner_floor(me.key_r);
+    OrderPlace o = order_place_zero();
+    for (uint32_t q = 0; q < n; ++q) order_count_one(recs[q], me, floor_s, floor_r, o);
+    return o;
+}
+
+// Words at the head of a plan's summary block.
+enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_HEADER = 8 };
+
+// Accumulate into a counter shared by all items of a step.
+VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    atomicAdd((unsigned long long*)p, (unsigned long long)v);
+#else
+    *p += v;
+#endif
+}
+
+VPS_HD void be_atomic_or(uint32_t* p, uint32_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    atomicOr(p, v);
+#else
+    *p |= v;
+#endif
 }
 
 // ------------------------------------------------------------------------------------------
@@ -468,14 +696,6 @@ VPS_HD int32_t num_slots(const PtrLayout& L)
 // A box that would need 2^31 tiles or more saturates the count; the planner then reports
 // VPS_ERR_OOM instead of building a wrapped-around table.
 VPS_HD uint32_t clamp_tiles(uint64_t n) { return n >= (1ull << 31) ? (1u << 31) : (uint32_t)n; }
-
-// A box whose source and destination rank coincide is copied directly old-local -> new-local
-// (T_retain of Section 4.2.1), unless the plan sends everything through the peer buffers: then
-// a rank is its own peer and the box is packed and unpacked like any other.
-VPS_HD bool box_retained(const vps_box& b, bool through_buffers)
-{
-    return !through_buffers && b.src_rank == b.dst_rank;
-}
 
 // Super-block shape of a transposed box as sa | sb << 16 (see xpose_plane_order), 64 blocks per
 // super-block.  Rows of a block are 64 elements long and lie `pitch` bytes apart.  On the side
@@ -794,6 +1014,51 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
     return t;
 }
 
+// What the planner's last per-box step needs: where the statistics, the per-pair byte counts,
+// the used-slot flags, the copy descriptors and their tile counts go.
+struct FinishCtx {
+    int32_t rank, wa, wb;
+    bool through_buffers, routes_only;
+    PtrLayout layout;
+    uint32_t tile_bytes, xpose_shape;
+    uint64_t* sum;      // summary block (SUM_* counters at its head)
+    uint64_t* pairs;    // all ranks: [src*wb + dst]; one rank r: [src] = src -> r, [wa + dst] = r -> dst
+    uint8_t* used;      // [op][slot]
+    int64_t nslots;
+    CopyDesc* descs;    // [3n]
+    int64_t* ntiles;    // [3n + 1]
+};
+
+// Once per box: statistics and the payload bytes per (source, destination) pair.
+VPS_HD void account_box(const FinishCtx& c, const vps_box& b)
+{
+    const uint64_t bytes = box_volume(b) * kind_bytes(b.kind);
+    if (c.rank < 0) be_atomic_add(&c.pairs[(int64_t)b.src_rank * c.wb + b.dst_rank], bytes);
+    else {
+        if (b.dst_rank == c.rank) be_atomic_add(&c.pairs[b.src_rank], bytes);
+        if (b.src_rank == c.rank) be_atomic_add(&c.pairs[c.wa + b.dst_rank], bytes);
+    }
+    if (box_retained(b, c.through_buffers)) be_atomic_add(&c.sum[SUM_NRETAIN], 1);
+    else {
+        if (c.rank < 0 || b.src_rank == c.rank) be_atomic_add(&c.sum[SUM_NSEND], 1);
+        if (c.rank < 0 || b.dst_rank == c.rank) be_atomic_add(&c.sum[SUM_NRECV], 1);
+    }
+}
+
+// Copy descriptor `i` (operation op of box b) and its tile count.
+VPS_HD void describe_box_op(const FinishCtx& c, const vps_box& b, int op, int64_t i)
+{
+    if (c.routes_only) { c.ntiles[i] = 0; return; }
+    CopyDesc d;
+    make_copy_desc(b, op, c.layout, c.rank, c.through_buffers, c.tile_bytes, c.xpose_shape, d);
+    c.descs[i] = d;
+    c.ntiles[i] = d.ntiles;
+    if (d.ntiles) {
+        c.used[op * c.nslots + d.src_slot] = 1;
+        c.used[op * c.nslots + d.dst_slot] = 1;
+    }
+}
+
 // Element k of an ELEM descriptor: byte offsets relative to the descriptor bases.
 VPS_HD void elem_offsets(const CopyDesc& d, uint64_t k, int64_t& so, int64_t& to)
 {
@@ -805,25 +1070,6 @@ VPS_HD void elem_offsets(const CopyDesc& d, uint64_t k, int64_t& so, int64_t& to
           (int64_t)c3 * d.sstr[3]) * (int64_t)d.es;
     to = ((int64_t)c0 * d.dstr[0] + (int64_t)c1 * d.dstr[1] + (int64_t)c2 * d.dstr[2] +
           (int64_t)c3 * d.dstr[3]) * (int64_t)d.es;
-}
-
-// Accumulate into a counter shared by all items of a step.
-VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    atomicAdd((unsigned long long*)p, (unsigned long long)v);
-#else
-    *p += v;
-#endif
-}
-
-VPS_HD void be_atomic_or(uint32_t* p, uint32_t v)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    atomicOr(p, v);
-#else
-    *p |= v;
-#endif
 }
 
 // ------------------------------------------------------------------------------------------

@@ -33,29 +33,21 @@ namespace vps {
 
 // One tag per data-parallel step: it names the kernel in profiles.
 namespace step {
-struct map_tensor_class {};
-struct map_shard_lengths {};
-struct map_class_bounds {};
-struct map_class_lengths {};
-struct map_tensor_offsets {};
+struct map_inventory {};
 struct map_count_pieces {};
 struct map_emit_pieces {};
-struct plan_piece_slots {};
-struct plan_count_boxes {};
-struct plan_emit_boxes {};
-struct plan_key_lo {};
+struct plan_order_by_counting {};
+struct plan_keys {};
 struct plan_key_send {};
 struct plan_key_recv {};
 struct plan_slot_sizes {};
-struct plan_rank_bounds {};
 struct plan_positions {};
-struct plan_rank_bases {};
-struct plan_pair_bytes {};
-struct plan_copy_descs {};
-struct plan_tile_table {};
 struct plan_sorted_boxes {};
 struct plan_recv_perm {};
-struct plan_count_retained {};
+struct plan_pair_bytes {};
+struct plan_copy_descs {};
+struct plan_rank_tables {};
+struct plan_tile_table {};
 struct coll_keys {};
 struct coll_group_key {};
 struct coll_flags {};
@@ -71,15 +63,18 @@ struct ConfigData {
     vps_model_desc model;
     vps_parallel_desc par;
     ParConst P;
+    ModelConst M;
     int32_t rank_filter = -1;
     // backend memory
     TensorRec* T = nullptr;
     TensorLayout* TL = nullptr;
     ClassRec* C = nullptr;
+    // made on demand by the piece queries
     int64_t* piece_base = nullptr;  // map_num_items + 1
     vps_piece* pieces = nullptr;
-    int64_t npieces = 0;
+    int64_t npieces = -1;
     // host copies
+    bool host_ready = false;        // hC holds the class table
     std::vector<ClassRec> hC;
     uint64_t tensor_numel_max = 1;  // elements of the largest logical tensor
 };
@@ -91,6 +86,8 @@ inline int bits_for(uint64_t max_value_exclusive)
     return b;
 }
 
+// What the host keeps of a plan.  Everything here arrives with the one device-to-host copy of the
+// plan's summary block; the boxes themselves stay on the device until a query asks for them.
 struct PlanData {
     ParConst A, B;
     int32_t rank = -1;
@@ -102,22 +99,22 @@ struct PlanData {
     // backend memory
     CopyDesc* descs = nullptr;  // 3*nboxes: retain | pack (send order), unpack (receive order)
     TileRef* tiles = nullptr;
+    int64_t* d_tile_base = nullptr;  // 3*nboxes + 1: first tile of every descriptor
     void** ptr_table = nullptr;  // all-ranks plans: device copy of the pointer table
-    vps_box* d_boxes = nullptr;      // the boxes in send order (device copy of boxes_send_order)
-    uint32_t* d_recv_perm = nullptr; // device copy of recv_perm
-    // host copies
-    // An all-ranks plan without copy tables brings the two arrays below to the host only when a
-    // query asks for them (host_boxes_ready): for thousands of ranks they are tens of megabytes,
-    // several times the cost of planning itself.
+    vps_box* d_boxes = nullptr;      // the boxes in send order: (src, dst, kind order, tensor, lo)
+    uint32_t* d_recv_perm = nullptr; // receive order -> index into d_boxes
+    // host copies, fetched on first use
     bool host_boxes_ready = false;
-    std::vector<vps_box> boxes_send_order;   // sorted by (src, dst, kind order, tensor, lo)
-    std::vector<uint32_t> recv_perm;         // receive order -> index into boxes_send_order
-    std::vector<int64_t> tile_base;          // 3*nboxes + 1
+    std::vector<vps_box> boxes_send_order;
+    std::vector<uint32_t> recv_perm;
+    std::vector<int64_t> tile_base;
+    // host copies that come with the plan
     std::vector<int64_t> first_send, first_recv;  // per rank: first box index, W+1 long
     std::vector<uint64_t> send_base, recv_base;   // per rank: offset of its buffer, W+1 long
+    std::vector<int64_t> op_tile[3];              // per operation and rank: first tile, W+1 long
     std::vector<uint64_t> pair_bytes;             // all ranks: [src*WB + dst]; one rank r:
                                                   // [src] = src -> r for src < WA, [WA + dst] = r -> dst
-    std::vector<void*> host_ptrs;                 // staging for the pointer table
+    std::vector<uint8_t> used[3];                 // per operation: pointer-table slots it dereferences
     vps_plan_stats_t stats;
 };
 
@@ -132,83 +129,63 @@ template <class BE>
 void free_plan(BE& be, PlanData& p)
 {
     be.free(p.descs); be.free(p.tiles); be.free(p.ptr_table); be.free(p.d_boxes); be.free(p.d_recv_perm);
+    be.free(p.d_tile_base);
     p.descs = nullptr; p.tiles = nullptr; p.ptr_table = nullptr; p.d_boxes = nullptr; p.d_recv_perm = nullptr;
+    p.d_tile_base = nullptr;
 }
 
 // ---------------------------------------------------------------------------------- mapper
 
+// F_P (Section 4.1, 4.2.2): the tensor table and, per flat-buffer class, the offsets of the
+// tensors' shards.  Two launches on the null stream, nothing waits: the class table is copied
+// to the host when the first size query asks for it.
 template <class BE>
 void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& par,
                   int32_t rank_filter, ConfigData& c)
 {
     check_descs(model, par);
-    std::vector<TensorRec> inv;
-    build_inventory(model, inv);
-    const int32_t nt = (int32_t)inv.size();
+    c.M = make_model_const(model);
+    const ModelConst M = c.M;
+    const int32_t nt = M.nt;
     c.model = model; c.par = par; c.rank_filter = rank_filter;
     c.P = make_par_const(model, par, nt);
     const ParConst P = c.P;
     if (rank_filter < -1 || rank_filter >= P.world) throw Error{ VPS_ERR_RANK_RANGE, "rank outside the configuration's world" };
+    c.tensor_numel_max = model_numel_max(M);
 
     c.T = be.template alloc<TensorRec>(nt);
     c.TL = be.template alloc<TensorLayout>(nt);
     c.C = be.template alloc<ClassRec>(P.ncls);
-    be.upload(c.T, inv.data(), sizeof(TensorRec) * (size_t)nt);
-    c.tensor_numel_max = 1;
-    for (const TensorRec& x : inv)
-        if (numel4(x.shape) > c.tensor_numel_max) c.tensor_numel_max = numel4(x.shape);
+    {
+        TensorRec* T = c.T;
+        be.for_each(step::map_inventory(), nt, [=] VPS_LAMBDA(int64_t t) { T[t] = inventory_rec(M, (int32_t)t); });
+    }
+    be.layout_classes(P, c.T, c.TL, c.C);
+    c.hC.resize((size_t)P.ncls);
+    c.host_ready = false;
+}
 
-    // (1) class and shard length of every tensor; sort keys in flat-buffer order
-    uint64_t* key = be.template alloc<uint64_t>(nt);
-    uint32_t* val = be.template alloc<uint32_t>(nt);
-    int64_t* len = be.template alloc<int64_t>(nt + 1);
-    int64_t* ofs = be.template alloc<int64_t>(nt + 1);
-    int64_t* cbeg = be.template alloc<int64_t>(P.ncls + 1);
-    {
-        const TensorRec* T = c.T; TensorLayout* TL = c.TL;
-        be.for_each(step::map_tensor_class(), nt, [=] VPS_LAMBDA(int64_t q) {
-            const int32_t t = P.flat_order ? nt - 1 - (int32_t)q : (int32_t)q;
-            const TensorRec x = T[t];
-            TensorLayout tl;
-            tl.cls = class_of_tensor(P, x);
-            tl.shard_len = shard_elems(P, x);
-            tl.start = 0; tl.pad_ = 0;
-            TL[t] = tl;
-            key[q] = (uint64_t)tl.cls;
-            val[q] = (uint32_t)t;
-        });
-    }
-    // (2) group the tensors by class, keeping flat order inside a class
-    be.sort_pairs(key, val, nt, bits_for((uint64_t)P.ncls));
-    {
-        const TensorLayout* TL = c.TL;
-        be.for_each(step::map_shard_lengths(), nt + 1, [=] VPS_LAMBDA(int64_t k) { len[k] = k < nt ? (int64_t)TL[val[k]].shard_len : 0; });
-    }
-    be.exclusive_scan(len, ofs, nt);
-    // (3) class boundaries, lengths and padding
-    {
-        ClassRec* C = c.C;
-        be.for_each(step::map_class_bounds(), P.ncls + 1, [=] VPS_LAMBDA(int64_t cls) { cbeg[cls] = lower_bound_idx(key, (int64_t)nt, (uint64_t)cls); });
-        be.for_each(step::map_class_lengths(), P.ncls, [=] VPS_LAMBDA(int64_t cls) {
-            ClassRec r;
-            r.len = (uint64_t)(ofs[cbeg[cls + 1]] - ofs[cbeg[cls]]);
-            const uint64_t quantum = 8ull * (uint64_t)(cls < P.pp ? P.ddp : P.dp);
-            r.padded = (r.len + quantum - 1) / quantum * quantum;
-            C[cls] = r;
-        });
-        TensorLayout* TL = c.TL;
-        be.for_each(step::map_tensor_offsets(), nt, [=] VPS_LAMBDA(int64_t k) {
-            TL[val[k]].start = (uint64_t)(ofs[k] - ofs[cbeg[key[k]]]);
-        });
-    }
-    be.free(key); be.free(val); be.free(len); be.free(ofs); be.free(cbeg);
+// The class table on the host (buffer sizes), waiting for the mapping kernels if need be.
+template <class BE>
+void ensure_config_host(BE& be, ConfigData& c)
+{
+    if (c.host_ready) return;
+    be.download(c.hC.data(), c.C, sizeof(ClassRec) * c.hC.size());
+    c.host_ready = true;
+}
 
-    // (4) pieces: count, scan, emit
+// The piece table (Section 4.1, sub-VPS): only the piece queries need it; the planner derives
+// the pieces of an item on the fly.
+template <class BE>
+void ensure_pieces(BE& be, ConfigData& c)
+{
+    if (c.npieces >= 0) return;
+    const ParConst P = c.P;
     const int64_t nitems = map_num_items(P);
     int64_t* cnt = be.template alloc<int64_t>(nitems + 1);
     c.piece_base = be.template alloc<int64_t>(nitems + 1);
     MapCtx mc;
-    mc.P = P; mc.T = c.T; mc.TL = c.TL; mc.C = c.C; mc.rank_filter = rank_filter;
+    mc.P = P; mc.T = c.T; mc.TL = c.TL; mc.C = c.C; mc.rank_filter = c.rank_filter;
     be.for_each(step::map_count_pieces(), nitems + 1, [=] VPS_LAMBDA(int64_t i) { cnt[i] = i < nitems ? map_item_pieces(mc, i, nullptr) : 0; });
     be.exclusive_scan(cnt, c.piece_base, nitems);
     be.download(&c.npieces, c.piece_base + nitems, sizeof(int64_t));
@@ -220,8 +197,6 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
         });
     }
     be.free(cnt);
-    c.hC.resize((size_t)P.ncls);
-    be.download_later(c.hC.data(), c.C, sizeof(ClassRec) * (size_t)P.ncls);
     be.sync();
 }
 
@@ -230,16 +205,27 @@ inline uint64_t config_buffer_elems(const ConfigData& c, int32_t rank, int32_t b
     const RankCoord rc = decode_rank(c.P, rank);
     const int group = buf / 4, kind = buf % 4;
     const ClassRec& cl = c.hC[(size_t)(group == 0 ? rc.pp : c.P.pp + rc.pp * c.P.ep + rc.ep)];
-    const int D = group == 0 ? c.P.ddp : c.P.dp;
+    const int D = group_dp(c.P, group);
     return (c.P.zero == 1 && kind != 0) ? cl.padded / (uint64_t)D : cl.padded;
 }
 
 // --------------------------------------------------------------------------------- planner
 
+// Layout of a plan's summary block (64-bit words): counters, per-rank tables, pair bytes, then
+// one byte per (operation, pointer-table slot).  It is cleared before planning, filled by the
+// planning kernels and copied to the host once.
+struct SummaryLayout {
+    int64_t W, npairs, nslots;
+    int64_t rank_tables() const { return SUM_HEADER; }
+    int64_t pairs() const { return SUM_HEADER + 7 * (W + 1); }
+    int64_t used() const { return pairs() + npairs; }
+    int64_t words() const { return used() + (3 * nslots + 7) / 8; }
+};
+
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
-                uint32_t tile_bytes, uint32_t xpose_shape, bool routes_only,
-                bool through_buffers, PlanData& p)
+                uint32_t tile_bytes, uint32_t xpose_shape, uint32_t small_limit, bool routes_only,
+                bool through_buffers, int64_t tile_hint, PlanData& p)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -249,227 +235,277 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     const ParConst A = ca.P, B = cb.P;
     const int32_t WA = A.world, WB = B.world, W = WA > WB ? WA : WB;
     if (rank < -1 || rank >= W) throw Error{ VPS_ERR_RANK_RANGE, "rank outside both worlds" };
+    if (rank < 0 && (int64_t)WA * WB > ((int64_t)1 << 26))
+        throw Error{ VPS_ERR_OOM, "an all-ranks plan of this many ranks needs a byte matrix above 512 MiB" };
     p.A = A; p.B = B; p.rank = rank; p.tile_bytes = tile_bytes; p.routes_only = routes_only;
     p.through_buffers = through_buffers;
     p.layout.all_ranks = rank < 0; p.layout.wa = WA; p.layout.wb = WB;
     const PtrLayout layout = p.layout;
+    be.after_null_stream();   // the configurations were mapped on the null stream
 
-    // (1) intersections: one item per (destination piece, distinct piece of source data)
     PlanCtx pc;
-    pc.A = A; pc.B = B; pc.T = ca.T; pc.SP = ca.pieces; pc.DP = cb.pieces; pc.sbase = ca.piece_base;
-    pc.rank = rank;
-    const int64_t npb = cb.npieces;
-    int64_t* nslot = be.template alloc<int64_t>(npb + 1);
-    int64_t* slot0 = be.template alloc<int64_t>(npb + 1);
-    {
-        const vps_piece* DPp = cb.pieces; const TensorRec* T = ca.T;
-        be.for_each(step::plan_piece_slots(), npb + 1, [=] VPS_LAMBDA(int64_t d) {
-            nslot[d] = d < npb ? plan_piece_slots(A, T[DPp[d].tensor], DPp[d].kind) : 0;
+    pc.A = A; pc.B = B; pc.rank = rank;
+    pc.ma.P = A; pc.ma.T = ca.T; pc.ma.TL = ca.TL; pc.ma.C = ca.C; pc.ma.rank_filter = -1;
+    pc.mb.P = B; pc.mb.T = cb.T; pc.mb.TL = cb.TL; pc.mb.C = cb.C; pc.mb.rank_filter = -1;
+    plan_set_rank_ranges(pc);
+
+    SummaryLayout SL;
+    SL.W = W; SL.npairs = rank < 0 ? (int64_t)WA * WB : (int64_t)WA + WB; SL.nslots = num_slots(layout);
+    uint64_t* sum = be.template alloc<uint64_t>(SL.words());
+    be.zero(sum, sizeof(uint64_t) * (size_t)SL.words());
+    uint64_t* pairs = sum + SL.pairs();
+    uint8_t* used = (uint8_t*)(sum + SL.used());
+    const int64_t nslots = SL.nslots;
+
+    // (1) intersections: every lane walks the routed boxes of its item and writes each, with its
+    // ordering keys, into the next free slot of the raw table (one atomic per wavefront and
+    // step).  The table holds `cap` boxes; a plan with more is planned again with the exact size.
+    int64_t cap = small_limit;
+    vps_box* raw = be.template alloc<vps_box>(cap);
+    OrderRec* recs = be.template alloc<OrderRec>(cap);
+    auto emit = [&]() { be.plan_emit(pc, rank < 0 ? PLAN_ALL : PLAN_RANK, through_buffers, raw, recs, (uint64_t)cap, sum + SUM_NBOXES); };
+    emit();
+
+    FinishCtx fc;
+    fc.rank = rank; fc.wa = WA; fc.wb = WB; fc.through_buffers = through_buffers; fc.routes_only = routes_only;
+    fc.layout = layout; fc.tile_bytes = tile_bytes; fc.xpose_shape = xpose_shape;
+    fc.sum = sum; fc.pairs = pairs; fc.used = used; fc.nslots = nslots;
+
+    // (2) up to small_limit boxes: order and buffer positions by counting.  Box k's index in the
+    // send order is the number of boxes with a smaller (src, dst, kind order, tensor, lo) key, its
+    // position the bytes of the travelling ones among them that share its source; the same for
+    // the receive order.  The lane then writes the box to its place and builds its copy
+    // descriptors.  One launch, no sort, no scan.
+    const int64_t ns = small_limit;          // bound of the optimistic path
+    vps_box* sorted = be.template alloc<vps_box>(ns);
+    uint32_t* rperm = be.template alloc<uint32_t>(ns);
+    uint64_t* gs = be.template alloc<uint64_t>(ns + 1);
+    uint64_t* gr = be.template alloc<uint64_t>(ns + 1);
+    CopyDesc* descs = routes_only ? nullptr : be.template alloc<CopyDesc>(3 * ns);
+    int64_t* ntl = be.template alloc<int64_t>(3 * ns + 1);
+    int64_t* tb = be.template alloc<int64_t>(3 * ns + 1);
+    const uint64_t* nbox = sum + SUM_NBOXES;
+    fc.descs = descs; fc.ntiles = ntl;
+    be.order_by_counting_each(step::plan_order_by_counting(), recs, nbox, ns, [=] VPS_LAMBDA(uint32_t k, const OrderPlace& o, uint32_t part) {
+        if (part > 2) return;   // three lanes go on, one per copy operation
+        const int64_t n = (int64_t)*nbox;
+        vps_box b = raw[k];
+        const OrderRec rec = recs[k];
+        if (rec.bytes_flags & ORD_SENDS) b.send_pos = o.gpos_s - o.base_s;
+        if (rec.bytes_flags & ORD_RECEIVES) b.recv_pos = o.gpos_r - o.base_r;
+        if (part == 0) {
+            sorted[o.idx_s] = b;
+            rperm[o.idx_r] = o.idx_s;
+            gs[o.idx_s] = o.gpos_s; gr[o.idx_r] = o.gpos_r;
+            // the last box of either order closes the cumulative positions
+            if (o.idx_s == n - 1) gs[n] = o.gpos_s + order_send_bytes(rec);
+            if (o.idx_r == n - 1) gr[n] = o.gpos_r + order_recv_bytes(rec);
+            if (k == 0) ntl[3 * n] = 0;
+            account_box(fc, b);
+        }
+        describe_box_op(fc, b, (int)part, part * n + (part == OP_UNPACK ? o.idx_r : o.idx_s));
+    });
+    // (3) tile bases by a prefix sum, and per rank: first box, buffer offset and first tile of
+    // every operation
+    int64_t* rt = (int64_t*)(sum + SL.rank_tables());
+    auto rank_row = [=] VPS_LAMBDA(int64_t r, int64_t n, const vps_box* sboxes, const uint32_t* perm, const uint64_t* gsend,
+                                   const uint64_t* grecv, const int64_t* tbase) {
+        if (n == 0) {   // nothing is routed at all: no box has written the cumulative positions
+            for (int c = 0; c < 7; ++c) rt[c * (W + 1) + r] = 0;
+            return;
+        }
+        int64_t lo = 0, hi = n;
+        while (lo < hi) { const int64_t mid = (lo + hi) / 2; if (sboxes[mid].src_rank < r) lo = mid + 1; else hi = mid; }
+        const int64_t fs = lo;
+        lo = 0; hi = n;
+        while (lo < hi) { const int64_t mid = (lo + hi) / 2; if (sboxes[perm[mid]].dst_rank < r) lo = mid + 1; else hi = mid; }
+        const int64_t fr = lo;
+        rt[0 * (W + 1) + r] = fs;
+        rt[1 * (W + 1) + r] = fr;
+        rt[2 * (W + 1) + r] = (int64_t)gsend[fs];
+        rt[3 * (W + 1) + r] = (int64_t)grecv[fr];
+        rt[4 * (W + 1) + r] = tbase[fs];
+        rt[5 * (W + 1) + r] = tbase[n + fs];
+        rt[6 * (W + 1) + r] = tbase[2 * n + fr];
+    };
+    be.exclusive_scan_counted_then_each(step::plan_rank_tables(), ntl, tb, 3 * ns + 1, nbox, 3, W + 1, [=] VPS_LAMBDA(int64_t r) {
+        rank_row(r, (int64_t)*nbox, sorted, rperm, gs, gr, tb);
+    });
+
+    // (4) the tile table.  Its size is only known on the device so far; when the caller has seen
+    // this transition before it passes the size as a hint and the table is built before the host
+    // looks at anything, so that the whole plan needs one synchronisation.
+    TileRef* tiles = nullptr;
+    int64_t tiles_cap = 0;
+    auto tile_of = [=] VPS_LAMBDA(int64_t t, int64_t n, const int64_t* tbase, const CopyDesc* dd) {
+        const int64_t d = upper_bound_idx(tbase, 3 * n + 1, t) - 1;
+        return make_tile(dd[d], (uint32_t)d, (uint32_t)(t - tbase[d]));
+    };
+    if (!routes_only && tile_hint > 0) {
+        tiles_cap = tile_hint;
+        tiles = be.template alloc<TileRef>(tiles_cap);
+        be.for_each(step::plan_tile_table(), tiles_cap, [=] VPS_LAMBDA(int64_t t) {
+            const int64_t n = (int64_t)*nbox;
+            if (n > ns || t >= tb[3 * n]) return;
+            tiles[t] = tile_of(t, n, tb, descs);
         });
     }
-    be.exclusive_scan(nslot, slot0, npb);
-    int64_t nd = 0;
-    be.download(&nd, slot0 + npb, sizeof(int64_t));
-    if (nd >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 piece pairs to examine" };
-    int64_t* cnt = be.template alloc<int64_t>(nd + 1);
-    int64_t* bbase = be.template alloc<int64_t>(nd + 1);
-    be.for_each(step::plan_count_boxes(), nd + 1, [=] VPS_LAMBDA(int64_t i) {
-        if (i == nd) { cnt[i] = 0; return; }
-        const int64_t d = upper_bound_idx(slot0, npb + 1, i) - 1;
-        cnt[i] = plan_item_boxes(pc, d, (int32_t)(i - slot0[d]), nullptr);
-    });
-    be.exclusive_scan(cnt, bbase, nd);
-    int64_t n = 0;
-    be.download(&n, bbase + nd, sizeof(int64_t));
+
+    std::vector<uint64_t> hsum((size_t)SL.words());
+    be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());     // the one synchronisation
+    int64_t n = (int64_t)hsum[SUM_NBOXES];
     if (n >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 boxes" };
     p.nboxes = n;
-    vps_box* boxes = be.template alloc<vps_box>(n);
-    be.for_each(step::plan_emit_boxes(), nd, [=] VPS_LAMBDA(int64_t i) {
-        if (bbase[i + 1] > bbase[i]) {
-            const int64_t d = upper_bound_idx(slot0, npb + 1, i) - 1;
-            plan_item_boxes(pc, d, (int32_t)(i - slot0[d]), boxes + bbase[i]);
-        }
-    });
-    be.free(cnt); be.free(bbase); be.free(nslot); be.free(slot0);
 
-    // (2) order: by lo corner first, then stably by (owner rank, peer, kind order, tensor)
-    uint64_t* kmin = be.template alloc<uint64_t>(n);
-    uint64_t* kmaj = be.template alloc<uint64_t>(n);
-    uint32_t* by_lo = be.template alloc<uint32_t>(n);
-    uint32_t* ord_s = be.template alloc<uint32_t>(n);
-    uint32_t* ord_r = be.template alloc<uint32_t>(n);
-    // bits of the largest lo-corner key: the largest tensor of the model
-    const int lo_bits = bits_for(ca.tensor_numel_max);
-    {
-        const TensorRec* T = ca.T;
-        be.for_each(step::plan_key_lo(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = box_minor_key(boxes[k], T[boxes[k].tensor]); by_lo[k] = (uint32_t)k; });
-        be.sort_pairs(kmin, by_lo, n, lo_bits);
-        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], false); });
-        be.sort_pairs(kmaj, ord_s, n, 58);
-        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = box_major_key(boxes[by_lo[k]], true); });
-        be.sort_pairs(kmaj, ord_r, n, 58);
-    }
-    be.free(kmin); be.free(kmaj); be.free(by_lo);
-
-    // (3) buffer positions: exclusive scan of 16-byte aligned box sizes in each order
-    int64_t* sz = be.template alloc<int64_t>(n + 1);
-    int64_t* pos = be.template alloc<int64_t>(n + 1);
-    int32_t* owner = be.template alloc<int32_t>(n);
-    int64_t* first = be.template alloc<int64_t>(W + 1);
-    uint64_t* rbase = be.template alloc<uint64_t>(2 * (W + 1));
-    p.first_send.assign((size_t)W + 1, 0); p.first_recv.assign((size_t)W + 1, 0);
-    p.send_base.assign((size_t)W + 1, 0); p.recv_base.assign((size_t)W + 1, 0);
-    for (int side = 0; side < 2; ++side) {
-        const uint32_t* ord = side == 0 ? ord_s : ord_r;
-        be.for_each(step::plan_slot_sizes(), n + 1, [=] VPS_LAMBDA(int64_t k) {
-            if (k == n) { sz[k] = 0; return; }
-            const vps_box& b = boxes[ord[k]];
-            const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
-            owner[k] = own;
-            const bool resident = rank < 0 || own == rank;
-            sz[k] = (!box_retained(b, through_buffers) && resident) ? (int64_t)box_slot_bytes(b) : 0;
-        });
-        be.exclusive_scan(sz, pos, n);
-        be.for_each(step::plan_rank_bounds(), W + 1, [=] VPS_LAMBDA(int64_t r) { first[r] = lower_bound_idx(owner, n, (int32_t)r); });
-        be.for_each(step::plan_positions(), n, [=] VPS_LAMBDA(int64_t k) {
-            vps_box& b = boxes[ord[k]];
-            if (sz[k] == 0) return;
-            const uint64_t rel = (uint64_t)(pos[k] - pos[first[owner[k]]]);
-            if (side == 0) b.send_pos = rel; else b.recv_pos = rel;
-        });
-        std::vector<int64_t>& hf = side == 0 ? p.first_send : p.first_recv;
-        std::vector<uint64_t>& hb = side == 0 ? p.send_base : p.recv_base;
-        be.for_each(step::plan_rank_bases(), W + 1, [=] VPS_LAMBDA(int64_t r) { rbase[side * (W + 1) + r] = (uint64_t)pos[first[r]]; });
-        be.download_later(hf.data(), first, sizeof(int64_t) * (size_t)(W + 1));
-        be.download_later(hb.data(), rbase + side * (W + 1), sizeof(uint64_t) * (size_t)(W + 1));
-    }
-    be.free(sz); be.free(pos); be.free(owner); be.free(first); be.free(rbase);
-
-    // (4) payload bytes per (source, destination) pair
-    // (a full matrix for all-ranks plans, one row and one column for single-rank plans)
-    if (rank < 0 && (int64_t)WA * WB > ((int64_t)1 << 26))
-        throw Error{ VPS_ERR_OOM, "an all-ranks plan of this many ranks needs a byte matrix above 512 MiB" };
-    const int64_t npairs = rank < 0 ? (int64_t)WA * WB : (int64_t)WA + WB;
-    uint64_t* pairs = be.template alloc<uint64_t>(npairs);
-    be.zero(pairs, sizeof(uint64_t) * (size_t)npairs);
-    be.for_each(step::plan_pair_bytes(), n, [=] VPS_LAMBDA(int64_t k) {
-        const vps_box& b = boxes[k];
-        const uint64_t bytes = box_volume(b) * kind_bytes(b.kind);
-        if (rank < 0) { be_atomic_add(&pairs[(int64_t)b.src_rank * WB + b.dst_rank], bytes); return; }
-        if (b.dst_rank == rank) be_atomic_add(&pairs[b.src_rank], bytes);
-        if (b.src_rank == rank) be_atomic_add(&pairs[WA + b.dst_rank], bytes);
-    });
-    p.pair_bytes.resize((size_t)npairs);
-    be.download_later(p.pair_bytes.data(), pairs, sizeof(uint64_t) * (size_t)npairs);
-    be.free(pairs);
-
-    // (5) copy descriptors and tile table
-    p.tile_base.assign((size_t)(3 * n + 1), 0);
-    if (!routes_only) {
-    p.descs = be.template alloc<CopyDesc>(3 * n);
-    int64_t* nt = be.template alloc<int64_t>(3 * n + 1);
-    int64_t* tb = be.template alloc<int64_t>(3 * n + 1);
-    {
-        CopyDesc* descs = p.descs;
-        be.for_each(step::plan_copy_descs(), 3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
-            if (i == 3 * n) { nt[i] = 0; return; }
-            const int op = (int)(i / n);
-            const int64_t k = i % n;
-            const vps_box& b = boxes[op == OP_UNPACK ? ord_r[k] : ord_s[k]];
-            CopyDesc d;
-            make_copy_desc(b, op, layout, rank, through_buffers, tile_bytes, xpose_shape, d);
-            descs[i] = d;
-            nt[i] = d.ntiles;
-        });
-    }
-    be.exclusive_scan(nt, tb, 3 * n);
-    p.tile_base.resize((size_t)(3 * n + 1));
-    be.download(p.tile_base.data(), tb, sizeof(int64_t) * (size_t)(3 * n + 1));
-    const int64_t ntiles = p.tile_base[(size_t)(3 * n)];
-    if (ntiles >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 tiles" };
-    p.tiles = be.template alloc<TileRef>(ntiles);
-    {
-        TileRef* tiles = p.tiles;
-        const CopyDesc* descs = p.descs;
-        be.for_each(step::plan_tile_table(), ntiles, [=] VPS_LAMBDA(int64_t t) {
-            const int64_t d = upper_bound_idx(tb, 3 * n + 1, t) - 1;
-            tiles[t] = make_tile(descs[d], (uint32_t)d, (uint32_t)(t - tb[d]));
-        });
-    }
-    be.free(nt); be.free(tb);
-    }
-
-    // (6) boxes in send order and the receive permutation: kept on the device, copied to the host
-    // now, or on demand for an all-ranks plan without copy tables
-    const bool lazy = routes_only && rank < 0;
-    int64_t* counts = be.template alloc<int64_t>(2);
-    int64_t hcounts[2] = { 0, 0 };
-    {
-        vps_box* sorted = be.template alloc<vps_box>(n);
-        uint32_t* inv = be.template alloc<uint32_t>(n);
-        uint32_t* rperm = be.template alloc<uint32_t>(n);
-        be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = boxes[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
-        be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
-        p.d_boxes = sorted;
-        p.d_recv_perm = rperm;
-        be.free(inv);
-        if (!lazy) {
-            p.boxes_send_order.resize((size_t)n);
-            p.recv_perm.resize((size_t)n);
-            be.download_later(p.boxes_send_order.data(), sorted, sizeof(vps_box) * (size_t)n);
-            be.download_later(p.recv_perm.data(), rperm, sizeof(uint32_t) * (size_t)n);
-            p.host_boxes_ready = true;
+    if (n > ns) {
+        // ---- more boxes than the counting path takes: sort them (a stable radix sort by lo
+        // corner, then by (owner, peer, kind order, tensor)), positions by scans
+        be.free(sorted); be.free(rperm); be.free(gs); be.free(gr); be.free(descs); be.free(ntl); be.free(tb);
+        be.free(tiles);
+        tiles = nullptr; tiles_cap = 0;
+        if (n > cap) {
+            be.free(raw); be.free(recs);
+            cap = n;
+            raw = be.template alloc<vps_box>(cap);
+            recs = be.template alloc<OrderRec>(cap);
+            be.zero(sum, sizeof(uint64_t) * (size_t)SL.words());
+            emit();
         } else {
-            // the only statistic that needs the boxes: how many stay on their rank
-            be.zero(counts, sizeof(int64_t) * 2);
-            be.for_each(step::plan_count_retained(), n, [=] VPS_LAMBDA(int64_t k) {
-                if (box_retained(sorted[k], through_buffers)) be_atomic_add((uint64_t*)&counts[0], 1);
-            });
-            be.download_later(hcounts, counts, sizeof(int64_t) * 2);
-            p.host_boxes_ready = false;
+            be.zero(sum + 1, sizeof(uint64_t) * (size_t)(SL.words() - 1));
         }
+        uint64_t* kmin = be.template alloc<uint64_t>(n);
+        uint64_t* kmaj = be.template alloc<uint64_t>(n);
+        uint32_t* by_lo = be.template alloc<uint32_t>(n);
+        uint32_t* ord_s = be.template alloc<uint32_t>(n);
+        uint32_t* ord_r = be.template alloc<uint32_t>(n);
+        const int lo_bits = bits_for(ca.tensor_numel_max);
+        be.for_each(step::plan_keys(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = recs[k].klo; by_lo[k] = (uint32_t)k; });
+        be.sort_pairs(kmin, by_lo, n, lo_bits);
+        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = recs[by_lo[k]].key_s; });
+        be.sort_pairs(kmaj, ord_s, n, 58);
+        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = recs[by_lo[k]].key_r; });
+        be.sort_pairs(kmaj, ord_r, n, 58);
+        be.free(kmin); be.free(kmaj); be.free(by_lo);
+        int64_t* sz = be.template alloc<int64_t>(n + 1);
+        gs = be.template alloc<uint64_t>(n + 1);
+        gr = be.template alloc<uint64_t>(n + 1);
+        for (int side = 0; side < 2; ++side) {
+            const uint32_t* ord = side == 0 ? ord_s : ord_r;
+            uint64_t* g = side == 0 ? gs : gr;
+            be.for_each(step::plan_slot_sizes(), n + 1, [=] VPS_LAMBDA(int64_t k) {
+                if (k == n) { sz[k] = 0; return; }
+                const uint64_t bf = recs[ord[k]].bytes_flags;
+                sz[k] = (bf & (side == 0 ? ORD_SENDS : ORD_RECEIVES)) ? (int64_t)(bf & ~(uint64_t)15) : 0;
+            });
+            be.exclusive_scan(sz, (int64_t*)g, n);
+            // position inside the owner's buffer: cumulative bytes minus those of the ranks before
+            be.for_each(step::plan_positions(), n, [=] VPS_LAMBDA(int64_t k) {
+                vps_box& b = raw[ord[k]];
+                if (!(recs[ord[k]].bytes_flags & (side == 0 ? ORD_SENDS : ORD_RECEIVES))) return;
+                const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
+                int64_t lo = 0, hi = k;   // first box of the owner in this order
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) / 2;
+                    const vps_box& m = raw[ord[mid]];
+                    if ((side == 0 ? m.src_rank : m.dst_rank) < own) lo = mid + 1; else hi = mid;
+                }
+                const uint64_t rel = g[k] - g[lo];
+                if (side == 0) b.send_pos = rel; else b.recv_pos = rel;
+            });
+        }
+        be.free(sz);
+        sorted = be.template alloc<vps_box>(n);
+        rperm = be.template alloc<uint32_t>(n);
+        uint32_t* inv = be.template alloc<uint32_t>(n);
+        be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = raw[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
+        be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
+        be.free(inv); be.free(ord_s); be.free(ord_r);
+        descs = routes_only ? nullptr : be.template alloc<CopyDesc>(3 * n);
+        ntl = be.template alloc<int64_t>(3 * n + 1);
+        tb = be.template alloc<int64_t>(3 * n + 1);
+        fc.descs = descs; fc.ntiles = ntl;
+        be.for_each(step::plan_copy_descs(), 3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
+            if (i == 3 * n) { ntl[i] = 0; return; }
+            const int op = (int)(i / n);
+            const int64_t k = i - op * n;
+            const vps_box& b = sorted[op == OP_UNPACK ? rperm[k] : k];
+            if (op == OP_RETAIN) account_box(fc, b);
+            describe_box_op(fc, b, op, i);
+        });
+        be.exclusive_scan(ntl, tb, 3 * n);
+        be.for_each(step::plan_rank_tables(), W + 1, [=] VPS_LAMBDA(int64_t r) { rank_row(r, n, sorted, rperm, gs, gr, tb); });
+        be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());
+        if ((int64_t)hsum[SUM_NBOXES] != n) throw Error{ VPS_ERR_HIP, "planning passes disagree on the number of boxes" };
     }
-    be.free(counts);
-    be.free(ord_s); be.free(ord_r); be.free(boxes);
+    be.free(raw); be.free(recs); be.free(gs); be.free(gr); be.free(ntl);
+
+    // (5) the host's view of the plan
+    {
+        const int64_t* rt = (const int64_t*)(hsum.data() + SL.rank_tables());
+        auto col = [&](int c, std::vector<int64_t>& v) { v.assign(rt + c * (W + 1), rt + (c + 1) * (W + 1)); };
+        std::vector<int64_t> sb, rb;
+        col(0, p.first_send); col(1, p.first_recv); col(2, sb); col(3, rb);
+        p.send_base.assign(sb.begin(), sb.end());
+        p.recv_base.assign(rb.begin(), rb.end());
+        for (int op = 0; op < 3; ++op) col(4 + op, p.op_tile[op]);
+        p.pair_bytes.assign(hsum.begin() + SL.pairs(), hsum.begin() + SL.pairs() + SL.npairs);
+        const uint8_t* hu = (const uint8_t*)(hsum.data() + SL.used());
+        for (int op = 0; op < 3; ++op) p.used[op].assign(hu + op * nslots, hu + (op + 1) * nslots);
+    }
+    const int64_t ntiles = routes_only ? 0 : p.op_tile[OP_UNPACK][(size_t)W];
+    if (ntiles >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 tiles" };
+    p.d_boxes = sorted;
+    p.d_recv_perm = rperm;
+    p.descs = descs;
+    p.d_tile_base = tb;
+    p.host_boxes_ready = false;
+    be.free(sum);
+
+    // (6) the tile table, unless the hinted one above already holds it
+    if (!routes_only && ntiles > tiles_cap) {
+        be.free(tiles);
+        tiles = be.template alloc<TileRef>(ntiles);
+        TileRef* tl = tiles;
+        be.for_each(step::plan_tile_table(), ntiles, [=] VPS_LAMBDA(int64_t t) { tl[t] = tile_of(t, n, tb, descs); });
+        be.sync();
+    }
+    p.tiles = tiles;
     if (layout.all_ranks) p.ptr_table = be.template alloc<void*>(num_slots(layout));
-    p.host_ptrs.assign((size_t)num_slots(layout), nullptr);
-    be.sync();
 
     vps_plan_stats_t& st = p.stats;
     st = vps_plan_stats_t();
     st.num_boxes = n;
-    if (lazy) {
-        st.num_retain_boxes = hcounts[0];
-        st.num_send_boxes = st.num_recv_boxes = n - hcounts[0];
-    } else {
-        std::vector<char> peer_out((size_t)W, 0), peer_in((size_t)W, 0);
-        for (const vps_box& b : p.boxes_send_order) {
-            if (box_retained(b, through_buffers)) { st.num_retain_boxes++; continue; }
-            if (rank < 0 || b.src_rank == rank) { st.num_send_boxes++; if (rank >= 0) peer_out[(size_t)b.dst_rank] = 1; }
-            if (rank < 0 || b.dst_rank == rank) { st.num_recv_boxes++; if (rank >= 0) peer_in[(size_t)b.src_rank] = 1; }
+    st.num_retain_boxes = (int64_t)hsum[SUM_NRETAIN];
+    st.num_send_boxes = (int64_t)hsum[SUM_NSEND];
+    st.num_recv_boxes = (int64_t)hsum[SUM_NRECV];
+    if (rank >= 0)
+        for (int32_t q = 0; q < W; ++q) {
+            if (q == rank && !through_buffers) continue;
+            if (q < WB && p.pair_bytes[(size_t)WA + (size_t)q]) st.num_peers_out++;
+            if (q < WA && p.pair_bytes[(size_t)q]) st.num_peers_in++;
         }
-        for (int r = 0; r < W; ++r) { st.num_peers_out += peer_out[(size_t)r]; st.num_peers_in += peer_in[(size_t)r]; }
-    }
-    st.num_retain_tiles = p.tile_base[(size_t)n] - p.tile_base[0];
-    st.num_pack_tiles = p.tile_base[(size_t)(2 * n)] - p.tile_base[(size_t)n];
-    st.num_unpack_tiles = p.tile_base[(size_t)(3 * n)] - p.tile_base[(size_t)(2 * n)];
+    st.num_retain_tiles = p.op_tile[0][(size_t)W] - p.op_tile[0][0];
+    st.num_pack_tiles = p.op_tile[1][(size_t)W] - p.op_tile[1][0];
+    st.num_unpack_tiles = p.op_tile[2][(size_t)W] - p.op_tile[2][0];
     st.plan_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_start).count();
 }
 
-// The host copies of the boxes, fetched on first use for plans that did not bring them along.
+// The host copies of the boxes and of the tile bases, fetched on first use.
 template <class BE>
 void ensure_host_boxes(BE& be, PlanData& p)
 {
     if (p.host_boxes_ready) return;
     p.boxes_send_order.resize((size_t)p.nboxes);
     p.recv_perm.resize((size_t)p.nboxes);
+    p.tile_base.assign((size_t)(3 * p.nboxes + 1), 0);
     be.download_later(p.boxes_send_order.data(), p.d_boxes, sizeof(vps_box) * (size_t)p.nboxes);
     be.download_later(p.recv_perm.data(), p.d_recv_perm, sizeof(uint32_t) * (size_t)p.nboxes);
+    if (!p.routes_only)
+        be.download_later(p.tile_base.data(), p.d_tile_base, sizeof(int64_t) * (size_t)(3 * p.nboxes + 1));
     be.sync();
     p.host_boxes_ready = true;
 }
 
-// Tile range [begin, end) of operation `op` for `rank` (-1: every rank).
 // Payload bytes src -> dst known to the plan (0 for pairs outside a single-rank plan).
 inline uint64_t plan_pair_bytes(const PlanData& p, int32_t src, int32_t dst)
 {
@@ -480,14 +516,12 @@ inline uint64_t plan_pair_bytes(const PlanData& p, int32_t src, int32_t dst)
     return 0;
 }
 
+// Tile range [begin, end) of operation `op` for `rank` (-1: every rank).
 inline void plan_tile_range(const PlanData& p, int op, int32_t rank, int64_t& begin, int64_t& end)
 {
-    const int64_t n = p.nboxes;
-    const std::vector<int64_t>& first = op == OP_UNPACK ? p.first_recv : p.first_send;
-    const int64_t k0 = rank < 0 ? 0 : first[(size_t)rank];
-    const int64_t k1 = rank < 0 ? n : first[(size_t)rank + 1];
-    begin = p.tile_base[(size_t)(op * n + k0)];
-    end = p.tile_base[(size_t)(op * n + k1)];
+    const std::vector<int64_t>& t = p.op_tile[op];
+    begin = rank < 0 ? t.front() : t[(size_t)rank];
+    end = rank < 0 ? t.back() : t[(size_t)rank + 1];
 }
 
 // ------------------------------------------------------------------- staged XOR exchange

@@ -51,10 +51,34 @@ uint32_t g_tile_bytes_setting();
 class HostBackend {
 public:
     explicit HostBackend(void*) {}
-    template <class T> T* alloc(int64_t n) { return (T*)calloc((size_t)(n > 0 ? n : 1), sizeof(T)); }
-    void free(void* p) { ::free(p); }
-    void commit() {}
-    void release_all() {}
+    ~HostBackend() { release_all(); }
+    // Ownership as in the device backend: what a build allocates belongs to the backend until
+    // commit() hands it to the handle; a backend that goes away without commit() takes its
+    // allocations with it (so a handle that kept a pointer reads freed memory, which the
+    // sanitizer build reports).
+    template <class T> T* alloc(int64_t n)
+    {
+        // filled with a pattern, not zeros: pooled device memory holds whatever the last user left
+        const size_t bytes = (size_t)(n > 0 ? n : 1) * sizeof(T);
+        void* p = malloc(bytes);
+        memset(p, 0xCD, bytes);
+        live_.push_back(p);
+        return (T*)p;
+    }
+    void free(void* p)
+    {
+        if (!p) return;
+        auto it = std::find(live_.begin(), live_.end(), p);
+        if (it != live_.end()) live_.erase(it);
+        ::free(p);
+    }
+    void commit() { live_.clear(); }
+    void release_all()
+    {
+        for (void* p : live_) ::free(p);
+        live_.clear();
+    }
+    std::vector<void*> live_;
     template <class Step, class F> void for_each(Step, int64_t n, F f) { for (int64_t i = 0; i < n; ++i) f(i); }
     void exclusive_scan(const int64_t* in, int64_t* out, int64_t n)
     {
@@ -80,7 +104,61 @@ public:
     void download_later(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
     void zero(void* d, size_t b) { if (b) memset(d, 0, b); }
     void sync() {}
-    void quiesce() {}
+    void wait_stream(void*) {}
+    void* stream() const { return nullptr; }
+    static void set_xcd_chunk(uint32_t) {}
+    void after_null_stream() {}
+
+    // The same per-item code as the device kernels, one item after the other.
+    void layout_classes(const ParConst& P, const TensorRec* T, TensorLayout* TL, ClassRec* C)
+    {
+        for (int32_t cls = 0; cls < P.ncls; ++cls) {
+            uint64_t running = 0;
+            for (int32_t q = 0; q < P.nt; ++q) {
+                const int32_t t = P.flat_order ? P.nt - 1 - q : q;
+                if (class_of_tensor(P, T[t]) != cls) continue;
+                TensorLayout tl;
+                tl.start = running; tl.shard_len = shard_elems(P, T[t]); tl.cls = cls; tl.pad_ = 0;
+                TL[t] = tl;
+                running += tl.shard_len;
+            }
+            C[cls] = make_class_rec(P, cls, running);
+        }
+    }
+
+    void plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter)
+    {
+        const int64_t lanes = plan_num_lanes(pc, mode);
+        for (int64_t lane = 0; lane < lanes; ++lane)
+            plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
+                const uint64_t k = (*counter)++;
+                if (k < cap) {
+                    raw[k] = b;
+                    recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through);
+                }
+            });
+    }
+
+    template <class Step, class F>
+    void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
+                                          int mult, int64_t m, F f)
+    {
+        const int64_t len = (int64_t)*count * mult + 1;
+        if (len > bound) return;
+        exclusive_scan(in, out, len - 1);
+        for (int64_t i = 0; i < m; ++i) f(i);
+    }
+
+    template <class Step, class F>
+    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, F f)
+    {
+        const uint64_t n = *nbox;
+        if (n > (uint64_t)bound) return;
+        for (uint64_t k = 0; k < n; ++k) {
+            const OrderPlace o = order_by_counting(recs, (uint32_t)n, (uint32_t)k);
+            for (uint32_t part = 0; part < 16; ++part) f((uint32_t)k, o, part);
+        }
+    }
     void set_ptr_table(void** table, void* const* host_ptrs, int n) { memcpy(table, host_ptrs, sizeof(void*) * (size_t)n); }
 
     void launch_plain_copy(void* dst, const void* src, uint64_t bytes)

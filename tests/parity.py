@@ -136,10 +136,6 @@ def kind_dtype(buf):
     return np.uint16 if buf % 4 == 0 else np.uint32
 
 
-def to_oracle_parallel(p):
-    return p
-
-
 def check_config_against_oracle(cfg, orc):
     assert cfg.world == orc.world
     assert cfg.num_tensors == orc.num_tensors
@@ -338,16 +334,23 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
             g = gather_box(got[buf], bx["dst_off"], bx["dst_stride"], bx["ext"])
             assert (g == (SENT16 if buf % 4 == 0 else SENT32)).all(), "unpack wrote a retained box"
 
-    # (3) send payloads: row-major box contents at send_pos
+    # (3) per-peer buffers against the oracle (Algorithm 1, PackData): every receive buffer as a
+    # whole (unwritten pad bytes still hold the fill byte, which is the oracle's pad byte), every
+    # segment of every send buffer, and the segment table
     if check_send_payload:
-        for i in range(a.world):
-            sb = mem.download(sends[i])
-            for bx in boxes[(boxes["src_rank"] == i) & travels]:
-                buf = int(bx["src_buf"])
-                w = gather_box(src_host[(i, buf)], bx["src_off"], bx["src_stride"], bx["ext"])
-                pos = int(bx["send_pos"])
-                g = sb[pos:pos + w.nbytes].view(w.dtype)
-                assert np.array_equal(g, w), ("send payload", i, bx)
+        send_host = {i: mem.download(sends[i]) for i in range(a.world)}
+        for j in range(b.world):
+            want_recv, seg = oracle.recv_payload(a, b, j, seed, rank_salt, through=through, pad_byte=SENTINEL)
+            got_recv = mem.download(recvs[j])
+            assert got_recv.size == want_recv.size, ("receive buffer size", j, got_recv.size, want_recv.size)
+            assert np.array_equal(got_recv, want_recv), ("receive buffer", j)
+            for i in range(a.world):
+                lo, hi = int(seg[i]), int(seg[i + 1])
+                sg = plan.peer_segment(i, j)
+                assert sg["bytes"] == hi - lo, ("segment size", i, j)
+                if hi > lo:
+                    assert sg["recv_off"] == lo
+                    assert np.array_equal(send_host[i][sg["send_off"]:sg["send_off"] + hi - lo], want_recv[lo:hi]), ("send segment", i, j)
     return dict(boxes=len(boxes), moved=moved, stats=plan.stats())
 
 
@@ -367,7 +370,7 @@ def synth_recv_buffer(a, boxes, rank, nbytes, seed, rank_salt):
 
 
 def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_samples=0,
-                    full_compare=True, chunk=1 << 24, check_bytes=True, through=False):
+                    full_compare=True, chunk=1 << 24, check_bytes=True, through=False, send_payload_ranks=None):
     """One rank's share: retain + pack + unpack in one apply_transition call, peers' buffers
     synthesized from the seeded pattern."""
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
@@ -388,7 +391,17 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
         mem.upload(src[buf], src_host[buf])
         dst[buf] = mem.alloc((b.buffer_elems(rank, buf) if in_b else 0) * oracle.KIND_BYTES[buf % 4])
     scratch = mem.alloc(info["scratch_needed"])
-    recv = synth_recv_buffer(a, boxes, rank, info["recv_total"], seed, rank_salt)
+    # what the peers would have packed for this rank: from the oracle, not from the plan
+    if in_b:
+        recv, recv_seg = oracle.recv_payload(a, b, rank, seed, rank_salt, through=through, pad_byte=SENTINEL)
+    else:
+        recv, recv_seg = np.zeros(0, np.uint8), np.zeros(a.world + 1, np.uint64)
+    assert recv.size == info["recv_total"], ("receive buffer size", recv.size, info["recv_total"])
+    if through and rank < a.world:
+        # the rank's own segment is read out of the send region, where its pack launch writes it
+        lo, hi = int(recv_seg[rank]), int(recv_seg[rank + 1])
+        recv = recv.copy()
+        recv[lo:hi] = SENTINEL
     if recv.size:
         mem.upload(scratch[info["recv_offset"]:info["recv_offset"] + recv.size], recv)
     mem.register_bounds()
@@ -426,13 +439,24 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
             assert plan.pair_bytes(rank, j) == sbytes[j], (rank, j)
         outgoing = int(sbytes.sum()) - (0 if through or rank >= b.world else int(sbytes[rank]))
         assert outgoing <= info["send_total"] <= outgoing + 16 * nb
-    # send payload
+    # send buffer against the oracle: the segment of every destination, in ascending order
     sb = mem.download(scratch)[:info["send_total"]]
-    for bx in boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]:
-        buf = int(bx["src_buf"])
-        w = gather_box(src_host[buf], bx["src_off"], bx["src_stride"], bx["ext"])
-        pos = int(bx["send_pos"])
-        assert np.array_equal(sb[pos:pos + w.nbytes].view(w.dtype), w), ("send payload", bx)
+    if rank < a.world and send_payload_ranks != 0:
+        pos = 0
+        dsts = range(b.world) if send_payload_ranks is None else send_payload_ranks
+        for j in dsts:
+            sg = plan.peer_segment(rank, j)
+            if send_payload_ranks is None:
+                assert sg["bytes"] == 0 or sg["send_off"] == pos, ("send segments must be dense and ascending", j)
+                pos += sg["bytes"]
+            if not sg["bytes"]:
+                continue
+            want, seg = oracle.recv_payload(a, b, j, seed, rank_salt, through=through, pad_byte=SENTINEL)
+            lo, hi = int(seg[rank]), int(seg[rank + 1])
+            assert sg["bytes"] == hi - lo, ("segment size", rank, j)
+            assert np.array_equal(sb[sg["send_off"]:sg["send_off"] + hi - lo], want[lo:hi]), ("send segment", rank, j)
+        if send_payload_ranks is None:
+            assert pos == info["send_total"]
     return dict(boxes=len(boxes), info=info, stats=plan.stats())
 
 

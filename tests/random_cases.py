@@ -17,7 +17,9 @@ def random_parallel(rng, m):
                        dp=rng.choice([1, 1, 2, 3, 4]), ep=rng.choice([1, 2, 3, 4]) if moe else 1,
                        zero=rng.choice([0, 1, 1]), gpus_per_node=rng.choice([2, 4, 8]),
                        qkv_layout=rng.choice([0, 1]), expert_layout=rng.choice([0, 1]) if moe else 0,
-                       flat_order=rng.choice([0, 0, 1]))
+                       flat_order=rng.choice([0, 0, 1]),
+                       # drawn from a stream of its own, so that the other fields keep their values
+                       ep_placement=random.Random(rng.random()).choice([0, 0, 1]) if moe else 0)
 
 
 def legal(lib, m, p):

@@ -4,7 +4,7 @@ import pytest
 
 import parity
 from datagen import configs as cf
-from test_oracle_pins import TRANSITIONS
+from test_oracle_pins import ALL_TRANSITIONS, TRANSITIONS
 from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH, check_error_codes
 
 pytestmark = pytest.mark.gpu
@@ -16,7 +16,7 @@ def lib():
     return vps.load()
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_all_ranks_resident(lib, name, m, pa, pb):
     out = parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0x5EED + len(name))
     assert out["boxes"] > 0
@@ -31,18 +31,39 @@ def test_medium_shapes_all_ranks(lib, name, m, pa, pb):
 
 @pytest.mark.parametrize("name,rank", SINGLE, ids=[f"{n}-r{r}" for n, r in SINGLE])
 def test_single_rank_share(lib, name, rank):
-    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
     parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=0xBEEF + rank)
 
 
 @pytest.mark.parametrize("name,rank", THROUGH, ids=[f"{n}-r{r}" for n, r in THROUGH])
 def test_rank_as_its_own_peer(lib, name, rank):
-    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
     mem = parity.GpuMem()
     if rank < 0:
         parity.run_all_ranks(lib, mem, m, pa, pb, seed=0xD00D, through=True)
     else:
         parity.run_single_rank(lib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
+
+
+@pytest.mark.parametrize("limit", [1, 7, 64])
+def test_plans_beyond_the_counting_limit(lib, limit):
+    """The radix-sort path of the planner on the device, reached by lowering the limit of the
+    counting path (see the CPU-build test of the same name)."""
+    from paper_2605_18815_amd import binding as B
+    lib.set_option(B.OPT_SMALL_PLAN_BOXES, limit)
+    try:
+        for name, rank in (("gpt-zero-to-replicated", -1), ("gpt-blocked-rev", -1), ("moe-odd", -1), ("moe-carved-ep-grows", -1),
+                           ("gpt-tp-pp", 5), ("moe-transposed", 3), ("gpt-world-grows", 11)):
+            _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
+            if rank < 0:
+                parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0x1A46E + limit, through=(limit == 7))
+            else:
+                parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=0x1A46E + rank, through=(limit == 7))
+        _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == "moe-ep"][0]
+        parity.run_staged(lib, parity.GpuMem(), m, pa, pb, seed=3, budget=1 << 12)
+        parity.run_classify(lib, m, pa, pb)
+    finally:
+        lib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
 
 
 def test_toy_workload_all_ranks(lib):
@@ -112,7 +133,8 @@ def test_largest_world(lib):
     m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
     pa, pb = cf.parallel(tp=4, pp=8, dp=1024, zero=1), cf.parallel(tp=8, pp=8, dp=512, zero=1)
     for rank in (0, 32767, 12345):
-        parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False)
+        parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False,
+                               send_payload_ranks=0)
 
 
 @pytest.mark.parametrize("rank", [-1, 1])

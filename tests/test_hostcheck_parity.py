@@ -14,7 +14,7 @@ import parity
 from datagen import configs as cf
 from hostcheck import build as hc_build
 from paper_2605_18815_amd.binding import Library, VpsError
-from test_oracle_pins import TRANSITIONS
+from test_oracle_pins import ALL_TRANSITIONS, TRANSITIONS
 
 P = cf.parallel
 
@@ -26,7 +26,7 @@ def hlib():
     return Library(os.environ.get("VPSH_LIB") or hc_build.build(), prefix="vpsh_")
 
 
-@pytest.mark.parametrize("name,m,pa,pb", TRANSITIONS, ids=[c[0] for c in TRANSITIONS])
+@pytest.mark.parametrize("name,m,pa,pb", ALL_TRANSITIONS, ids=[c[0] for c in ALL_TRANSITIONS])
 def test_all_ranks_resident(hlib, name, m, pa, pb):
     mem = parity.HostMem(hlib)
     out = parity.run_all_ranks(hlib, mem, m, pa, pb, seed=0x5EED + len(name))
@@ -89,6 +89,36 @@ def test_collective_intent_matches_bruteforce(hlib, name, m, pa, pb):
     assert counts.sum() == 4 * len(__import__("textbook").inventory(m))
 
 
+def test_parity_subset_under_address_sanitizer():
+    """The CPU build again with AddressSanitizer, in a child process that preloads its runtime:
+    heap bounds of every table the mapper, the planner, the stage plan and the classification
+    touch, and the lifetime of what the handles own (a backend that goes out of scope takes along
+    whatever it was not told to hand over)."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    select = ("error_codes or staged_xor_exchange or beyond_the_counting_limit or single_rank_share or routes_only "
+              "or (all_ranks_resident and (odd or carved)) or collective_intent_cases or piece_queries")
+    res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(root, "tests", "test_hostcheck_parity.py"), "-x", "-q",
+                          "-k", select, "-p", "no:cacheprovider"], env=hc_build.asan_env(), cwd=root, capture_output=True, text=True)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
+
+
+def test_piece_queries_then_planning(hlib):
+    """Regression: the piece table is built on the first piece query, by a backend that lives only
+    for that call; it has to hand the table over to the configuration (once, a second query reuses
+    it), and the tables of later plans must not land in the same memory."""
+    ca, cb = hlib.describe_config(cf.TINY_MOE, P(tp=1, pp=4, dp=2, ep=2)), hlib.describe_config(cf.TINY_MOE, P(tp=1, pp=2, dp=2, ep=4))
+    n = ca.num_pieces
+    first = ca.get_pieces()
+    plans = [hlib.plan_intersections(ca, cb, r) for r in (-1, 0, 5)]
+    assert ca.num_pieces == n and np.array_equal(ca.get_pieces(), first)
+    assert cb.num_pieces > 0 and all(p.num_boxes > 0 for p in plans)
+    parity.run_all_ranks(hlib, parity.HostMem(hlib), cf.TINY_MOE, P(tp=1, pp=4, dp=2, ep=2), P(tp=1, pp=2, dp=2, ep=4), seed=12)
+    assert np.array_equal(ca.get_pieces(), first)
+
+
 def test_routes_only_plan_refuses_copies(hlib):
     from paper_2605_18815_amd import binding as B
     ca = hlib.describe_config(cf.TINY_GPT, P(tp=2, dp=2))
@@ -113,31 +143,54 @@ def test_routes_only_plan_refuses_copies(hlib):
 SINGLE = [
     ("gpt-zero-to-replicated", 0), ("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-blocked-rev", 2),
     ("gpt-odd", 1), ("gpt-world-grows", 11), ("gpt-world-grows", 3), ("gqa", 6), ("moe-ep", 9),
-    ("moe-transposed", 3), ("moe-odd", 7),
+    ("moe-transposed", 3), ("moe-odd", 7), ("moe-carved-ep-shrinks", 5), ("moe-carved-ep-grows", 13), ("moe-grid-to-carved", 3),
+    ("moe-odd-carved", 4),
 ]
 
 
 @pytest.mark.parametrize("name,rank", SINGLE, ids=[f"{n}-r{r}" for n, r in SINGLE])
 def test_single_rank_share(hlib, name, rank):
-    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
     mem = parity.HostMem(hlib)
     parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xBEEF + rank)
 
 
 THROUGH = [("gpt-zero-to-replicated", 3), ("gpt-tp-pp", 5), ("gpt-world-grows", 3), ("moe-transposed", 3), ("moe-odd", -1),
-           ("gpt-blocked-rev", -1)]
+           ("gpt-blocked-rev", -1), ("moe-carved-ep-shrinks", -1), ("moe-grid-to-carved", 6)]
 
 
 @pytest.mark.parametrize("name,rank", THROUGH, ids=[f"{n}-r{r}" for n, r in THROUGH])
 def test_rank_as_its_own_peer(hlib, name, rank):
     """VPS_PLAN_THROUGH_BUFFERS: retained data travels through the rank's own segment; the
     destination bits and the payload in the send buffer stay those of the oracle."""
-    _, m, pa, pb = [t for t in TRANSITIONS if t[0] == name][0]
+    _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
     mem = parity.HostMem(hlib)
     if rank < 0:
         parity.run_all_ranks(hlib, mem, m, pa, pb, seed=0xD00D, through=True)
     else:
         parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
+
+
+@pytest.mark.parametrize("limit", [1, 7, 64])
+def test_plans_beyond_the_counting_limit(hlib, limit):
+    """Plans with more boxes than the counting path takes are ordered by the radix sort and
+    positioned by scans: same boxes, same buffers.  The limit is lowered so that tiny models
+    reach that path (and, at 64, so that some plans take one path and some the other)."""
+    from paper_2605_18815_amd import binding as B
+    hlib.set_option(B.OPT_SMALL_PLAN_BOXES, limit)
+    try:
+        for name, rank in (("gpt-zero-to-replicated", -1), ("gpt-blocked-rev", -1), ("moe-odd", -1), ("moe-carved-ep-grows", -1),
+                           ("gpt-tp-pp", 5), ("moe-transposed", 3), ("gpt-world-grows", 11)):
+            _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
+            if rank < 0:
+                parity.run_all_ranks(hlib, parity.HostMem(hlib), m, pa, pb, seed=0x1A46E + limit, through=(limit == 7))
+            else:
+                parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, rank, seed=0x1A46E + rank, through=(limit == 7))
+        _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == "moe-ep"][0]
+        parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=3, budget=1 << 12)
+        parity.run_classify(hlib, m, pa, pb)
+    finally:
+        hlib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
 
 
 def test_toy_workload_all_ranks(hlib):
@@ -373,7 +426,8 @@ def test_largest_world(hlib):
     m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
     pa, pb = P(tp=4, pp=8, dp=1024, zero=1), P(tp=8, pp=8, dp=512, zero=1)
     for rank in (32767, 12345):
-        parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False)
+        parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, rank, seed=9, box_samples=4, check_bytes=False,
+                               send_payload_ranks=0)
     with pytest.raises(VpsError):
         hlib.describe_config(m, P(tp=4, pp=8, dp=2048))
 
@@ -464,6 +518,12 @@ def check_error_codes(hlib, mem):
     with pytest.raises(VpsError) as e:
         hlib.describe_config(cf.TINY_MOE, P(ep=3))
     assert e.value.code == B.ERR_INDIVISIBLE
+    with pytest.raises(VpsError) as e:   # ep carved out of tp*dp must divide it
+        hlib.describe_config(cf.TINY_MOE, P(tp=2, dp=3, ep=4, ep_placement=1))
+    assert e.value.code == B.ERR_INDIVISIBLE
+    with pytest.raises(VpsError) as e:
+        hlib.describe_config(cf.TINY_MOE, P(ep_placement=2))
+    assert e.value.code == B.ERR_INVALID_ARG
     with pytest.raises(VpsError) as e:
         hlib.describe_config(cf.TINY_GPT, P(tp=0))
     assert e.value.code == B.ERR_INVALID_ARG
