@@ -101,10 +101,28 @@ PAPER_TRANSITIONS = {
 }
 
 
+# Variants of the benchmark workloads for the copy engine's unfavourable cases.
+EXTRA_WORKLOADS = {
+    # the 70B switch with odd sizes everywhere: rows of 8191, 3585 and 1016 elements, so that the
+    # tensors of a flat buffer start at odd element offsets and the 16-byte phase of the source
+    # differs from that of the destination for most runs
+    "gqa70b-odd": dict(
+        index=6,
+        model=model(FAMILY_GQA, 80, 8191, 64, 8, 127, 28680, 128264),
+        src=parallel(tp=8, pp=8, dp=2, zero=1),
+        dst=parallel(tp=8, pp=4, dp=4, zero=1),
+        rank=11,
+    ),
+}
+
+
 def workload(name):
-    """A benchmark workload or one of the paper's transitions (those have no default rank)."""
+    """A benchmark workload, a variant of one, or one of the paper's transitions (those have no
+    default rank)."""
     if name in WORKLOADS:
         return WORKLOADS[name]
+    if name in EXTRA_WORKLOADS:
+        return EXTRA_WORKLOADS[name]
     return dict(PAPER_TRANSITIONS[name], rank=None, index=16 + sorted(PAPER_TRANSITIONS).index(name))
 
 

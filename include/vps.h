@@ -306,6 +306,11 @@ int vps_set_tile_bytes(uint32_t bytes);
  * aligned, not overlapping; bytes a multiple of 16 (VPS_ERR_INVALID_ARG otherwise).
  * Asynchronous on `stream`. */
 int vps_plain_copy(void* dst, const void* src, uint64_t bytes, void* stream);
+/* The two halves of that copy alone, in the same launch shape: read `bytes` bytes from src (the
+ * loads feed a value that is stored to `sink`, 4 bytes of device memory, only if it equals a
+ * sentinel), or fill `bytes` bytes at dst with the byte 0xA5.  Same argument rules. */
+int vps_plain_read(const void* src, uint64_t bytes, void* sink, void* stream);
+int vps_plain_fill(void* dst, uint64_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

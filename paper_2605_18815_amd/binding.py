@@ -114,6 +114,8 @@ class Library:
             "set_tile_bytes": [u32],
             "set_option": [i32, u32],
             "plain_copy": [vp, vp, u64, vp],
+            "plain_read": [vp, u64, vp, vp],
+            "plain_fill": [vp, u64, vp],
             "stage_exchange": [vp, u64, vp, P(vp)],
             "plan_classify_collectives": [vp, vp, vp, P(i32), i64],
             "stage_info": [vp, P(i32), P(i32), P(u64)],
@@ -151,7 +153,7 @@ class Library:
                "plan_peer_segment", "plan_num_boxes", "plan_get_boxes", "plan_stats",
                "set_tile_bytes", "plain_copy", "config_destroy", "plan_destroy", "last_error", "stage_exchange", "plan_intersections_ex", "plan_classify_collectives",
                "stage_info", "stage_steps", "apply_transition_staged", "stage_plan_destroy",
-               "apply_transition_static", "static_scratch_bytes", "set_option")
+               "apply_transition_static", "static_scratch_bytes", "set_option", "plain_read", "plain_fill")
 
     def last_error(self):
         return self._fn["last_error"]().decode()
@@ -207,6 +209,12 @@ class Library:
 
     def plain_copy(self, dst, src, nbytes, stream=0):
         self._check(self._fn["plain_copy"](dst, src, nbytes, stream))
+
+    def plain_read(self, src, nbytes, sink, stream=0):
+        self._check(self._fn["plain_read"](src, nbytes, sink, stream))
+
+    def plain_fill(self, dst, nbytes, stream=0):
+        self._check(self._fn["plain_fill"](dst, nbytes, stream))
 
     def set_tile_bytes(self, n):
         self._check(self._fn["set_tile_bytes"](n))

@@ -25,12 +25,15 @@ static std::atomic<uint32_t> g_tile_bytes{ 8u << 10 };
 static std::atomic<uint32_t> g_small_plan_boxes{ 8192u };   // boxes ordered by counting, without a sort
 static std::atomic<uint32_t> g_xpose_shape{ 0u };           // 0 = chosen per box from the pitches
 
-// Number of tiles of the plans made so far, by what determines it (model, both configurations,
-// rank, flags, tile size).  A repeated transition then sizes its tile table without waiting for
-// the device.  Only a size: every plan computes all of its tables anew.
+// Number of tiles and boxes of the plans made so far, by what determines them (model, both
+// configurations, rank, flags, tile size).  A repeated transition then sizes its tables without
+// waiting for the device.  Only sizes: every plan computes all of its tables anew.
 struct TileHints {
+    struct Sizes {
+        int64_t tiles, boxes;
+    };
     std::mutex m;
-    std::unordered_map<uint64_t, int64_t> tiles;
+    std::unordered_map<uint64_t, Sizes> tiles;
     static uint64_t key(const vps_model_desc& model, const vps_parallel_desc& a, const vps_parallel_desc& b, int32_t rank,
                         uint32_t flags, uint32_t tile_bytes, uint32_t xpose_shape)
     {
@@ -42,13 +45,13 @@ struct TileHints {
         mix(&flags, sizeof flags); mix(&tile_bytes, sizeof tile_bytes); mix(&xpose_shape, sizeof xpose_shape);
         return h;
     }
-    int64_t get(uint64_t k)
+    Sizes get(uint64_t k)
     {
         std::lock_guard<std::mutex> g(m);
         auto it = tiles.find(k);
-        return it == tiles.end() ? 0 : it->second;
+        return it == tiles.end() ? Sizes{ 0, 0 } : it->second;
     }
-    void put(uint64_t k, int64_t n)
+    void put(uint64_t k, Sizes n)
     {
         std::lock_guard<std::mutex> g(m);
         if (tiles.size() > 4096) tiles.clear();
@@ -175,6 +178,30 @@ int VPS_FN(plain_copy)(void* dst, const void* src, uint64_t bytes, void* stream)
     VPS_CATCH
 }
 
+int VPS_FN(plain_read)(const void* src, uint64_t bytes, void* sink, void* stream)
+{
+    if (!bytes) return VPS_OK;
+    if (!src || !sink) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t)src | bytes) & 15) return vps::fail(VPS_ERR_INVALID_ARG, "plain read needs a 16-byte aligned pointer and a multiple of 16 bytes");
+    VPS_TRY
+    VPS_BACKEND be(stream);
+    be.launch_plain_half(0, nullptr, src, bytes, sink);
+    return VPS_OK;
+    VPS_CATCH
+}
+
+int VPS_FN(plain_fill)(void* dst, uint64_t bytes, void* stream)
+{
+    if (!bytes) return VPS_OK;
+    if (!dst) return vps::fail(VPS_ERR_INVALID_ARG, "null argument");
+    if (((uintptr_t)dst | bytes) & 15) return vps::fail(VPS_ERR_INVALID_ARG, "plain fill needs a 16-byte aligned pointer and a multiple of 16 bytes");
+    VPS_TRY
+    VPS_BACKEND be(stream);
+    be.launch_plain_half(1, dst, nullptr, bytes, nullptr);
+    return VPS_OK;
+    VPS_CATCH
+}
+
 int VPS_FN(describe_config)(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
                             vps_config** out)
 {
@@ -228,9 +255,10 @@ int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, 
         const uint64_t hk = vps::TileHints::key(src->d.model, src->d.par, dst->d.par, rank, flags, tile_bytes, xpose_shape);
         vps::build_plan(be, src->d, dst->d, rank, tile_bytes, xpose_shape,
                         vps::g_small_plan_boxes.load(), (flags & VPS_PLAN_ROUTES_ONLY) != 0,
-                        (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, vps::g_tile_hints.get(hk), p->d);
+                        (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, vps::g_tile_hints.get(hk).tiles,
+                        vps::g_tile_hints.get(hk).boxes, p->d);
         const vps_plan_stats_t& st = p->d.stats;
-        vps::g_tile_hints.put(hk, st.num_retain_tiles + st.num_pack_tiles + st.num_unpack_tiles);
+        vps::g_tile_hints.put(hk, { st.num_retain_tiles + st.num_pack_tiles + st.num_unpack_tiles, st.num_boxes });
     } catch (...) {
         be.release_all();
         delete p;

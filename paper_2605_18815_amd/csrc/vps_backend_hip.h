@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void k_layout_classes(ParConst P, const Tensor
     __shared__ uint64_t carry[4];
     const int32_t cls = (int32_t)blockIdx.x;
     int32_t lo, hi;
-    stage_tensor_range(P, cls < P.pp ? cls : (cls - P.pp) / P.ep, lo, hi);
+    const int32_t stage = cls < P.pp ? cls : (cls - P.pp) / P.ep;
+    stage_tensor_range(P, stage, lo, hi);
     const int32_t count = hi - lo;
     uint64_t running = 0;
     for (int32_t q0 = 0; q0 < count; q0 += 1024) {
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(256) void k_layout_classes(ParConst P, const Tensor
         for (int k = 0; k < 4; ++k) {
             if (t[k] >= 0) {
                 TensorLayout tl;
-                tl.start = before; tl.shard_len = len[k]; tl.cls = cls; tl.pad_ = 0;
+                tl.start = before; tl.shard_len = len[k]; tl.cls = cls; tl.stage = stage;
                 TL[t[k]] = tl;
             }
             before += len[k];
@@ -140,15 +141,16 @@ __global__ __launch_bounds__(256) void k_plan_emit(PlanCtx pc, int mode, int thr
                                                    vps_box* __restrict__ raw, OrderRec* __restrict__ recs,
                                                    uint64_t cap, unsigned long long* counter)
 {
-    const int64_t lane = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (lane >= lanes) return;
-    plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
-        const uint64_t k = take_box_slot(counter);
-        if (k < cap) {
-            raw[k] = b;
-            recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
-        }
-    });
+    // a workgroup walks many lanes: millions of short-lived workgroups would be bound by the rate
+    // at which the hardware starts them
+    for (int64_t lane = (int64_t)blockIdx.x * 256 + threadIdx.x; lane < lanes; lane += (int64_t)gridDim.x * 256)
+        plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
+            const uint64_t k = take_box_slot(counter);
+            if (k < cap) {
+                raw[k] = b;
+                recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
+            }
+        });
 }
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
@@ -156,6 +158,59 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
     const unsigned lo = (unsigned)__shfl_xor((int)(unsigned)v, mask, 64);
     const unsigned hi = (unsigned)__shfl_xor((int)(unsigned)(v >> 32), mask, 64);
     return ((uint64_t)hi << 32) | lo;
+}
+
+// The same in two launches, for item grids of millions of lanes of which few have work: the
+// first writes the indices of the lanes that pass the cheap tests into a list (same ballot
+// allocation), the second walks the list with every lane busy.
+__global__ __launch_bounds__(256) void k_plan_filter(PlanCtx pc, int mode, int64_t lanes, uint64_t* __restrict__ list,
+                                                     uint64_t cap, unsigned long long* count)
+{
+    // Every wavefront collects the lanes that pass in LDS and moves them to the list 64 at a
+    // time: one atomic on the list's counter per 64 entries (an atomic per ballot would serialise
+    // hundreds of thousands of updates of one address).
+    __shared__ uint64_t staged[4][128];
+    const unsigned wave = threadIdx.x >> 6, lid = threadIdx.x & 63u;
+    uint32_t held = 0;   // entries of staged[wave], the same in every lane
+    auto flush = [&](uint32_t m) {   // move the first m (<= 64) staged entries to the list
+        unsigned long long base = 0;
+        if (lid == 0) base = atomicAdd(count, (unsigned long long)m);
+        const unsigned lo = (unsigned)__shfl((int)(unsigned)base, 0, 64), hi = (unsigned)__shfl((int)(unsigned)(base >> 32), 0, 64);
+        const uint64_t k = (((uint64_t)hi << 32) | lo) + lid;
+        if (lid < m && k < cap) list[k] = staged[wave][lid];
+    };
+    for (int64_t first = (int64_t)blockIdx.x * 256; first < lanes; first += (int64_t)gridDim.x * 256) {
+        const int64_t lane = first + threadIdx.x;
+        LaneItem it;
+        const bool pass = lane < lanes && plan_lane_decode(pc, mode, lane, it);
+        const uint64_t mask = __ballot(pass ? 1 : 0);
+        if (pass) staged[wave][held + (uint32_t)__popcll(mask & ((1ull << lid) - 1ull))] = (uint64_t)lane;
+        held += (uint32_t)__popcll(mask);
+        if (held >= 64) {
+            flush(64);
+            const uint64_t moved = lid < held - 64 ? staged[wave][64 + lid] : 0;
+            if (lid < held - 64) staged[wave][lid] = moved;
+            held -= 64;
+        }
+    }
+    if (held) flush(held);
+}
+
+__global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, int through, const uint64_t* __restrict__ list,
+                                                          uint64_t list_cap, const unsigned long long* __restrict__ count,
+                                                          vps_box* __restrict__ raw, OrderRec* __restrict__ recs,
+                                                          uint64_t cap, unsigned long long* counter)
+{
+    uint64_t n = *count;
+    if (n > list_cap) return;   // the list overflowed: the caller plans again in one launch
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256)
+        plan_lane_boxes(pc, mode, (int64_t)list[i], [&](const vps_box& b) {
+            const uint64_t k = take_box_slot(counter);
+            if (k < cap) {
+                raw[k] = b;
+                recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
+            }
+        });
 }
 
 // Place of every box in the send and in the receive order by counting (order_by_counting).  A
@@ -419,12 +474,12 @@ public:
     }
 
     // out[i] = in[0] + ... + in[i-1] for i in [0, n]; both arrays hold n+1 entries and in[n]
-    // must be 0.  Up to 64 Ki entries one workgroup walks the array; beyond, every workgroup sums
+    // must be 0.  Up to 8 Ki entries one workgroup walks the array; beyond, every workgroup sums
     // its 2048 entries, one workgroup scans those sums, and a third launch finishes.
     void exclusive_scan(const int64_t* in, int64_t* out, int64_t n)
     {
         const int64_t count = n + 1;
-        if (count <= 32 * SCAN_PER_GROUP) {
+        if (count <= 4 * SCAN_PER_GROUP) {
             hipLaunchKernelGGL(k_scan_one_group, dim3(1), dim3(256), 0, stream_, in, out, count);
             VPS_HIP_CHECK(hipGetLastError());
             return;
@@ -466,15 +521,34 @@ public:
         VPS_HIP_CHECK(hipGetLastError());
     }
 
-    void plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter)
+    // `listed` (one 64-bit word, cleared by the caller) receives the length of the lane list when
+    // the two-launch form is used; more than PLAN_LIST_CAP means that the list overflowed and
+    // nothing was emitted: the caller then calls again with two_launches = false.
+    static constexpr uint64_t PLAN_LIST_CAP = 1ull << 22;
+    static constexpr int64_t PLAN_LIST_FROM = 1ll << 17;   // item grids from this many lanes on use the list
+
+    bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
+                   uint64_t* listed, bool two_launches)
     {
         const int64_t lanes = plan_num_lanes(pc, mode);
-        if (lanes <= 0) return;
-        const int64_t blocks = (lanes + 255) / 256;
-        if (blocks > 0x7fffffffLL) throw Error{ VPS_ERR_OOM, "more than 2^39 piece pairs to examine" };
+        if (lanes <= 0) return false;
+        int64_t blocks = (lanes + 255) / 256;
+        if (blocks > 8192) blocks = 8192;   // the kernels stride over the lanes
+        if (two_launches && lanes >= PLAN_LIST_FROM) {
+            uint64_t* list = alloc<uint64_t>((int64_t)PLAN_LIST_CAP);
+            hipLaunchKernelGGL(k_plan_filter, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, lanes, list,
+                               PLAN_LIST_CAP, (unsigned long long*)listed);
+            hipLaunchKernelGGL(k_plan_emit_listed, dim3(2048), dim3(256), 0, stream_, pc, mode, through ? 1 : 0,
+                               (const uint64_t*)list, PLAN_LIST_CAP, (const unsigned long long*)listed, raw, recs, cap,
+                               (unsigned long long*)counter);
+            VPS_HIP_CHECK(hipGetLastError());
+            free(list);
+            return true;
+        }
         hipLaunchKernelGGL(k_plan_emit, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, through ? 1 : 0, lanes,
                            raw, recs, cap, (unsigned long long*)counter);
         VPS_HIP_CHECK(hipGetLastError());
+        return false;
     }
 
     // Work queued on the null stream so far (the mapping kernels of vps_describe_config) comes
@@ -590,6 +664,24 @@ public:
             const uint64_t blocks = (n + PLAIN_TILE_VECS - 1) / PLAIN_TILE_VECS;
             hipLaunchKernelGGL(k_plain_copy, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
                                (const char*)src + v0 * 16, (char*)dst + v0 * 16, n, xcd_chunk());
+            VPS_HIP_CHECK(hipGetLastError());
+        }
+    }
+
+    // mode 0: read `bytes` from src (sink: 4 bytes of device memory), mode 1: fill dst
+    void launch_plain_half(int mode, void* dst, const void* src, uint64_t bytes, void* sink)
+    {
+        const uint64_t nvec = bytes / 16;
+        const uint64_t per_launch = (uint64_t)MAX_GROUPS_PER_LAUNCH * PLAIN_TILE_VECS;
+        for (uint64_t v0 = 0; v0 < nvec; v0 += per_launch) {
+            const uint64_t n = nvec - v0 < per_launch ? nvec - v0 : per_launch;
+            const uint64_t blocks = (n + PLAIN_TILE_VECS - 1) / PLAIN_TILE_VECS;
+            if (mode == 0)
+                hipLaunchKernelGGL(k_plain_read, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
+                                   (const char*)src + v0 * 16, n, xcd_chunk(), (uint32_t*)sink);
+            else
+                hipLaunchKernelGGL(k_plain_fill, dim3((unsigned)blocks), dim3(COPY_THREADS), 0, stream_,
+                                   (char*)dst + v0 * 16, n, xcd_chunk());
             VPS_HIP_CHECK(hipGetLastError());
         }
     }

@@ -232,4 +232,43 @@ __global__ __launch_bounds__(COPY_THREADS) void k_plain_copy(const char* __restr
     copy_full_vectors(s, t, 0, n, threadIdx.x, COPY_THREADS);
 }
 
+// The two halves of that copy on their own, in the same launch shape: every vector is only
+// read (and folded into a value that is stored if it equals a sentinel, so that the loads stay),
+// or only written.  Their rates bound what a copy can reach on this memory system.
+__global__ __launch_bounds__(COPY_THREADS) void k_plain_read(const char* __restrict__ src, uint64_t nvec,
+                                                             uint32_t xcd_chunk, uint32_t* __restrict__ sink)
+{
+    uint32_t b = blockIdx.x;
+    if (xcd_chunk) {
+        const uint32_t x = b & 7, j = b >> 3;
+        const uint32_t grp = j / xcd_chunk;
+        if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
+    }
+    const uint64_t v0 = (uint64_t)b * PLAIN_TILE_VECS;
+    const uint32_t n = (uint32_t)(nvec - v0 < PLAIN_TILE_VECS ? nvec - v0 : PLAIN_TILE_VECS);
+    const uint64_t s = (uint64_t)(uintptr_t)src + v0 * 16;
+    uint32_t acc = 0;
+    for (uint32_t w = threadIdx.x; w < n; w += COPY_THREADS) {
+        const u32x4 v = __builtin_nontemporal_load((gsrc16_t)(s + (uint64_t)w * 16));
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    if (acc == 0x9E3779B9u) *sink = acc;
+}
+
+__global__ __launch_bounds__(COPY_THREADS) void k_plain_fill(char* __restrict__ dst, uint64_t nvec, uint32_t xcd_chunk)
+{
+    uint32_t b = blockIdx.x;
+    if (xcd_chunk) {
+        const uint32_t x = b & 7, j = b >> 3;
+        const uint32_t grp = j / xcd_chunk;
+        if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
+    }
+    const uint64_t v0 = (uint64_t)b * PLAIN_TILE_VECS;
+    const uint32_t n = (uint32_t)(nvec - v0 < PLAIN_TILE_VECS ? nvec - v0 : PLAIN_TILE_VECS);
+    const uint64_t t = (uint64_t)(uintptr_t)dst + v0 * 16;
+    u32x4 v;
+    v.x = v.y = v.z = v.w = 0xA5A5A5A5u;
+    for (uint32_t w = threadIdx.x; w < n; w += COPY_THREADS) __builtin_nontemporal_store(v, (gdst16_t)(t + (uint64_t)w * 16));
+}
+
 }  // namespace vps

@@ -56,12 +56,13 @@ struct TensorLayout {
     uint64_t start;      // offset in the unsharded flat buffer
     uint64_t shard_len;  // elements of one local shard
     int32_t cls;         // flat-buffer class: dense -> pp, expert -> PP + pp*EP + ep
-    int32_t pad_;
+    int32_t stage;       // pipeline stage that holds the tensor
 };
 
 struct ClassRec {
     uint64_t len;     // unpadded flat length
     uint64_t padded;  // rounded up to 8*D
+    uint64_t per;     // padded / D: elements of one data-parallel rank's range
 };
 
 struct RankCoord {
@@ -129,6 +130,7 @@ VPS_HD ClassRec make_class_rec(const ParConst& P, int32_t cls, uint64_t len)
     r.len = len;
     const uint64_t quantum = 8ull * (uint64_t)(cls < P.pp ? P.ddp : P.edp);
     r.padded = (len + quantum - 1) / quantum * quantum;
+    r.per = r.padded / (uint64_t)(cls < P.pp ? P.ddp : P.edp);
     return r;
 }
 
@@ -210,17 +212,15 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
     const TensorRec x = c.T[t];
     const int32_t D = group_dp(P, x.group), TPg = group_tp(P, x.group);
     if (didx >= D || tp >= TPg) return 0;
-    const int32_t pp = stage_of_layer(P, x.layer);
+    const TensorLayout tl = c.TL[t];
     const int32_t ep = x.group ? x.expert / (P.experts / P.ep) : 0;
-    const int32_t rank = encode_rank(P, x.group, tp, didx, pp, ep);
+    const int32_t rank = encode_rank(P, x.group, tp, didx, tl.stage, ep);
     if (c.rank_filter >= 0 && rank != c.rank_filter) return 0;
 
-    const TensorLayout tl = c.TL[t];
     const ClassRec cl = c.C[tl.cls];
     const bool sharded = P.zero == 1 && kind != 0;
-    const uint64_t per = cl.padded / (uint64_t)D;
-    const uint64_t r0 = sharded ? per * (uint64_t)didx : 0;
-    const uint64_t r1 = sharded ? r0 + per : cl.padded;
+    const uint64_t r0 = sharded ? cl.per * (uint64_t)didx : 0;
+    const uint64_t r1 = sharded ? r0 + cl.per : cl.padded;
     const uint64_t f0 = tl.start > r0 ? tl.start : r0;
     const uint64_t fe = tl.start + tl.shard_len;
     const uint64_t f1 = fe < r1 ? fe : r1;
@@ -278,6 +278,17 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
         bbase += bvol;
     }
     return npieces;
+}
+
+// Does data-parallel index didx hold any part of tensor t's shard for this kind?  (The flat
+// range of the rank against the shard's place in the flat buffer: no division, no pieces.)
+VPS_HD bool map_item_nonempty(const MapCtx& c, int32_t t, int32_t kind, int32_t didx)
+{
+    if (!(c.P.zero == 1 && kind != 0)) return true;
+    const TensorLayout tl = c.TL[t];
+    const ClassRec cl = c.C[tl.cls];
+    const uint64_t r0 = cl.per * (uint64_t)didx, r1 = r0 + cl.per;
+    return tl.start < r1 && r0 < tl.start + tl.shard_len;
 }
 
 VPS_HD void map_decode_item(const ParConst& P, int64_t item, int32_t& t, int32_t& kind, int32_t& tp, int32_t& didx)
@@ -375,17 +386,10 @@ struct PlanCtx {
     int32_t rank;              // planned rank or -1
     // single-rank plans: the tensor ids the rank can hold as a destination / as a source
     int32_t recv_lo, recv_n, send_lo, send_n;
+    // all-ranks plans: bits of the (destination tp, dp index) field and of the slot field of a lane
+    // index (both padded to powers of two, so that a lane finds its item with shifts)
+    int32_t item_bits, slot_bits;
 };
-
-// Fill the tensor ranges of a single-rank plan from the rank's pipeline stages.
-VPS_HD void plan_set_rank_ranges(PlanCtx& c)
-{
-    c.recv_lo = c.recv_n = c.send_lo = c.send_n = 0;
-    if (c.rank < 0) return;
-    int32_t lo, hi;
-    if (c.rank < c.B.world) { stage_tensor_range(c.B, decode_rank(c.B, c.rank).pp, lo, hi); c.recv_lo = lo; c.recv_n = hi - lo; }
-    if (c.rank < c.A.world) { stage_tensor_range(c.A, decode_rank(c.A, c.rank).pp, lo, hi); c.send_lo = lo; c.send_n = hi - lo; }
-}
 
 // A destination item is paired with every distinct piece of source data of its (tensor, kind):
 // one slot per source tp index if the tensor is TP-sharded, times one slot per source
@@ -399,6 +403,21 @@ VPS_HD int32_t plan_piece_slots(const ParConst& A, const TensorRec& x, int32_t k
 }
 
 VPS_HD int32_t plan_max_slots(const ParConst& A) { return A.tp * A.dmax; }
+
+// Fill the lane geometry of a plan: tensor ranges from the planned rank's pipeline stages,
+// field widths of an all-ranks lane index.
+VPS_HD void plan_set_rank_ranges(PlanCtx& c)
+{
+    c.recv_lo = c.recv_n = c.send_lo = c.send_n = 0;
+    c.item_bits = c.slot_bits = 0;
+    while ((1 << c.item_bits) < c.B.tp * c.B.dmax) ++c.item_bits;
+    while ((1 << c.slot_bits) < plan_max_slots(c.A)) ++c.slot_bits;
+    if (c.rank < 0) return;
+    int32_t lo, hi;
+    if (c.rank < c.B.world) { stage_tensor_range(c.B, decode_rank(c.B, c.rank).pp, lo, hi); c.recv_lo = lo; c.recv_n = hi - lo; }
+    if (c.rank < c.A.world) { stage_tensor_range(c.A, decode_rank(c.A, c.rank).pp, lo, hi); c.send_lo = lo; c.send_n = hi - lo; }
+}
+
 
 // Which lanes a planning launch enumerates.
 //   PLAN_ALL   every (tensor, kind, destination tp, destination dp index, slot)
@@ -414,14 +433,19 @@ VPS_HD int64_t plan_num_lanes(const PlanCtx& c, int mode)
     if (mode == PLAN_RECV) return (int64_t)c.recv_n * 4 * plan_max_slots(c.A);
     if (mode == PLAN_SEND) return (int64_t)c.send_n * 4 * c.B.tp * c.B.dmax;
     if (mode == PLAN_RANK) return plan_num_lanes(c, PLAN_RECV) + plan_num_lanes(c, PLAN_SEND);
-    return tk * c.B.tp * c.B.dmax * plan_max_slots(c.A);
+    return tk << (c.item_bits + c.slot_bits);
 }
 
-// The routed boxes of one lane: the pieces of one destination item intersected with the pieces
-// of the source rank that serves one slot of source data.  Calls f(box) for each non-empty
-// intersection (lo corners ascending within one pair of pieces only); returns their number.
-template <class F>
-VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
+// What a lane works on: one destination item and one slot of source data.
+struct LaneItem {
+    TensorRec x;
+    int32_t t, kind, tpb, db, dst_rank, tp_rep, d_rep;
+};
+
+// The item of a lane, or false when the lane has nothing to do: an index beyond the item grid, a
+// tensor that the rank does not hold, a destination item and a slot that share no data.  Cheap:
+// no division by a run-time 64-bit value, no pieces, no source selection.
+VPS_HD bool plan_lane_decode(const PlanCtx& c, int mode, int64_t lane, LaneItem& it)
 {
     const ParConst& A = c.A;
     const ParConst& B = c.B;
@@ -432,9 +456,12 @@ VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
         if (mode == PLAN_SEND) lane -= nrecv;
     }
     if (mode == PLAN_ALL) {
-        const int32_t smax = plan_max_slots(A);
-        u = (int32_t)(lane % smax);
-        map_decode_item(B, lane / smax, t, kind, tpb, db);
+        u = (int32_t)(lane & ((1 << c.slot_bits) - 1));
+        const int32_t ib = (int32_t)((lane >> c.slot_bits) & ((1 << c.item_bits) - 1));
+        const int32_t tk = (int32_t)(lane >> (c.slot_bits + c.item_bits));
+        if (ib >= B.tp * B.dmax) return false;
+        kind = tk & 3; t = tk >> 2;
+        tpb = ib / B.dmax; db = ib - tpb * B.dmax;
     } else if (mode == PLAN_RECV) {
         const int32_t smax = plan_max_slots(A);
         u = (int32_t)(lane % smax);
@@ -448,33 +475,50 @@ VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
     }
     const TensorRec x = c.ma.T[t];
     if (mode == PLAN_RECV) {
-        if (c.rank >= B.world) return 0;
+        if (c.rank >= B.world) return false;
         const RankCoord cr = decode_rank(B, c.rank);
         tpb = x.group ? cr.etp : cr.tp;
         db = x.group ? cr.edp : cr.ddp;
         // the rank holds the tensor only on its own stage (and expert block)
-        if (stage_of_layer(B, x.layer) != cr.pp || (x.group && x.expert / (B.experts / B.ep) != cr.ep)) return 0;
+        if (c.mb.TL[t].stage != cr.pp || (x.group && x.expert / (B.experts / B.ep) != cr.ep)) return false;
     }
-    if (tpb >= group_tp(B, x.group) || db >= group_dp(B, x.group)) return 0;
+    if (tpb >= group_tp(B, x.group) || db >= group_dp(B, x.group)) return false;
     const int32_t nd = (A.zero == 1 && kind != 0) ? group_dp(A, x.group) : 1;
     if (mode == PLAN_SEND) {
-        if (c.rank >= A.world) return 0;
+        if (c.rank >= A.world) return false;
         const RankCoord cs = decode_rank(A, c.rank);
-        if (stage_of_layer(A, x.layer) != cs.pp || (x.group && x.expert / (A.experts / A.ep) != cs.ep)) return 0;
+        if (c.ma.TL[t].stage != cs.pp || (x.group && x.expert / (A.experts / A.ep) != cs.ep)) return false;
         u = (x.tp_axis < 0 ? 0 : (x.group ? cs.etp : cs.tp)) * nd + (nd > 1 ? (x.group ? cs.edp : cs.ddp) : 0);
     }
-    if (u >= plan_piece_slots(A, x, kind)) return 0;
-    const int32_t ppb = stage_of_layer(B, x.layer), epb = x.group ? x.expert / (B.experts / B.ep) : 0;
+    if (u >= plan_piece_slots(A, x, kind)) return false;
+    const int32_t ppb = c.mb.TL[t].stage, epb = x.group ? x.expert / (B.experts / B.ep) : 0;
     const int32_t dst_rank = encode_rank(B, x.group, tpb, db, ppb, epb);
-    if (mode == PLAN_SEND && dst_rank == c.rank) return 0;
+    if (mode == PLAN_SEND && dst_rank == c.rank) return false;
     const int32_t tp_rep = x.tp_axis < 0 ? 0 : u / nd, d_rep = u % nd;
+    // cheap rejections first: most pairs of a destination item and a slot share no data
+    if (!map_item_nonempty(c.mb, t, kind, db) || !map_item_nonempty(c.ma, t, kind, d_rep)) return false;
     if (x.tp_axis >= 0) {
         // the two shards must overlap on the tensor-parallel axis
         const int32_t ea = x.shape[x.tp_axis] / group_tp(A, x.group), eb = x.shape[x.tp_axis] / group_tp(B, x.group);
-        if (tp_rep * ea >= (tpb + 1) * eb || tpb * eb >= (tp_rep + 1) * ea) return 0;
+        if (tp_rep * ea >= (tpb + 1) * eb || tpb * eb >= (tp_rep + 1) * ea) return false;
     }
-    const int32_t ppa = stage_of_layer(A, x.layer), epa = x.group ? x.expert / (A.experts / A.ep) : 0;
-    const int32_t src = select_source_rank(A, B, x, kind, encode_rank(A, x.group, tp_rep, d_rep, ppa, epa), dst_rank);
+    it.x = x; it.t = t; it.kind = kind; it.tpb = tpb; it.db = db; it.dst_rank = dst_rank;
+    it.tp_rep = tp_rep; it.d_rep = d_rep;
+    return true;
+}
+
+// The routed boxes of one item: the pieces of the destination item intersected with the pieces
+// of the source rank that serves the slot.  Calls f(box) for each non-empty intersection (lo
+// corners ascending within one pair of pieces only); returns their number.
+template <class F>
+VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f)
+{
+    const ParConst& A = c.A;
+    const ParConst& B = c.B;
+    const TensorRec& x = it.x;
+    const int32_t t = it.t, kind = it.kind, tpb = it.tpb, db = it.db, dst_rank = it.dst_rank;
+    const int32_t ppa = c.ma.TL[t].stage, epa = x.group ? x.expert / (A.experts / A.ep) : 0;
+    const int32_t src = select_source_rank(A, B, x, kind, encode_rank(A, x.group, it.tp_rep, it.d_rep, ppa, epa), dst_rank);
     if (c.rank >= 0 && dst_rank != c.rank && src != c.rank) return 0;
     const RankCoord cs = decode_rank(A, src);
     const int32_t tps = x.group ? cs.etp : cs.tp, ds = x.group ? cs.edp : cs.ddp;
@@ -504,6 +548,14 @@ VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
         });
     });
     return n;
+}
+
+template <class F>
+VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
+{
+    LaneItem it;
+    if (!plan_lane_decode(c, mode, lane, it)) return 0;
+    return plan_item_boxes(c, it, f);
 }
 
 VPS_HD uint64_t box_volume(const vps_box& b)
@@ -536,6 +588,15 @@ VPS_HD uint64_t box_major_key(const vps_box& b, bool by_dst)
     return (((first << 16 | second) << 2 | korder) << 24) | (uint64_t)b.tensor;
 }
 enum { MAJOR_KEY_OWNER_SHIFT = 42 };  // key >> 42 = the rank that owns the buffer
+
+// The same order in fewer bits, for the radix sort: rank fields of rank_bits, tensor ids of
+// tensor_bits (2 * rank_bits + 2 + tensor_bits bits in all).
+VPS_HD uint64_t compact_major_key(uint64_t key, int rank_bits, int tensor_bits)
+{
+    const uint64_t first = key >> MAJOR_KEY_OWNER_SHIFT, second = (key >> 26) & 0xffffull;
+    const uint64_t korder = (key >> 24) & 3ull, tensor = key & 0xffffffull;
+    return (((first << rank_bits | second) << 2 | korder) << tensor_bits) | tensor;
+}
 
 VPS_HD uint64_t box_minor_key(const vps_box& b, const TensorRec& x)
 {
@@ -612,7 +673,7 @@ VPS_HD OrderPlace order_by_counting(const OrderRec* recs, uint32_t n, uint32_t k
 }
 
 // Words at the head of a plan's summary block.
-enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_HEADER = 8 };
+enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_NLISTED = 4, SUM_HEADER = 8 };
 
 // Accumulate into a counter shared by all items of a step.
 VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
@@ -621,6 +682,19 @@ VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
     atomicAdd((unsigned long long*)p, (unsigned long long)v);
 #else
     *p += v;
+#endif
+}
+
+// Count the lanes for which `pred` holds into a counter that every item of a step shares: on the
+// device one atomic per wavefront (a ballot names the lanes) instead of one per lane.
+VPS_HD void be_atomic_count(uint64_t* p, bool pred)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint64_t mask = __ballot(pred ? 1 : 0);
+    if (mask && (threadIdx.x & 63u) == (unsigned)(__ffsll((unsigned long long)mask) - 1))
+        atomicAdd((unsigned long long*)p, (unsigned long long)__popcll(mask));
+#else
+    if (pred) *p += 1;
 #endif
 }
 
@@ -1038,11 +1112,10 @@ VPS_HD void account_box(const FinishCtx& c, const vps_box& b)
         if (b.dst_rank == c.rank) be_atomic_add(&c.pairs[b.src_rank], bytes);
         if (b.src_rank == c.rank) be_atomic_add(&c.pairs[c.wa + b.dst_rank], bytes);
     }
-    if (box_retained(b, c.through_buffers)) be_atomic_add(&c.sum[SUM_NRETAIN], 1);
-    else {
-        if (c.rank < 0 || b.src_rank == c.rank) be_atomic_add(&c.sum[SUM_NSEND], 1);
-        if (c.rank < 0 || b.dst_rank == c.rank) be_atomic_add(&c.sum[SUM_NRECV], 1);
-    }
+    const bool retained = box_retained(b, c.through_buffers);
+    be_atomic_count(&c.sum[SUM_NRETAIN], retained);
+    be_atomic_count(&c.sum[SUM_NSEND], !retained && (c.rank < 0 || b.src_rank == c.rank));
+    be_atomic_count(&c.sum[SUM_NRECV], !retained && (c.rank < 0 || b.dst_rank == c.rank));
 }
 
 // Copy descriptor `i` (operation op of box b) and its tile count.

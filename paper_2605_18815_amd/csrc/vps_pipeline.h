@@ -225,7 +225,7 @@ struct SummaryLayout {
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
                 uint32_t tile_bytes, uint32_t xpose_shape, uint32_t small_limit, bool routes_only,
-                bool through_buffers, int64_t tile_hint, PlanData& p)
+                bool through_buffers, int64_t tile_hint, int64_t box_hint, PlanData& p, bool lane_list = true)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -260,11 +260,16 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     // (1) intersections: every lane walks the routed boxes of its item and writes each, with its
     // ordering keys, into the next free slot of the raw table (one atomic per wavefront and
     // step).  The table holds `cap` boxes; a plan with more is planned again with the exact size.
-    int64_t cap = small_limit;
+    // (a caller that has seen this transition before passes its box count, see the tile hint below)
+    int64_t cap = box_hint > (int64_t)small_limit ? box_hint : (int64_t)small_limit;
     vps_box* raw = be.template alloc<vps_box>(cap);
     OrderRec* recs = be.template alloc<OrderRec>(cap);
-    auto emit = [&]() { be.plan_emit(pc, rank < 0 ? PLAN_ALL : PLAN_RANK, through_buffers, raw, recs, (uint64_t)cap, sum + SUM_NBOXES); };
-    emit();
+    bool listed = false;
+    auto emit = [&](bool two_launches) {
+        listed = be.plan_emit(pc, rank < 0 ? PLAN_ALL : PLAN_RANK, through_buffers, raw, recs, (uint64_t)cap, sum + SUM_NBOXES,
+                              sum + SUM_NLISTED, two_launches);
+    };
+    emit(lane_list);
 
     FinishCtx fc;
     fc.rank = rank; fc.wa = WA; fc.wb = WB; fc.through_buffers = through_buffers; fc.routes_only = routes_only;
@@ -353,6 +358,13 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
 
     std::vector<uint64_t> hsum((size_t)SL.words());
     be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());     // the one synchronisation
+    if (listed && hsum[SUM_NLISTED] > BE::PLAN_LIST_CAP) {
+        // more busy lanes than the list holds: nothing was emitted, so plan again without the list
+        be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);
+        be.free(descs); be.free(ntl); be.free(tb); be.free(tiles);
+        build_plan(be, ca, cb, rank, tile_bytes, xpose_shape, small_limit, routes_only, through_buffers, tile_hint, box_hint, p, false);
+        return;
+    }
     int64_t n = (int64_t)hsum[SUM_NBOXES];
     if (n >= (int64_t)1 << 31) throw Error{ VPS_ERR_OOM, "more than 2^31 boxes" };
     p.nboxes = n;
@@ -369,7 +381,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             raw = be.template alloc<vps_box>(cap);
             recs = be.template alloc<OrderRec>(cap);
             be.zero(sum, sizeof(uint64_t) * (size_t)SL.words());
-            emit();
+            emit(lane_list);
         } else {
             be.zero(sum + 1, sizeof(uint64_t) * (size_t)(SL.words() - 1));
         }
@@ -381,10 +393,19 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         const int lo_bits = bits_for(ca.tensor_numel_max);
         be.for_each(step::plan_keys(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = recs[k].klo; by_lo[k] = (uint32_t)k; });
         be.sort_pairs(kmin, by_lo, n, lo_bits);
-        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) { ord_s[k] = by_lo[k]; kmaj[k] = recs[by_lo[k]].key_s; });
-        be.sort_pairs(kmaj, ord_s, n, 58);
-        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) { ord_r[k] = by_lo[k]; kmaj[k] = recs[by_lo[k]].key_r; });
-        be.sort_pairs(kmaj, ord_r, n, 58);
+        // (keys cut to the bits this transition needs: every bit less is work the sort does not do)
+        const int rank_bits = bits_for((uint64_t)W), tensor_bits = bits_for((uint64_t)A.nt);
+        const int major_bits = 2 * rank_bits + 2 + tensor_bits;
+        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) {
+            ord_s[k] = by_lo[k];
+            kmaj[k] = compact_major_key(recs[by_lo[k]].key_s, rank_bits, tensor_bits);
+        });
+        be.sort_pairs(kmaj, ord_s, n, major_bits);
+        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) {
+            ord_r[k] = by_lo[k];
+            kmaj[k] = compact_major_key(recs[by_lo[k]].key_r, rank_bits, tensor_bits);
+        });
+        be.sort_pairs(kmaj, ord_r, n, major_bits);
         be.free(kmin); be.free(kmaj); be.free(by_lo);
         int64_t* sz = be.template alloc<int64_t>(n + 1);
         gs = be.template alloc<uint64_t>(n + 1);

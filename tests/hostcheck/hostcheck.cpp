@@ -118,7 +118,7 @@ public:
                 const int32_t t = P.flat_order ? P.nt - 1 - q : q;
                 if (class_of_tensor(P, T[t]) != cls) continue;
                 TensorLayout tl;
-                tl.start = running; tl.shard_len = shard_elems(P, T[t]); tl.cls = cls; tl.pad_ = 0;
+                tl.start = running; tl.shard_len = shard_elems(P, T[t]); tl.cls = cls; tl.stage = cls < P.pp ? cls : (cls - P.pp) / P.ep;
                 TL[t] = tl;
                 running += tl.shard_len;
             }
@@ -126,7 +126,9 @@ public:
         }
     }
 
-    void plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter)
+    static constexpr uint64_t PLAN_LIST_CAP = 1ull << 22;
+    bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
+                   uint64_t*, bool)
     {
         const int64_t lanes = plan_num_lanes(pc, mode);
         for (int64_t lane = 0; lane < lanes; ++lane)
@@ -137,6 +139,7 @@ public:
                     recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through);
                 }
             });
+        return false;
     }
 
     template <class Step, class F>
@@ -165,6 +168,13 @@ public:
     {
         if (!in_bounds((const char*)src, bytes) || !in_bounds((char*)dst, bytes)) { ++g_violations; return; }
         memcpy(dst, src, bytes);
+    }
+
+    void launch_plain_half(int mode, void* dst, const void* src, uint64_t bytes, void* sink)
+    {
+        if (mode == 0) { if (!in_bounds((const char*)src, bytes) || !in_bounds((char*)sink, 4)) ++g_violations; return; }
+        if (!in_bounds((char*)dst, bytes)) { ++g_violations; return; }
+        memset(dst, 0xA5, bytes);
     }
 
     // Same slot walk as the device kernel, one lane at a time, with bounds checks.
