@@ -462,6 +462,81 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
 
 # ----------------------------------------------------------------------------- full size
 
+def check_send_buffer_on_device(mem, a, out_boxes, src, scratch, seed, pattern_budget):
+    """Every element of every outgoing box against the send buffer, on the device: (1) the box as
+    a strided view of the source buffer (which the oracle filled, element by element) must equal
+    the bytes at the box's position in the send buffer; (2) those bytes must also be the pattern
+    words of the box's global coordinates (generated on the host, box by box, up to
+    pattern_budget bytes), which ties the source addressing of a box to the coordinates it claims."""
+    torch = mem.torch
+    dts = {2: torch.int16, 4: torch.int32}
+    gathered = patterned = 0
+    spent = 0
+    for bx in out_boxes:
+        kind, buf = int(bx["kind"]), int(bx["src_buf"])
+        es = 2 if kind == 0 else 4
+        ext = [int(e) for e in bx["ext"]]
+        vol = ext[0] * ext[1] * ext[2] * ext[3]
+        pos = int(bx["send_pos"])
+        words = src[buf].view(dts[es])
+        got = scratch[pos:pos + vol * es].view(dts[es])
+        step = max(1, (1 << 28) // max(1, ext[1] * ext[2] * ext[3]))     # slabs of the outer axis, 256 Mi elements at most
+        for o in range(0, ext[0], step):
+            m = min(step, ext[0] - o)
+            view = torch.as_strided(words, (m, ext[1], ext[2], ext[3]), tuple(int(v) for v in bx["src_stride"]),
+                                    words.storage_offset() + int(bx["src_off"]) + o * int(bx["src_stride"][0]))
+            inner = ext[1] * ext[2] * ext[3]
+            assert torch.equal(view.reshape(-1), got[o * inner:(o + m) * inner]), ("send payload differs from the source box", bx, o)
+        gathered += vol
+        if spent + vol * es <= pattern_budget:
+            want = np.empty(vol, dtype=np.uint16 if kind == 0 else np.uint32)
+            t = int(bx["tensor"])
+            boxfill.fill_box(seed, kind, t, a.tensor_info(t)["shape"], bx["lo"], bx["ext"], want)
+            dev = torch.from_numpy(want.view(np.int16 if kind == 0 else np.int32)).to(got.device)
+            assert torch.equal(dev, got), ("send payload is not the pattern of the box's coordinates", bx)
+            patterned += vol
+            spent += vol * es
+            del dev, want
+    return gathered, patterned
+
+
+def check_cross_plan_segments(lib, model, pa, pb, pairs):
+    """Two ranks plan on their own (single-rank plans): for every pair (i, j) the sender's plan and
+    the receiver's plan must list the same boxes for the segment i -> j, at the same offsets
+    inside the segment, and agree on its size: what i packs is what j expects to unpack."""
+    ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
+    plans = {}
+
+    def plan_of(r):
+        if r not in plans:
+            p = lib.plan_intersections(ca, cb, r)
+            plans[r] = (p, p.get_boxes())
+        return plans[r]
+
+    checked = 0
+    for i, j in pairs:
+        if i == j:
+            continue
+        (pi, bi), (pj, bj) = plan_of(i), plan_of(j)
+        si, sj = pi.peer_segment(i, j), pj.peer_segment(i, j)
+        assert si["bytes"] == sj["bytes"], ("segment size seen by sender and receiver", i, j, si, sj)
+        mine = bi[(bi["src_rank"] == i) & (bi["dst_rank"] == j)]
+        theirs = bj[(bj["src_rank"] == i) & (bj["dst_rank"] == j)]
+        assert len(mine) == len(theirs)
+        if not len(mine):
+            assert si["bytes"] == 0
+            continue
+        key = ["tensor", "kind", "lo", "ext", "src_buf", "dst_buf", "src_off", "dst_off"]
+        om = np.argsort(mine["send_pos"], kind="stable")
+        ot = np.argsort(theirs["recv_pos"], kind="stable")
+        for k in key:
+            assert np.array_equal(mine[k][om], theirs[k][ot]), ("box lists of the segment differ in " + k, i, j)
+        assert np.array_equal(mine["send_pos"][om] - np.uint64(si["send_off"]), theirs["recv_pos"][ot] - np.uint64(sj["recv_off"])), \
+            ("offsets inside the segment differ between sender and receiver", i, j)
+        checked += len(mine)
+    return checked
+
+
 def _sample_chunks(n, chunk, fraction, edges, rng):
     """Chunk indices to verify: every chunk that holds a box edge, the first and last chunk, and
     a random fraction of the rest."""
@@ -475,22 +550,23 @@ def _sample_chunks(n, chunk, fraction, edges, rng):
 
 
 def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05, chunk=1 << 20,
-                             box_samples=32, rows_per_box=4, log=print):
+                             box_samples=32, pattern_budget=8 << 30, log=print, through=False):
     """One rank's share at full size, in the launch configuration the benchmark times.
 
     The source buffers are filled by the oracle (every element), the receive buffer with the
     pattern of the incoming boxes.  After one vps_apply_transition the destination buffers are
-    compared with the oracle on sampled 1 Mi-element chunks (all chunks holding a box edge, plus
-    a random fraction), the padding must be untouched, every box is validated by the oracle on
-    its corners and random interior points, and sampled rows of every outgoing box are compared
-    with the send buffer."""
+    compared with the oracle on 1 Mi-element chunks (all of them when fraction = 1: every chunk
+    holding a box edge plus a random fraction otherwise), the padding must be untouched, every box
+    is validated by the oracle on its corners and random interior points, and every element of
+    every outgoing box is compared with the send buffer (see check_send_buffer_on_device).
+    through = True plans with VPS_PLAN_THROUGH_BUFFERS: the whole share is packed and unpacked."""
     import time
     t0 = time.time()
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
-    plan = lib.plan_intersections(ca, cb, rank)
+    plan = lib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
     info = plan.buffer_bytes(rank)
     log(f"  plan: {len(boxes)} boxes, send {info['send_total'] >> 20} MiB, recv {info['recv_total'] >> 20} MiB, "
         f"retain {info['retain_total'] >> 20} MiB ({time.time() - t0:.1f}s)")
@@ -536,21 +612,10 @@ def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05,
         del got
     log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
 
-    sb = mem.download(scratch[:info["send_total"]]) if info["send_total"] else np.zeros(0, np.uint8)
-    nrows_checked = 0
-    for bx in boxes[(boxes["src_rank"] == rank) & (boxes["dst_rank"] != rank)]:
-        ext = [int(e) for e in bx["ext"]]
-        rows = ext[0] * ext[1] * ext[2]
-        es = 2 if bx["kind"] == 0 else 4
-        for r in sorted(set([0, rows - 1] + rng.integers(0, rows, rows_per_box).tolist())):
-            c2, c1, c0 = r % ext[2], (r // ext[2]) % ext[1], r // (ext[2] * ext[1])
-            so = int(bx["src_off"]) + c0 * int(bx["src_stride"][0]) + c1 * int(bx["src_stride"][1]) + c2 * int(bx["src_stride"][2])
-            idx = so + np.arange(ext[3], dtype=np.int64) * int(bx["src_stride"][3])
-            w = src_host[int(bx["src_buf"])][idx]
-            pos = int(bx["send_pos"]) + r * ext[3] * es
-            assert np.array_equal(sb[pos:pos + ext[3] * es].view(w.dtype), w), ("send payload", bx, r)
-            nrows_checked += 1
-    log(f"  {nrows_checked} rows of outgoing boxes compared with the send buffer ({time.time() - t0:.1f}s)")
+    out_boxes = boxes[(boxes["src_rank"] == rank) & ((boxes["dst_rank"] != rank) | through)]
+    n_gathered, n_pattern = check_send_buffer_on_device(mem, a, out_boxes, src, scratch, seed, pattern_budget)
+    log(f"  send buffer: {n_gathered} elements of {len(out_boxes)} outgoing boxes equal the source data they name, "
+        f"{n_pattern} of them also the pattern of their global coordinates ({time.time() - t0:.1f}s)")
     assert mem.violations() == 0, "a kernel wrote outside its buffers"
     return dict(boxes=len(boxes), info=info, checked=checked, stats=plan.stats())
 

@@ -27,7 +27,7 @@ def _release_cached_device_memory():
     yield
 
 
-def _run(lib, name, rank=None, src_over=None, dst_over=None, fraction=None):
+def _run(lib, name, rank=None, src_over=None, dst_over=None, fraction=None, through=False):
     w = cf.WORKLOADS[name]
     pa, pb = dict(w["src"]), dict(w["dst"])
     pa.update(src_over or {})
@@ -36,7 +36,7 @@ def _run(lib, name, rank=None, src_over=None, dst_over=None, fraction=None):
     print(f"\n{name} rank {rank}", flush=True)
     out = parity.run_single_rank_fullsize(lib, parity.GpuMem(), w["model"], pa, pb, rank,
                                           seed=cf.seed_of(name), fraction=FRACTION if fraction is None else fraction,
-                                          log=lambda s: print(s, flush=True))
+                                          log=lambda s: print(s, flush=True), through=through)
     assert out["checked"] > 0
     return out
 
@@ -46,6 +46,28 @@ def test_gqa70b_rank11_full_size(lib):
     out = _run(lib, "gqa70b")
     # first-stage rank: the embedding shifts the flat edges, fp32 state really moves
     assert out["info"]["send_total"] > 0 and out["info"]["recv_total"] > 0
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["gqa70b", "gqa8b"])
+def test_whole_share_through_the_buffers_full_size(lib, name):
+    """The all-through-buffers stress at full size: the rank is its own peer, so pack and unpack
+    each run over the whole share; every destination element and every byte of the send buffer is
+    compared."""
+    out = _run(lib, name, through=True)
+    assert out["info"]["retain_total"] == 0 and out["stats"]["num_retain_tiles"] == 0
+    assert out["info"]["send_total"] > 0
+
+
+def test_sender_and_receiver_agree_on_segments_70b(lib):
+    """Rank 11 of the 70B switch and each of its peers, planned independently: same boxes at the
+    same offsets inside every segment (planning only: no state is resident)."""
+    w = cf.WORKLOADS["gqa70b"]
+    ca, cb = lib.describe_config(w["model"], w["src"]), lib.describe_config(w["model"], w["dst"])
+    boxes = lib.plan_intersections(ca, cb, 11).get_boxes()
+    pairs = sorted({(int(s), int(d)) for s, d in zip(boxes["src_rank"], boxes["dst_rank"]) if s != d})
+    assert len(pairs) >= 6
+    assert parity.check_cross_plan_segments(lib, w["model"], w["src"], w["dst"], pairs) > 0
 
 
 @pytest.mark.timeout(600)

@@ -66,6 +66,11 @@ def test_plans_beyond_the_counting_limit(lib, limit):
         lib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
 
 
+def test_sender_and_receiver_agree_on_segments_toy(lib):
+    w = cf.WORKLOADS["toy"]
+    assert parity.check_cross_plan_segments(lib, w["model"], w["src"], w["dst"], [(i, j) for i in range(4) for j in range(4)]) > 0
+
+
 def test_toy_workload_all_ranks(lib):
     w = cf.WORKLOADS["toy"]
     out = parity.run_all_ranks(lib, parity.GpuMem(), w["model"], w["src"], w["dst"], seed=cf.seed_of("toy"))

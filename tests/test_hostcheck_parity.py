@@ -193,6 +193,15 @@ def test_plans_beyond_the_counting_limit(hlib, limit):
         hlib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
 
 
+@pytest.mark.parametrize("name", ["gpt-zero-to-replicated", "gpt-world-grows", "moe-odd", "moe-carved-ep-grows"])
+def test_sender_and_receiver_agree_on_segments(hlib, name):
+    """Single-rank plans of the two ends of every segment list the same boxes at the same offsets."""
+    import oracle
+    _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
+    wa, wb = oracle.Config(m, pa).world, oracle.Config(m, pb).world
+    assert parity.check_cross_plan_segments(hlib, m, pa, pb, [(i, j) for i in range(wa) for j in range(wb)]) > 0
+
+
 def test_toy_workload_all_ranks(hlib):
     w = cf.WORKLOADS["toy"]
     mem = parity.HostMem(hlib)
