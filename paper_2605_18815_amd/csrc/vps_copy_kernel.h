@@ -52,16 +52,52 @@ __device__ __forceinline__ uint64_t slot_addr(const PtrArgs& pa, int32_t slot)
     return (uint64_t)(uintptr_t)(pa.tbl ? pa.tbl[slot] : pa.inl[slot]);
 }
 
+typedef const VPS_GLOBAL u32x4* gsrc16a_t;   // source vectors at 16-byte alignment
+
+// Bytes [shift, shift + 16) of the 32 bytes lo | hi (shift = 2, 4, ... 14; the same for the whole
+// wavefront, so the switch is a uniform branch).
+__device__ __forceinline__ u32x4 realign16(const u32x4 lo, const u32x4 hi, uint32_t shift)
+{
+    const uint32_t sh = (shift & 2u) * 8u;   // 0 or 16 bits inside a dword
+    uint32_t c0, c1, c2, c3, c4;
+    switch (shift >> 2) {
+        case 0: c0 = lo.x; c1 = lo.y; c2 = lo.z; c3 = lo.w; c4 = hi.x; break;
+        case 1: c0 = lo.y; c1 = lo.z; c2 = lo.w; c3 = hi.x; c4 = hi.y; break;
+        case 2: c0 = lo.z; c1 = lo.w; c2 = hi.x; c3 = hi.y; c4 = hi.z; break;
+        default: c0 = lo.w; c1 = hi.x; c2 = hi.y; c3 = hi.z; c4 = hi.w; break;
+    }
+    u32x4 r;
+    r.x = (uint32_t)((((uint64_t)c1 << 32) | c0) >> sh);
+    r.y = (uint32_t)((((uint64_t)c2 << 32) | c1) >> sh);
+    r.z = (uint32_t)((((uint64_t)c3 << 32) | c2) >> sh);
+    r.w = (uint32_t)((((uint64_t)c4 << 32) | c3) >> sh);
+    return r;
+}
+
 // Full vectors [wbeg, wend) of one run: vector w sits at dst `dvec + 16*w` (16-byte aligned)
 // and src `svec + 16*w`.  `lane` strides by `nlanes`.  One load in flight per lane: with eight
 // waves per SIMD resident this measured faster than unrolled batches of loads, whose stores
-// then arrive in bursts.
+// then arrive in bursts.  A source that is 4-byte aligned where the destination is 16-byte
+// aligned is loaded as it is (measured: within 1 % of the aligned rate).  At 2 bytes off a dword
+// such loads cost 4-5 %: there a lane takes the two aligned source vectors that cover its 16
+// bytes (its neighbour's first one is its second one, so the second load finds its line in the
+// cache) and shifts them together in registers, which measured 2 % faster.
 __device__ __forceinline__ void copy_full_vectors(uint64_t svec, uint64_t dvec, uint32_t wbeg,
                                                   uint32_t wend, uint32_t lane, uint32_t nlanes)
 {
+    const uint32_t shift = uniform32((uint32_t)svec & 15u);
+    if ((shift & 3u) == 0) {
+        for (uint32_t w = wbeg + lane; w < wend; w += nlanes) {
+            const u32x4 v = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)w * 16));
+            __builtin_nontemporal_store(v, (gdst16_t)(dvec + (uint64_t)w * 16));
+        }
+        return;
+    }
+    const uint64_t abase = svec - shift;
     for (uint32_t w = wbeg + lane; w < wend; w += nlanes) {
-        const u32x4 v = __builtin_nontemporal_load((gsrc16_t)(svec + (uint64_t)w * 16));
-        __builtin_nontemporal_store(v, (gdst16_t)(dvec + (uint64_t)w * 16));
+        const u32x4 lo = *(gsrc16a_t)(abase + (uint64_t)w * 16);
+        const u32x4 hi = *(gsrc16a_t)(abase + (uint64_t)w * 16 + 16);
+        __builtin_nontemporal_store(realign16(lo, hi, shift), (gdst16_t)(dvec + (uint64_t)w * 16));
     }
 }
 
@@ -83,11 +119,52 @@ __device__ __forceinline__ void copy_run_window(uint64_t srow, uint64_t drow, ui
     if (g.tail_bytes) copy_units(g.svec + g.tail_off, g.dvec + g.tail_off, g.tail_bytes, nlanes - 1 - lane);
 }
 
+constexpr uint32_t COPY_LDS_WORDS = XPOSE_T * (XPOSE_T + 1);   // the transposes' block: 16.25 KiB
+
+// The same for one long piece whose source is 2 bytes off a dword where its destination is
+// 16-byte aligned: whole source lines are loaded (aligned 16-byte loads, every 128-byte line
+// once) into LDS, and the destination vectors are put together from there.  Measured on a 70B
+// share whose tensors all start at odd offsets: 2 % faster for such pieces than loading two
+// aligned vectors per lane, which in turn is 2 % faster than 16-byte loads at 2-byte alignment.
+// (Pieces that are only off by a multiple of 4 bytes are loaded as they are: staging them
+// measured slower.)  The lines at both ends hold at least one byte of the piece, so no access
+// leaves the pages of the buffer.
+__device__ __forceinline__ void copy_run_staged(uint64_t srow, uint64_t drow, uint32_t run_bytes,
+                                                uint32_t tid, uint32_t* lds_words)
+{
+    const RunWindow g = run_window(srow, drow, run_bytes, 0, (run_bytes + 30) >> 4);
+    if (g.wbeg < g.wend) {
+        const uint64_t s0 = g.svec + 16ull * g.wbeg;           // first source byte of the full vectors
+        const uint64_t a0 = s0 & ~127ull;
+        const uint32_t off = uniform32((uint32_t)(s0 - a0));     // even, below 128
+        const uint32_t nfull = g.wend - g.wbeg;
+        const uint32_t nstage = (off + 16u * nfull + 15u) >> 4;
+        u32x4* stage = reinterpret_cast<u32x4*>(lds_words);
+        for (uint32_t i = tid; i < nstage; i += COPY_THREADS)
+            stage[i] = __builtin_nontemporal_load((gsrc16a_t)(a0 + (uint64_t)i * 16));
+        __syncthreads();
+        const uint32_t shift = off & 15u, v0 = off >> 4;
+        const uint64_t d0 = g.dvec + 16ull * g.wbeg;
+        if (shift == 0) {
+            for (uint32_t w = tid; w < nfull; w += COPY_THREADS)
+                __builtin_nontemporal_store(stage[v0 + w], (gdst16_t)(d0 + (uint64_t)w * 16));
+        } else {
+            for (uint32_t w = tid; w < nfull; w += COPY_THREADS)
+                __builtin_nontemporal_store(realign16(stage[v0 + w], stage[v0 + w + 1], shift), (gdst16_t)(d0 + (uint64_t)w * 16));
+        }
+    }
+    if (g.head_bytes) copy_units(srow, drow, g.head_bytes, tid);
+    if (g.tail_bytes) copy_units(g.svec + g.tail_off, g.dvec + g.tail_off, g.tail_bytes, COPY_THREADS - 1 - tid);
+}
+
 // A block of up to 64 x 64 elements whose contiguous axis differs between source and
 // destination (transposed expert storage): rows along the source's contiguous axis are read
 // with 16-byte loads into LDS, columns are gathered from LDS and written as 16-byte vectors
 // along the destination's contiguous axis.  The LDS pitch of 64+2 (2-byte) / 64+1 (4-byte)
-// elements keeps rows dword aligned and spreads a column over the banks.
+// elements keeps rows dword aligned and moves consecutive rows one bank on.  A half-wavefront
+// spans two quads of lanes that would meet in the same banks (a row of 64 dwords wraps the 32
+// banks twice): the upper quad of lanes takes its dwords in rotated order, which puts the two on
+// different banks in every access.
 template <class E>
 __device__ __forceinline__ void copy_xpose_tile(uint64_t s0, uint64_t t0, int64_t src_pitch,
                                                 int64_t dst_pitch, uint32_t ta, uint32_t tb,
@@ -103,14 +180,21 @@ __device__ __forceinline__ void copy_xpose_tile(uint64_t s0, uint64_t t0, int64_
 
     // phase 1: source rows (fixed b, a contiguous) -> lds[b][a]
     for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
-        const uint32_t b = v / NV, a = (v % NV) * V;
+        const uint32_t b = v / NV, q = v % NV, a = q * V;
         if (b >= tb || a >= ta) continue;
         const uint64_t g = s0 + (uint64_t)((int64_t)b * src_pitch) + a * sizeof(E);
         E* row = lds + b * PITCH + a;
         if (a + V <= ta) {
             const u32x4 x = __builtin_nontemporal_load((gsrc16_t)g);
             uint32_t* r32 = reinterpret_cast<uint32_t*>(row);
-            r32[0] = x.x; r32[1] = x.y; r32[2] = x.z; r32[3] = x.w;
+            // 4-byte rows: lanes q and q + 8 would meet in the same banks, so the upper ones write
+            // their dwords two places on (same instruction, other bank)
+            const bool rot = sizeof(E) == 4 && (q & 8u);
+            const uint32_t o = rot ? 2u : 0u;
+            r32[o] = rot ? x.z : x.x;
+            r32[o + 1] = rot ? x.w : x.y;
+            r32[o ^ 2u] = rot ? x.x : x.z;
+            r32[(o ^ 2u) + 1] = rot ? x.y : x.w;
         } else {
             for (uint32_t k = 0; a + k < ta; ++k) row[k] = *(gsrc_t)(g + k * sizeof(E));
         }
@@ -118,19 +202,28 @@ __device__ __forceinline__ void copy_xpose_tile(uint64_t s0, uint64_t t0, int64_
     __syncthreads();
     // phase 2: lds columns (fixed a, b contiguous) -> destination rows
     for (uint32_t v = tid; v < T * NV; v += COPY_THREADS) {
-        const uint32_t a = v / NV, b = (v % NV) * V;
+        const uint32_t a = v / NV, q = v % NV, b = q * V;
         if (a >= ta || b >= tb) continue;
         const uint64_t g = t0 + (uint64_t)((int64_t)a * dst_pitch) + b * sizeof(E);
         const E* col = lds + b * PITCH + a;
         if (b + V <= tb && (g & 15) == 0) {
             u32x4 x;
             if (sizeof(E) == 2) {
-                x.x = (uint32_t)col[0] | ((uint32_t)col[PITCH] << 16);
-                x.y = (uint32_t)col[2 * PITCH] | ((uint32_t)col[3 * PITCH] << 16);
-                x.z = (uint32_t)col[4 * PITCH] | ((uint32_t)col[5 * PITCH] << 16);
-                x.w = (uint32_t)col[6 * PITCH] | ((uint32_t)col[7 * PITCH] << 16);
+                // lanes q and q + 4 read rows 32 apart, i.e. the same banks: the upper ones take
+                // their eight rows starting four further on (same instructions, other banks)
+                const bool rot = (q & 4u) != 0;
+                const uint32_t o = rot ? 4u : 0u;
+                const uint32_t r0 = col[o * PITCH], r1 = col[(o + 1) * PITCH], r2 = col[(o + 2) * PITCH], r3 = col[(o + 3) * PITCH];
+                const uint32_t r4 = col[(o ^ 4u) * PITCH], r5 = col[((o ^ 4u) + 1) * PITCH], r6 = col[((o ^ 4u) + 2) * PITCH],
+                               r7 = col[((o ^ 4u) + 3) * PITCH];
+                const uint32_t lo01 = r0 | (r1 << 16), lo23 = r2 | (r3 << 16), hi01 = r4 | (r5 << 16), hi23 = r6 | (r7 << 16);
+                x.x = rot ? hi01 : lo01; x.y = rot ? hi23 : lo23; x.z = rot ? lo01 : hi01; x.w = rot ? lo23 : hi23;
             } else {
-                x.x = col[0]; x.y = col[PITCH]; x.z = col[2 * PITCH]; x.w = col[3 * PITCH];
+                // 4-byte columns: lanes q and q + 8 likewise, two rows on
+                const bool rot = (q & 8u) != 0;
+                const uint32_t o = rot ? 2u : 0u;
+                const uint32_t r0 = col[o * PITCH], r1 = col[(o + 1) * PITCH], r2 = col[(o ^ 2u) * PITCH], r3 = col[((o ^ 2u) + 1) * PITCH];
+                x.x = rot ? r2 : r0; x.y = rot ? r3 : r1; x.z = rot ? r0 : r2; x.w = rot ? r1 : r3;
             }
             __builtin_nontemporal_store(x, (gdst16_t)g);
         } else {
@@ -152,6 +245,7 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
         const uint32_t grp = j / xcd_chunk;
         if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
     }
+    __shared__ __attribute__((aligned(16))) uint32_t lds_words[COPY_LDS_WORDS];
     const TileRef* tp = tiles + (tile0 + b);
     const uint32_t tid = threadIdx.x;
     const uint32_t nf = uniform32(tp->nruns_flags);
@@ -163,7 +257,6 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
         const uint64_t s = uniform64(slot_addr(pa, tile_slot(sa)) + tile_offset(sa));
         const uint64_t t = uniform64(slot_addr(pa, tile_slot(da)) + tile_offset(da));
         if (nf & TILE_XPOSE) {
-            __shared__ uint32_t lds_words[XPOSE_T * (XPOSE_T + 1)];
             const int64_t sp = (int64_t)uniform64((uint64_t)tp->src_pitch), dp = (int64_t)uniform64((uint64_t)tp->dst_pitch);
             const uint32_t ta = nbytes & 0xffffu, tb = nbytes >> 16;
             if (nf & TILE_ES2) copy_xpose_tile<uint16_t>(s, t, sp, dp, ta, tb, tid, lds_words);
@@ -175,7 +268,11 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
         const uint32_t nw = (nbytes + 30) >> 4;
         if (nruns == 1) {
             // a contiguous piece of one long run: the whole workgroup walks its vectors
-            copy_run_window(s, t, nbytes, 0, nw, tid, COPY_THREADS);
+            // (a source 2 bytes off a dword where the destination is aligned: through LDS)
+            if (((uint32_t)(s - t) & 2u) && nbytes >= 2048u && nbytes + 160u <= COPY_LDS_WORDS * 4u)
+                copy_run_staged(s, t, nbytes, tid, lds_words);
+            else
+                copy_run_window(s, t, nbytes, 0, nw, tid, COPY_THREADS);
         } else {
             const uint64_t sp = uniform64((uint64_t)tp->src_pitch), dp = uniform64((uint64_t)tp->dst_pitch);
             if (nruns < COPY_WAVES) {

@@ -787,6 +787,14 @@ VPS_HD uint32_t xpose_auto_shape(int64_t src_pitch_bytes, int64_t dst_pitch_byte
     return 8u | 8u << 16;
 }
 
+// Long runs are cut into tiles at destination offsets that are multiples of this many bytes
+// (when the tile size is such a multiple): a memory line that two workgroups share is written
+// in two parts, which costs a few per cent of the copy rate; with the cuts on line boundaries
+// only the two ends of a run are left with partial lines.  Offsets are relative to the buffer;
+// allocations of the HIP runtime start on such a boundary.
+constexpr uint64_t RUN_CUT_ALIGN = 256;
+VPS_HD uint64_t run_cut_align(uint64_t tile_vectors) { return (tile_vectors * 16) % RUN_CUT_ALIGN ? 16 : RUN_CUT_ALIGN; }
+
 // Build the copy descriptor of one box for one operation.  resident(rank) tells whether the
 // rank's buffers exist on this GPU (planned rank, or every rank for all-ranks plans); boxes
 // whose operation does not apply get ntiles = 0.
@@ -875,7 +883,15 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         const uint64_t nv_max = (run_bytes + (aligned ? 15 : 30)) / 16;
         const uint64_t vt = tile_bytes / 16;
         if (nv_max > vt) {
-            d.chunks_per_row = (uint32_t)((nv_max + vt - 1) / vt);
+            // chunks are cut at multiples of the tile size counted from the RUN_CUT_ALIGN boundary
+            // at or below the run's first destination byte (see make_tile): room for the bytes
+            // between that boundary and the run, exact when every run starts at the same phase
+            const uint64_t cut = run_cut_align(vt);
+            bool same_phase = true;
+            for (int a = 0; a < 3; ++a)
+                if (d.ext[a] > 1 && ((uint64_t)(d.dstr[a] * (int64_t)d.es) & (cut - 1))) same_phase = false;
+            const uint64_t pre = same_phase ? (d.dst_byte & (cut - 1)) : cut - d.es;
+            d.chunks_per_row = (uint32_t)((pre + run_bytes + vt * 16 - 1) / (vt * 16));
             d.vec_window = (uint32_t)vt;
             d.rows_per_tile = 1;
             d.ntiles = clamp_tiles(rows * d.chunks_per_row);
@@ -1032,9 +1048,9 @@ VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uin
 }
 
 // Tile q of descriptor `di`.  Chunks of a long run become direct tiles: chunk c covers the
-// destination vectors [c*vec_window, (c+1)*vec_window) counted from the 16-byte boundary at or
-// below the run's first destination byte (buffer bases are at least 16-byte aligned; with a
-// less aligned base the tiles are still disjoint and complete, only less evenly cut).
+// destination vectors [c*vec_window, (c+1)*vec_window) counted from the RUN_CUT_ALIGN boundary
+// at or below the run's first destination byte (with a less aligned buffer base the tiles are
+// still disjoint and complete, only less evenly cut).
 VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
 {
     TileRef t;
@@ -1044,7 +1060,7 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         uint64_t so, to;
         run_row_offsets(d, row, so, to);
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-        const uint64_t d0 = d.dst_byte + to, end = d0 + run_bytes, ab = d0 & ~15ull;
+        const uint64_t d0 = d.dst_byte + to, end = d0 + run_bytes, ab = d0 & ~(run_cut_align(d.vec_window) - 1);
         uint64_t lo = ab + 16ull * c * d.vec_window, hi = lo + 16ull * d.vec_window;
         if (lo < d0) lo = d0;
         if (hi > end) hi = end;

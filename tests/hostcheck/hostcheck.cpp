@@ -36,6 +36,7 @@ static bool g_dry_run = false;
 // Tiles seen by the copy step since the last vpsh_tile_histogram call, by kind: count and bytes.
 enum { TK_FULL_RUN = 0, TK_PART_RUN = 1, TK_FEW_RUNS = 2, TK_MANY_RUNS = 3, TK_XPOSE = 4, TK_ELEM = 5, TK_EMPTY = 6, TK_KINDS = 7 };
 static uint64_t g_hist_count[TK_KINDS], g_hist_bytes[TK_KINDS];
+static uint64_t g_unaligned_run_tiles = 0;
 static std::vector<Interval> g_dry_writes;
 
 static bool in_bounds(const void* p, size_t n)
@@ -211,6 +212,7 @@ public:
                 const uint64_t sa = (alias_exchange && tr.alt_src != VPS_TILE_NO_ALT) ? tr.alt_src : tr.src;
                 const uint64_t s0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(sa)) + tile_offset(sa);
                 const uint64_t d0 = (uint64_t)(uintptr_t)slot_ptr(tile_slot(tr.dst)) + tile_offset(tr.dst);
+                if (!(tr.nruns_flags & TILE_XPOSE) && nruns == 1 && (d0 & 255)) ++g_unaligned_run_tiles;
                 if (tr.nruns_flags & TILE_XPOSE) {
                     const uint32_t ta = tr.nbytes & 0xffffu, tb = tr.nbytes >> 16;
                     const uint32_t es = (tr.nruns_flags & TILE_ES2) ? 2 : 4;
@@ -323,6 +325,15 @@ uint64_t vpsh_dry_run_written(uint64_t lo, uint64_t hi, int64_t* overlaps)
     }
     if (overlaps) *overlaps = bad;
     return total;
+}
+
+// Single-run tiles walked since the previous call whose destination does not start on a
+// multiple of 256 bytes (the buffers of the caller are assumed to).  Resets the counter.
+uint64_t vpsh_unaligned_run_tiles(void)
+{
+    const uint64_t n = vps::g_unaligned_run_tiles;
+    vps::g_unaligned_run_tiles = 0;
+    return n;
 }
 
 // Split a linear range of a row-major array: writes (start, axis, count) triples, returns n.

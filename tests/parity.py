@@ -720,6 +720,7 @@ class DryRun:
     def __enter__(self):
         skip = (C.c_uint64 * 7)()
         self.dll.vpsh_tile_histogram(skip, skip)    # reset
+        self.dll.vpsh_unaligned_run_tiles()
         arr = (C.c_void_p * (2 * len(self.ranges)))()
         for i, (lo, hi) in enumerate(self.ranges):
             arr[2 * i], arr[2 * i + 1] = lo, hi
@@ -738,6 +739,8 @@ class DryRun:
         n, by = (C.c_uint64 * 7)(), (C.c_uint64 * 7)()
         self.dll.vpsh_tile_histogram(n, by)
         self.tiles = {k: (int(n[i]), int(by[i])) for i, k in enumerate(self.TILE_KINDS)}   # kind -> (count, bytes)
+        self.dll.vpsh_unaligned_run_tiles.restype = C.c_uint64
+        self.unaligned_run_tiles = int(self.dll.vpsh_unaligned_run_tiles())
         return False
 
 
@@ -767,7 +770,7 @@ def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16, through=False
     assert dry.dst_overlaps == 0 and dry.scratch_overlaps == 0, "a byte is written twice"
     assert dry.dst_written == dst_payload and dry.scratch_written == sent, (dry.dst_written, dst_payload, dry.scratch_written, sent)
     return dict(written=dry.dst_written + dry.scratch_written, dst_payload=dst_payload, sent=sent, stats=plan.stats(), info=info,
-                tiles=dry.tiles)
+                tiles=dry.tiles, unaligned_run_tiles=dry.unaligned_run_tiles)
 
 
 def dry_run_all_ranks(hlib, model, pa, pb, staged_budget=None, box_samples=4):
@@ -810,21 +813,23 @@ def dry_run_all_ranks(hlib, model, pa, pb, staged_budget=None, box_samples=4):
 
 # ----------------------------------------------------------------------------- staged exchange
 
-def memory_aware_chunk(cost, budget):
-    """Algorithm 1, MemoryAwareChunk, written out step by step (steps 1..len(cost)-1), with the
-    two declared readings: steps without traffic are skipped and no empty stage is emitted."""
-    stages, current, current_mem = [], [], 0
-    for s in range(1, len(cost)):
-        if cost[s] == 0:
-            continue
-        if current and current_mem + cost[s] > budget:
-            stages.append(current)
-            current, current_mem = [s], cost[s]
-        else:
-            current.append(s)
-            current_mem += cost[s]
-    if current:
-        stages.append(current)
+def check_stage_assignment(cost, budget, stage_of_step):
+    """Algorithm 1, MemoryAwareChunk, as the properties that define its result (with the two
+    declared readings: steps without traffic belong to no stage, no stage is empty).  The stages
+    are consecutive groups of the busy steps, in step order; a stage fits the budget unless it is
+    a single step; and no stage could have taken the first step of the next one.  These fix the
+    partition.  Returns the stages as lists of steps."""
+    busy = [s for s in range(1, len(cost)) if cost[s] > 0]
+    assert all(stage_of_step[s] == -1 for s in range(1, len(cost)) if cost[s] == 0), "a step without traffic has a stage"
+    ids = [stage_of_step[s] for s in busy]
+    assert all(g >= 0 for g in ids)
+    assert ids == sorted(ids) and (not ids or (ids[0] == 0 and set(ids) == set(range(ids[-1] + 1)))), "stages are not consecutive groups"
+    stages = [[s for s in busy if stage_of_step[s] == g] for g in range(ids[-1] + 1)] if ids else []
+    load = [sum(cost[s] for s in st) for st in stages]
+    for g, st in enumerate(stages):
+        assert load[g] <= budget or len(st) == 1, ("a stage of several steps exceeds the budget", g)
+        if g + 1 < len(stages):
+            assert load[g] + cost[stages[g + 1][0]] > budget, ("a stage was closed although the next step still fitted", g)
     return stages
 
 
@@ -839,7 +844,7 @@ def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
     W = max(a.world, b.world)
     assert info["num_steps"] == (1 << max(W - 1, 0).bit_length()) - 1
 
-    # the schedule against Algorithm 1 written out in Python
+    # the schedule against the properties that define Algorithm 1's stages
     seg = np.zeros((W, W), dtype=np.int64)
     for i in range(a.world):
         rb = None
@@ -850,12 +855,8 @@ def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
     for s in range(1, info["num_steps"] + 1):
         cost[s] = max(int(seg[r, r ^ s] if (r ^ s) < W else 0) + int(seg[r ^ s, r] if (r ^ s) < W else 0) for r in range(W))
     assert cost == [int(c) for c in step_cost]
-    stages = memory_aware_chunk(cost, budget)
+    stages = check_stage_assignment(cost, budget, stage_of_step)
     assert len(stages) == info["num_stages"]
-    for g, steps in enumerate(stages):
-        for s in steps:
-            assert stage_of_step[s] == g
-    assert all(stage_of_step[s] == -1 for s in range(1, len(cost)) if cost[s] == 0)
     # XOR pairing: an involution, and every pair with traffic is met in exactly one step
     for i in range(W):
         for j in range(W):
@@ -896,37 +897,30 @@ def run_staged(lib, mem, model, pa, pb, seed, budget, rank_salt=0x9E37):
 # ----------------------------------------------------------------------------- collective intent
 
 def classify_bruteforce(boxes, shapes):
-    """Algorithm 1 (OptimizePrimitives) over a box list, written with plain sets and lists.
-    Returns {(tensor, kind): code}; codes as in include/vps.h."""
-    NONE, P2P, BROADCAST, SCATTER, GATHER = range(5)
+    """Algorithm 1, OptimizePrimitives, from its definitions over plain index sets: per logical
+    tensor and kind, the slices that leave their rank as sets of positions in the flattened
+    tensor.  Identical = all the same set; a tiling = every slice an interval, the slices disjoint
+    and their union an interval again.  One source and several destinations make a broadcast
+    (identical slices) or a scatter (tiling), several sources and one destination with a tiling a
+    gather, anything else stays point-to-point.  Returns {(tensor, kind): code} as in vps.h."""
+    P2P, BROADCAST, SCATTER, GATHER = 1, 2, 3, 4
     groups = {}
     for bx in boxes:
         if bx["src_rank"] != bx["dst_rank"]:
-            groups.setdefault((int(bx["tensor"]), int(bx["kind"])), []).append(bx)
+            cells = np.ix_(*[np.arange(int(l), int(l) + int(e)) for l, e in zip(bx["lo"], bx["ext"])])
+            where = frozenset(np.ravel_multi_index(cells, shapes[int(bx["tensor"])]).ravel().tolist())
+            g = groups.setdefault((int(bx["tensor"]), int(bx["kind"])), dict(src=set(), dst=set(), slices=[]))
+            g["src"].add(int(bx["src_rank"]))
+            g["dst"].add(int(bx["dst_rank"]))
+            g["slices"].append(where)
+    interval = lambda cells: max(cells) - min(cells) + 1 == len(cells)
     out = {}
-    for (t, kind), bl in groups.items():
-        shape = shapes[t]
-        srcs = {int(b["src_rank"]) for b in bl}
-        dsts = {int(b["dst_rank"]) for b in bl}
-        slices = [(tuple(int(x) for x in b["lo"]), tuple(int(x) for x in b["ext"])) for b in bl]
-        identical = len(set(slices)) == 1
-
-        def as_range(lo, ext):
-            # the set of linear indices of the slice, and whether it is one range
-            idx = np.ravel_multi_index(np.meshgrid(*[np.arange(l, l + e) for l, e in zip(lo, ext)], indexing="ij"), shape).ravel()
-            idx.sort()
-            return int(idx[0]), int(idx[-1]) + 1, bool((np.diff(idx) == 1).all())
-
-        ranges = sorted(as_range(lo, ext) for lo, ext in slices)
-        cont = all(r[2] for r in ranges) and all(ranges[k][1] == ranges[k + 1][0] for k in range(len(ranges) - 1))
-        if len(srcs) == 1 and len(dsts) > 1 and identical:
-            out[(t, kind)] = BROADCAST
-        elif len(srcs) == 1 and len(dsts) > 1 and cont:
-            out[(t, kind)] = SCATTER
-        elif len(srcs) > 1 and len(dsts) == 1 and cont:
-            out[(t, kind)] = GATHER
-        else:
-            out[(t, kind)] = P2P
+    for key, g in groups.items():
+        union = frozenset().union(*g["slices"])
+        identical = len(set(g["slices"])) == 1
+        tiling = all(interval(c) for c in g["slices"]) and sum(len(c) for c in g["slices"]) == len(union) and interval(union)
+        fan_out, fan_in = len(g["src"]) == 1 and len(g["dst"]) > 1, len(g["src"]) > 1 and len(g["dst"]) == 1
+        out[key] = BROADCAST if fan_out and identical else SCATTER if fan_out and tiling else GATHER if fan_in and tiling else P2P
     return out
 
 

@@ -28,7 +28,7 @@ def _release_cached_device_memory():
 
 
 def _run(lib, name, rank=None, src_over=None, dst_over=None, fraction=None, through=False):
-    w = cf.WORKLOADS[name]
+    w = cf.workload(name)
     pa, pb = dict(w["src"]), dict(w["dst"])
     pa.update(src_over or {})
     pb.update(dst_over or {})
@@ -46,6 +46,16 @@ def test_gqa70b_rank11_full_size(lib):
     out = _run(lib, "gqa70b")
     # first-stage rank: the embedding shifts the flat edges, fp32 state really moves
     assert out["info"]["send_total"] > 0 and out["info"]["recv_total"] > 0
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("through", [False, True], ids=["direct", "through-buffers"])
+def test_gqa70b_odd_sizes_full_size(lib, through):
+    """Every tensor starts at an odd element offset: the long runs take the paths for a source
+    that is 2 bytes (bf16: through LDS) or a multiple of 4 bytes (fp32) off the destination's
+    16-byte phase, and are cut at 256-byte boundaries of the destination."""
+    out = _run(lib, "gqa70b-odd", through=through)
+    assert out["info"]["send_total"] > 0
 
 
 @pytest.mark.timeout(600)

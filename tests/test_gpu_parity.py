@@ -202,5 +202,29 @@ def test_plain_copy_reference(lib):
     assert torch.equal(dst[:n], src) and bool((dst[n:] == 0xA5).all())
 
 
+def test_plain_read_and_fill(lib):
+    """The two halves of the plain copy that the benchmark times: the fill writes every byte of
+    its range and nothing else, the read leaves its source and (bar a 2^-32 accident) the sink alone."""
+    import torch
+    stream = torch.cuda.current_stream().cuda_stream
+    n = 8192 * 777 + 4096 + 48
+    dst = torch.zeros(n + 64, dtype=torch.uint8, device="cuda:0")
+    lib.plain_fill(dst.data_ptr() + 32, n, stream)
+    torch.cuda.synchronize()
+    assert bool((dst[32:32 + n] == 0xA5).all()) and not bool(dst[:32].any()) and not bool(dst[32 + n:].any())
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device="cuda:0")
+    keep = src.clone()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    lib.plain_read(src.data_ptr(), n, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep) and not bool(sink.any())
+    from paper_2605_18815_amd.binding import VpsError
+    with pytest.raises(VpsError):
+        lib.plain_fill(dst.data_ptr() + 8, 64, stream)
+    with pytest.raises(VpsError):
+        lib.plain_read(src.data_ptr(), 24, sink.data_ptr(), stream)
+    lib.plain_fill(dst.data_ptr(), 0, stream)   # nothing to do
+
+
 def test_error_codes(lib):
     check_error_codes(lib, parity.GpuMem())
