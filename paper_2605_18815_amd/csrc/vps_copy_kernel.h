@@ -246,7 +246,14 @@ __global__ __launch_bounds__(COPY_THREADS) void k_copy_tiles(const CopyDesc* __r
         if (grp < (gridDim.x >> 3) / xcd_chunk) b = (grp * 8 + x) * xcd_chunk + (j - grp * xcd_chunk);
     }
     __shared__ __attribute__((aligned(16))) uint32_t lds_words[COPY_LDS_WORDS];
-    const TileRef* tp = tiles + (tile0 + b);
+    // the tile record is the same for the whole workgroup and never written while the kernel
+    // runs: read it through the constant address space, i.e. with scalar loads
+    typedef const __attribute__((address_space(4))) TileRef* ctile_t;
+    const ctile_t cp = (ctile_t)(uintptr_t)(tiles + (tile0 + b));
+    TileRef tr;   // the whole record at once
+    tr.src = cp->src; tr.dst = cp->dst; tr.alt_src = cp->alt_src; tr.src_pitch = cp->src_pitch;
+    tr.dst_pitch = cp->dst_pitch; tr.nbytes = cp->nbytes; tr.nruns_flags = cp->nruns_flags;
+    const TileRef* tp = &tr;
     const uint32_t tid = threadIdx.x;
     const uint32_t nf = uniform32(tp->nruns_flags);
     if (!(nf & TILE_INDIRECT)) {
