@@ -11,7 +11,7 @@ for the copy kernel alone the achieved HBM rate against the 8 TB/s peak.
 After the headline the default run also times, with the plan reused, the copy of every other
 workload (`workloads`), the planning of all ranks of the two large transitions (`planning`) and
 a plain copy, a read-only and a write-only kernel in the copy engine's launch shape (inside
-`roofline`); `--headline-only` skips those.
+`roofline`); `--headline-only` skips the first two.
 """
 import argparse
 import gc
@@ -24,6 +24,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+
+
+def kernel_sources_fingerprint():
+    """Hash of the library's sources: a stored counter figure is only reported next to a run of
+    the same kernels."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2605_18815_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def _median(v):
@@ -162,7 +174,7 @@ def main():
     ap.add_argument("--rank", type=int, default=None)
     ap.add_argument("--tile-bytes", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--headline-only", action="store_true", help="skip the other workloads, the planning rates and the memory-system kernels")
+    ap.add_argument("--headline-only", action="store_true", help="skip the other workloads and the planning rates")
     ap.add_argument("--apply-only", action="store_true", help="time only vps_apply_transition (plan reused)")
     ap.add_argument("--only", choices=["pack", "unpack"], default=None,
                     help="time vps_pack or vps_unpack alone (implies --apply-only)")
@@ -281,14 +293,19 @@ def main():
     # this very workload and tile size: a stored figure of profiles/, null for anything else
     traffic, traffic_source = None, None
     prof = os.path.join(ROOT, "profiles", f"k_copy_tiles_{args.workload}_rank{rank}_hbm_traffic.txt")
+    fingerprint = kernel_sources_fingerprint()
     if os.path.exists(prof) and not variant:
-        for line in open(prof):
-            if line.startswith("traffic_bytes_per_launch"):
-                traffic = int(line.split("=")[1])
-                traffic_source = "stored profile figure: profiles/" + os.path.basename(prof)
+        stored = {k.strip(): v.strip() for k, v in (ln.split("=", 1) for ln in open(prof) if "=" in ln and not ln.startswith(" "))}
+        if stored.get("kernel_sources_fingerprint") == fingerprint and "traffic_bytes_per_launch" in stored:
+            traffic = int(stored["traffic_bytes_per_launch"])
+            traffic_source = "stored profile figure: profiles/" + os.path.basename(prof)
+        else:
+            traffic_source = ("none: profiles/" + os.path.basename(prof) + " was measured on other kernel sources (fingerprint "
+                              + stored.get("kernel_sources_fingerprint", "missing") + ", now " + fingerprint + ")")
     achieved = bytes_moved / (apply_avg * 1e-3) / 1e9
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s", frac=achieved / HBM_PEAK_GBPS,
                     traffic=traffic, traffic_source=traffic_source,
+                    kernel_sources_fingerprint=fingerprint,
                     kernel="k_copy_tiles", launches_per_step=launches, kernel_ms_avg=apply_avg,
                     kernel_ms_median=apply_ms[len(apply_ms) // 2], algorithmic_bytes_per_step=bytes_moved)
 

@@ -84,9 +84,9 @@ WORKLOADS = {
 }
 
 
-# Transitions of the paper's evaluation on the published LLaMA-2 shapes: the world-size-changing
-# dense rows of its hybrid reconfiguration table and the pair of its ablation (tuples there are
-# (TP, PP, DP)).  ZeRO-1 on both sides.  Planned at model
+# Transitions of the paper's evaluation on the published model shapes: the world-size-changing
+# dense rows of its hybrid reconfiguration table, the pair of its ablation (tuples there are
+# (TP, PP, DP)) and the table's two MoE pairs.  ZeRO-1 on both sides.  Planned at model
 # scale (routes, dry runs); no state of this size is materialised.
 PAPER_TRANSITIONS = {
     "llama7b-8-to-16": dict(model=model(FAMILY_GQA, 32, 4096, 32, 32, 128, 11008, 32000),
@@ -98,6 +98,16 @@ PAPER_TRANSITIONS = {
                                    src=parallel(tp=2, pp=8, dp=1), dst=parallel(tp=2, pp=2, dp=4)),
     "llama70b-64-to-128": dict(model=model(FAMILY_GQA, 80, 8192, 64, 8, 128, 28672, 32000),
                                src=parallel(tp=4, pp=8, dp=2), dst=parallel(tp=8, pp=16, dp=1)),
+    # the MoE rows of the same table, tuples (TP, PP, DP, EP) with EP carved out of the TP x DP
+    # ranks of a stage (world = TP * PP * DP: 32 and 128 GPUs), on the published Qwen3-MoE shapes.
+    # The 235B model has 4 KV heads; its TP = 8 side would need replicated KV heads, which the
+    # paper does not describe: the stand-in has 8 KV heads (every other size as published).
+    "qwen30b-hybrid": dict(model=model(FAMILY_MOE, 48, 2048, 32, 4, 128, 0, 151936, experts=128, expert_ffn=768),
+                           src=parallel(tp=4, pp=8, dp=1, ep=4, ep_placement=1),
+                           dst=parallel(tp=2, pp=4, dp=4, ep=2, ep_placement=1)),
+    "qwen235b-hybrid": dict(model=model(FAMILY_MOE, 94, 4096, 64, 8, 128, 0, 151936, experts=128, expert_ffn=1536),
+                            src=parallel(tp=4, pp=8, dp=4, ep=16, ep_placement=1),
+                            dst=parallel(tp=8, pp=16, dp=1, ep=8, ep_placement=1)),
 }
 
 

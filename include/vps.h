@@ -26,14 +26,39 @@
  *                   order without gaps and the tail is padded to a multiple of 8*D elements
  *                   (D = data-parallel group size).  Kind 0 holds the whole padded buffer;
  *                   kinds 1..3 hold the rank's 1/D range when zero_stage = 1.
- *   ranks           rank = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp, DDP = EP*DP.
+ *   ranks           ep_placement 0: rank = tp + TP*(ddp + DDP*pp), ddp = ep + EP*edp, DDP = EP*DP.
+ *                   ep_placement 1: rank = tp + TP*(dp + DP*pp) for dense tensors; for expert
+ *                   tensors the position q = tp + TP*dp inside the stage gives ep = q mod EP and
+ *                   the expert data-parallel index q div EP (see vps_parallel_desc).
  *   limits          at most 32768 ranks per configuration and 2^24 logical tensors; fewer than
  *                   2^31 pieces, boxes and tiles per table (VPS_ERR_OOM beyond); an all-ranks
  *                   plan keeps a src x dst byte matrix and is refused above 2^26 rank pairs;
  *                   tensor axes are 31-bit, offsets and strides 64-bit.
  *   return values   0 on success, a negative vps_status otherwise; vps_last_error() returns
- *                   a thread-local message.  Functions never throw and never synchronise the
- *                   stream, except where stated.  On error no device work has been enqueued.
+ *                   a thread-local message.  Functions never throw.  On error no device work
+ *                   has been enqueued.
+ *   synchronisation which calls wait for the device, and how often:
+ *                   vps_describe_config          never (two kernels on the null stream)
+ *                   vps_plan_intersections[_ex]  once, for the counts and byte totals the host
+ *                                                needs; twice when the tile table has to be
+ *                                                built after that wait (the first plan of a
+ *                                                (model, configurations, rank, flags, tile size)
+ *                                                combination in the process; later plans of the
+ *                                                same combination size the table from the first
+ *                                                one's counts) and for plans above
+ *                                                VPS_OPT_SMALL_PLAN_BOXES boxes
+ *                   vps_pack, vps_unpack, vps_apply_transition[_static|_staged], vps_plain_*
+ *                                                never
+ *                   vps_stage_exchange, vps_plan_classify_collectives
+ *                                                their stream, once or twice
+ *                   vps_plan_get_boxes, vps_plan_peer_segment, vps_config_buffer_bytes,
+ *                   vps_config_num_pieces, vps_config_get_pieces
+ *                                                once, on first use (they fetch or build
+ *                                                tables that planning itself does not need)
+ *                   other queries                never
+ *                   vps_plan_destroy, vps_stage_plan_destroy
+ *                                                the streams the plan was used on (its tables
+ *                                                go back to the pool)
  */
 #ifndef VPS_H
 #define VPS_H
@@ -123,7 +148,8 @@ typedef struct vps_plan_stats_t {
 /* F_P (Section 4.1, Section 4.2.2): map configuration `par` of `model` onto the VPS.
  * rank = -1 maps every rank (needed for planning); rank >= 0 keeps only that rank's pieces.
  * Both descriptors are caller-owned host structs, copied on entry.  *out is library-owned;
- * release with vps_config_destroy.  Synchronises the device internally.
+ * release with vps_config_destroy.  The tables are filled by two kernels queued on the null
+ * stream; the call does not wait for them (planning orders itself after them).
  * Errors: VPS_ERR_INVALID_ARG (null pointers, non-positive sizes), VPS_ERR_INDIVISIBLE,
  * VPS_ERR_RANK_RANGE, VPS_ERR_HIP. */
 int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
@@ -135,8 +161,8 @@ int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* pa
  * < max(world_src, world_dst)); rank = -1 plans all ranks (all virtual ranks resident).
  * Source rule for replicated data: the destination rank itself if it is an owner, else the
  * owners on its node if any, else all owners; ascending; index = destination data-parallel
- * index modulo count.  `stream` (hipStream_t) orders the device work; the call synchronises it
- * before returning.  Both configs must have been described with rank = -1 for the same model
+ * index modulo count.  `stream` (hipStream_t) orders the device work; the call waits for it
+ * once or twice before returning (see "synchronisation" above).  Both configs must have been described with rank = -1 for the same model
  * (VPS_ERR_MODEL_MISMATCH otherwise).  *out is library-owned (vps_plan_destroy). */
 int vps_plan_intersections(const vps_config* src, const vps_config* dst, int32_t rank,
                            void* stream, vps_plan** out);

@@ -47,9 +47,12 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v)
     return ((uint64_t)hi << 32) | lo;
 }
 
+// The pointer table of an all-ranks plan is written before the launch and only read by it: it
+// is read through the constant address space (scalar loads; `slot` is the same for a workgroup).
 __device__ __forceinline__ uint64_t slot_addr(const PtrArgs& pa, int32_t slot)
 {
-    return (uint64_t)(uintptr_t)(pa.tbl ? pa.tbl[slot] : pa.inl[slot]);
+    typedef const __attribute__((address_space(4))) uint64_t* ctable_t;
+    return pa.tbl ? ((ctable_t)(uintptr_t)pa.tbl)[slot] : (uint64_t)(uintptr_t)pa.inl[slot];
 }
 
 typedef const VPS_GLOBAL u32x4* gsrc16a_t;   // source vectors at 16-byte alignment

@@ -414,8 +414,9 @@ def test_all_ranks_full_size_dry_run(hlib, name, budget):
 @pytest.mark.parametrize("reverse", [False, True], ids=["forward", "back"])
 def test_paper_table_transitions_at_model_scale(hlib, name, reverse):
     """The world-size-changing (TP, PP, DP) transitions of the paper's hybrid reconfiguration table
-    (dense rows) and the pair of its ablation study, both directions, on the full model shapes: routes of every rank
-    validated by the oracle, and the copy tables of the last rank walked in a dry run."""
+    (dense rows), the pair of its ablation study and the table's two MoE pairs (EP carved out of
+    the TP x DP ranks), both directions, on the full model shapes: routes of every rank validated
+    by the oracle, and the copy tables of the last rank walked in a dry run."""
     import oracle
     from paper_2605_18815_amd import binding as B
     w = cf.PAPER_TRANSITIONS[name]
