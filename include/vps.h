@@ -317,11 +317,17 @@ const char* vps_last_error(void);
  *   VPS_OPT_TILE_BYTES        target payload bytes per workgroup tile: a power of two between
  *                             4 KiB and 1 MiB, default 8 KiB (vps_set_tile_bytes sets the same)
  *   VPS_OPT_SMALL_PLAN_BOXES  plans with at most this many boxes (1 .. 65536, default 8192) are
- *                             ordered by counting in one launch; larger ones by a radix sort
+ *                             ordered by counting in one launch; larger ones pair by pair or by
+ *                             a radix sort (see VPS_OPT_PAIR_ORDER_WORK)
  *   VPS_OPT_XPOSE_SHAPE       super-block shape of transposed boxes, sa | sb << 16 (1 .. 64 each);
  *                             0 = chosen per box from the row pitches (default)
- *   VPS_OPT_XCD_RUN           consecutive tiles handed to one XCD (0 = round-robin, default 64) */
-enum { VPS_OPT_TILE_BYTES = 0, VPS_OPT_SMALL_PLAN_BOXES = 1, VPS_OPT_XPOSE_SHAPE = 2, VPS_OPT_XCD_RUN = 3 };
+ *   VPS_OPT_XCD_RUN           consecutive tiles handed to one XCD (0 = round-robin, default 64)
+ *   VPS_OPT_PAIR_ORDER_WORK   larger all-ranks plans are ordered pair by pair (source rank x
+ *                             destination rank) by counting as long as the sum over the pairs of
+ *                             the squared number of their boxes stays below 2^value (default 32,
+ *                             at most 40), and by a radix sort otherwise; 0 = always the sort */
+enum { VPS_OPT_TILE_BYTES = 0, VPS_OPT_SMALL_PLAN_BOXES = 1, VPS_OPT_XPOSE_SHAPE = 2, VPS_OPT_XCD_RUN = 3,
+       VPS_OPT_PAIR_ORDER_WORK = 4 };
 int vps_set_option(int32_t option, uint32_t value);
 int vps_set_tile_bytes(uint32_t bytes);
 

@@ -16,7 +16,7 @@ ERR_INVALID_ARG, ERR_INDIVISIBLE, ERR_RANK_RANGE, ERR_MODEL_MISMATCH = -1, -2, -
 ERR_SCRATCH_TOO_SMALL, ERR_OOM, ERR_HIP = -5, -6, -7
 NUM_BUFFERS = 8
 NO_POS = (1 << 64) - 1
-OPT_TILE_BYTES, OPT_SMALL_PLAN_BOXES, OPT_XPOSE_SHAPE, OPT_XCD_RUN = range(4)
+OPT_TILE_BYTES, OPT_SMALL_PLAN_BOXES, OPT_XPOSE_SHAPE, OPT_XCD_RUN, OPT_PAIR_ORDER_WORK = range(5)
 PLAN_ROUTES_ONLY = 1
 PLAN_THROUGH_BUFFERS = 2
 COLL_NONE, COLL_P2P, COLL_BROADCAST, COLL_SCATTER, COLL_GATHER = range(5)

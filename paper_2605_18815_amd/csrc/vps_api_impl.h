@@ -23,6 +23,7 @@ static thread_local std::string g_last_error;
 // them once, when it is made.
 static std::atomic<uint32_t> g_tile_bytes{ 8u << 10 };
 static std::atomic<uint32_t> g_small_plan_boxes{ 8192u };   // boxes ordered by counting, without a sort
+static std::atomic<uint32_t> g_pair_work_log2{ (uint32_t)PAIR_BUCKET_WORK_LOG2 };   // 0: all-ranks plans are always sorted
 static std::atomic<uint32_t> g_xpose_shape{ 0u };           // 0 = chosen per box from the pitches
 
 // Number of tiles and boxes of the plans made so far, by what determines them (model, both
@@ -154,6 +155,11 @@ int VPS_FN(set_option)(int32_t option, uint32_t value)
         vps::g_xpose_shape = value;
         return VPS_OK;
     }
+    if (option == VPS_OPT_PAIR_ORDER_WORK) {
+        if (value > 40) return vps::fail(VPS_ERR_INVALID_ARG, "log2 of the pair-ordering work bound must be at most 40");
+        vps::g_pair_work_log2 = value;
+        return VPS_OK;
+    }
     if (option == VPS_OPT_XCD_RUN) {
         if (value > 4096) return vps::fail(VPS_ERR_INVALID_ARG, "XCD run length must be at most 4096 tiles");
         VPS_BACKEND::set_xcd_chunk(value);
@@ -256,7 +262,7 @@ int VPS_FN(plan_intersections_ex)(const vps_config* src, const vps_config* dst, 
         vps::build_plan(be, src->d, dst->d, rank, tile_bytes, xpose_shape,
                         vps::g_small_plan_boxes.load(), (flags & VPS_PLAN_ROUTES_ONLY) != 0,
                         (flags & VPS_PLAN_THROUGH_BUFFERS) != 0, vps::g_tile_hints.get(hk).tiles,
-                        vps::g_tile_hints.get(hk).boxes, p->d);
+                        vps::g_tile_hints.get(hk).boxes, p->d, true, (int)vps::g_pair_work_log2.load());
         const vps_plan_stats_t& st = p->d.stats;
         vps::g_tile_hints.put(hk, { st.num_retain_tiles + st.num_pack_tiles + st.num_unpack_tiles, st.num_boxes });
     } catch (...) {

@@ -161,39 +161,95 @@ __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
 }
 
 // The same in two launches, for item grids of millions of lanes of which few have work: the
-// first writes the indices of the lanes that pass the cheap tests into a list (same ballot
-// allocation), the second walks the list with every lane busy.
-__global__ __launch_bounds__(256) void k_plan_filter(PlanCtx pc, int mode, int64_t lanes, uint64_t* __restrict__ list,
-                                                     uint64_t cap, unsigned long long* count)
-{
-    // Every wavefront collects the lanes that pass in LDS and moves them to the list 64 at a
-    // time: one atomic on the list's counter per 64 entries (an atomic per ballot would serialise
-    // hundreds of thousands of updates of one address).
-    __shared__ uint64_t staged[4][128];
-    const unsigned wave = threadIdx.x >> 6, lid = threadIdx.x & 63u;
-    uint32_t held = 0;   // entries of staged[wave], the same in every lane
-    auto flush = [&](uint32_t m) {   // move the first m (<= 64) staged entries to the list
-        unsigned long long base = 0;
-        if (lid == 0) base = atomicAdd(count, (unsigned long long)m);
-        const unsigned lo = (unsigned)__shfl((int)(unsigned)base, 0, 64), hi = (unsigned)__shfl((int)(unsigned)(base >> 32), 0, 64);
-        const uint64_t k = (((uint64_t)hi << 32) | lo) + lid;
-        if (lid < m && k < cap) list[k] = staged[wave][lid];
-    };
-    for (int64_t first = (int64_t)blockIdx.x * 256; first < lanes; first += (int64_t)gridDim.x * 256) {
-        const int64_t lane = first + threadIdx.x;
-        LaneItem it;
-        const bool pass = lane < lanes && plan_lane_decode(pc, mode, lane, it);
+// first writes the indices of the lanes that pass the cheap tests into a list, the second walks
+// the list with every lane busy.
+//
+// Appending to the list: every wavefront collects its entries in LDS and moves them to the list 64
+// at a time; what is left at the end goes out with one reservation for the whole workgroup.  The
+// list's counter is one address, and atomics on one address are served one after the other (a
+// few ns each): an atomic per ballot, or per wavefront at the end of tens of thousands of
+// wavefronts, would take longer than the tests themselves.
+struct LaneListAppender {
+    uint64_t (*staged)[128];
+    uint32_t* left;               // [4] entries the wavefronts hold at the end
+    unsigned long long* wg_base;
+    uint64_t* list;
+    uint64_t cap;
+    unsigned long long* count;
+    uint32_t held = 0;            // entries of staged[wave], the same in every lane
+
+    __device__ void add(bool pass, uint64_t value)
+    {
+        const unsigned wave = threadIdx.x >> 6, lid = threadIdx.x & 63u;
         const uint64_t mask = __ballot(pass ? 1 : 0);
-        if (pass) staged[wave][held + (uint32_t)__popcll(mask & ((1ull << lid) - 1ull))] = (uint64_t)lane;
+        if (pass) staged[wave][held + (uint32_t)__popcll(mask & ((1ull << lid) - 1ull))] = value;
         held += (uint32_t)__popcll(mask);
         if (held >= 64) {
-            flush(64);
+            unsigned long long base = 0;
+            if (lid == 0) base = atomicAdd(count, 64ull);
+            const unsigned lo = (unsigned)__shfl((int)(unsigned)base, 0, 64), hi = (unsigned)__shfl((int)(unsigned)(base >> 32), 0, 64);
+            const uint64_t k = (((uint64_t)hi << 32) | lo) + lid;
+            if (k < cap) list[k] = staged[wave][lid];
             const uint64_t moved = lid < held - 64 ? staged[wave][64 + lid] : 0;
             if (lid < held - 64) staged[wave][lid] = moved;
             held -= 64;
         }
     }
-    if (held) flush(held);
+    // every lane of the workgroup calls this once, after its last add
+    __device__ void finish()
+    {
+        const unsigned wave = threadIdx.x >> 6, lid = threadIdx.x & 63u;
+        if (lid == 0) left[wave] = held;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t total = left[0] + left[1] + left[2] + left[3];
+            *wg_base = total ? atomicAdd(count, (unsigned long long)total) : 0ull;
+        }
+        __syncthreads();
+        uint64_t k = *wg_base + lid;
+        for (unsigned w = 0; w < wave; ++w) k += left[w];
+        if (lid < held && k < cap) list[k] = staged[wave][lid];
+    }
+};
+
+#define VPS_LANE_LIST_APPENDER(name, list, cap, count)         \
+    __shared__ uint64_t name##_staged[4][128];                   \
+    __shared__ uint32_t name##_left[4];                          \
+    __shared__ unsigned long long name##_base;                   \
+    LaneListAppender name;                                       \
+    name.staged = name##_staged; name.left = name##_left; name.wg_base = &name##_base; \
+    name.list = list; name.cap = cap; name.count = count
+
+__global__ __launch_bounds__(256) void k_plan_filter(PlanCtx pc, int mode, int64_t lanes, uint64_t* __restrict__ list,
+                                                     uint64_t cap, unsigned long long* count)
+{
+    VPS_LANE_LIST_APPENDER(app, list, cap, count);
+    for (int64_t first = (int64_t)blockIdx.x * 256; first < lanes; first += (int64_t)gridDim.x * 256) {
+        const int64_t lane = first + threadIdx.x;
+        LaneItem it;
+        app.add(lane < lanes && plan_lane_decode(pc, mode, lane, it), (uint64_t)lane);
+    }
+    app.finish();
+}
+
+// The filter for all-ranks plans.  A lane index there has power-of-two fields sized for the
+// largest group, and a tensor with few destination items and source slots (an expert held by two
+// ranks on each side, beside dense state sharded 32 ways) would leave nearly all of its lanes
+// idle.  Here the dense tensors and the expert tensors have lane ranges of their own, with
+// fields sized for their group (PlanGroupLanes); the entries of the list are the same lane
+// indices as k_plan_filter's.
+__global__ __launch_bounds__(256) void k_plan_filter_groups(PlanCtx pc, PlanGroupLanes gl, uint64_t* __restrict__ list,
+                                                            uint64_t cap, unsigned long long* count)
+{
+    VPS_LANE_LIST_APPENDER(app, list, cap, count);
+    const int64_t lanes = gl.lanes[0] + gl.lanes[1];
+    for (int64_t first = (int64_t)blockIdx.x * 256; first < lanes; first += (int64_t)gridDim.x * 256) {
+        const int64_t gl_lane = first + threadIdx.x;
+        int64_t lane = 0;
+        const bool pass = gl_lane < lanes && plan_group_lane_check(pc, gl, gl_lane, lane);
+        app.add(pass, (uint64_t)lane);
+    }
+    app.finish();
 }
 
 __global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, int through, const uint64_t* __restrict__ list,
@@ -248,6 +304,40 @@ __global__ __launch_bounds__(256) void k_order_by_counting(const OrderRec* __res
         o.base_r += shfl_xor_u64(o.base_r, d);
     }
     if (k < n) f(k, o, part);
+}
+
+// Rank of every record inside its pair's bucket (pair-by-pair ordering of large all-ranks plans):
+// the number of records of the bucket that come before it and the buffer bytes of the travelling
+// ones among them.  A group of 16 lanes shares one record and walks the bucket 16 records at a
+// time; f(j, before, bytes) continues on the group's first lane.  When *work exceeds work_max the
+// walk is skipped and a record keeps its place in the bucket (the caller plans again).
+template <class Step, class F>
+__global__ __launch_bounds__(256) void k_pair_rank(const PairRec* __restrict__ bucket, const uint64_t* __restrict__ pstart,
+                                                   const uint64_t* __restrict__ pcount, int64_t n, const uint64_t* work,
+                                                   uint64_t work_max, F f)
+{
+    const unsigned part = threadIdx.x % ORDER_GROUP;
+    const int64_t j = (int64_t)blockIdx.x * (256 / ORDER_GROUP) + threadIdx.x / ORDER_GROUP;
+    if (j >= n) return;   // whole groups leave together
+    const PairRec me = bucket[j];
+    const uint64_t pr = me.key >> 26, lo = pstart[pr], cnt = pcount[pr];
+    uint32_t before = (uint32_t)((uint64_t)j - lo);
+    uint64_t bytes = 0;
+    if (*work <= work_max) {
+        before = 0;
+        for (uint64_t q = lo + part; q < lo + cnt; q += ORDER_GROUP) {
+            const PairRec o = bucket[q];
+            const bool less = pair_rec_less(o, me);
+            before += less ? 1u : 0u;
+            bytes += (less && (o.bytes_flags & ORD_SENDS)) ? (o.bytes_flags & ~(uint64_t)15) : 0;
+        }
+#pragma unroll
+        for (int d = ORDER_GROUP / 2; d >= 1; d >>= 1) {
+            before += (uint32_t)__shfl_xor((int)before, d, 64);
+            bytes += shfl_xor_u64(bytes, d);
+        }
+    }
+    if (part == 0) f(j, (uint64_t)before, bytes);
 }
 
 // ---- exclusive prefix sum of n int64 values: out[i] = in[0] + ... + in[i-1] ----
@@ -515,6 +605,18 @@ public:
         VPS_HIP_CHECK(hipGetLastError());
     }
 
+    // f(j, before, bytes) for every record j of the pair buckets: see k_pair_rank.
+    template <class Step, class F>
+    void pair_rank_each(Step, const PairRec* bucket, const uint64_t* pstart, const uint64_t* pcount, int64_t n,
+                        const uint64_t* work, uint64_t work_max, F f)
+    {
+        if (n <= 0) return;
+        const int64_t per = 256 / ORDER_GROUP;
+        hipLaunchKernelGGL((k_pair_rank<Step, F>), dim3((unsigned)((n + per - 1) / per)), dim3(256), 0, stream_, bucket, pstart,
+                           pcount, n, work, work_max, f);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
     void layout_classes(const ParConst& P, const TensorRec* T, TensorLayout* TL, ClassRec* C)
     {
         hipLaunchKernelGGL(k_layout_classes, dim3((unsigned)P.ncls), dim3(256), 0, stream_, P, T, TL, C);
@@ -526,6 +628,7 @@ public:
     // nothing was emitted: the caller then calls again with two_launches = false.
     static constexpr uint64_t PLAN_LIST_CAP = 1ull << 22;
     static constexpr int64_t PLAN_LIST_FROM = 1ll << 17;   // item grids from this many lanes on use the list
+    static constexpr int64_t PLAN_LIST_FROM_ALL = 1ll << 13;   // the same for all-ranks plans
 
     bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
                    uint64_t* listed, bool two_launches)
@@ -534,10 +637,19 @@ public:
         if (lanes <= 0) return false;
         int64_t blocks = (lanes + 255) / 256;
         if (blocks > 8192) blocks = 8192;   // the kernels stride over the lanes
-        if (two_launches && lanes >= PLAN_LIST_FROM) {
+        if (two_launches && lanes >= (mode == PLAN_ALL ? PLAN_LIST_FROM_ALL : PLAN_LIST_FROM)) {
             uint64_t* list = alloc<uint64_t>((int64_t)PLAN_LIST_CAP);
-            hipLaunchKernelGGL(k_plan_filter, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, lanes, list,
-                               PLAN_LIST_CAP, (unsigned long long*)listed);
+            if (mode == PLAN_ALL) {
+                const PlanGroupLanes gl = plan_group_lanes(pc);
+                int64_t fb = (gl.lanes[0] + gl.lanes[1] + 255) / 256;
+                if (fb > 2048) fb = 2048;   // the kernel strides over the lanes; few workgroups, few reservations
+                if (fb < 1) fb = 1;
+                hipLaunchKernelGGL(k_plan_filter_groups, dim3((unsigned)fb), dim3(256), 0, stream_, pc, gl, list,
+                                   PLAN_LIST_CAP, (unsigned long long*)listed);
+            } else {
+                hipLaunchKernelGGL(k_plan_filter, dim3((unsigned)(blocks > 2048 ? 2048 : blocks)), dim3(256), 0, stream_, pc, mode, lanes,
+                                   list, PLAN_LIST_CAP, (unsigned long long*)listed);
+            }
             hipLaunchKernelGGL(k_plan_emit_listed, dim3(2048), dim3(256), 0, stream_, pc, mode, through ? 1 : 0,
                                (const uint64_t*)list, PLAN_LIST_CAP, (const unsigned long long*)listed, raw, recs, cap,
                                (unsigned long long*)counter);

@@ -21,6 +21,14 @@
 #define VPS_HD inline
 #endif
 
+// unroll hint for loops whose loads are independent (n iterations' loads in flight together)
+#define VPS_PRAGMA(x) _Pragma(#x)
+#if defined(__clang__)
+#define VPS_UNROLL(n) VPS_PRAGMA(unroll n)
+#else
+#define VPS_UNROLL(n) VPS_PRAGMA(GCC unroll n)
+#endif
+
 namespace vps {
 
 enum { PERM_NONE = 0, PERM_GATE_UP = 1, PERM_DOWN = 2 };
@@ -49,6 +57,7 @@ struct ParConst {
     int32_t nt;       // logical tensors
     int32_t ncls;     // flat-buffer classes: pp dense + pp*ep expert
     int32_t per_layer; // logical tensors per layer (ids 1 + l*per_layer .. of layer l)
+    int32_t expert_pl; // of which the last expert_pl belong to experts (group 1); 0 without experts
 };
 
 // Where a tensor's local shard sits in the flat buffer of the ranks that hold it.
@@ -442,6 +451,45 @@ struct LaneItem {
     int32_t t, kind, tpb, db, dst_rank, tp_rep, d_rep;
 };
 
+// The tensors of one group in ascending id order.  The inventory is the embedding, then per layer
+// per_layer tensors of which the last expert_pl are the experts', then the closing tensors.
+VPS_HD int32_t group_tensor_count(const ParConst& P, int group)
+{
+    const int32_t ne = P.layers * P.expert_pl;
+    return group ? ne : P.nt - ne;
+}
+VPS_HD int32_t group_tensor_id(const ParConst& P, int group, int32_t i)
+{
+    const int32_t dpl = P.per_layer - P.expert_pl;
+    if (group) { const int32_t layer = i / P.expert_pl; return 1 + layer * P.per_layer + dpl + (i - layer * P.expert_pl); }
+    if (i == 0) return 0;
+    const int32_t body = P.layers * dpl;
+    if (i > body) return 1 + P.layers * P.per_layer + (i - 1 - body);
+    const int32_t layer = (i - 1) / dpl;
+    return 1 + layer * P.per_layer + (i - 1 - layer * dpl);
+}
+
+// PLAN_ALL with lane ranges per group: group g has count[g] tensors x 4 kinds x 2^item_bits[g]
+// destination items x 2^slot_bits[g] source slots, the fields sized for the group's own degrees.
+struct PlanGroupLanes {
+    int64_t lanes[2];
+    int32_t item_bits[2], slot_bits[2];
+};
+VPS_HD PlanGroupLanes plan_group_lanes(const PlanCtx& c)
+{
+    PlanGroupLanes g;
+    for (int q = 0; q < 2; ++q) {
+        g.item_bits[q] = g.slot_bits[q] = 0;
+        while ((1 << g.item_bits[q]) < group_tp(c.B, q) * group_dp(c.B, q)) ++g.item_bits[q];
+        while ((1 << g.slot_bits[q]) < group_tp(c.A, q) * group_dp(c.A, q)) ++g.slot_bits[q];
+        g.lanes[q] = ((int64_t)group_tensor_count(c.A, q) * 4) << (g.item_bits[q] + g.slot_bits[q]);
+    }
+    return g;
+}
+
+VPS_HD bool plan_pair_check(const PlanCtx& c, int mode, const TensorRec& x, int32_t t, int32_t kind, int32_t tpb,
+                            int32_t db, int32_t u, LaneItem& it);
+
 // The item of a lane, or false when the lane has nothing to do: an index beyond the item grid, a
 // tensor that the rank does not hold, a destination item and a slot that share no data.  Cheap:
 // no division by a run-time 64-bit value, no pieces, no source selection.
@@ -473,7 +521,16 @@ VPS_HD bool plan_lane_decode(const PlanCtx& c, int mode, int64_t lane, LaneItem&
         t += c.send_lo;
         u = 0;
     }
-    const TensorRec x = c.ma.T[t];
+    return plan_pair_check(c, mode, c.ma.T[t], t, kind, tpb, db, u, it);
+}
+
+// The second half of plan_lane_decode, from the tensor's record on (mode: PLAN_ALL, PLAN_RECV or
+// PLAN_SEND).
+VPS_HD bool plan_pair_check(const PlanCtx& c, int mode, const TensorRec& x, int32_t t, int32_t kind, int32_t tpb,
+                            int32_t db, int32_t u, LaneItem& it)
+{
+    const ParConst& A = c.A;
+    const ParConst& B = c.B;
     if (mode == PLAN_RECV) {
         if (c.rank >= B.world) return false;
         const RankCoord cr = decode_rank(B, c.rank);
@@ -504,6 +561,24 @@ VPS_HD bool plan_lane_decode(const PlanCtx& c, int mode, int64_t lane, LaneItem&
     }
     it.x = x; it.t = t; it.kind = kind; it.tpb = tpb; it.db = db; it.dst_rank = dst_rank;
     it.tp_rep = tp_rep; it.d_rep = d_rep;
+    return true;
+}
+
+// Lane gl_lane of the per-group ranges: false when it has nothing to do, else `lane` is its index
+// in the PLAN_ALL numbering.
+VPS_HD bool plan_group_lane_check(const PlanCtx& c, const PlanGroupLanes& g, int64_t gl_lane, int64_t& lane)
+{
+    const int q = gl_lane < g.lanes[0] ? 0 : 1;
+    if (q) gl_lane -= g.lanes[0];
+    const int32_t u = (int32_t)(gl_lane & ((1 << g.slot_bits[q]) - 1));
+    const int32_t ib = (int32_t)((gl_lane >> g.slot_bits[q]) & ((1 << g.item_bits[q]) - 1));
+    const int32_t tk = (int32_t)(gl_lane >> (g.slot_bits[q] + g.item_bits[q]));
+    const int32_t kind = tk & 3, t = group_tensor_id(c.A, q, tk >> 2);
+    const int32_t gd = group_dp(c.B, q), tpb = ib / gd, db = ib - tpb * gd;
+    if (tpb >= group_tp(c.B, q)) return false;
+    LaneItem it;
+    if (!plan_pair_check(c, PLAN_ALL, c.ma.T[t], t, kind, tpb, db, u, it)) return false;
+    lane = ((((int64_t)t * 4 + kind) << c.item_bits | (int64_t)(tpb * c.B.dmax + db)) << c.slot_bits) | u;
     return true;
 }
 
@@ -673,7 +748,21 @@ VPS_HD OrderPlace order_by_counting(const OrderRec* recs, uint32_t n, uint32_t k
 }
 
 // Words at the head of a plan's summary block.
-enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_NLISTED = 4, SUM_HEADER = 8 };
+enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_NLISTED = 4, SUM_PAIR_WORK = 5, SUM_HEADER = 8 };
+
+// All-ranks plans with many boxes are ordered pair by pair: both orders keep the boxes of one
+// (source, destination) pair together and order them alike inside, by (kind order, tensor, lo
+// corner).  What the passes need of a box, in the pair's bucket:
+struct PairRec {
+    uint64_t key;          // pair index << 26 | kind order << 24 | tensor
+    uint64_t klo;          // lo corner, linearised
+    uint64_t bytes_flags;  // as in OrderRec
+    uint64_t box;          // index in the raw table
+};
+VPS_HD uint64_t pair_rec_key(const OrderRec& r, int64_t pair) { return ((uint64_t)pair << 26) | (r.key_s & 0x3ffffffull); }
+VPS_HD bool pair_rec_less(const PairRec& a, const PairRec& b) { return a.key < b.key || (a.key == b.key && a.klo < b.klo); }
+constexpr int64_t PAIR_BUCKET_MAX_PAIRS = (int64_t)1 << 20;     // source ranks x destination ranks
+constexpr int PAIR_BUCKET_WORK_LOG2 = 32;                      // bound (log2) on the sum over the pairs of (boxes of the pair)^2
 
 // Accumulate into a counter shared by all items of a step.
 VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
@@ -682,6 +771,49 @@ VPS_HD void be_atomic_add(uint64_t* p, uint64_t v)
     atomicAdd((unsigned long long*)p, (unsigned long long)v);
 #else
     *p += v;
+#endif
+}
+
+// The same, returning the value before the addition.
+VPS_HD uint64_t be_atomic_fetch_add(uint64_t* p, uint64_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint64_t)atomicAdd((unsigned long long*)p, (unsigned long long)v);
+#else
+    const uint64_t old = *p;
+    *p += v;
+    return old;
+#endif
+}
+
+// base[index] += v where neighbouring items often share the index (boxes in send order share their
+// (source, destination) pair): on the device the lanes of a wavefront first add up over runs of
+// consecutive lanes with the same index (a segmented scan over the wavefront), and the last lane
+// of every run does one atomic.  Same-address atomics are served one after the other, so this is
+// what keeps a pass over 10^5 boxes from waiting on a few hundred hot addresses.
+VPS_HD void be_atomic_add_runs(uint64_t* base, int64_t index, uint64_t v)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const unsigned lane = threadIdx.x & 63u;
+    const uint64_t active = __ballot(1);
+    const int ilo = (int)(uint32_t)index, ihi = (int)(uint32_t)((uint64_t)index >> 32);
+    const bool prev_same = __shfl_up(ilo, 1, 64) == ilo && __shfl_up(ihi, 1, 64) == ihi;
+    const bool next_same = __shfl_down(ilo, 1, 64) == ilo && __shfl_down(ihi, 1, 64) == ihi;
+    int head = (lane == 0 || !((active >> (lane - 1)) & 1ull) || !prev_same) ? 1 : 0;
+    uint32_t slo = (uint32_t)v, shi = (uint32_t)(v >> 32);
+    for (unsigned d = 1; d < 64; d <<= 1) {
+        const uint32_t ulo = (uint32_t)__shfl_up((int)slo, d, 64), uhi = (uint32_t)__shfl_up((int)shi, d, 64);
+        const int uhead = __shfl_up(head, d, 64);
+        if (lane >= d && !head) {   // (then every lane down to lane - d is active and of this run)
+            const uint64_t sum = (((uint64_t)shi << 32) | slo) + (((uint64_t)uhi << 32) | ulo);
+            slo = (uint32_t)sum; shi = (uint32_t)(sum >> 32);
+            head = uhead;
+        }
+    }
+    const bool tail = lane == 63 || !((active >> (lane + 1)) & 1ull) || !next_same;
+    if (tail) atomicAdd((unsigned long long*)(base + index), (unsigned long long)(((uint64_t)shi << 32) | slo));
+#else
+    base[index] += v;
 #endif
 }
 
@@ -1123,7 +1255,7 @@ struct FinishCtx {
 VPS_HD void account_box(const FinishCtx& c, const vps_box& b)
 {
     const uint64_t bytes = box_volume(b) * kind_bytes(b.kind);
-    if (c.rank < 0) be_atomic_add(&c.pairs[(int64_t)b.src_rank * c.wb + b.dst_rank], bytes);
+    if (c.rank < 0) be_atomic_add_runs(c.pairs, (int64_t)b.src_rank * c.wb + b.dst_rank, bytes);
     else {
         if (b.dst_rank == c.rank) be_atomic_add(&c.pairs[b.src_rank], bytes);
         if (b.src_rank == c.rank) be_atomic_add(&c.pairs[c.wa + b.dst_rank], bytes);

@@ -82,6 +82,7 @@ inline ParConst make_par_const(const vps_model_desc& m, const vps_parallel_desc&
     P.nt = nt;
     P.ncls = p.pp + p.pp * p.ep;
     P.per_layer = make_model_const(m).per_layer;
+    P.expert_pl = m.family == VPS_FAMILY_MOE ? 2 * m.experts : 0;
     return P;
 }
 

@@ -45,6 +45,12 @@ struct plan_positions {};
 struct plan_sorted_boxes {};
 struct plan_recv_perm {};
 struct plan_pair_bytes {};
+struct plan_pair_counts {};
+struct plan_pair_sums {};
+struct plan_pair_starts {};
+struct plan_pair_scatter {};
+struct plan_pair_rank {};
+struct plan_pair_place {};
 struct plan_copy_descs {};
 struct plan_rank_tables {};
 struct plan_tile_table {};
@@ -225,7 +231,8 @@ struct SummaryLayout {
 template <class BE>
 void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank,
                 uint32_t tile_bytes, uint32_t xpose_shape, uint32_t small_limit, bool routes_only,
-                bool through_buffers, int64_t tile_hint, int64_t box_hint, PlanData& p, bool lane_list = true)
+                bool through_buffers, int64_t tile_hint, int64_t box_hint, PlanData& p, bool lane_list = true,
+                int pair_work_log2 = PAIR_BUCKET_WORK_LOG2)
 {
     const auto t_start = std::chrono::steady_clock::now();
     if (ca.rank_filter != -1 || cb.rank_filter != -1)
@@ -362,7 +369,8 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         // more busy lanes than the list holds: nothing was emitted, so plan again without the list
         be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);
         be.free(descs); be.free(ntl); be.free(tb); be.free(tiles);
-        build_plan(be, ca, cb, rank, tile_bytes, xpose_shape, small_limit, routes_only, through_buffers, tile_hint, box_hint, p, false);
+        build_plan(be, ca, cb, rank, tile_bytes, xpose_shape, small_limit, routes_only, through_buffers, tile_hint, box_hint, p, false,
+                   pair_work_log2);
         return;
     }
     int64_t n = (int64_t)hsum[SUM_NBOXES];
@@ -385,62 +393,177 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         } else {
             be.zero(sum + 1, sizeof(uint64_t) * (size_t)(SL.words() - 1));
         }
-        uint64_t* kmin = be.template alloc<uint64_t>(n);
-        uint64_t* kmaj = be.template alloc<uint64_t>(n);
-        uint32_t* by_lo = be.template alloc<uint32_t>(n);
-        uint32_t* ord_s = be.template alloc<uint32_t>(n);
-        uint32_t* ord_r = be.template alloc<uint32_t>(n);
-        const int lo_bits = bits_for(ca.tensor_numel_max);
-        be.for_each(step::plan_keys(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = recs[k].klo; by_lo[k] = (uint32_t)k; });
-        be.sort_pairs(kmin, by_lo, n, lo_bits);
-        // (keys cut to the bits this transition needs: every bit less is work the sort does not do)
-        const int rank_bits = bits_for((uint64_t)W), tensor_bits = bits_for((uint64_t)A.nt);
-        const int major_bits = 2 * rank_bits + 2 + tensor_bits;
-        be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) {
-            ord_s[k] = by_lo[k];
-            kmaj[k] = compact_major_key(recs[by_lo[k]].key_s, rank_bits, tensor_bits);
-        });
-        be.sort_pairs(kmaj, ord_s, n, major_bits);
-        be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) {
-            ord_r[k] = by_lo[k];
-            kmaj[k] = compact_major_key(recs[by_lo[k]].key_r, rank_bits, tensor_bits);
-        });
-        be.sort_pairs(kmaj, ord_r, n, major_bits);
-        be.free(kmin); be.free(kmaj); be.free(by_lo);
-        int64_t* sz = be.template alloc<int64_t>(n + 1);
-        gs = be.template alloc<uint64_t>(n + 1);
-        gr = be.template alloc<uint64_t>(n + 1);
-        for (int side = 0; side < 2; ++side) {
-            const uint32_t* ord = side == 0 ? ord_s : ord_r;
-            uint64_t* g = side == 0 ? gs : gr;
-            be.for_each(step::plan_slot_sizes(), n + 1, [=] VPS_LAMBDA(int64_t k) {
-                if (k == n) { sz[k] = 0; return; }
-                const uint64_t bf = recs[ord[k]].bytes_flags;
-                sz[k] = (bf & (side == 0 ? ORD_SENDS : ORD_RECEIVES)) ? (int64_t)(bf & ~(uint64_t)15) : 0;
+        // ---- all ranks: order pair by pair.  Both orders keep the boxes of a (source, destination)
+        // pair together, in the same order inside; so the boxes are counted and scattered into one
+        // bucket per pair, ranked inside their bucket by counting, and the places of the buckets
+        // in the two orders and in the peer buffers come from sums over the rows and the columns
+        // of the pair matrix.  No sort; the work is the sum of the squared bucket sizes, and when
+        // that is out of proportion (or the matrix too large) the radix path below takes over.
+        bool ordered = false;
+        const uint64_t pair_work_max = pair_work_log2 > 0 ? (uint64_t)1 << pair_work_log2 : 0;
+        if (pair_work_log2 > 0 && rank < 0 && (int64_t)WA * WB <= PAIR_BUCKET_MAX_PAIRS) {
+            const int64_t np = (int64_t)WA * WB;
+            uint64_t* pcount = be.template alloc<uint64_t>(4 * np);     // boxes per pair
+            uint64_t* pbytes = pcount + np;                               // buffer bytes per pair
+            uint64_t* pcur = pbytes + np;                                 // scatter cursors
+            uint64_t* pstart_s = pcur + np;                               // first place of the pair in the send order
+            uint64_t* pstart_r = be.template alloc<uint64_t>(3 * np);   // ... in the receive order
+            uint64_t* poff_s = pstart_r + np;                             // offset of the pair's segment in the send buffer
+            uint64_t* poff_r = poff_s + np;                               // ... in the receive buffer
+            int64_t* edge = be.template alloc<int64_t>(8 * ((int64_t)W + 1));
+            int64_t* rows_n = edge, *cols_n = edge + (W + 1), *rows_b = edge + 2 * (W + 1), *cols_b = edge + 3 * (W + 1);
+            int64_t* rows_n0 = edge + 4 * (W + 1), *cols_n0 = edge + 5 * (W + 1), *rows_b0 = edge + 6 * (W + 1), *cols_b0 = edge + 7 * (W + 1);
+            PairRec* bucket = be.template alloc<PairRec>(n);
+            uint64_t* work = sum + SUM_PAIR_WORK;
+            be.zero(pcount, sizeof(uint64_t) * (size_t)(3 * np));
+            be.zero(edge, sizeof(int64_t) * (size_t)(4 * (W + 1)));
+            be.for_each(step::plan_pair_counts(), n, [=] VPS_LAMBDA(int64_t k) {
+                const vps_box& b = raw[k];
+                const int64_t pr = (int64_t)b.src_rank * WB + b.dst_rank;
+                be_atomic_add_runs(pcount, pr, 1);
+                const uint64_t bf = recs[k].bytes_flags;
+                be_atomic_add_runs(pbytes, pr, (bf & ORD_SENDS) ? (bf & ~(uint64_t)15) : 0);
             });
-            be.exclusive_scan(sz, (int64_t*)g, n);
-            // position inside the owner's buffer: cumulative bytes minus those of the ranks before
-            be.for_each(step::plan_positions(), n, [=] VPS_LAMBDA(int64_t k) {
-                vps_box& b = raw[ord[k]];
-                if (!(recs[ord[k]].bytes_flags & (side == 0 ? ORD_SENDS : ORD_RECEIVES))) return;
-                const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
-                int64_t lo = 0, hi = k;   // first box of the owner in this order
-                while (lo < hi) {
-                    const int64_t mid = (lo + hi) / 2;
-                    const vps_box& m = raw[ord[mid]];
-                    if ((side == 0 ? m.src_rank : m.dst_rank) < own) lo = mid + 1; else hi = mid;
+            // sums of the rows (one source rank each) and of the columns (one destination rank each)
+            be.for_each(step::plan_pair_sums(), (int64_t)WA + WB, [=] VPS_LAMBDA(int64_t i) {
+                uint64_t cn = 0, cb = 0, sq = 0;
+                if (i < WA) {
+                    VPS_UNROLL(8)
+                    for (int64_t d = 0; d < WB; ++d) { const uint64_t c = pcount[i * WB + d]; cn += c; cb += pbytes[i * WB + d]; sq += c * c; }
+                    rows_n[i] = (int64_t)cn; rows_b[i] = (int64_t)cb;
+                    if (sq) be_atomic_add(work, sq);
+                } else {
+                    const int64_t d = i - WA;
+                    VPS_UNROLL(8)
+                    for (int64_t r = 0; r < WA; ++r) { cn += pcount[r * WB + d]; cb += pbytes[r * WB + d]; }
+                    cols_n[d] = (int64_t)cn; cols_b[d] = (int64_t)cb;
                 }
-                const uint64_t rel = g[k] - g[lo];
-                if (side == 0) b.send_pos = rel; else b.recv_pos = rel;
             });
+            be.exclusive_scan(rows_n, rows_n0, W);
+            be.exclusive_scan(cols_n, cols_n0, W);
+            be.exclusive_scan(rows_b, rows_b0, W);
+            be.exclusive_scan(cols_b, cols_b0, W);
+            if (W <= 256) {
+                // one lane per pair: it adds up its row to the left of it and its column above it
+                be.for_each(step::plan_pair_starts(), np, [=] VPS_LAMBDA(int64_t pr) {
+                    const int64_t i = pr / WB, d = pr - i * WB;
+                    uint64_t at = (uint64_t)rows_n0[i], off = 0;
+                    VPS_UNROLL(8)
+                    for (int64_t q = 0; q < d; ++q) { at += pcount[i * WB + q]; off += pbytes[i * WB + q]; }
+                    pstart_s[pr] = at; poff_s[pr] = off;
+                    at = (uint64_t)cols_n0[d]; off = 0;
+                    VPS_UNROLL(8)
+                    for (int64_t q = 0; q < i; ++q) { at += pcount[q * WB + d]; off += pbytes[q * WB + d]; }
+                    pstart_r[pr] = at; poff_r[pr] = off;
+                });
+            } else {
+                be.for_each(step::plan_pair_starts(), (int64_t)WA + WB, [=] VPS_LAMBDA(int64_t i) {
+                    if (i < WA) {
+                        uint64_t at = (uint64_t)rows_n0[i], off = 0;
+                        VPS_UNROLL(8)
+                        for (int64_t d = 0; d < WB; ++d) { pstart_s[i * WB + d] = at; poff_s[i * WB + d] = off; at += pcount[i * WB + d]; off += pbytes[i * WB + d]; }
+                    } else {
+                        const int64_t d = i - WA;
+                        uint64_t at = (uint64_t)cols_n0[d], off = 0;
+                        VPS_UNROLL(8)
+                        for (int64_t r = 0; r < WA; ++r) { pstart_r[r * WB + d] = at; poff_r[r * WB + d] = off; at += pcount[r * WB + d]; off += pbytes[r * WB + d]; }
+                    }
+                });
+            }
+            be.for_each(step::plan_pair_scatter(), n, [=] VPS_LAMBDA(int64_t k) {
+                const vps_box& b = raw[k];
+                const int64_t pr = (int64_t)b.src_rank * WB + b.dst_rank;
+                const OrderRec r = recs[k];
+                PairRec q;
+                q.key = pair_rec_key(r, pr); q.klo = r.klo; q.bytes_flags = r.bytes_flags; q.box = (uint64_t)k;
+                bucket[pstart_s[pr] + be_atomic_fetch_add(&pcur[pr], 1)] = q;
+            });
+            sorted = be.template alloc<vps_box>(n);
+            rperm = be.template alloc<uint32_t>(n);
+            gs = be.template alloc<uint64_t>(n + 1);
+            gr = be.template alloc<uint64_t>(n + 1);
+            uint64_t* before_of = be.template alloc<uint64_t>(2 * n);
+            uint64_t* bytes_of = before_of + n;
+            be.pair_rank_each(step::plan_pair_rank(), bucket, pstart_s, pcount, n, work, pair_work_max,
+                              [=] VPS_LAMBDA(int64_t j, uint64_t before, uint64_t bytes) { before_of[j] = before; bytes_of[j] = bytes; });
+            be.for_each(step::plan_pair_place(), n, [=] VPS_LAMBDA(int64_t j) {
+                const PairRec me = bucket[j];
+                const int64_t pr = (int64_t)(me.key >> 26);
+                const uint64_t before = before_of[j], bytes = bytes_of[j];
+                vps_box b = raw[me.box];
+                const uint64_t is = pstart_s[pr] + before, ir = pstart_r[pr] + before;
+                const uint64_t ps = poff_s[pr] + bytes, pq = poff_r[pr] + bytes;
+                if (me.bytes_flags & ORD_SENDS) b.send_pos = ps;
+                if (me.bytes_flags & ORD_RECEIVES) b.recv_pos = pq;
+                sorted[is] = b;
+                rperm[ir] = (uint32_t)is;
+                gs[is] = (uint64_t)rows_b0[b.src_rank] + ps;
+                gr[ir] = (uint64_t)cols_b0[b.dst_rank] + pq;
+                if (j == 0) { gs[n] = (uint64_t)rows_b0[W]; gr[n] = (uint64_t)cols_b0[W]; }
+            });
+            be.free(before_of);
+            be.free(pcount); be.free(pstart_r); be.free(edge); be.free(bucket);
+            ordered = true;
         }
-        be.free(sz);
-        sorted = be.template alloc<vps_box>(n);
-        rperm = be.template alloc<uint32_t>(n);
-        uint32_t* inv = be.template alloc<uint32_t>(n);
-        be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = raw[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
-        be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
-        be.free(inv); be.free(ord_s); be.free(ord_r);
+        const bool pair_ordered = ordered;
+        if (!ordered) {
+            uint64_t* kmin = be.template alloc<uint64_t>(n);
+            uint64_t* kmaj = be.template alloc<uint64_t>(n);
+            uint32_t* by_lo = be.template alloc<uint32_t>(n);
+            uint32_t* ord_s = be.template alloc<uint32_t>(n);
+            uint32_t* ord_r = be.template alloc<uint32_t>(n);
+            const int lo_bits = bits_for(ca.tensor_numel_max);
+            be.for_each(step::plan_keys(), n, [=] VPS_LAMBDA(int64_t k) { kmin[k] = recs[k].klo; by_lo[k] = (uint32_t)k; });
+            be.sort_pairs(kmin, by_lo, n, lo_bits);
+            // (keys cut to the bits this transition needs: every bit less is work the sort does not do)
+            const int rank_bits = bits_for((uint64_t)W), tensor_bits = bits_for((uint64_t)A.nt);
+            const int major_bits = 2 * rank_bits + 2 + tensor_bits;
+            be.for_each(step::plan_key_send(), n, [=] VPS_LAMBDA(int64_t k) {
+                ord_s[k] = by_lo[k];
+                kmaj[k] = compact_major_key(recs[by_lo[k]].key_s, rank_bits, tensor_bits);
+            });
+            be.sort_pairs(kmaj, ord_s, n, major_bits);
+            be.for_each(step::plan_key_recv(), n, [=] VPS_LAMBDA(int64_t k) {
+                ord_r[k] = by_lo[k];
+                kmaj[k] = compact_major_key(recs[by_lo[k]].key_r, rank_bits, tensor_bits);
+            });
+            be.sort_pairs(kmaj, ord_r, n, major_bits);
+            be.free(kmin); be.free(kmaj); be.free(by_lo);
+            int64_t* sz = be.template alloc<int64_t>(n + 1);
+            gs = be.template alloc<uint64_t>(n + 1);
+            gr = be.template alloc<uint64_t>(n + 1);
+            for (int side = 0; side < 2; ++side) {
+                const uint32_t* ord = side == 0 ? ord_s : ord_r;
+                uint64_t* g = side == 0 ? gs : gr;
+                be.for_each(step::plan_slot_sizes(), n + 1, [=] VPS_LAMBDA(int64_t k) {
+                    if (k == n) { sz[k] = 0; return; }
+                    const uint64_t bf = recs[ord[k]].bytes_flags;
+                    sz[k] = (bf & (side == 0 ? ORD_SENDS : ORD_RECEIVES)) ? (int64_t)(bf & ~(uint64_t)15) : 0;
+                });
+                be.exclusive_scan(sz, (int64_t*)g, n);
+                // position inside the owner's buffer: cumulative bytes minus those of the ranks before
+                be.for_each(step::plan_positions(), n, [=] VPS_LAMBDA(int64_t k) {
+                    vps_box& b = raw[ord[k]];
+                    if (!(recs[ord[k]].bytes_flags & (side == 0 ? ORD_SENDS : ORD_RECEIVES))) return;
+                    const int32_t own = side == 0 ? b.src_rank : b.dst_rank;
+                    int64_t lo = 0, hi = k;   // first box of the owner in this order
+                    while (lo < hi) {
+                        const int64_t mid = (lo + hi) / 2;
+                        const vps_box& m = raw[ord[mid]];
+                        if ((side == 0 ? m.src_rank : m.dst_rank) < own) lo = mid + 1; else hi = mid;
+                    }
+                    const uint64_t rel = g[k] - g[lo];
+                    if (side == 0) b.send_pos = rel; else b.recv_pos = rel;
+                });
+            }
+            be.free(sz);
+            sorted = be.template alloc<vps_box>(n);
+            rperm = be.template alloc<uint32_t>(n);
+            uint32_t* inv = be.template alloc<uint32_t>(n);
+            be.for_each(step::plan_sorted_boxes(), n, [=] VPS_LAMBDA(int64_t k) { sorted[k] = raw[ord_s[k]]; inv[ord_s[k]] = (uint32_t)k; });
+            be.for_each(step::plan_recv_perm(), n, [=] VPS_LAMBDA(int64_t k) { rperm[k] = inv[ord_r[k]]; });
+            be.free(inv); be.free(ord_s); be.free(ord_r);
+        }
         descs = routes_only ? nullptr : be.template alloc<CopyDesc>(3 * n);
         ntl = be.template alloc<int64_t>(3 * n + 1);
         tb = be.template alloc<int64_t>(3 * n + 1);
@@ -457,6 +580,15 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         be.for_each(step::plan_rank_tables(), W + 1, [=] VPS_LAMBDA(int64_t r) { rank_row(r, n, sorted, rperm, gs, gr, tb); });
         be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());
         if ((int64_t)hsum[SUM_NBOXES] != n) throw Error{ VPS_ERR_HIP, "planning passes disagree on the number of boxes" };
+        if (pair_ordered && hsum[SUM_PAIR_WORK] > pair_work_max) {
+            // a few pairs hold nearly all boxes: the ranking inside the buckets was skipped, so
+            // plan again with the radix sort
+            be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);
+            be.free(descs); be.free(ntl); be.free(tb);
+            build_plan(be, ca, cb, rank, tile_bytes, xpose_shape, small_limit, routes_only, through_buffers, tile_hint, box_hint, p,
+                       lane_list, 0);
+            return;
+        }
     }
     be.free(raw); be.free(recs); be.free(gs); be.free(gr); be.free(ntl);
 

@@ -154,6 +154,27 @@ public:
     }
 
     template <class Step, class F>
+    void pair_rank_each(Step, const PairRec* bucket, const uint64_t* pstart, const uint64_t* pcount, int64_t n,
+                        const uint64_t* work, uint64_t work_max, F f)
+    {
+        for (int64_t j = 0; j < n; ++j) {
+            const PairRec me = bucket[j];
+            const uint64_t pr = me.key >> 26, lo = pstart[pr], cnt = pcount[pr];
+            uint64_t before = (uint64_t)j - lo, bytes = 0;
+            if (*work <= work_max) {
+                before = 0;
+                for (uint64_t q = lo; q < lo + cnt; ++q) {
+                    const PairRec o = bucket[q];
+                    const bool less = pair_rec_less(o, me);
+                    before += less ? 1 : 0;
+                    bytes += (less && (o.bytes_flags & ORD_SENDS)) ? (o.bytes_flags & ~(uint64_t)15) : 0;
+                }
+            }
+            f(j, before, bytes);
+        }
+    }
+
+    template <class Step, class F>
     void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, F f)
     {
         const uint64_t n = *nbox;
@@ -333,6 +354,21 @@ uint64_t vpsh_unaligned_run_tiles(void)
 {
     const uint64_t n = vps::g_unaligned_run_tiles;
     vps::g_unaligned_run_tiles = 0;
+    return n;
+}
+
+// The tensor ids of one group as the planner's per-group lane ranges enumerate them; returns
+// their number (ids beyond `max` are not written), or -1 for an illegal description.
+int vpsh_group_tensors(const vps_model_desc* m, const vps_parallel_desc* p, int group, int32_t* out, int max)
+{
+    try {
+        vps::check_descs(*m, *p);
+    } catch (const vps::Error&) {
+        return -1;
+    }
+    const vps::ParConst P = vps::make_par_const(*m, *p, vps::make_model_const(*m).nt);
+    const int n = vps::group_tensor_count(P, group);
+    for (int i = 0; i < n && i < max; ++i) out[i] = vps::group_tensor_id(P, group, i);
     return n;
 }
 

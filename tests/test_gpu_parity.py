@@ -5,7 +5,8 @@ import pytest
 import parity
 from datagen import configs as cf
 from test_oracle_pins import ALL_TRANSITIONS, TRANSITIONS
-from test_hostcheck_parity import COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH, check_error_codes
+from test_hostcheck_parity import (BEYOND, COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH, check_error_codes,
+                                   run_plans_beyond_the_counting_limit)
 
 pytestmark = pytest.mark.gpu
 
@@ -45,25 +46,12 @@ def test_rank_as_its_own_peer(lib, name, rank):
         parity.run_single_rank(lib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
 
 
-@pytest.mark.parametrize("limit", [1, 7, 64])
-def test_plans_beyond_the_counting_limit(lib, limit):
-    """The radix-sort path of the planner on the device, reached by lowering the limit of the
-    counting path (see the CPU-build test of the same name)."""
-    from paper_2605_18815_amd import binding as B
-    lib.set_option(B.OPT_SMALL_PLAN_BOXES, limit)
-    try:
-        for name, rank in (("gpt-zero-to-replicated", -1), ("gpt-blocked-rev", -1), ("moe-odd", -1), ("moe-carved-ep-grows", -1),
-                           ("gpt-tp-pp", 5), ("moe-transposed", 3), ("gpt-world-grows", 11)):
-            _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
-            if rank < 0:
-                parity.run_all_ranks(lib, parity.GpuMem(), m, pa, pb, seed=0x1A46E + limit, through=(limit == 7))
-            else:
-                parity.run_single_rank(lib, parity.GpuMem(), m, pa, pb, rank, seed=0x1A46E + rank, through=(limit == 7))
-        _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == "moe-ep"][0]
-        parity.run_staged(lib, parity.GpuMem(), m, pa, pb, seed=3, budget=1 << 12)
-        parity.run_classify(lib, m, pa, pb)
-    finally:
-        lib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
+@pytest.mark.parametrize("limit,pair_work", BEYOND, ids=[f"{a}-{['sort', 'bound-exceeded'][b] if b < 2 else 'pairs'}" for a, b in BEYOND])
+def test_plans_beyond_the_counting_limit(lib, limit, pair_work):
+    """The paths of the planner for many boxes on the device (pair-by-pair ordering, radix sort, and
+    the switch from the first to the second), reached by lowering the limit of the counting path
+    (see the CPU-build test of the same name)."""
+    run_plans_beyond_the_counting_limit(lib, parity.GpuMem, limit, pair_work)
 
 
 def test_sender_and_receiver_agree_on_segments_toy(lib):

@@ -105,6 +105,24 @@ def test_parity_subset_under_address_sanitizer():
     assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-3000:]
 
 
+@pytest.mark.parametrize("m", [cf.TINY_GPT, cf.TINY_GQA, cf.TINY_MOE, cf.ODD_MOE, cf.MID_MOE], ids=["gpt", "gqa", "moe", "odd-moe", "mid-moe"])
+def test_tensor_ids_by_group(hlib, m):
+    """The planner of all-ranks transitions enumerates the dense and the expert tensors separately,
+    from the layout of the inventory; the ids must be those whose pieces live in the group's
+    buffers, ascending."""
+    import ctypes as C
+    from paper_2605_18815_amd import binding as B
+    par = P(tp=2, dp=2, ep=2 if m["family"] == cf.FAMILY_MOE else 1)
+    pieces = hlib.describe_config(m, par).get_pieces()
+    nt = int(pieces["tensor"].max()) + 1
+    for group in (0, 1):
+        want = sorted(set(int(t) for t in pieces["tensor"][pieces["buf"] // 4 == group]))
+        out = (C.c_int32 * nt)()
+        n = hlib._dll.vpsh_group_tensors(C.byref(B.model_desc(m)), C.byref(B.parallel_desc(par)), group, out, nt)
+        assert n == len(want) and list(out[:n]) == want
+    assert sorted(set(int(t) for t in pieces["tensor"])) == list(range(nt))
+
+
 def test_piece_queries_then_planning(hlib):
     """Regression: the piece table is built on the first piece query, by a backend that lives only
     for that call; it has to hand the table over to the configuration (once, a second query reuses
@@ -171,26 +189,39 @@ def test_rank_as_its_own_peer(hlib, name, rank):
         parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
 
 
-@pytest.mark.parametrize("limit", [1, 7, 64])
-def test_plans_beyond_the_counting_limit(hlib, limit):
-    """Plans with more boxes than the counting path takes are ordered by the radix sort and
-    positioned by scans: same boxes, same buffers.  The limit is lowered so that tiny models
-    reach that path (and, at 64, so that some plans take one path and some the other)."""
+# (limit of the counting path, log2 of the work bound of the pair-by-pair ordering: 32 = the
+# default, 0 = all-ranks plans always take the radix sort, 1 = they start pair by pair, find the
+# bound exceeded and plan again with the sort)
+BEYOND = [(1, 32), (7, 32), (64, 32), (1, 0), (7, 1)]
+
+
+def run_plans_beyond_the_counting_limit(lib, mem_factory, limit, pair_work):
     from paper_2605_18815_amd import binding as B
-    hlib.set_option(B.OPT_SMALL_PLAN_BOXES, limit)
+    lib.set_option(B.OPT_SMALL_PLAN_BOXES, limit)
+    lib.set_option(B.OPT_PAIR_ORDER_WORK, pair_work)
     try:
         for name, rank in (("gpt-zero-to-replicated", -1), ("gpt-blocked-rev", -1), ("moe-odd", -1), ("moe-carved-ep-grows", -1),
-                           ("gpt-tp-pp", 5), ("moe-transposed", 3), ("gpt-world-grows", 11)):
+                           ("gpt-world-grows", -1), ("gpt-tp-pp", 5), ("moe-transposed", 3), ("gpt-world-grows", 11)):
             _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == name][0]
             if rank < 0:
-                parity.run_all_ranks(hlib, parity.HostMem(hlib), m, pa, pb, seed=0x1A46E + limit, through=(limit == 7))
+                parity.run_all_ranks(lib, mem_factory(), m, pa, pb, seed=0x1A46E + limit, through=(limit == 7))
             else:
-                parity.run_single_rank(hlib, parity.HostMem(hlib), m, pa, pb, rank, seed=0x1A46E + rank, through=(limit == 7))
+                parity.run_single_rank(lib, mem_factory(), m, pa, pb, rank, seed=0x1A46E + rank, through=(limit == 7))
         _, m, pa, pb = [t for t in ALL_TRANSITIONS if t[0] == "moe-ep"][0]
-        parity.run_staged(hlib, parity.HostMem(hlib), m, pa, pb, seed=3, budget=1 << 12)
-        parity.run_classify(hlib, m, pa, pb)
+        parity.run_staged(lib, mem_factory(), m, pa, pb, seed=3, budget=1 << 12)
+        parity.run_classify(lib, m, pa, pb)
     finally:
-        hlib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
+        lib.set_option(B.OPT_SMALL_PLAN_BOXES, 8192)
+        lib.set_option(B.OPT_PAIR_ORDER_WORK, 32)
+
+
+@pytest.mark.parametrize("limit,pair_work", BEYOND, ids=[f"{a}-{['sort', 'bound-exceeded'][b] if b < 2 else 'pairs'}" for a, b in BEYOND])
+def test_plans_beyond_the_counting_limit(hlib, limit, pair_work):
+    """Plans with more boxes than the counting path takes: all-ranks plans are ordered pair by pair
+    (or by the radix sort), single-rank plans by the radix sort, positions by sums and scans: same
+    boxes, same buffers.  The limit is lowered so that tiny models reach those paths (and, at 64,
+    so that some plans take one path and some the other)."""
+    run_plans_beyond_the_counting_limit(hlib, lambda: parity.HostMem(hlib), limit, pair_work)
 
 
 @pytest.mark.parametrize("name", ["gpt-zero-to-replicated", "gpt-world-grows", "moe-odd", "moe-carved-ep-grows"])
