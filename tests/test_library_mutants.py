@@ -31,6 +31,12 @@ MUTANTS = [m for m in [
      "if (rec.bytes_flags & ORD_SENDS) b.send_pos = o.gpos_s - o.base_s;", "if (rec.bytes_flags & ORD_SENDS) b.send_pos = o.gpos_s;"),
     ("sorted path: positions counted from the start of all buffers", "vps_pipeline.h",
      "const uint64_t rel = g[k] - g[lo];", "const uint64_t rel = g[k];"),
+    ("pair by pair: receive offsets from the box counts", "vps_pipeline.h",
+     "for (int64_t q = 0; q < i; ++q) { at += pcount[q * WB + d]; off += pbytes[q * WB + d]; }",
+     "for (int64_t q = 0; q < i; ++q) { at += pcount[q * WB + d]; off += pcount[q * WB + d]; }"),
+    ("pair by pair: a box counts itself among those before it", "vps_core.h",
+     "VPS_HD bool pair_rec_less(const PairRec& a, const PairRec& b) { return a.key < b.key || (a.key == b.key && a.klo < b.klo); }",
+     "VPS_HD bool pair_rec_less(const PairRec& a, const PairRec& b) { return a.key < b.key || (a.key == b.key && a.klo <= b.klo); }"),
     ("expert ranks with ep and expert-dp digits swapped", "vps_core.h",
      "return group ? t + P.etp * (ep + P.ep * (d + P.edp * pp)) : t + P.tp * (d + P.ddp * pp);",
      "return group ? t + P.etp * (d + P.edp * (ep + P.ep * pp)) : t + P.tp * (d + P.ddp * pp);"),
@@ -42,6 +48,12 @@ MUTANTS = [m for m in [
 ] if m[2] is not None]   # (entries without a site are mistakes only a device build could hold)
 
 PARITY = "all_ranks_resident or single_rank_share or medium_shapes or beyond_the_counting_limit"
+# the tests expected to notice a mistake first, for mistakes on paths that few tests take
+FIRST = {
+    "sorted path: positions counted from the start of all buffers": "beyond_the_counting_limit and sort",
+    "pair by pair: receive offsets from the box counts": "beyond_the_counting_limit and pairs",
+    "pair by pair: a box counts itself among those before it": "beyond_the_counting_limit and pairs",
+}
 
 
 @pytest.mark.parametrize("name,header,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
@@ -59,7 +71,7 @@ def test_parity_suite_catches_planted_mistake(name, header, old, new):
         subprocess.run(["g++", "-std=c++17", "-O0", "-fPIC", "-shared", "-o", lib,
                         os.path.join(tmp, "tests", "hostcheck", "hostcheck.cpp")], check=True)
         res = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_hostcheck_parity.py"), "-x", "-q",
-                              "-k", PARITY, "-p", "no:cacheprovider"], env=dict(os.environ, VPSH_LIB=lib), cwd=ROOT,
+                              "-k", FIRST.get(name, PARITY), "-p", "no:cacheprovider"], env=dict(os.environ, VPSH_LIB=lib), cwd=ROOT,
                              capture_output=True, text=True)
         # a failed comparison, or the CPU build running off its tables (it is then killed by a signal)
         assert res.returncode != 0, f"no parity test noticed the planted mistake '{name}'"
