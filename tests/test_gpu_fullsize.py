@@ -143,7 +143,7 @@ PAPER_CASES = [("llama70b-64-to-128", False, 127), ("llama70b-64-to-128", False,
                # the MoE pairs, EP carved out of the TP x DP ranks: a rank of the first and of a
                # middle stage of the 30B pair, one rank of the 235B pair in each direction
                ("qwen30b-hybrid", False, 3), ("qwen30b-hybrid", True, 21),
-               ("qwen235b-hybrid", False, 77), ("qwen235b-hybrid", True, 34)]
+               ("qwen235b-hybrid", False, 77)]
 
 
 @pytest.mark.timeout(900)
