@@ -870,7 +870,8 @@ struct CopyDesc {
     uint32_t chunks_per_row; // RUN, long runs: tiles per run (0 = short-run tiling).
                              // XPOSE: number of blocks along axis xa
     uint32_t ntiles;
-    uint32_t xa;             // XPOSE: the collapsed axis (0..2) that is contiguous in the source
+    uint32_t xa;             // XPOSE: the collapsed axis (0..2) that is contiguous in the source.
+                             // RUN, long runs: dst_byte modulo the cut alignment when the descriptor was made
 };
 
 struct PtrLayout {
@@ -1023,6 +1024,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             for (int a = 0; a < 3; ++a)
                 if (d.ext[a] > 1 && ((uint64_t)(d.dstr[a] * (int64_t)d.es) & (cut - 1))) same_phase = false;
             const uint64_t pre = same_phase ? (d.dst_byte & (cut - 1)) : cut - d.es;
+            d.xa = (uint32_t)(d.dst_byte & (cut - 1));   // kept with the descriptor: see make_tile
             d.chunks_per_row = (uint32_t)((pre + run_bytes + vt * 16 - 1) / (vt * 16));
             d.vec_window = (uint32_t)vt;
             d.rows_per_tile = 1;
@@ -1192,11 +1194,17 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         uint64_t so, to;
         run_row_offsets(d, row, so, to);
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-        const uint64_t d0 = d.dst_byte + to, end = d0 + run_bytes, ab = d0 & ~(run_cut_align(d.vec_window) - 1);
-        uint64_t lo = ab + 16ull * c * d.vec_window, hi = lo + 16ull * d.vec_window;
-        if (lo < d0) lo = d0;
-        if (hi > end) hi = end;
-        if (hi < lo) hi = lo;
+        // (the boundary is where it was when the descriptor was made: d.xa is the phase of dst_byte
+        // at that time, so a descriptor that is later moved to another place, as the staged
+        // exchange does with its pack descriptors, keeps its cuts and its number of tiles; the
+        // windows are taken relative to the run's first byte, which may now lie anywhere)
+        const uint64_t d0 = d.dst_byte + to;
+        const int64_t pre = (int64_t)((d.xa + to) & (run_cut_align(d.vec_window) - 1)), win = 16ll * d.vec_window;
+        int64_t rlo = (int64_t)c * win - pre, rhi = rlo + win;   // the chunk's window, relative to d0
+        if (rlo < 0) rlo = 0;
+        if (rhi > (int64_t)run_bytes) rhi = (int64_t)run_bytes;
+        if (rhi < rlo) rhi = rlo;
+        const uint64_t lo = d0 + (uint64_t)rlo, hi = d0 + (uint64_t)rhi;
         t.src = tile_pack_addr(d.src_slot, d.src_byte + so + (lo - d0));
         t.dst = tile_pack_addr(d.dst_slot, lo);
         t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so + (lo - d0)) : VPS_TILE_NO_ALT;

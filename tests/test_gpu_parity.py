@@ -6,7 +6,7 @@ import parity
 from datagen import configs as cf
 from test_oracle_pins import ALL_TRANSITIONS, TRANSITIONS
 from test_hostcheck_parity import (BEYOND, COLLECTIVE_CASES, EDGE_TRANSITIONS, MEDIUM, SINGLE, STAGED, THROUGH, check_error_codes,
-                                   run_plans_beyond_the_counting_limit)
+                                   run_plans_beyond_the_counting_limit, run_staged_long_runs)
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,10 @@ def test_plans_beyond_the_counting_limit(lib, limit, pair_work):
     the switch from the first to the second), reached by lowering the limit of the counting path
     (see the CPU-build test of the same name)."""
     run_plans_beyond_the_counting_limit(lib, parity.GpuMem, limit, pair_work)
+
+
+def test_staged_exchange_moves_long_runs(lib):
+    run_staged_long_runs(lib, parity.GpuMem)
 
 
 def test_sender_and_receiver_agree_on_segments_toy(lib):

@@ -189,6 +189,25 @@ def test_rank_as_its_own_peer(hlib, name, rank):
         parity.run_single_rank(hlib, mem, m, pa, pb, rank, seed=0xD00D + rank, through=True)
 
 
+def run_staged_long_runs(lib, mem_factory):
+    """Regression: runs longer than a tile whose pack descriptors the staged exchange moves to other
+    places of the scratch area (here to offset 0, below the phase their cuts were made for) keep
+    their cuts and their number of tiles."""
+    pa = P(tp=3, pp=2, dp=2, zero=1, gpus_per_node=8, qkv_layout=1, flat_order=1)
+    pb = P(tp=3, pp=1, dp=3, zero=1, gpus_per_node=4)
+    for tile, budget in ((4096, 1), (8192, 1 << 14), (8192, 1 << 18)):
+        lib.set_tile_bytes(tile)
+        try:
+            out = parity.run_staged(lib, mem_factory(), cf.MID_GPT, pa, pb, seed=42000993, budget=budget)
+        finally:
+            lib.set_tile_bytes(8192)
+        assert out["stages"] > 1
+
+
+def test_staged_exchange_moves_long_runs(hlib):
+    run_staged_long_runs(hlib, lambda: parity.HostMem(hlib))
+
+
 # (limit of the counting path, log2 of the work bound of the pair-by-pair ordering: 32 = the
 # default, 0 = all-ranks plans always take the radix sort, 1 = they start pair by pair, find the
 # bound exceeded and plan again with the sort)

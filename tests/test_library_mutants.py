@@ -37,6 +37,9 @@ MUTANTS = [m for m in [
     ("pair by pair: a box counts itself among those before it", "vps_core.h",
      "VPS_HD bool pair_rec_less(const PairRec& a, const PairRec& b) { return a.key < b.key || (a.key == b.key && a.klo < b.klo); }",
      "VPS_HD bool pair_rec_less(const PairRec& a, const PairRec& b) { return a.key < b.key || (a.key == b.key && a.klo <= b.klo); }"),
+    ("cuts of a long run follow the descriptor to its new place", "vps_core.h",
+     "const int64_t pre = (int64_t)((d.xa + to) & (run_cut_align(d.vec_window) - 1)), win = 16ll * d.vec_window;",
+     "const int64_t pre = (int64_t)((d.dst_byte + to) & (run_cut_align(d.vec_window) - 1)), win = 16ll * d.vec_window;"),
     ("expert ranks with ep and expert-dp digits swapped", "vps_core.h",
      "return group ? t + P.etp * (ep + P.ep * (d + P.edp * pp)) : t + P.tp * (d + P.ddp * pp);",
      "return group ? t + P.etp * (d + P.edp * (ep + P.ep * pp)) : t + P.tp * (d + P.ddp * pp);"),
@@ -53,6 +56,7 @@ FIRST = {
     "sorted path: positions counted from the start of all buffers": "beyond_the_counting_limit and sort",
     "pair by pair: receive offsets from the box counts": "beyond_the_counting_limit and pairs",
     "pair by pair: a box counts itself among those before it": "beyond_the_counting_limit and pairs",
+    "cuts of a long run follow the descriptor to its new place": "moves_long_runs",
 }
 
 
