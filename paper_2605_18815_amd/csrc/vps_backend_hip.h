@@ -73,11 +73,12 @@ __device__ __forceinline__ V group_exclusive_scan(V v, V& total, V* carry)
     return before + in_wave;
 }
 
-// F_P, flat offsets: workgroup `cls` walks the tensors of its pipeline stage in flat-buffer order
-// and gives every tensor of its class the running sum of the shard lengths before it (a
-// workgroup-wide prefix sum per 1024 tensors, four consecutive ones per lane); the class length
-// and its padded size fall out at the end.
-__global__ __launch_bounds__(256) void k_layout_classes(ParConst P, const TensorRec* __restrict__ T,
+// F_P, tensor table and flat offsets: workgroup `cls` walks the tensors of its pipeline stage in
+// flat-buffer order, takes each from the closed form of the inventory, and gives every tensor of
+// its class its record and the running sum of the shard lengths before it (a workgroup-wide
+// prefix sum per 1024 tensors, four consecutive ones per lane); the class length and its padded
+// size fall out at the end.  Every tensor belongs to exactly one class, so the table is complete.
+__global__ __launch_bounds__(256) void k_layout_classes(ParConst P, ModelConst M, TensorRec* __restrict__ T,
                                                         TensorLayout* __restrict__ TL, ClassRec* __restrict__ C)
 {
     __shared__ uint64_t carry[4];
@@ -97,8 +98,8 @@ __global__ __launch_bounds__(256) void k_layout_classes(ParConst P, const Tensor
             len[k] = 0;
             if (q < count) {
                 const int32_t id = P.flat_order ? hi - 1 - q : lo + q;
-                const TensorRec x = T[id];
-                if (class_of_tensor(P, x) == cls) { t[k] = id; len[k] = shard_elems(P, x); }
+                const TensorRec x = inventory_rec(M, id);
+                if (class_of_tensor(P, x) == cls) { t[k] = id; len[k] = shard_elems(P, x); T[id] = x; }
             }
             mine += len[k];
         }
@@ -617,9 +618,9 @@ public:
         VPS_HIP_CHECK(hipGetLastError());
     }
 
-    void layout_classes(const ParConst& P, const TensorRec* T, TensorLayout* TL, ClassRec* C)
+    void layout_classes(const ParConst& P, const ModelConst& M, TensorRec* T, TensorLayout* TL, ClassRec* C)
     {
-        hipLaunchKernelGGL(k_layout_classes, dim3((unsigned)P.ncls), dim3(256), 0, stream_, P, T, TL, C);
+        hipLaunchKernelGGL(k_layout_classes, dim3((unsigned)P.ncls), dim3(256), 0, stream_, P, M, T, TL, C);
         VPS_HIP_CHECK(hipGetLastError());
     }
 

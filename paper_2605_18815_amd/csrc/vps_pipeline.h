@@ -33,7 +33,6 @@ namespace vps {
 
 // One tag per data-parallel step: it names the kernel in profiles.
 namespace step {
-struct map_inventory {};
 struct map_count_pieces {};
 struct map_emit_pieces {};
 struct plan_order_by_counting {};
@@ -162,11 +161,7 @@ void build_config(BE& be, const vps_model_desc& model, const vps_parallel_desc& 
     c.T = be.template alloc<TensorRec>(nt);
     c.TL = be.template alloc<TensorLayout>(nt);
     c.C = be.template alloc<ClassRec>(P.ncls);
-    {
-        TensorRec* T = c.T;
-        be.for_each(step::map_inventory(), nt, [=] VPS_LAMBDA(int64_t t) { T[t] = inventory_rec(M, (int32_t)t); });
-    }
-    be.layout_classes(P, c.T, c.TL, c.C);
+    be.layout_classes(P, M, c.T, c.TL, c.C);   // tensor table and flat offsets in one launch
     c.hC.resize((size_t)P.ncls);
     c.host_ready = false;
 }

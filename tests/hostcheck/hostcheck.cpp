@@ -111,8 +111,9 @@ public:
     void after_null_stream() {}
 
     // The same per-item code as the device kernels, one item after the other.
-    void layout_classes(const ParConst& P, const TensorRec* T, TensorLayout* TL, ClassRec* C)
+    void layout_classes(const ParConst& P, const ModelConst& M, TensorRec* T, TensorLayout* TL, ClassRec* C)
     {
+        for (int32_t t = 0; t < P.nt; ++t) T[t] = inventory_rec(M, t);
         for (int32_t cls = 0; cls < P.ncls; ++cls) {
             uint64_t running = 0;
             for (int32_t q = 0; q < P.nt; ++q) {
