@@ -38,7 +38,7 @@
  *                   a thread-local message.  Functions never throw.  On error no device work
  *                   has been enqueued.
  *   synchronisation which calls wait for the device, and how often:
- *                   vps_describe_config          never (two kernels on the null stream)
+ *                   vps_describe_config          never (one kernel on the null stream)
  *                   vps_plan_intersections[_ex]  once, for the counts and byte totals the host
  *                                                needs; twice when the tile table has to be
  *                                                built after that wait (the first plan of a
@@ -148,8 +148,8 @@ typedef struct vps_plan_stats_t {
 /* F_P (Section 4.1, Section 4.2.2): map configuration `par` of `model` onto the VPS.
  * rank = -1 maps every rank (needed for planning); rank >= 0 keeps only that rank's pieces.
  * Both descriptors are caller-owned host structs, copied on entry.  *out is library-owned;
- * release with vps_config_destroy.  The tables are filled by two kernels queued on the null
- * stream; the call does not wait for them (planning orders itself after them).
+ * release with vps_config_destroy.  The tables are filled by a kernel queued on the null
+ * stream; the call does not wait for it (planning orders itself after it).
  * Errors: VPS_ERR_INVALID_ARG (null pointers, non-positive sizes), VPS_ERR_INDIVISIBLE,
  * VPS_ERR_RANK_RANGE, VPS_ERR_HIP. */
 int vps_describe_config(const vps_model_desc* model, const vps_parallel_desc* par, int32_t rank,
