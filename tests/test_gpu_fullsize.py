@@ -201,6 +201,15 @@ def test_all_ranks_planning_at_scale(lib, name):
     keys = ["tensor", "kind", "src_rank", "dst_rank", "src_off", "dst_off"]
     assert len(one) == len(sel)
     assert np.array_equal(np.sort(one[keys], order=keys), np.sort(sel[keys], order=keys))
+    # the two ways of ordering a large all-ranks plan (pair by pair, radix sort) and the switch from
+    # the first to the second give the same table, positions included
+    for work in (0, 1):
+        lib.set_option(B.OPT_PAIR_ORDER_WORK, work)
+        try:
+            again = lib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY).get_boxes()
+        finally:
+            lib.set_option(B.OPT_PAIR_ORDER_WORK, 32)
+        assert again.tobytes() == boxes.tobytes(), f"ordering with work bound 2^{work} differs"
     cls = plan.classify_collectives(ca)
     print("  collective intent per (tensor, kind) [none, p2p, broadcast, scatter, gather]:", np.bincount(cls, minlength=5), flush=True)
 

@@ -476,6 +476,14 @@ def test_paper_table_transitions_at_model_scale(hlib, name, reverse):
     ca, cb = hlib.describe_config(w["model"], pa), hlib.describe_config(w["model"], pb)
     routes = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
     parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=2)
+    if not reverse:
+        # ordered by the radix sort instead of pair by pair: the same table
+        hlib.set_option(B.OPT_PAIR_ORDER_WORK, 0)
+        try:
+            again = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY).get_boxes()
+        finally:
+            hlib.set_option(B.OPT_PAIR_ORDER_WORK, 32)
+        assert again.tobytes() == routes.get_boxes().tobytes()
     for rank in {max(a.world, b.world) - 1, min(a.world, b.world) - 1}:
         parity.dry_run_single_rank(hlib, w["model"], pa, pb, rank, box_samples=2)
 
