@@ -341,6 +341,56 @@ __global__ __launch_bounds__(256) void k_pair_rank(const PairRec* __restrict__ b
     if (part == 0) f(j, (uint64_t)before, bytes);
 }
 
+// The tile table: one lane per tile builds its record from the tile's descriptor.  Finding the
+// descriptor is a search in the table of tile bases; a workgroup's 256 consecutive tiles lie
+// between the descriptors of its first and of its last tile, which are the same for the whole
+// workgroup: those two searches run on the scalar unit (the bases are read through the constant
+// address space; ten dependent loads from the scalar cache instead of from L2), and a lane then
+// only searches between them, which mostly is no step at all.  nbox < 0: the number of boxes is
+// n_host; else it is read from *nbox and the kernel leaves when it exceeds `bound`.
+__global__ __launch_bounds__(256) void k_tile_table(const int64_t* __restrict__ tbase, const CopyDesc* __restrict__ descs,
+                                                    const uint64_t* nbox, int64_t n_host, int64_t bound, TileRef* __restrict__ tiles,
+                                                    int64_t cap)
+{
+    typedef const __attribute__((address_space(4))) int64_t* cbase_t;
+    const int64_t n = nbox ? (int64_t)*(const __attribute__((address_space(4))) uint64_t*)(uintptr_t)nbox : n_host;
+    if (nbox && n > bound) return;
+    const cbase_t tb = (cbase_t)(uintptr_t)tbase;
+    const int64_t nd = 3 * n;
+    const int64_t total = tb[nd] < cap ? tb[nd] : cap;
+    const int64_t t0 = (int64_t)blockIdx.x * 256;
+    if (t0 >= total) return;
+    const int64_t t1 = t0 + 255 < total ? t0 + 255 : total - 1;
+    auto last_not_above = [&](int64_t t) {   // the descriptor that holds tile t: last d with tb[d] <= t
+        int64_t lo = 0, hi = nd + 1;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (tb[mid] <= t) lo = mid + 1; else hi = mid;
+        }
+        return lo - 1;
+    };
+    const int64_t d_first = last_not_above(t0), d_last = last_not_above(t1);
+    const int64_t t = t0 + threadIdx.x;
+    // The 48-byte records of the workgroup go through LDS so that the table is written in whole
+    // lines: a lane storing its own record would touch every third 16-byte piece, and each of its
+    // three stores would open every line of the wavefront's stretch again.
+    static_assert(sizeof(TileRef) == 48, "three 16-byte vectors per record");
+    __shared__ __attribute__((aligned(16))) TileRef staged[256];
+    if (t < total) {
+        int64_t lo = d_first, hi = d_last + 1;    // the lane's own descriptor lies in [d_first, d_last]
+        while (hi - lo > 1) {
+            const int64_t mid = (lo + hi) >> 1;
+            if (tbase[mid] <= t) lo = mid; else hi = mid;
+        }
+        staged[threadIdx.x] = make_tile(descs[lo], (uint32_t)lo, (uint32_t)(t - tbase[lo]));
+    }
+    __syncthreads();
+    const uint32_t nvec = 3u * (uint32_t)(total - t0 < 256 ? total - t0 : 256);
+    const u32x4* from = reinterpret_cast<const u32x4*>(staged);
+    u32x4* to = reinterpret_cast<u32x4*>(tiles + t0);
+    for (uint32_t v = threadIdx.x; v < nvec; v += 256) to[v] = from[v];
+}
+
 // ---- exclusive prefix sum of n int64 values: out[i] = in[0] + ... + in[i-1] ----
 constexpr int SCAN_PER_LANE = 8;
 constexpr int SCAN_PER_GROUP = 256 * SCAN_PER_LANE;
@@ -603,6 +653,17 @@ public:
         const int64_t per = 256 / ORDER_GROUP;
         const int64_t blocks = (bound + per - 1) / per;
         hipLaunchKernelGGL((k_order_by_counting<Step, F>), dim3((unsigned)blocks), dim3(256), 0, stream_, recs, nbox, (uint32_t)bound, f);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
+    // tiles[t] for every tile t < min(tile_base[3n], cap), n = *nbox (skipped when n > bound) or,
+    // with nbox = nullptr, n = n_host.  `lanes` tiles are launched.
+    void tile_table(const int64_t* tile_base, const CopyDesc* descs, const uint64_t* nbox, int64_t n_host, int64_t bound,
+                    TileRef* tiles, int64_t cap, int64_t lanes)
+    {
+        if (lanes <= 0) return;
+        hipLaunchKernelGGL(k_tile_table, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, stream_, tile_base, descs, nbox, n_host,
+                           bound, tiles, cap);
         VPS_HIP_CHECK(hipGetLastError());
     }
 

@@ -52,7 +52,6 @@ struct plan_pair_rank {};
 struct plan_pair_place {};
 struct plan_copy_descs {};
 struct plan_rank_tables {};
-struct plan_tile_table {};
 struct coll_keys {};
 struct coll_group_key {};
 struct coll_flags {};
@@ -344,18 +343,10 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     // looks at anything, so that the whole plan needs one synchronisation.
     TileRef* tiles = nullptr;
     int64_t tiles_cap = 0;
-    auto tile_of = [=] VPS_LAMBDA(int64_t t, int64_t n, const int64_t* tbase, const CopyDesc* dd) {
-        const int64_t d = upper_bound_idx(tbase, 3 * n + 1, t) - 1;
-        return make_tile(dd[d], (uint32_t)d, (uint32_t)(t - tbase[d]));
-    };
     if (!routes_only && tile_hint > 0) {
         tiles_cap = tile_hint;
         tiles = be.template alloc<TileRef>(tiles_cap);
-        be.for_each(step::plan_tile_table(), tiles_cap, [=] VPS_LAMBDA(int64_t t) {
-            const int64_t n = (int64_t)*nbox;
-            if (n > ns || t >= tb[3 * n]) return;
-            tiles[t] = tile_of(t, n, tb, descs);
-        });
+        be.tile_table(tb, descs, nbox, 0, ns, tiles, tiles_cap, tiles_cap);
     }
 
     std::vector<uint64_t> hsum((size_t)SL.words());
@@ -613,8 +604,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     if (!routes_only && ntiles > tiles_cap) {
         be.free(tiles);
         tiles = be.template alloc<TileRef>(ntiles);
-        TileRef* tl = tiles;
-        be.for_each(step::plan_tile_table(), ntiles, [=] VPS_LAMBDA(int64_t t) { tl[t] = tile_of(t, n, tb, descs); });
+        be.tile_table(tb, descs, nullptr, n, 0, tiles, ntiles, ntiles);
         be.sync();
     }
     p.tiles = tiles;

@@ -154,6 +154,19 @@ public:
         for (int64_t i = 0; i < m; ++i) f(i);
     }
 
+    void tile_table(const int64_t* tile_base, const CopyDesc* descs, const uint64_t* nbox, int64_t n_host, int64_t bound,
+                    TileRef* tiles, int64_t cap, int64_t)
+    {
+        const int64_t n = nbox ? (int64_t)*nbox : n_host;
+        if (nbox && n > bound) return;
+        const int64_t total = tile_base[3 * n] < cap ? tile_base[3 * n] : cap;
+        int64_t d = 0;
+        for (int64_t t = 0; t < total; ++t) {
+            while (t >= tile_base[d + 1]) ++d;   // (descriptors without tiles are stepped over)
+            tiles[t] = make_tile(descs[d], (uint32_t)d, (uint32_t)(t - tile_base[d]));
+        }
+    }
+
     template <class Step, class F>
     void pair_rank_each(Step, const PairRec* bucket, const uint64_t* pstart, const uint64_t* pcount, int64_t n,
                         const uint64_t* work, uint64_t work_max, F f)
