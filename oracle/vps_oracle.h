@@ -21,10 +21,13 @@
  * Parity pins (tests/test_oracle_*.py): inverse property by brute force, replica counts,
  * an independent assemble-then-slice reshard in numpy, identity and round-trip transitions,
  * closed-form byte counts, the Figure 4 worked example, parameter counts.
- * parity unpinned: the replica source rule (orc_select_source) and the order of elements
- * inside a per-peer buffer (orc_piece_key, orc_recv_payload) are conventions of this repository;
- * the paper only says that the source is chosen by proximity (Section 4.3) and that slices are
- * packed per peer.  They are checked against a second, box-based formulation in numpy.
+ * parity unpinned by the paper: the replica source rule (orc_select_source), the placement of
+ * EP inside TP x DP (ep_placement = 1) and the order of elements inside a per-peer buffer
+ * (orc_piece_key, orc_recv_payload) are conventions of this repository; the paper only says that
+ * the source is chosen by proximity (Section 4.3), prints (TP, PP, DP, EP) tuples without a
+ * placement, and says that slices are packed per peer.  They are checked against examples
+ * evaluated by hand (tests/golden/declared_readings.txt) and against a second, box-based
+ * formulation in numpy.
  */
 #ifndef VPS_ORACLE_H
 #define VPS_ORACLE_H

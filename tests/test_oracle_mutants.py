@@ -31,6 +31,8 @@ MUTANTS = [
     ("TP shards in reverse order", "s->lo[x->tp_axis] = tp * s->ext[x->tp_axis];", "s->lo[x->tp_axis] = (c->p.tp - 1 - tp) * s->ext[x->tp_axis];"),
     ("expert block by modulo", "return expert / (c->m.experts / c->p.ep);", "return expert % c->p.ep;"),
     ("retain rule dropped", "if (r[k] == j) pick = k; /* the destination rank already holds it: retain */", "(void)j;"),
+    ("node preference ignored", "if (r[k] / a->p.gpus_per_node == node) idx[m++] = k;", "if (node >= 0) idx[m++] = k;"),
+    ("replica chosen by the destination's rank instead of its data-parallel index", "pick = idx[dpi % m];", "pick = idx[j % m];"),
     ("piece level ignores the end of the flat range", "if (unit >= v0 && unit + st[q] <= v1) break;", "if (unit >= v0) break;"),
     ("peer buffer orders kinds 0, 1, 2, 3", "const int kx = (x->id.kind + 3) & 3, ky = (y->id.kind + 3) & 3; /* kinds 1, 2, 3, then 0 */",
      "const int kx = x->id.kind, ky = y->id.kind;"),
@@ -45,7 +47,7 @@ MUTANTS = [
 ]
 
 PINS = ("textbook or bruteforce or assemble or closed_form or figure4 or figure6 or identity or region_algebra or moves_whole "
-        "or hand_table or hand_example or pieces or recv_payload")
+        "or hand_table or hand_example or pieces or recv_payload or source_rule")
 
 
 # The pins that are expected to notice each mistake first (running only those keeps the CPU suite
@@ -56,6 +58,8 @@ FIRST_PINS = {
     "padding quantum 4*D": "textbook and odd",
     "expert block by modulo": "hand_table",
     "retain rule dropped": "identity",
+    "node preference ignored": "source_rule",
+    "replica chosen by the destination's rank instead of its data-parallel index": "source_rule or region_algebra",
     "piece level ignores the end of the flat range": "pieces",
     "peer buffer orders kinds 0, 1, 2, 3": "recv_payload and gpt-tp-pp",
     "boxes of a peer buffer not aligned to 16 bytes": "recv_payload and gpt-odd",

@@ -559,6 +559,33 @@ def test_carved_expert_ranks_follow_the_hand_example():
     assert [c.rank_coords(r)["ddp"] for r in range(8)] == d["carved_tp2_dp4_ep2_dp_of_rank"]
 
 
+def test_source_rule_follows_the_hand_examples():
+    """The choice among replicas (itself, else its node's owners, else all; index = destination
+    data-parallel index modulo count) on the three examples evaluated by hand in
+    tests/golden/declared_readings.txt."""
+    d = _declared()
+    m = cf.TINY_GPT                       # 4 layers, hidden 16, ffn 32; fc1.w of layer 0 is tensor 9: (32, 16), TP on rows
+    fc1 = 1 + 0 * 12 + 8
+    assert list(oracle.Config(m, P(tp=1)).tensor_info(fc1)["shape"][2:]) == [m["ffn"], m["hidden"]]
+    for gpn in (2, 8):
+        a = oracle.Config(m, P(tp=2, pp=1, dp=2, zero=0, gpus_per_node=gpn))
+        b = oracle.Config(m, P(tp=1, pp=1, dp=4, zero=0, gpus_per_node=gpn))
+        for half, row in (("first", 3), ("second", 20)):
+            got = [oracle.select_source(a, b, j, 0, fc1, (0, 0, row, 5))[0] for j in range(4)]
+            assert got == d[f"select_tp2dp2_to_dp4_gpn{gpn}_{half}_half"], (gpn, half, got)
+    a = oracle.Config(m, P(tp=1, pp=2, dp=4, zero=0, gpus_per_node=4))
+    b = oracle.Config(m, P(tp=1, pp=1, dp=8, zero=0, gpus_per_node=4))
+    for layer in (0, 3):
+        t = 1 + layer * 12 + 8
+        got = [oracle.select_source(a, b, j, 1, t, (0, 0, 7, 2))[0] for j in range(8)]
+        assert got == d[f"select_pp2dp4_to_dp8_gpn4_layer{layer}"], (layer, got)
+    a = oracle.Config(m, P(tp=1, pp=1, dp=2, zero=0, gpus_per_node=8))
+    b = oracle.Config(m, P(tp=2, pp=1, dp=2, zero=0, gpus_per_node=8))
+    ln1 = 1                               # ln1.w of layer 0: a vector of `hidden` elements, replicated over TP
+    got = [oracle.select_source(a, b, j, 0, ln1, (0, 0, 0, 9))[0] for j in range(4)]
+    assert got == d["select_dp2_to_tp2dp2_gpn8_replicated"], got
+
+
 # ----------------------------------------------------------------------------- per-peer buffers
 
 @pytest.mark.parametrize("name,m,p", LAYOUT_CASES, ids=[c[0] for c in LAYOUT_CASES])
