@@ -47,7 +47,7 @@ MUTANTS = [
 ]
 
 PINS = ("textbook or bruteforce or assemble or closed_form or figure4 or figure6 or identity or region_algebra or moves_whole "
-        "or hand_table or hand_example or pieces or recv_payload or source_rule")
+        "or hand_table or hand_example or pieces or recv_payload or source_rule or written_out_by_hand")
 
 
 # The pins that are expected to notice each mistake first (running only those keeps the CPU suite
@@ -61,8 +61,8 @@ FIRST_PINS = {
     "node preference ignored": "source_rule",
     "replica chosen by the destination's rank instead of its data-parallel index": "source_rule or region_algebra",
     "piece level ignores the end of the flat range": "pieces",
-    "peer buffer orders kinds 0, 1, 2, 3": "recv_payload and gpt-tp-pp",
-    "boxes of a peer buffer not aligned to 16 bytes": "recv_payload and gpt-odd",
+    "peer buffer orders kinds 0, 1, 2, 3": "written_out_by_hand",
+    "boxes of a peer buffer not aligned to 16 bytes": "written_out_by_hand or (recv_payload and gpt-odd)",
     "expert ranks: ep and expert-dp digits swapped": "bruteforce and moe",
     "carved expert dp degree forgets tp": "hand_example or (textbook and carved)",
     "box serialised with the two inner axes swapped": "recv_payload and gpt-tp-pp",

@@ -669,3 +669,25 @@ def test_recv_payload_equals_the_box_based_formulation(name, m, pa, pb):
                     if i != j:
                         assert int(rb[i]) <= nbytes
                         assert (nbytes == 0) == (rb[i] == 0)
+
+
+def test_recv_payload_of_a_pipeline_merge_written_out_by_hand():
+    """A case in which order A13 can be written down without any box logic: (TP, PP, DP) = (1, 2, 1)
+    -> (1, 1, 1) without ZeRO.  Rank 0 keeps stage 0 and receives every tensor of stage 1 whole
+    from rank 1: the buffer is, for the kinds in the order 1, 2, 3, 0 and the tensors of stage 1 in
+    ascending id order, the tensor's words in row-major order, each tensor padded to 16 bytes."""
+    m = cf.TINY_GPT
+    a, b = oracle.Config(m, P(tp=1, pp=2, dp=1, zero=0)), oracle.Config(m, P(tp=1, pp=1, dp=1, zero=0))
+    got, seg = oracle.recv_payload(a, b, 0, seed=77, rank_salt=0x33, pad_byte=0xEE)
+    first = 1 + (m["layers"] // 2) * 12                      # first tensor of stage 1 (12 tensors per GPT layer)
+    want = []
+    for kind in (1, 2, 3, 0):
+        for t in range(first, a.num_tensors):
+            n = int(np.prod(a.tensor_info(t)["shape"]))
+            words = pattern.word(pattern.seed_for_rank(77, 0x33, 1), kind, t, np.arange(n, dtype=np.uint64))
+            raw = words.astype(np.uint16 if kind == 0 else np.uint32).tobytes()
+            want.append(raw + bytes([0xEE]) * ((-len(raw)) % 16))
+    want = np.frombuffer(b"".join(want), dtype=np.uint8)
+    assert list(seg) == [0, 0, len(want)]
+    assert np.array_equal(got, want)
+
