@@ -1,13 +1,12 @@
 // vps_backend_hip.h - device backend of the mapper/planner pipeline: one kernel lane per item,
-// wavefront prefix sums for compaction and scans, rocPRIM only for the radix sort of plans with
-// more boxes than the counting path takes.
+// wavefront ballots and prefix sums for compaction, scans and the radix sort.  No library
+// routines: everything that runs on the device is in these headers.
 #pragma once
 
 #include <cstdlib>
 #include <cstring>
 
 #include <hip/hip_runtime.h>
-#include <rocprim/rocprim.hpp>
 
 #include <algorithm>
 #include <atomic>
@@ -339,6 +338,83 @@ __global__ __launch_bounds__(256) void k_pair_rank(const PairRec* __restrict__ b
         }
     }
     if (part == 0) f(j, (uint64_t)before, bytes);
+}
+
+// ---- stable least-significant-digit radix sort of (64-bit key, 32-bit value) pairs, 8 bits per
+// pass.  A workgroup owns a tile of SORT_TILE consecutive pairs.  Pass = three launches: digit
+// counts per tile (k_sort_count) -> exclusive scan of the table laid out digit-major (all tiles'
+// counts of digit 0, then of digit 1, ...: the scanned entry is where the tile's first pair with
+// that digit goes) -> k_sort_scatter, which gives every pair its rank among the tile's pairs of
+// the same digit.  The rank keeps the input order: the tile is taken in rounds of 256 pairs; in a
+// round the lanes of a wavefront find the lanes with their digit by eight ballots (one per bit)
+// and count those below them, the wavefronts' counts per digit are added up in wavefront order
+// through LDS, and a per-digit counter carries on from round to round.
+constexpr int SORT_ROUNDS = 8;
+constexpr int SORT_TILE = 256 * SORT_ROUNDS;
+
+__global__ __launch_bounds__(256) void k_sort_count(const uint64_t* __restrict__ keys, int64_t n, int shift, int64_t ntiles,
+                                                    int64_t* __restrict__ table)
+{
+    __shared__ uint32_t hist[256];
+    hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * SORT_TILE;
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const int64_t i = base + r * 256 + threadIdx.x;
+        if (i < n) atomicAdd(&hist[(uint32_t)(keys[i] >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    table[(int64_t)threadIdx.x * ntiles + blockIdx.x] = hist[threadIdx.x];
+    if (blockIdx.x == 0 && threadIdx.x == 0) table[256 * ntiles] = 0;   // the scan's closing entry
+}
+
+__global__ __launch_bounds__(256) void k_sort_scatter(const uint64_t* __restrict__ keys, const uint32_t* __restrict__ vals,
+                                                      int64_t n, int shift, int64_t ntiles, const int64_t* __restrict__ start,
+                                                      uint64_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out)
+{
+    __shared__ uint32_t seen[256];        // pairs of the tile with this digit in the rounds so far
+    __shared__ uint32_t wave_cnt[4][256]; // this round: pairs with this digit per wavefront
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    seen[threadIdx.x] = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) wave_cnt[w][threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t first = start[(int64_t)threadIdx.x * ntiles + blockIdx.x];   // thread d: where digit d of this tile starts
+    __shared__ int64_t digit_start[256];
+    digit_start[threadIdx.x] = first;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * SORT_TILE;
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const int64_t i = base + r * 256 + threadIdx.x;
+        const bool valid = i < n;
+        const uint64_t key = valid ? keys[i] : 0;
+        const uint32_t digit = (uint32_t)(key >> shift) & 255u;
+        // lanes of this wavefront with the same digit
+        uint64_t peers = __ballot(valid ? 1 : 0);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const uint64_t m = __ballot((digit >> b) & 1u);
+            peers &= ((digit >> b) & 1u) ? m : ~m;
+        }
+        const uint32_t below = (uint32_t)__popcll(peers & ((1ull << lane) - 1ull));
+        if (valid && below == 0) wave_cnt[wave][digit] = (uint32_t)__popcll(peers);   // the first lane of its digit
+        __syncthreads();
+        if (valid) {
+            uint32_t rank = seen[digit] + below;
+            for (unsigned w = 0; w < wave; ++w) rank += wave_cnt[w][digit];
+            const int64_t to = digit_start[digit] + rank;
+            keys_out[to] = key;
+            vals_out[to] = vals[i];
+        }
+        __syncthreads();
+        {   // thread d closes digit d of this round
+            uint32_t add = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) { add += wave_cnt[w][threadIdx.x]; wave_cnt[w][threadIdx.x] = 0; }
+            seen[threadIdx.x] += add;
+        }
+        __syncthreads();
+    }
 }
 
 // The tile table: one lane per tile builds its record from the tile's descriptor.  Finding the
@@ -749,12 +825,20 @@ public:
         if (n <= 1) return;
         uint64_t* k2 = alloc<uint64_t>(n);
         uint32_t* v2 = alloc<uint32_t>(n);
-        size_t tmp_bytes = 0;
-        VPS_HIP_CHECK(rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, (unsigned)bits, stream_));
-        void* tmp = alloc<char>((int64_t)tmp_bytes);
-        VPS_HIP_CHECK(rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, k2, vals, v2, (size_t)n, 0, (unsigned)bits, stream_));
-        free(tmp); free(keys); free(vals);
-        keys = k2; vals = v2;
+        const int64_t ntiles = (n + SORT_TILE - 1) / SORT_TILE;
+        int64_t* count = alloc<int64_t>(256 * ntiles + 1);
+        int64_t* start = alloc<int64_t>(256 * ntiles + 1);
+        for (int shift = 0; shift < bits; shift += 8) {
+            hipLaunchKernelGGL(k_sort_count, dim3((unsigned)ntiles), dim3(256), 0, stream_, (const uint64_t*)keys, n, shift, ntiles, count);
+            VPS_HIP_CHECK(hipGetLastError());
+            exclusive_scan(count, start, 256 * ntiles);
+            hipLaunchKernelGGL(k_sort_scatter, dim3((unsigned)ntiles), dim3(256), 0, stream_, (const uint64_t*)keys,
+                               (const uint32_t*)vals, n, shift, ntiles, (const int64_t*)start, k2, v2);
+            VPS_HIP_CHECK(hipGetLastError());
+            std::swap(keys, k2);
+            std::swap(vals, v2);
+        }
+        free(count); free(start); free(k2); free(v2);
     }
 
     // The host array must stay valid until the next sync(); builders keep it alive.

@@ -3,8 +3,8 @@
 // backend interface:
 //
 //   for_each(n, f)            run f(i) for i in [0, n)      -> one HIP kernel lane per item
-//   exclusive_scan(in,out,n)  out[i] = sum in[0..i), n+1 long -> rocPRIM device scan
-//   sort_pairs(keys,vals,n)   stable ascending by 64-bit key -> rocPRIM device radix sort
+//   exclusive_scan(in,out,n)  out[i] = sum in[0..i), n+1 long -> workgroup scans (k_scan_*)
+//   sort_pairs(keys,vals,n)   stable ascending by 64-bit key -> radix sort (k_sort_count, k_sort_scatter)
 //
 // The product library instantiates it with the HIP backend only.  The test-suite also
 // instantiates it with a sequential CPU backend to exercise the per-item code under bounds
