@@ -621,9 +621,12 @@ def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05,
 
 
 def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 << 22, box_samples=16, log=print,
-                           round_trip=True):
+                           round_trip=True, staged_budget=None):
     """Every virtual rank resident at full size: one vps_apply_transition(rank=-1) call, all
-    destination buffers against the oracle (layout-B fill of the same coordinate hash)."""
+    destination buffers against the oracle (layout-B fill of the same coordinate hash).  With
+    staged_budget the transition then runs once more through vps_stage_exchange and
+    vps_apply_transition_staged under that per-rank budget, into fresh destination buffers that
+    must equal the ones just compared with the oracle byte for byte."""
     import time
     t0 = time.time()
     a, b = oracle.Config(model, pa), oracle.Config(model, pb)
@@ -669,6 +672,21 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
                     raise AssertionError(f"dst ({j},{buf}): {bad.size} wrong elements in chunk at {o}, first {o + bad[0]}")
                 checked += m
     log(f"  {checked} destination elements compared with the oracle ({time.time() - t0:.1f}s)")
+    if staged_budget is not None:
+        sp = lib.stage_exchange(plan, staged_budget)
+        sinfo = sp.info()
+        assert sinfo["scratch_needed"] <= info["scratch_needed"]
+        sscratch = mem.alloc(sinfo["scratch_needed"])
+        again = {k: mem.alloc(len(v)) for k, v in dst.items()}
+        lib.apply_transition_staged(sp, [mem.ptr(src[(r, buf)]) for r in range(a.world) for buf in range(8)],
+                                    [mem.ptr(again[(j, buf)]) for j in range(b.world) for buf in range(8)],
+                                    mem.ptr(sscratch), sinfo["scratch_needed"])
+        mem.sync()
+        for k, v in dst.items():
+            assert mem.equal(again[k], v), f"staged exchange differs from the one-shot result in buffer {k}"
+        log(f"  staged: {sinfo['num_stages']} stages over {sinfo['num_steps']} steps, scratch {sinfo['scratch_needed'] >> 20} MiB "
+            f"(one shot {info['scratch_needed'] >> 20} MiB), same bytes as the one-shot transition ({time.time() - t0:.1f}s)")
+        del sscratch, again, sp
     if round_trip:
         # A -> B -> A gives back every payload element of every source buffer (replicas hold the
         # same bits under the seeded pattern, so the choice of source does not show)

@@ -168,7 +168,7 @@ def test_gpt1p3b_all_ranks_full_size(lib):
     w = cf.WORKLOADS["gpt1p3b"]
     print("\ngpt1p3b all 32 ranks", flush=True)
     out = parity.run_all_ranks_fullsize(lib, parity.GpuMem(), w["model"], w["src"], w["dst"],
-                                        seed=cf.seed_of("gpt1p3b"), fraction=FRACTION,
+                                        seed=cf.seed_of("gpt1p3b"), fraction=FRACTION, staged_budget=512 << 20,
                                         log=lambda s: print(s, flush=True))
     assert out["checked"] > 0
 
