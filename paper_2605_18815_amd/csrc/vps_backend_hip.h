@@ -143,14 +143,16 @@ __global__ __launch_bounds__(256) void k_plan_emit(PlanCtx pc, int mode, int thr
 {
     // a workgroup walks many lanes: millions of short-lived workgroups would be bound by the rate
     // at which the hardware starts them
-    for (int64_t lane = (int64_t)blockIdx.x * 256 + threadIdx.x; lane < lanes; lane += (int64_t)gridDim.x * 256)
-        plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
+    // (`lanes` counts the callers: 2^plan_part_bits(mode) per item lane)
+    const int pb = plan_part_bits(mode);
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < lanes; e += (int64_t)gridDim.x * 256)
+        plan_lane_boxes(pc, mode, e >> pb, [&](const vps_box& b) {
             const uint64_t k = take_box_slot(counter);
             if (k < cap) {
                 raw[k] = b;
                 recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
             }
-        });
+        }, (int)(e & ((1 << pb) - 1)), 1 << pb);
 }
 
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
@@ -259,14 +261,16 @@ __global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, 
 {
     uint64_t n = *count;
     if (n > list_cap) return;   // the list overflowed: the caller plans again in one launch
+    const int pb = plan_part_bits(mode);
+    n <<= pb;
     for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256)
-        plan_lane_boxes(pc, mode, (int64_t)list[i], [&](const vps_box& b) {
+        plan_lane_boxes(pc, mode, (int64_t)list[i >> pb], [&](const vps_box& b) {
             const uint64_t k = take_box_slot(counter);
             if (k < cap) {
                 raw[k] = b;
                 recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
             }
-        });
+        }, (int)(i & ((1u << pb) - 1)), 1 << pb);
 }
 
 // Place of every box in the send and in the receive order by counting (order_by_counting).  A
@@ -437,15 +441,18 @@ __global__ __launch_bounds__(256) void k_tile_table(const int64_t* __restrict__ 
     const int64_t t0 = (int64_t)blockIdx.x * 256;
     if (t0 >= total) return;
     const int64_t t1 = t0 + 255 < total ? t0 + 255 : total - 1;
-    auto last_not_above = [&](int64_t t) {   // the descriptor that holds tile t: last d with tb[d] <= t
-        int64_t lo = 0, hi = nd + 1;
+    auto last_not_above = [&](int64_t t, int64_t lo) {   // the descriptor that holds tile t: last d >= lo - 1 with tb[d] <= t
+        int64_t hi = nd + 1;
         while (lo < hi) {
             const int64_t mid = (lo + hi) >> 1;
             if (tb[mid] <= t) lo = mid + 1; else hi = mid;
         }
         return lo - 1;
     };
-    const int64_t d_first = last_not_above(t0), d_last = last_not_above(t1);
+    // (a descriptor of a long run has thousands of tiles: mostly the workgroup's last tile lies in
+    // the same one, which a single load shows)
+    const int64_t d_first = last_not_above(t0, 0);
+    const int64_t d_last = tb[d_first + 1] > t1 ? d_first : last_not_above(t1, d_first + 2);
     const int64_t t = t0 + threadIdx.x;
     // The 48-byte records of the workgroup go through LDS so that the table is written in whole
     // lines: a lane storing its own record would touch every third 16-byte piece, and each of its
@@ -494,15 +501,21 @@ __global__ __launch_bounds__(256) void k_scan_one_group(const int64_t* in, int64
     scan_by_one_group(in, out, n);
 }
 
-// The same over the first mult * (*count) + 1 entries (at most n; nothing happens beyond), and
-// then, in the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.
+// The same over the first mult * (*count) + 1 entries (at most n; nothing happens beyond); then
+// the nrows rows of row_len counters at `rows` become their own exclusive prefix sums, in place;
+// and then, in the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.
 template <class Step, class F>
 __global__ __launch_bounds__(256) void k_scan_counted_then_each(const int64_t* in, int64_t* out, int64_t n,
-                                                                const uint64_t* count, int mult, int64_t m, F f)
+                                                                const uint64_t* count, int mult, int64_t* rows,
+                                                                int64_t row_len, int nrows, int64_t m, F f)
 {
     const int64_t len = (int64_t)*count * mult + 1;
     if (len > n) return;
     scan_by_one_group(in, out, len);
+    for (int r = 0; r < nrows; ++r) {
+        __syncthreads();   // the carries of the scan before are free again
+        scan_by_one_group(rows + r * row_len, rows + r * row_len, row_len);
+    }
     __syncthreads();   // the sums are in memory for every lane of the workgroup
     for (int64_t i = threadIdx.x; i < m; i += 256) f(i);
 }
@@ -715,9 +728,10 @@ public:
     // f(i) for i in [0, m).
     template <class Step, class F>
     void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
-                                          int mult, int64_t m, F f)
+                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f)
     {
-        hipLaunchKernelGGL((k_scan_counted_then_each<Step, F>), dim3(1), dim3(256), 0, stream_, in, out, bound, count, mult, m, f);
+        hipLaunchKernelGGL((k_scan_counted_then_each<Step, F>), dim3(1), dim3(256), 0, stream_, in, out, bound, count, mult, rows,
+                           row_len, nrows, m, f);
         VPS_HIP_CHECK(hipGetLastError());
     }
 
@@ -795,7 +809,10 @@ public:
             free(list);
             return true;
         }
-        hipLaunchKernelGGL(k_plan_emit, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, through ? 1 : 0, lanes,
+        const int64_t callers = lanes << plan_part_bits(mode);
+        blocks = (callers + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        hipLaunchKernelGGL(k_plan_emit, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, through ? 1 : 0, callers,
                            raw, recs, cap, (unsigned long long*)counter);
         VPS_HIP_CHECK(hipGetLastError());
         return false;

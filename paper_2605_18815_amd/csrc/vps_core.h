@@ -177,25 +177,34 @@ VPS_HD int64_t map_group_item(const ParConst& P, int32_t tensor, int32_t kind)
 // aligned and the unit still fits, descend again near the end.  Calls emit(start, axis, count)
 // for each box: it begins at linear position `start`, spans `count` units of `axis` and is
 // full on all finer axes.
+// (Entry q of a four-entry table by selects: an array indexed at run time would be kept in
+// scratch memory, and the planner's kernels are chains of dependent accesses.)
+template <class V>
+VPS_HD V pick4(int q, V a0, V a1, V a2, V a3) { return q == 0 ? a0 : (q == 1 ? a1 : (q == 2 ? a2 : a3)); }
+
 template <class U, class Emit>
 VPS_HD int split_linear_range_t(const int64_t* n, U v0, U v1, Emit emit)
 {
-    U st[4];
-    st[3] = 1;
-    st[2] = (U)n[3];
-    st[1] = st[2] * (U)n[2];
-    st[0] = st[1] * (U)n[1];
+    const U n0 = (U)n[0], n1 = (U)n[1], n2 = (U)n[2], n3 = (U)n[3];
+    const U st3 = 1, st2 = n3, st1 = st2 * n2, st0 = st1 * n1;
     int count = 0;
     U cur = v0;
     while (cur < v1) {
-        int q = 3;
-        while (q > 0 && cur % st[q - 1] == 0 && v1 - cur >= st[q - 1]) --q;
-        const U cq = (cur / st[q]) % (U)n[q];
-        U cnt = (U)n[q] - cq;
-        const U fit = (v1 - cur) / st[q];
+        int q = 3;   // the coarsest axis on whose unit `cur` is aligned and whose unit still fits
+        if (cur % st2 == 0 && v1 - cur >= st2) {
+            q = 2;
+            if (cur % st1 == 0 && v1 - cur >= st1) {
+                q = 1;
+                if (cur % st0 == 0 && v1 - cur >= st0) q = 0;
+            }
+        }
+        const U sq = pick4(q, st0, st1, st2, st3), nq = pick4(q, n0, n1, n2, n3);
+        const U cq = (cur / sq) % nq;
+        U cnt = nq - cq;
+        const U fit = (v1 - cur) / sq;
         if (fit < cnt) cnt = fit;
         emit((uint64_t)cur, q, (uint64_t)cnt);
-        cur += cnt * st[q];
+        cur += cnt * sq;
         ++count;
     }
     return count;
@@ -238,15 +247,24 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
 
     // the shard's box in global coordinates
     int32_t slo[4], sext[4];
-    for (int a = 0; a < 4; ++a) { slo[a] = 0; sext[a] = x.shape[a]; }
-    if (x.tp_axis >= 0) {
-        sext[x.tp_axis] = x.shape[x.tp_axis] / TPg;
-        slo[x.tp_axis] = tp * sext[x.tp_axis];
+    VPS_UNROLL(4)
+    for (int a = 0; a < 4; ++a) {
+        slo[a] = 0; sext[a] = x.shape[a];
+        if (a == x.tp_axis) { sext[a] = x.shape[a] / TPg; slo[a] = tp * sext[a]; }
     }
-    // storage order of the axes, outermost first
-    int order[4] = { 0, 1, 2, 3 };
-    if (P.expert_layout == 1 && x.perm == PERM_GATE_UP) { order[1] = 3; order[2] = 1; order[3] = 2; }
-    if (P.expert_layout == 1 && x.perm == PERM_DOWN) { order[2] = 3; order[3] = 2; }
+    // storage order of the axes, outermost first: 0,1,2,3; gate/up experts stored transposed
+    // 0,3,1,2; down experts 0,1,3,2.  ord_q is the axis at position q, e_q the shard's extent there.
+    const int mode = (P.expert_layout == 1 && x.perm == PERM_GATE_UP) ? 1 : ((P.expert_layout == 1 && x.perm == PERM_DOWN) ? 2 : 0);
+    const int ord1 = mode == 1 ? 3 : 1, ord2 = mode == 1 ? 1 : (mode == 2 ? 3 : 2), ord3 = mode == 0 ? 3 : 2;
+    const int32_t e0 = sext[0], e1 = mode == 1 ? sext[3] : sext[1];
+    const int32_t e2 = mode == 1 ? sext[1] : (mode == 2 ? sext[3] : sext[2]), e3 = mode == 0 ? sext[3] : sext[2];
+    // the entry of tensor axis a (a constant wherever this is called) in a table kept in storage order
+    auto of_axis = [mode](int a, auto v0, auto v1, auto v2, auto v3) {
+        if (a == 0) return v0;
+        if (a == 1) return mode == 1 ? v2 : v1;
+        if (a == 2) return mode == 0 ? v2 : v3;
+        return mode == 1 ? v1 : (mode == 2 ? v2 : v3);
+    };
     const bool blocked = x.blk_axis >= 0 && P.qkv_layout == 1;
     const int nblk = blocked ? 3 : 1;
 
@@ -259,7 +277,10 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
             bl = b == 0 ? P.q_per_g : 1;
         }
         int64_t n[4];
-        for (int q = 0; q < 4; ++q) n[q] = (blocked && order[q] == x.blk_axis) ? bl : sext[order[q]];
+        n[0] = (blocked && 0 == x.blk_axis) ? bl : e0;
+        n[1] = (blocked && ord1 == x.blk_axis) ? bl : e1;
+        n[2] = (blocked && ord2 == x.blk_axis) ? bl : e2;
+        n[3] = (blocked && ord3 == x.blk_axis) ? bl : e3;
         const uint64_t bvol = (uint64_t)n[0] * (uint64_t)n[1] * (uint64_t)n[2] * (uint64_t)n[3];
         const uint64_t lo = u0 > bbase ? u0 : bbase;
         const uint64_t hi = u1 < bbase + bvol ? u1 : bbase + bvol;
@@ -270,15 +291,22 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
                 [&](uint64_t start, int axis, uint64_t cnt) {
                     vps_piece p;
                     p.tensor = t; p.rank = rank; p.kind = kind; p.buf = x.group * 4 + kind;
+                    // coordinates and extents of the piece along the storage positions
+                    int32_t cq[4], xq[4];
                     uint64_t rem = start;
+                    VPS_UNROLL(4)
                     for (int q = 0; q < 4; ++q) {
-                        const int a = order[q];
-                        const int64_t cq = bvol <= 0xffffffffull ? (int64_t)((uint32_t)rem / (uint32_t)st[q])
-                                                                 : (int64_t)(rem / (uint64_t)st[q]);
-                        rem -= (uint64_t)cq * (uint64_t)st[q];
-                        p.lo[a] = slo[a] + ((blocked && a == x.blk_axis) ? bo : 0) + (int32_t)cq;
-                        p.ext[a] = q < axis ? 1 : (q == axis ? (int32_t)cnt : (int32_t)n[q]);
-                        p.stride[a] = st[q];
+                        const int64_t c = bvol <= 0xffffffffull ? (int64_t)((uint32_t)rem / (uint32_t)st[q])
+                                                                : (int64_t)(rem / (uint64_t)st[q]);
+                        rem -= (uint64_t)c * (uint64_t)st[q];
+                        cq[q] = (int32_t)c;
+                        xq[q] = q < axis ? 1 : (q == axis ? (int32_t)cnt : (int32_t)n[q]);
+                    }
+                    VPS_UNROLL(4)
+                    for (int a = 0; a < 4; ++a) {
+                        p.lo[a] = slo[a] + ((blocked && a == x.blk_axis) ? bo : 0) + of_axis(a, cq[0], cq[1], cq[2], cq[3]);
+                        p.ext[a] = of_axis(a, xq[0], xq[1], xq[2], xq[3]);
+                        p.stride[a] = of_axis(a, st[0], st[1], st[2], st[3]);
                     }
                     p.off = (int64_t)(tl.start + bbase + start - r0);
                     f(p);
@@ -584,9 +612,11 @@ VPS_HD bool plan_group_lane_check(const PlanCtx& c, const PlanGroupLanes& g, int
 
 // The routed boxes of one item: the pieces of the destination item intersected with the pieces
 // of the source rank that serves the slot.  Calls f(box) for each non-empty intersection (lo
-// corners ascending within one pair of pieces only); returns their number.
+// corners ascending within one pair of pieces only); returns their number.  With parts > 1 only
+// the destination pieces number part, part + parts, ... are taken: the item's work split over
+// `parts` callers.
 template <class F>
-VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f)
+VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f, int part = 0, int parts = 1)
 {
     const ParConst& A = c.A;
     const ParConst& B = c.B;
@@ -597,8 +627,9 @@ VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f)
     if (c.rank >= 0 && dst_rank != c.rank && src != c.rank) return 0;
     const RankCoord cs = decode_rank(A, src);
     const int32_t tps = x.group ? cs.etp : cs.tp, ds = x.group ? cs.edp : cs.ddp;
-    int n = 0;
+    int n = 0, dpi = 0;
     map_item_each_piece(c.mb, t, kind, tpb, db, [&](const vps_piece& dp) {
+        if (parts > 1 && (dpi++ & (parts - 1)) != part) return;
         map_item_each_piece(c.ma, t, kind, tps, ds, [&](const vps_piece& sp) {
             vps_box b;
             for (int a = 0; a < 4; ++a) {
@@ -626,12 +657,20 @@ VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f)
 }
 
 template <class F>
-VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f)
+VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f, int part = 0, int parts = 1)
 {
     LaneItem it;
     if (!plan_lane_decode(c, mode, lane, it)) return 0;
-    return plan_item_boxes(c, it, f);
+    return plan_item_boxes(c, it, f, part, parts);
 }
+
+// A single-rank plan is a few hundred items of which a handful are cut into many pieces (the
+// tensors that a data-parallel range begins or ends in), and the pieces of the source are made
+// again for every piece of the destination: the item with the most pieces is the length of the
+// whole launch.  So such a plan gives every item 2^PLAN_PART_BITS callers, one per residue of the
+// destination piece's number.  All-ranks plans have items enough to fill the chip as they are.
+constexpr int PLAN_PART_BITS = 3;
+VPS_HD int plan_part_bits(int mode) { return mode == PLAN_ALL ? 0 : PLAN_PART_BITS; }
 
 VPS_HD uint64_t box_volume(const vps_box& b)
 {
@@ -974,32 +1013,36 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
     }
     if (!active) { d.ntiles = 0; return; }
 
-    // Collapse: drop unit axes, order by destination stride (largest first), merge axes that
-    // are contiguous on both sides.
-    int64_t e[4]; int n = 0;
-    int64_t s2[4], d2[4];
-    for (int a = 0; a < 4; ++a)
-        if (b.ext[a] != 1) { e[n] = b.ext[a]; s2[n] = ss[a]; d2[n] = ds[a]; ++n; }
-    for (int i = 1; i < n; ++i)  // insertion sort, descending destination stride
-        for (int k = i; k > 0 && d2[k - 1] < d2[k]; --k) {
-            int64_t t;
-            t = e[k]; e[k] = e[k - 1]; e[k - 1] = t;
-            t = s2[k]; s2[k] = s2[k - 1]; s2[k - 1] = t;
-            t = d2[k]; d2[k] = d2[k - 1]; d2[k - 1] = t;
-        }
+    // Collapse: drop unit axes, order by destination stride (largest first, equal strides in axis
+    // order), merge axes that are contiguous on both sides.  Written so that every index is a
+    // constant once the loops are unrolled: arrays indexed at run time live in scratch memory,
+    // and the planner's kernels are chains of dependent accesses.
+    struct Axis { int64_t e, s, d; int32_t i; bool unit; };
+    Axis x[4];
+    VPS_UNROLL(4)
+    for (int a = 0; a < 4; ++a) { x[a].e = b.ext[a]; x[a].s = ss[a]; x[a].d = ds[a]; x[a].i = a; x[a].unit = b.ext[a] == 1; }
+    auto in_order = [](Axis& p, Axis& q) {   // p stands before q: exchange them if q belongs first
+        const bool q_first = !q.unit && (p.unit || q.d > p.d || (q.d == p.d && q.i < p.i));
+        if (q_first) { const Axis t = p; p = q; q = t; }
+    };
+    in_order(x[0], x[1]); in_order(x[2], x[3]); in_order(x[0], x[2]); in_order(x[1], x[3]); in_order(x[1], x[2]);
+    Axis o0, o1, o2, o3;   // the merged axes, the innermost in o3; unused outer ones have extent 1
+    o0.e = o1.e = o2.e = o3.e = 1; o0.s = o1.s = o2.s = o3.s = 0; o0.d = o1.d = o2.d = o3.d = 0;
     int m = 0;
-    for (int i = 0; i < n; ++i) {
+    VPS_UNROLL(4)
+    for (int i = 0; i < 4; ++i) {
+        if (x[i].unit) continue;
         // (extents stay below 2^31: a longer contiguous stretch is kept as rows of a 2-D box)
-        if (m > 0 && s2[m - 1] == s2[i] * e[i] && d2[m - 1] == d2[i] * e[i] && e[m - 1] * e[i] < ((int64_t)1 << 31)) {
-            e[m - 1] *= e[i]; s2[m - 1] = s2[i]; d2[m - 1] = d2[i];
+        if (m > 0 && o3.s == x[i].s * x[i].e && o3.d == x[i].d * x[i].e && o3.e * x[i].e < ((int64_t)1 << 31)) {
+            o3.e *= x[i].e; o3.s = x[i].s; o3.d = x[i].d;
         } else {
-            e[m] = e[i]; s2[m] = s2[i]; d2[m] = d2[i]; ++m;
+            o0 = o1; o1 = o2; o2 = o3; o3 = x[i]; ++m;
         }
     }
-    for (int a = 0; a < 4; ++a) { d.ext[a] = 1; d.sstr[a] = 0; d.dstr[a] = 0; }
-    for (int i = 0; i < m; ++i) {
-        d.ext[4 - m + i] = (uint32_t)e[i]; d.sstr[4 - m + i] = s2[i]; d.dstr[4 - m + i] = d2[i];
-    }
+    d.ext[0] = (uint32_t)o0.e; d.sstr[0] = o0.s; d.dstr[0] = o0.d;
+    d.ext[1] = (uint32_t)o1.e; d.sstr[1] = o1.s; d.dstr[1] = o1.d;
+    d.ext[2] = (uint32_t)o2.e; d.sstr[2] = o2.s; d.dstr[2] = o2.d;
+    d.ext[3] = (uint32_t)o3.e; d.sstr[3] = o3.s; d.dstr[3] = o3.d;
     if (m == 0) { d.sstr[3] = 1; d.dstr[3] = 1; }
 
     const uint64_t vol = (uint64_t)d.ext[0] * d.ext[1] * d.ext[2] * d.ext[3];
@@ -1047,11 +1090,13 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         // transposes of XPOSE_T x XPOSE_T element blocks staged through LDS.
         d.mode = MODE_XPOSE;
         d.xa = (d.sstr[2] == 1 && d.ext[2] > 1) ? 2u : ((d.sstr[1] == 1 && d.ext[1] > 1) ? 1u : 0u);
-        const uint64_t na = (d.ext[d.xa] + XPOSE_T - 1) / XPOSE_T, nb = (d.ext[3] + XPOSE_T - 1) / XPOSE_T;
+        const uint32_t ext_xa = d.xa == 2u ? d.ext[2] : (d.xa == 1u ? d.ext[1] : d.ext[0]);   // (no run-time index, see above)
+        const int64_t dstr_xa = d.xa == 2u ? d.dstr[2] : (d.xa == 1u ? d.dstr[1] : d.dstr[0]);
+        const uint64_t na = (ext_xa + XPOSE_T - 1) / XPOSE_T, nb = (d.ext[3] + XPOSE_T - 1) / XPOSE_T;
         d.chunks_per_row = (uint32_t)na;
         d.vec_window = (uint32_t)nb;
-        d.rows_per_tile = xpose_shape ? xpose_shape : xpose_auto_shape(d.sstr[3] * (int64_t)d.es, d.dstr[d.xa] * (int64_t)d.es);
-        d.ntiles = clamp_tiles(vol / d.ext[d.xa] / d.ext[3] * na * nb);
+        d.rows_per_tile = xpose_shape ? xpose_shape : xpose_auto_shape(d.sstr[3] * (int64_t)d.es, dstr_xa * (int64_t)d.es);
+        d.ntiles = clamp_tiles(vol / ext_xa / d.ext[3] * na * nb);
     } else {
         d.mode = MODE_ELEM;
         uint64_t per = tile_bytes / (4 * d.es);

@@ -292,6 +292,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     int64_t* tb = be.template alloc<int64_t>(3 * ns + 1);
     const uint64_t* nbox = sum + SUM_NBOXES;
     fc.descs = descs; fc.ntiles = ntl;
+    uint64_t* rank_rows = sum + SL.rank_tables();
     be.order_by_counting_each(step::plan_order_by_counting(), recs, nbox, ns, [=] VPS_LAMBDA(uint32_t k, const OrderPlace& o, uint32_t part) {
         if (part > 2) return;   // three lanes go on, one per copy operation
         const int64_t n = (int64_t)*nbox;
@@ -308,6 +309,10 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             if (o.idx_r == n - 1) gr[n] = o.gpos_r + order_recv_bytes(rec);
             if (k == 0) ntl[3 * n] = 0;
             account_box(fc, b);
+            // boxes per source and per destination rank, in the first two rows of the rank
+            // tables: their prefix sums are every rank's first box in the two orders
+            be_atomic_add(rank_rows + b.src_rank, 1);
+            be_atomic_add(rank_rows + (W + 1) + b.dst_rank, 1);
         }
         describe_box_op(fc, b, (int)part, part * n + (part == OP_UNPACK ? o.idx_r : o.idx_s));
     });
@@ -334,8 +339,19 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         rt[5 * (W + 1) + r] = tbase[n + fs];
         rt[6 * (W + 1) + r] = tbase[2 * n + fr];
     };
-    be.exclusive_scan_counted_then_each(step::plan_rank_tables(), ntl, tb, 3 * ns + 1, nbox, 3, W + 1, [=] VPS_LAMBDA(int64_t r) {
-        rank_row(r, (int64_t)*nbox, sorted, rperm, gs, gr, tb);
+    be.exclusive_scan_counted_then_each(step::plan_rank_tables(), ntl, tb, 3 * ns + 1, nbox, 3, rt, W + 1, 2, W + 1, [=] VPS_LAMBDA(int64_t r) {
+        // (rows 0 and 1 hold the first boxes by now: the counts of the ordering pass, summed)
+        const int64_t n = (int64_t)*nbox;
+        if (n == 0) {   // nothing is routed at all: no box has written the cumulative positions
+            for (int c = 2; c < 7; ++c) rt[c * (W + 1) + r] = 0;
+            return;
+        }
+        const int64_t fs = rt[0 * (W + 1) + r], fr = rt[1 * (W + 1) + r];
+        rt[2 * (W + 1) + r] = (int64_t)gs[fs];
+        rt[3 * (W + 1) + r] = (int64_t)gr[fr];
+        rt[4 * (W + 1) + r] = tb[fs];
+        rt[5 * (W + 1) + r] = tb[n + fs];
+        rt[6 * (W + 1) + r] = tb[2 * n + fr];
     });
 
     // (4) the tile table.  Its size is only known on the device so far; when the caller has seen

@@ -132,25 +132,30 @@ public:
     bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
                    uint64_t*, bool)
     {
-        const int64_t lanes = plan_num_lanes(pc, mode);
-        for (int64_t lane = 0; lane < lanes; ++lane)
-            plan_lane_boxes(pc, mode, lane, [&](const vps_box& b) {
+        const int pb = plan_part_bits(mode);
+        const int64_t callers = plan_num_lanes(pc, mode) << pb;
+        for (int64_t e = 0; e < callers; ++e)
+            plan_lane_boxes(pc, mode, e >> pb, [&](const vps_box& b) {
                 const uint64_t k = (*counter)++;
                 if (k < cap) {
                     raw[k] = b;
                     recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through);
                 }
-            });
+            }, (int)(e & ((1 << pb) - 1)), 1 << pb);
         return false;
     }
 
     template <class Step, class F>
     void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
-                                          int mult, int64_t m, F f)
+                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f)
     {
         const int64_t len = (int64_t)*count * mult + 1;
         if (len > bound) return;
         exclusive_scan(in, out, len - 1);
+        for (int r = 0; r < nrows; ++r) {
+            int64_t run = 0;
+            for (int64_t i = 0; i < row_len; ++i) { const int64_t v = rows[r * row_len + i]; rows[r * row_len + i] = run; run += v; }
+        }
         for (int64_t i = 0; i < m; ++i) f(i);
     }
 
