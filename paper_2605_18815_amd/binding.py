@@ -60,10 +60,18 @@ class VpsError(RuntimeError):
 
 
 def model_desc(m):
+    """The vps_model_desc of a dict of its fields (a struct made earlier passes through: callers
+    that describe the same model again and again build it once)."""
+    if isinstance(m, ModelDesc):
+        return m
     return ModelDesc(**{k: int(m[k]) for k in MODEL_FIELDS})
 
 
 def parallel_desc(p):
+    """The vps_parallel_desc of a dict of its fields (`zero` is accepted for `zero_stage`); a
+    struct made earlier passes through."""
+    if isinstance(p, ParallelDesc):
+        return p
     d = dict(p)
     if "zero" in d:
         d["zero_stage"] = d.pop("zero")

@@ -422,12 +422,20 @@ __global__ __launch_bounds__(256) void k_sort_scatter(const uint64_t* __restrict
 }
 
 // The tile table: one lane per tile builds its record from the tile's descriptor.  Finding the
-// descriptor is a search in the table of tile bases; a workgroup's 256 consecutive tiles lie
+// descriptor is a search in the table of tile bases; a workgroup's consecutive tiles lie
 // between the descriptors of its first and of its last tile, which are the same for the whole
 // workgroup: those two searches run on the scalar unit (the bases are read through the constant
 // address space; ten dependent loads from the scalar cache instead of from L2), and a lane then
 // only searches between them, which mostly is no step at all.  nbox < 0: the number of boxes is
 // n_host; else it is read from *nbox and the kernel leaves when it exceeds `bound`.
+// (kept out of line: inlined beside the call with the descriptor in registers, the two would be
+// merged into one body that reads its descriptor through a pointer, i.e. from scratch memory)
+__device__ __noinline__ TileRef make_tile_from_table(const CopyDesc* descs, uint32_t di, uint32_t q)
+{
+    return make_tile(descs[di], di, q);
+}
+
+constexpr int TILE_TABLE_ROUNDS = 4;   // a workgroup writes this many stretches of 256 records
 __global__ __launch_bounds__(256) void k_tile_table(const int64_t* __restrict__ tbase, const CopyDesc* __restrict__ descs,
                                                     const uint64_t* nbox, int64_t n_host, int64_t bound, TileRef* __restrict__ tiles,
                                                     int64_t cap)
@@ -438,9 +446,9 @@ __global__ __launch_bounds__(256) void k_tile_table(const int64_t* __restrict__ 
     const cbase_t tb = (cbase_t)(uintptr_t)tbase;
     const int64_t nd = 3 * n;
     const int64_t total = tb[nd] < cap ? tb[nd] : cap;
-    const int64_t t0 = (int64_t)blockIdx.x * 256;
-    if (t0 >= total) return;
-    const int64_t t1 = t0 + 255 < total ? t0 + 255 : total - 1;
+    const int64_t g0 = (int64_t)blockIdx.x * (256 * TILE_TABLE_ROUNDS);
+    if (g0 >= total) return;
+    const int64_t g1 = g0 + 256 * TILE_TABLE_ROUNDS - 1 < total ? g0 + 256 * TILE_TABLE_ROUNDS - 1 : total - 1;
     auto last_not_above = [&](int64_t t, int64_t lo) {   // the descriptor that holds tile t: last d >= lo - 1 with tb[d] <= t
         int64_t hi = nd + 1;
         while (lo < hi) {
@@ -451,27 +459,53 @@ __global__ __launch_bounds__(256) void k_tile_table(const int64_t* __restrict__ 
     };
     // (a descriptor of a long run has thousands of tiles: mostly the workgroup's last tile lies in
     // the same one, which a single load shows)
-    const int64_t d_first = last_not_above(t0, 0);
-    const int64_t d_last = tb[d_first + 1] > t1 ? d_first : last_not_above(t1, d_first + 2);
-    const int64_t t = t0 + threadIdx.x;
+    const int64_t d_first = last_not_above(g0, 0);
+    const int64_t d_last = tb[d_first + 1] > g1 ? d_first : last_not_above(g1, d_first + 2);
     // The 48-byte records of the workgroup go through LDS so that the table is written in whole
     // lines: a lane storing its own record would touch every third 16-byte piece, and each of its
     // three stores would open every line of the wavefront's stretch again.
     static_assert(sizeof(TileRef) == 48, "three 16-byte vectors per record");
     __shared__ __attribute__((aligned(16))) TileRef staged[256];
-    if (t < total) {
-        int64_t lo = d_first, hi = d_last + 1;    // the lane's own descriptor lies in [d_first, d_last]
-        while (hi - lo > 1) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (tbase[mid] <= t) lo = mid; else hi = mid;
-        }
-        staged[threadIdx.x] = make_tile(descs[lo], (uint32_t)lo, (uint32_t)(t - tbase[lo]));
+    // One descriptor of runs for the whole workgroup (the usual case): it is read once, with scalar
+    // loads, instead of by every lane.
+    CopyDesc one = CopyDesc();
+    const int64_t first_base = tb[d_first];
+    bool one_of_runs = false;
+    if (d_first == d_last) {
+        // (field by field, and only what make_run_tile reads: a struct assignment would go through
+        // scratch memory)
+        const __attribute__((address_space(4))) CopyDesc* c = (const __attribute__((address_space(4))) CopyDesc*)(uintptr_t)(descs + d_first);
+        one.mode = c->mode;
+        one_of_runs = one.mode == MODE_RUN;
+        one.src_byte = c->src_byte; one.dst_byte = c->dst_byte;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) { one.sstr[a] = c->sstr[a]; one.dstr[a] = c->dstr[a]; one.ext[a] = c->ext[a]; }
+        one.src_slot = c->src_slot; one.dst_slot = c->dst_slot; one.alt_src_slot = c->alt_src_slot;
+        one.es = c->es; one.alt_src_byte = c->alt_src_byte;
+        one.rows_per_tile = c->rows_per_tile; one.vec_window = c->vec_window;
+        one.chunks_per_row = c->chunks_per_row; one.xa = c->xa;
     }
-    __syncthreads();
-    const uint32_t nvec = 3u * (uint32_t)(total - t0 < 256 ? total - t0 : 256);
-    const u32x4* from = reinterpret_cast<const u32x4*>(staged);
-    u32x4* to = reinterpret_cast<u32x4*>(tiles + t0);
-    for (uint32_t v = threadIdx.x; v < nvec; v += 256) to[v] = from[v];
+    for (int64_t t0 = g0; t0 <= g1; t0 += 256) {
+        const int64_t t = t0 + threadIdx.x;
+        if (t0 > g0) __syncthreads();   // the stretch before has left the staging area
+        if (t < total) {
+            if (one_of_runs) {
+                staged[threadIdx.x] = make_run_tile(one, (uint32_t)(t - first_base));
+            } else {
+                int64_t lo = d_first, hi = d_last + 1;    // the lane's own descriptor lies in [d_first, d_last]
+                while (hi - lo > 1) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (tbase[mid] <= t) lo = mid; else hi = mid;
+                }
+                staged[threadIdx.x] = make_tile_from_table(descs, (uint32_t)lo, (uint32_t)(t - tbase[lo]));
+            }
+        }
+        __syncthreads();
+        const uint32_t nvec = 3u * (uint32_t)(total - t0 < 256 ? total - t0 : 256);
+        const u32x4* from = reinterpret_cast<const u32x4*>(staged);
+        u32x4* to = reinterpret_cast<u32x4*>(tiles + t0);
+        for (uint32_t v = threadIdx.x; v < nvec; v += 256) to[v] = from[v];
+    }
 }
 
 // ---- exclusive prefix sum of n int64 values: out[i] = in[0] + ... + in[i-1] ----
@@ -501,23 +535,33 @@ __global__ __launch_bounds__(256) void k_scan_one_group(const int64_t* in, int64
     scan_by_one_group(in, out, n);
 }
 
-// The same over the first mult * (*count) + 1 entries (at most n; nothing happens beyond); then
-// the nrows rows of row_len counters at `rows` become their own exclusive prefix sums, in place;
-// and then, in the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.
+// The same over the first mult * (*count) + 1 entries (at most n; no sums beyond); then the nrows
+// rows of row_len counters at `rows` become their own exclusive prefix sums, in place; then, in
+// the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.  At the end
+// the `words` 64-bit words at `blk` (the plan's summary block) are copied to `mirror`, which is
+// pinned host memory: the host reads them after its wait, without a copy command of its own; and
+// as many words at `clear` (if not null) are set to zero: the summary block of the next plan.
 template <class Step, class F>
 __global__ __launch_bounds__(256) void k_scan_counted_then_each(const int64_t* in, int64_t* out, int64_t n,
                                                                 const uint64_t* count, int mult, int64_t* rows,
-                                                                int64_t row_len, int nrows, int64_t m, F f)
+                                                                int64_t row_len, int nrows, int64_t m, F f,
+                                                                const uint64_t* blk, uint64_t* mirror, int64_t words,
+                                                                uint64_t* clear)
 {
+    if (clear)
+        for (int64_t i = threadIdx.x; i < words; i += 256) clear[i] = 0;
     const int64_t len = (int64_t)*count * mult + 1;
-    if (len > n) return;
-    scan_by_one_group(in, out, len);
-    for (int r = 0; r < nrows; ++r) {
-        __syncthreads();   // the carries of the scan before are free again
-        scan_by_one_group(rows + r * row_len, rows + r * row_len, row_len);
+    if (len <= n) {   // (uniform over the workgroup)
+        scan_by_one_group(in, out, len);
+        for (int r = 0; r < nrows; ++r) {
+            __syncthreads();   // the carries of the scan before are free again
+            scan_by_one_group(rows + r * row_len, rows + r * row_len, row_len);
+        }
+        __syncthreads();   // the sums are in memory for every lane of the workgroup
+        for (int64_t i = threadIdx.x; i < m; i += 256) f(i);
+        __syncthreads();   // and so is what f wrote into the block
     }
-    __syncthreads();   // the sums are in memory for every lane of the workgroup
-    for (int64_t i = threadIdx.x; i < m; i += 256) f(i);
+    for (int64_t i = threadIdx.x; i < words; i += 256) mirror[i] = blk[i];
 }
 
 __global__ __launch_bounds__(256) void k_scan_group_sums(const int64_t* in, int64_t* sums, int64_t n)
@@ -684,8 +728,9 @@ public:
 
     void release_all()
     {
-        if (live_.empty() && dead_.empty() && stages_.empty()) return;
+        if (live_.empty() && dead_.empty() && stages_.empty() && !pending_zeroed_.p) return;
         (void)hipStreamSynchronize(stream_);
+        if (pending_zeroed_.p) { DevicePool::get().give(pending_zeroed_.p); pending_zeroed_.p = nullptr; }
         for (const Stage& st : stages_) PinnedPool::get().give(st.pinned);
         stages_.clear();
         for (void* p : live_) DevicePool::get().give(p);
@@ -728,10 +773,13 @@ public:
     // f(i) for i in [0, m).
     template <class Step, class F>
     void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
-                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f)
+                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f,
+                                          const uint64_t* blk, uint64_t* mirror, int64_t words)
     {
+        // (a block of up to 1 MiB for the next plan is cleared here, see alloc_zeroed)
+        uint64_t* clear = words <= ((int64_t)1 << 17) ? (uint64_t*)next_zeroed(sizeof(uint64_t) * (size_t)words) : nullptr;
         hipLaunchKernelGGL((k_scan_counted_then_each<Step, F>), dim3(1), dim3(256), 0, stream_, in, out, bound, count, mult, rows,
-                           row_len, nrows, m, f);
+                           row_len, nrows, m, f, blk, mirror, words, clear);
         VPS_HIP_CHECK(hipGetLastError());
     }
 
@@ -752,7 +800,8 @@ public:
                     TileRef* tiles, int64_t cap, int64_t lanes)
     {
         if (lanes <= 0) return;
-        hipLaunchKernelGGL(k_tile_table, dim3((unsigned)((lanes + 255) / 256)), dim3(256), 0, stream_, tile_base, descs, nbox, n_host,
+        const int64_t per = 256 * TILE_TABLE_ROUNDS;
+        hipLaunchKernelGGL(k_tile_table, dim3((unsigned)((lanes + per - 1) / per)), dim3(256), 0, stream_, tile_base, descs, nbox, n_host,
                            bound, tiles, cap);
         VPS_HIP_CHECK(hipGetLastError());
     }
@@ -869,6 +918,51 @@ public:
         VPS_HIP_CHECK(hipMemcpyAsync(dev, stage, bytes, hipMemcpyHostToDevice, stream_));
     }
 
+    // Pinned host memory that a kernel of this stream writes: its first `bytes` bytes arrive in
+    // `host` at the next sync().
+    void* host_mirror(void* host, size_t bytes)
+    {
+        size_t got = 0;
+        void* stage = PinnedPool::get().take(bytes ? bytes : 1, got);
+        stages_.push_back(Stage{ host, stage, bytes });
+        return stage;
+    }
+
+    // A block of device memory that holds zeros.  Clearing it is a command of its own with a
+    // launch of its own, at the very start of a plan, when the device has nothing else to do; so
+    // a plan's last small kernel clears the block of the *next* plan on the side (next_zeroed
+    // hands it the block), and the block is published at the plan's wait, after which the
+    // clearing has certainly happened.
+    void* alloc_zeroed(size_t bytes)
+    {
+        void* p = nullptr;
+        {
+            std::lock_guard<std::mutex> g(zeroed_mutex());
+            ZeroedBlock& z = zeroed_slot();
+            if (z.p && z.bytes == bytes) { p = z.p; z.p = nullptr; }
+        }
+        if (p) { live_.push_back(p); return p; }
+        p = alloc<uint8_t>((int64_t)bytes);
+        zero(p, bytes);
+        return p;
+    }
+
+    // The block that a kernel launched next on this stream is going to clear, or nullptr when a
+    // cleared block of this size is waiting already.
+    void* next_zeroed(size_t bytes)
+    {
+        if (pending_zeroed_.p) return nullptr;
+        {
+            std::lock_guard<std::mutex> g(zeroed_mutex());
+            const ZeroedBlock& z = zeroed_slot();
+            if (z.p && z.bytes == bytes) return nullptr;
+        }
+        size_t got = 0;
+        pending_zeroed_.p = DevicePool::get().take(bytes, got);
+        pending_zeroed_.bytes = bytes;
+        return pending_zeroed_.p;
+    }
+
     // Needed at once (a count that sizes the next allocation).
     void download(void* host, const void* dev, size_t bytes)
     {
@@ -900,6 +994,18 @@ public:
             PinnedPool::get().give(st.pinned);
         }
         stages_.clear();
+        if (pending_zeroed_.p) {
+            // cleared by now (or never, after an error): publish it, or put it back
+            void* back = pending_zeroed_.p;
+            if (e == hipSuccess) {
+                std::lock_guard<std::mutex> g(zeroed_mutex());
+                ZeroedBlock& z = zeroed_slot();
+                back = z.p;   // a block of another size that nobody took
+                z = pending_zeroed_;
+            }
+            pending_zeroed_.p = nullptr;
+            if (back) DevicePool::get().give(back);
+        }
         VPS_HIP_CHECK(e);
     }
 
@@ -992,9 +1098,17 @@ private:
     };
 
     hipStream_t stream_;
+    struct ZeroedBlock {
+        void* p = nullptr;
+        size_t bytes = 0;
+    };
+    static std::mutex& zeroed_mutex() { static std::mutex m; return m; }
+    static ZeroedBlock& zeroed_slot() { static ZeroedBlock z; return z; }
+
     std::vector<void*> live_;
     std::vector<void*> dead_;
     std::vector<Stage> stages_;
+    ZeroedBlock pending_zeroed_;
 };
 
 }  // namespace vps

@@ -328,14 +328,26 @@ VPS_HD bool map_item_nonempty(const MapCtx& c, int32_t t, int32_t kind, int32_t 
     return tl.start < r1 && r0 < tl.start + tl.shard_len;
 }
 
+// a / b and the remainder for a >= 0, b > 0: in 32 bits when a fits (the GPU divides integers in
+// software, and the 64-bit form is several times the work of the 32-bit one).
+VPS_HD int64_t div_small(int64_t a, int32_t b, int32_t& rem)
+{
+    if ((uint64_t)a <= 0xffffffffull) {
+        const uint32_t q = (uint32_t)a / (uint32_t)b;
+        rem = (int32_t)((uint32_t)a - q * (uint32_t)b);
+        return (int64_t)q;
+    }
+    const int64_t q = a / b;
+    rem = (int32_t)(a - q * b);
+    return q;
+}
+
 VPS_HD void map_decode_item(const ParConst& P, int64_t item, int32_t& t, int32_t& kind, int32_t& tp, int32_t& didx)
 {
-    didx = (int32_t)(item % P.dmax);
-    int64_t r = item / P.dmax;
-    tp = (int32_t)(r % P.tp);
-    r /= P.tp;
-    kind = (int32_t)(r % 4);
-    t = (int32_t)(r / 4);
+    int64_t r = div_small(item, P.dmax, didx);
+    r = div_small(r, P.tp, tp);
+    kind = (int32_t)(r & 3);
+    t = (int32_t)(r >> 2);
 }
 
 // The pieces of mapper item `item`; writes them when out != nullptr.  Returns their number.
@@ -351,7 +363,7 @@ VPS_HD int map_item_pieces(const MapCtx& c, int64_t item, vps_piece* out)
 // Planner: one item per (destination mapper item, distinct piece of source data).
 // ------------------------------------------------------------------------------------------
 
-VPS_HD int64_t floor_div(int64_t a, int64_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
+VPS_HD int32_t floor_div(int32_t a, int32_t b) { return a / b - ((a % b != 0) && ((a < 0) != (b < 0)) ? 1 : 0); }
 
 // The source rank selected for destination rank j among the ranks that hold the same data as
 // source rank i (i's TP replicas when the tensor is TP-replicated, i's data-parallel replicas
@@ -383,38 +395,38 @@ VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const Te
     const int32_t dpj = x.group ? cb.edp : cb.ddp;
     const int32_t nt = t1 - t0;
     // (2) candidates on j's node.  Row q holds the ranks T*q + t: q = d + DDP*pp for dense
-    // tensors, q = ep + EP*(d + EDP*pp) for experts.
-    const int64_t n0 = (int64_t)(j / A.gpn) * A.gpn, n1 = n0 + A.gpn;
-    const int64_t step = x.group ? A.ep : 1;                       // rows of consecutive candidates
-    const int64_t qfirst = x.group ? ci.ep + (int64_t)A.ep * (d0 + (int64_t)A.edp * ci.pp)
-                                   : d0 + (int64_t)A.ddp * ci.pp;
-    const int64_t qlast = qfirst + step * (d1 - d0 - 1);
-    int64_t qlo = floor_div(n0 - t1, T) + 1, qhi = floor_div(n1 - t0 - 1, T);
+    // tensors, q = ep + EP*(d + EDP*pp) for experts.  (Ranks are below 2^15, rows and counts too:
+    // 32-bit arithmetic throughout.)
+    const int32_t n0 = (j / A.gpn) * A.gpn, n1 = n0 + A.gpn;
+    const int32_t step = x.group ? A.ep : 1;                       // rows of consecutive candidates
+    const int32_t qfirst = x.group ? ci.ep + A.ep * (d0 + A.edp * ci.pp) : d0 + A.ddp * ci.pp;
+    const int32_t qlast = qfirst + step * (d1 - d0 - 1);
+    int32_t qlo = floor_div(n0 - t1, T) + 1, qhi = floor_div(n1 - t0 - 1, T);
     if (qlo < qfirst) qlo = qfirst;
     if (qhi > qlast) qhi = qlast;
     // align qlo up to a candidate row
-    if (qlo > qfirst) qlo = qfirst + (qlo - qfirst + step - 1) / step * step;
-    int64_t n_node = 0;
-    for (int64_t q = qlo; q <= qhi; q += step) {
-        const int64_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
-        const int64_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
+    if (qlo > qfirst && step > 1) qlo = qfirst + (qlo - qfirst + step - 1) / step * step;
+    int32_t n_node = 0;
+    for (int32_t q = qlo; q <= qhi; q += step) {
+        const int32_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
+        const int32_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
         if (hi > lo) n_node += hi - lo;
     }
     if (n_node > 0) {
-        int64_t want = dpj % n_node;
-        for (int64_t q = qlo; q <= qhi; q += step) {
-            const int64_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
-            const int64_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
+        int32_t want = dpj % n_node;
+        for (int32_t q = qlo; q <= qhi; q += step) {
+            const int32_t lo = T * q + t0 > n0 ? T * q + t0 : n0;
+            const int32_t hi = T * q + t1 < n1 ? T * q + t1 : n1;
             if (hi <= lo) continue;
-            if (want < hi - lo) return (int32_t)(lo + want);
+            if (want < hi - lo) return lo + want;
             want -= hi - lo;
         }
         return -1;
     }
     // (3) no candidate on the node: index into all of them, ascending
-    const int64_t want = dpj % ((int64_t)nt * (d1 - d0));
-    const int64_t q = qfirst + step * (want / nt);
-    return (int32_t)(T * q + t0 + want % nt);
+    const int32_t want = dpj % (nt * (d1 - d0));
+    const int32_t q = qfirst + step * (want / nt);
+    return T * q + t0 + want % nt;
 }
 
 struct PlanCtx {
@@ -426,6 +438,9 @@ struct PlanCtx {
     // all-ranks plans: bits of the (destination tp, dp index) field and of the slot field of a lane
     // index (both padded to powers of two, so that a lane finds its item with shifts)
     int32_t item_bits, slot_bits;
+    // single-rank plans: the planned rank's coordinates under the two configurations (the same
+    // for every lane, so they are decoded once, on the host)
+    RankCoord ra, rb;
 };
 
 // A destination item is paired with every distinct piece of source data of its (tensor, kind):
@@ -449,10 +464,11 @@ VPS_HD void plan_set_rank_ranges(PlanCtx& c)
     c.item_bits = c.slot_bits = 0;
     while ((1 << c.item_bits) < c.B.tp * c.B.dmax) ++c.item_bits;
     while ((1 << c.slot_bits) < plan_max_slots(c.A)) ++c.slot_bits;
+    c.ra = c.rb = RankCoord();
     if (c.rank < 0) return;
     int32_t lo, hi;
-    if (c.rank < c.B.world) { stage_tensor_range(c.B, decode_rank(c.B, c.rank).pp, lo, hi); c.recv_lo = lo; c.recv_n = hi - lo; }
-    if (c.rank < c.A.world) { stage_tensor_range(c.A, decode_rank(c.A, c.rank).pp, lo, hi); c.send_lo = lo; c.send_n = hi - lo; }
+    if (c.rank < c.B.world) { c.rb = decode_rank(c.B, c.rank); stage_tensor_range(c.B, c.rb.pp, lo, hi); c.recv_lo = lo; c.recv_n = hi - lo; }
+    if (c.rank < c.A.world) { c.ra = decode_rank(c.A, c.rank); stage_tensor_range(c.A, c.ra.pp, lo, hi); c.send_lo = lo; c.send_n = hi - lo; }
 }
 
 
@@ -539,10 +555,9 @@ VPS_HD bool plan_lane_decode(const PlanCtx& c, int mode, int64_t lane, LaneItem&
         kind = tk & 3; t = tk >> 2;
         tpb = ib / B.dmax; db = ib - tpb * B.dmax;
     } else if (mode == PLAN_RECV) {
-        const int32_t smax = plan_max_slots(A);
-        u = (int32_t)(lane % smax);
-        kind = (int32_t)((lane / smax) % 4);
-        t = c.recv_lo + (int32_t)(lane / smax / 4);
+        const int64_t tk = div_small(lane, plan_max_slots(A), u);
+        kind = (int32_t)(tk & 3);
+        t = c.recv_lo + (int32_t)(tk >> 2);
         tpb = db = 0;
     } else {
         map_decode_item(B, lane, t, kind, tpb, db);
@@ -561,7 +576,7 @@ VPS_HD bool plan_pair_check(const PlanCtx& c, int mode, const TensorRec& x, int3
     const ParConst& B = c.B;
     if (mode == PLAN_RECV) {
         if (c.rank >= B.world) return false;
-        const RankCoord cr = decode_rank(B, c.rank);
+        const RankCoord cr = c.rb;
         tpb = x.group ? cr.etp : cr.tp;
         db = x.group ? cr.edp : cr.ddp;
         // the rank holds the tensor only on its own stage (and expert block)
@@ -571,7 +586,7 @@ VPS_HD bool plan_pair_check(const PlanCtx& c, int mode, const TensorRec& x, int3
     const int32_t nd = (A.zero == 1 && kind != 0) ? group_dp(A, x.group) : 1;
     if (mode == PLAN_SEND) {
         if (c.rank >= A.world) return false;
-        const RankCoord cs = decode_rank(A, c.rank);
+        const RankCoord cs = c.ra;
         if (c.ma.TL[t].stage != cs.pp || (x.group && x.expert / (A.experts / A.ep) != cs.ep)) return false;
         u = (x.tp_axis < 0 ? 0 : (x.group ? cs.etp : cs.tp)) * nd + (nd > 1 ? (x.group ? cs.edp : cs.ddp) : 0);
     }
@@ -1170,6 +1185,11 @@ VPS_HD RunWindow run_window(uint64_t srow, uint64_t drow, uint64_t run_bytes, ui
 // Byte offsets of the first element of run `row` relative to the descriptor bases.
 VPS_HD void run_row_offsets(const CopyDesc& d, uint32_t row, uint64_t& so, uint64_t& to)
 {
+    if (d.ext[0] == 1 && d.ext[1] == 1) {   // the rows lie along one axis: no division
+        so = (uint64_t)((int64_t)row * d.sstr[2] * (int64_t)d.es);
+        to = (uint64_t)((int64_t)row * d.dstr[2] * (int64_t)d.es);
+        return;
+    }
     const uint32_t c2 = row % d.ext[2];
     const uint32_t r1 = row / d.ext[2];
     const uint32_t c1 = r1 % d.ext[1];
@@ -1209,7 +1229,13 @@ VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uin
     uint32_t o = q / (na * nb);
     uint32_t ia, ib;
     xpose_plane_order(q - o * na * nb, na, nb, d.rows_per_tile & 0xffffu, d.rows_per_tile >> 16, ia, ib);
+    // (the fields of axis xa by selects, the loop unrolled: no array is indexed at run time, so
+    // a descriptor held in registers stays there)
+    const uint32_t ext_xa = d.xa == 2u ? d.ext[2] : (d.xa == 1u ? d.ext[1] : d.ext[0]);
+    const int64_t sstr_xa = d.xa == 2u ? d.sstr[2] : (d.xa == 1u ? d.sstr[1] : d.sstr[0]);
+    const int64_t dstr_xa = d.xa == 2u ? d.dstr[2] : (d.xa == 1u ? d.dstr[1] : d.dstr[0]);
     int64_t s = 0, t = 0;
+    VPS_UNROLL(3)
     for (int ax = 2; ax >= 0; --ax) {  // the two remaining axes, innermost first
         if ((uint32_t)ax == d.xa) continue;
         const uint32_t c = o % d.ext[ax];
@@ -1218,11 +1244,11 @@ VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uin
         t += (int64_t)c * d.dstr[ax];
     }
     const uint32_t a0 = ia * XPOSE_T, b0 = ib * XPOSE_T;
-    s += (int64_t)a0 * d.sstr[d.xa] + (int64_t)b0 * d.sstr[3];
-    t += (int64_t)a0 * d.dstr[d.xa] + (int64_t)b0 * d.dstr[3];
+    s += (int64_t)a0 * sstr_xa + (int64_t)b0 * d.sstr[3];
+    t += (int64_t)a0 * dstr_xa + (int64_t)b0 * d.dstr[3];
     so = (uint64_t)(s * (int64_t)d.es);
     to = (uint64_t)(t * (int64_t)d.es);
-    ta = d.ext[d.xa] - a0 < (uint32_t)XPOSE_T ? d.ext[d.xa] - a0 : (uint32_t)XPOSE_T;
+    ta = ext_xa - a0 < (uint32_t)XPOSE_T ? ext_xa - a0 : (uint32_t)XPOSE_T;
     tb = d.ext[3] - b0 < (uint32_t)XPOSE_T ? d.ext[3] - b0 : (uint32_t)XPOSE_T;
 }
 
@@ -1230,12 +1256,13 @@ VPS_HD void xpose_tile_geometry(const CopyDesc& d, uint32_t q, uint64_t& so, uin
 // destination vectors [c*vec_window, (c+1)*vec_window) counted from the RUN_CUT_ALIGN boundary
 // at or below the run's first destination byte (with a less aligned buffer base the tiles are
 // still disjoint and complete, only less evenly cut).
-VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
+VPS_HD TileRef make_run_tile(const CopyDesc& d, uint32_t q)   // (d.mode == MODE_RUN; no field of d is indexed at run time)
 {
     TileRef t;
     t.src_pitch = 0; t.dst_pitch = 0;
-    if (d.mode == MODE_RUN && d.chunks_per_row) {
-        const uint32_t row = q / d.chunks_per_row, c = q - row * d.chunks_per_row;
+    if (d.chunks_per_row) {
+        const bool one_run = d.ext[0] == 1 && d.ext[1] == 1 && d.ext[2] == 1;   // (then every tile is a chunk of it)
+        const uint32_t row = one_run ? 0u : q / d.chunks_per_row, c = q - row * d.chunks_per_row;
         uint64_t so, to;
         run_row_offsets(d, row, so, to);
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
@@ -1255,7 +1282,7 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so + (lo - d0)) : VPS_TILE_NO_ALT;
         t.nbytes = (uint32_t)(hi - lo);
         t.nruns_flags = (hi > lo ? 1u : 0u) << 8;
-    } else if (d.mode == MODE_RUN) {
+    } else {
         const uint32_t k = d.rows_per_tile;
         const uint32_t tps = (d.ext[2] + k - 1) / k;
         const uint32_t slab = q / tps, r0 = (q - slab * tps) * k;
@@ -1269,7 +1296,16 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         t.dst_pitch = d.dstr[2] * (int64_t)d.es;
         t.nbytes = d.ext[3] * d.es;
         t.nruns_flags = nruns << 8;
-    } else if (d.mode == MODE_XPOSE) {
+    }
+    return t;
+}
+
+VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
+{
+    if (d.mode == MODE_RUN) return make_run_tile(d, q);
+    TileRef t;
+    t.src_pitch = 0; t.dst_pitch = 0;
+    if (d.mode == MODE_XPOSE) {
         uint64_t so, to;
         uint32_t ta, tb;
         xpose_tile_geometry(d, q, so, to, ta, tb);
@@ -1277,7 +1313,7 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
         t.dst = tile_pack_addr(d.dst_slot, d.dst_byte + to);
         t.alt_src = d.alt_src_slot >= 0 ? tile_pack_addr(d.alt_src_slot, d.alt_src_byte + so) : VPS_TILE_NO_ALT;
         t.src_pitch = d.sstr[3] * (int64_t)d.es;
-        t.dst_pitch = d.dstr[d.xa] * (int64_t)d.es;
+        t.dst_pitch = (d.xa == 2u ? d.dstr[2] : (d.xa == 1u ? d.dstr[1] : d.dstr[0])) * (int64_t)d.es;
         t.nbytes = ta | tb << 16;
         t.nruns_flags = TILE_XPOSE | (d.es == 2 ? TILE_ES2 : 0u);
     } else {

@@ -252,8 +252,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
 
     SummaryLayout SL;
     SL.W = W; SL.npairs = rank < 0 ? (int64_t)WA * WB : (int64_t)WA + WB; SL.nslots = num_slots(layout);
-    uint64_t* sum = be.template alloc<uint64_t>(SL.words());
-    be.zero(sum, sizeof(uint64_t) * (size_t)SL.words());
+    uint64_t* sum = (uint64_t*)be.alloc_zeroed(sizeof(uint64_t) * (size_t)SL.words());
     uint64_t* pairs = sum + SL.pairs();
     uint8_t* used = (uint8_t*)(sum + SL.used());
     const int64_t nslots = SL.nslots;
@@ -339,6 +338,9 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         rt[5 * (W + 1) + r] = tbase[n + fs];
         rt[6 * (W + 1) + r] = tbase[2 * n + fr];
     };
+    // (the same launch leaves a copy of the summary block in pinned host memory)
+    std::vector<uint64_t> hsum((size_t)SL.words());
+    uint64_t* hmirror = (uint64_t*)be.host_mirror(hsum.data(), sizeof(uint64_t) * hsum.size());
     be.exclusive_scan_counted_then_each(step::plan_rank_tables(), ntl, tb, 3 * ns + 1, nbox, 3, rt, W + 1, 2, W + 1, [=] VPS_LAMBDA(int64_t r) {
         // (rows 0 and 1 hold the first boxes by now: the counts of the ordering pass, summed)
         const int64_t n = (int64_t)*nbox;
@@ -352,7 +354,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         rt[4 * (W + 1) + r] = tb[fs];
         rt[5 * (W + 1) + r] = tb[n + fs];
         rt[6 * (W + 1) + r] = tb[2 * n + fr];
-    });
+    }, sum, hmirror, SL.words());
 
     // (4) the tile table.  Its size is only known on the device so far; when the caller has seen
     // this transition before it passes the size as a hint and the table is built before the host
@@ -365,8 +367,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         be.tile_table(tb, descs, nbox, 0, ns, tiles, tiles_cap, tiles_cap);
     }
 
-    std::vector<uint64_t> hsum((size_t)SL.words());
-    be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());     // the one synchronisation
+    be.sync();   // the one synchronisation
     if (listed && hsum[SUM_NLISTED] > BE::PLAN_LIST_CAP) {
         // more busy lanes than the list holds: nothing was emitted, so plan again without the list
         be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);

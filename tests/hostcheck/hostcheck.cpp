@@ -104,6 +104,8 @@ public:
     void download(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
     void download_later(void* h, const void* d, size_t b) { if (b) memcpy(h, d, b); }
     void zero(void* d, size_t b) { if (b) memset(d, 0, b); }
+    void* host_mirror(void* host, size_t) { return host; }
+    void* alloc_zeroed(size_t bytes) { void* p = alloc<uint8_t>((int64_t)bytes); memset(p, 0, bytes); return p; }
     void sync() {}
     void wait_stream(void*) {}
     void* stream() const { return nullptr; }
@@ -147,16 +149,19 @@ public:
 
     template <class Step, class F>
     void exclusive_scan_counted_then_each(Step, const int64_t* in, int64_t* out, int64_t bound, const uint64_t* count,
-                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f)
+                                          int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f,
+                                          const uint64_t* blk, uint64_t* mirror, int64_t words)
     {
         const int64_t len = (int64_t)*count * mult + 1;
-        if (len > bound) return;
-        exclusive_scan(in, out, len - 1);
-        for (int r = 0; r < nrows; ++r) {
-            int64_t run = 0;
-            for (int64_t i = 0; i < row_len; ++i) { const int64_t v = rows[r * row_len + i]; rows[r * row_len + i] = run; run += v; }
+        if (len <= bound) {
+            exclusive_scan(in, out, len - 1);
+            for (int r = 0; r < nrows; ++r) {
+                int64_t run = 0;
+                for (int64_t i = 0; i < row_len; ++i) { const int64_t v = rows[r * row_len + i]; rows[r * row_len + i] = run; run += v; }
+            }
+            for (int64_t i = 0; i < m; ++i) f(i);
         }
-        for (int64_t i = 0; i < m; ++i) f(i);
+        for (int64_t i = 0; i < words; ++i) mirror[i] = blk[i];
     }
 
     void tile_table(const int64_t* tile_base, const CopyDesc* descs, const uint64_t* nbox, int64_t n_host, int64_t bound,

@@ -17,7 +17,7 @@ MUTANTS = [m for m in [
      "bo = b == 0 ? 0 : (b == 1 ? P.q_per_g + 1 : P.q_per_g);"),
     ("source offset of a box with the destination's strides", "vps_core.h",
      "b.src_off += (int64_t)(b.lo[a] - sp.lo[a]) * sp.stride[a];", "b.src_off += (int64_t)(b.lo[a] - sp.lo[a]) * dp.stride[a];"),
-    ("replica choice ignores the data-parallel index", "vps_core.h", "int64_t want = dpj % n_node;", "int64_t want = 0 % n_node;"),
+    ("replica choice ignores the data-parallel index", "vps_core.h", "int32_t want = dpj % n_node;", "int32_t want = 0 % n_node;"),
     ("partial last vector of a run dropped at a window end", "vps_core.h",
      "const bool has_tail = tailb && !(wl == 0 && head) && wl >= w0 && wl < wend_win;",
      "const bool has_tail = tailb && !(wl == 0 && head) && wl >= w0 && wl + 1 < wend_win;"),
@@ -46,8 +46,13 @@ MUTANTS = [m for m in [
     ("kinds in plain order inside a peer segment", "vps_core.h", "const uint64_t korder = (uint64_t)((b.kind + 3) & 3);",
      "const uint64_t korder = (uint64_t)b.kind;"),
     ("unpack reads at the sender's position", "vps_core.h", "d.src_byte = b.recv_pos;", "d.src_byte = b.send_pos;"),
+    ("a rank's first box counted by the boxes it receives", "vps_pipeline.h", "be_atomic_add(rank_rows + b.src_rank, 1);",
+     "be_atomic_add(rank_rows + b.dst_rank, 1);"),
+    ("axes merged when only the source side is contiguous", "vps_core.h",
+     "if (m > 0 && o3.s == x[i].s * x[i].e && o3.d == x[i].d * x[i].e && o3.e * x[i].e < ((int64_t)1 << 31)) {",
+     "if (m > 0 && o3.s == x[i].s * x[i].e && o3.e * x[i].e < ((int64_t)1 << 31)) {"),
     ("block extent of a transpose not clipped", "vps_core.h",
-     "ta = d.ext[d.xa] - a0 < (uint32_t)XPOSE_T ? d.ext[d.xa] - a0 : (uint32_t)XPOSE_T;", "ta = (uint32_t)XPOSE_T;"),
+     "ta = ext_xa - a0 < (uint32_t)XPOSE_T ? ext_xa - a0 : (uint32_t)XPOSE_T;", "ta = (uint32_t)XPOSE_T;"),
 ] if m[2] is not None]   # (entries without a site are mistakes only a device build could hold)
 
 PARITY = "all_ranks_resident or single_rank_share or medium_shapes or beyond_the_counting_limit"
