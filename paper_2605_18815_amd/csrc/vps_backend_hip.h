@@ -279,23 +279,32 @@ __global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, 
 // counts up.  f(k, place, part) continues with box k on the group's lanes part = 0 .. 15.
 constexpr unsigned ORDER_GROUP = 16;
 
-template <class Step, class F>
+template <class Step, class P, class F>
 __global__ __launch_bounds__(256) void k_order_by_counting(const OrderRec* __restrict__ recs, const uint64_t* __restrict__ nbox,
-                                                           uint32_t bound, F f)
+                                                           uint32_t bound, P pre, F f)
 {
     constexpr unsigned BOXES = 256 / ORDER_GROUP;
-    __shared__ OrderRec tile[256];
+    __shared__ OrderRec tile[512];
     const uint64_t n64 = *nbox;
     if (n64 > bound || (uint64_t)blockIdx.x * BOXES >= n64) return;   // uniform over the workgroup
     const uint32_t n = (uint32_t)n64, part = threadIdx.x % ORDER_GROUP, k = blockIdx.x * BOXES + threadIdx.x / ORDER_GROUP;
-    const OrderRec me = recs[k < n ? k : n - 1];
+    const uint32_t kk = k < n ? k : n - 1;
+    const OrderRec me = recs[kk];
+    // what f needs of box k besides its place is asked for now: it arrives while the counting runs
+    const auto held = pre(kk, part);
     const uint64_t floor_s = order_owner_floor(me.key_s), floor_r = order_owner_floor(me.key_r);
     OrderPlace o = order_place_zero();
-    for (uint32_t q0 = 0; q0 < n; q0 += 256) {
+    for (uint32_t q0 = 0; q0 < n; q0 += 512) {
         __syncthreads();
-        if (q0 + threadIdx.x < n) tile[threadIdx.x] = recs[q0 + threadIdx.x];
+        // (two records per lane, both loads in flight together)
+        const uint32_t i0 = q0 + threadIdx.x, i1 = i0 + 256;
+        OrderRec r0 = me, r1 = me;
+        if (i0 < n) r0 = recs[i0];
+        if (i1 < n) r1 = recs[i1];
+        if (i0 < n) tile[threadIdx.x] = r0;
+        if (i1 < n) tile[threadIdx.x + 256] = r1;
         __syncthreads();
-        const uint32_t m = n - q0 < 256u ? n - q0 : 256u;
+        const uint32_t m = n - q0 < 512u ? n - q0 : 512u;
         for (uint32_t q = part; q < m; q += ORDER_GROUP) order_count_one(tile[q], me, floor_s, floor_r, o);
     }
 #pragma unroll
@@ -307,7 +316,7 @@ __global__ __launch_bounds__(256) void k_order_by_counting(const OrderRec* __res
         o.base_s += shfl_xor_u64(o.base_s, d);
         o.base_r += shfl_xor_u64(o.base_r, d);
     }
-    if (k < n) f(k, o, part);
+    if (k < n) f(k, o, part, held);
 }
 
 // Rank of every record inside its pair's bucket (pair-by-pair ordering of large all-ranks plans):
@@ -783,14 +792,15 @@ public:
         VPS_HIP_CHECK(hipGetLastError());
     }
 
-    // f(k, place, part) for every box k < *nbox (at most `bound` boxes) and part = 0 .. 15,
-    // place = order_by_counting.
-    template <class Step, class F>
-    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, F f)
+    // f(k, place, part, pre(k, part)) for every box k < *nbox (at most `bound` boxes) and
+    // part = 0 .. 15, place = order_by_counting; pre is evaluated before the counting.
+    template <class Step, class P, class F>
+    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, P pre, F f)
     {
         const int64_t per = 256 / ORDER_GROUP;
         const int64_t blocks = (bound + per - 1) / per;
-        hipLaunchKernelGGL((k_order_by_counting<Step, F>), dim3((unsigned)blocks), dim3(256), 0, stream_, recs, nbox, (uint32_t)bound, f);
+        hipLaunchKernelGGL((k_order_by_counting<Step, P, F>), dim3((unsigned)blocks), dim3(256), 0, stream_, recs, nbox, (uint32_t)bound,
+                           pre, f);
         VPS_HIP_CHECK(hipGetLastError());
     }
 

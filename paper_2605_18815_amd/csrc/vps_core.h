@@ -687,6 +687,16 @@ VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f, int pa
 constexpr int PLAN_PART_BITS = 3;
 VPS_HD int plan_part_bits(int mode) { return mode == PLAN_ALL ? 0 : PLAN_PART_BITS; }
 
+// *out = *in, as 64-bit words.
+VPS_HD void copy_box_words(vps_box* out, const vps_box* in)
+{
+    static_assert(sizeof(vps_box) % 8 == 0 && alignof(vps_box) == 8, "a whole number of 64-bit words");
+    const uint64_t* from = reinterpret_cast<const uint64_t*>(in);
+    uint64_t* to = reinterpret_cast<uint64_t*>(out);
+    VPS_UNROLL(32)
+    for (unsigned i = 0; i < sizeof(vps_box) / 8; ++i) to[i] = from[i];
+}
+
 VPS_HD uint64_t box_volume(const vps_box& b)
 {
     return (uint64_t)b.ext[0] * (uint64_t)b.ext[1] * (uint64_t)b.ext[2] * (uint64_t)b.ext[3];

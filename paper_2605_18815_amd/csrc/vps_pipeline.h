@@ -292,10 +292,12 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     const uint64_t* nbox = sum + SUM_NBOXES;
     fc.descs = descs; fc.ntiles = ntl;
     uint64_t* rank_rows = sum + SL.rank_tables();
-    be.order_by_counting_each(step::plan_order_by_counting(), recs, nbox, ns, [=] VPS_LAMBDA(uint32_t k, const OrderPlace& o, uint32_t part) {
+    be.order_by_counting_each(step::plan_order_by_counting(), recs, nbox, ns, [=] VPS_LAMBDA(uint32_t k, uint32_t part) {
+        return part > 2 ? vps_box() : raw[k];   // (the box itself, for the three lanes that go on)
+    }, [=] VPS_LAMBDA(uint32_t k, const OrderPlace& o, uint32_t part, const vps_box& held) {
         if (part > 2) return;   // three lanes go on, one per copy operation
         const int64_t n = (int64_t)*nbox;
-        vps_box b = raw[k];
+        vps_box b = held;
         const OrderRec rec = recs[k];
         if (rec.bytes_flags & ORD_SENDS) b.send_pos = o.gpos_s - o.base_s;
         if (rec.bytes_flags & ORD_RECEIVES) b.recv_pos = o.gpos_r - o.base_r;
@@ -493,15 +495,18 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
                 const PairRec me = bucket[j];
                 const int64_t pr = (int64_t)(me.key >> 26);
                 const uint64_t before = before_of[j], bytes = bytes_of[j];
-                vps_box b = raw[me.box];
+                const vps_box* in = raw + me.box;
                 const uint64_t is = pstart_s[pr] + before, ir = pstart_r[pr] + before;
                 const uint64_t ps = poff_s[pr] + bytes, pq = poff_r[pr] + bytes;
-                if (me.bytes_flags & ORD_SENDS) b.send_pos = ps;
-                if (me.bytes_flags & ORD_RECEIVES) b.recv_pos = pq;
-                sorted[is] = b;
+                // (word by word, then the two positions: a box changed in a local copy and stored
+                // whole would pass through scratch memory)
+                vps_box* out = sorted + is;
+                copy_box_words(out, in);
+                if (me.bytes_flags & ORD_SENDS) out->send_pos = ps;
+                if (me.bytes_flags & ORD_RECEIVES) out->recv_pos = pq;
                 rperm[ir] = (uint32_t)is;
-                gs[is] = (uint64_t)rows_b0[b.src_rank] + ps;
-                gr[ir] = (uint64_t)cols_b0[b.dst_rank] + pq;
+                gs[is] = (uint64_t)rows_b0[in->src_rank] + ps;
+                gr[ir] = (uint64_t)cols_b0[in->dst_rank] + pq;
                 if (j == 0) { gs[n] = (uint64_t)rows_b0[W]; gr[n] = (uint64_t)cols_b0[W]; }
             });
             be.free(before_of);

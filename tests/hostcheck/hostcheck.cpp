@@ -198,14 +198,14 @@ public:
         }
     }
 
-    template <class Step, class F>
-    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, F f)
+    template <class Step, class P, class F>
+    void order_by_counting_each(Step, const OrderRec* recs, const uint64_t* nbox, int64_t bound, P pre, F f)
     {
         const uint64_t n = *nbox;
         if (n > (uint64_t)bound) return;
         for (uint64_t k = 0; k < n; ++k) {
             const OrderPlace o = order_by_counting(recs, (uint32_t)n, (uint32_t)k);
-            for (uint32_t part = 0; part < 16; ++part) f((uint32_t)k, o, part);
+            for (uint32_t part = 0; part < 16; ++part) f((uint32_t)k, o, part, pre((uint32_t)k, part));
         }
     }
     void set_ptr_table(void** table, void* const* host_ptrs, int n) { memcpy(table, host_ptrs, sizeof(void*) * (size_t)n); }
