@@ -544,6 +544,12 @@ __global__ __launch_bounds__(256) void k_scan_one_group(const int64_t* in, int64
     scan_by_one_group(in, out, n);
 }
 
+// Several short arrays at a constant distance from each other, one workgroup each.
+__global__ __launch_bounds__(256) void k_scan_rows(const int64_t* in, int64_t* out, int64_t n, int64_t stride)
+{
+    scan_by_one_group(in + (int64_t)blockIdx.x * stride, out + (int64_t)blockIdx.x * stride, n);
+}
+
 // The same over the first mult * (*count) + 1 entries (at most n; no sums beyond); then the nrows
 // rows of row_len counters at `rows` become their own exclusive prefix sums, in place; then, in
 // the same workgroup, f(i) for i in [0, m): the per-rank tables that read the sums.  At the end
@@ -777,6 +783,17 @@ public:
         free(sums);
     }
 
+    // exclusive_scan(in + r * stride, out + r * stride, n) for r in [0, rows), in one launch.
+    void exclusive_scan_rows(const int64_t* in, int64_t* out, int64_t n, int64_t stride, int rows)
+    {
+        if (n + 1 > 4 * SCAN_PER_GROUP) {
+            for (int r = 0; r < rows; ++r) exclusive_scan(in + r * stride, out + r * stride, n);
+            return;
+        }
+        hipLaunchKernelGGL(k_scan_rows, dim3((unsigned)rows), dim3(256), 0, stream_, in, out, n + 1, stride);
+        VPS_HIP_CHECK(hipGetLastError());
+    }
+
     // The same over the first mult * (*count) + 1 entries, *count read on the device (at most
     // `bound` entries; nothing happens if there would be more), followed in the same launch by
     // f(i) for i in [0, m).
@@ -785,8 +802,8 @@ public:
                                           int mult, int64_t* rows, int64_t row_len, int nrows, int64_t m, F f,
                                           const uint64_t* blk, uint64_t* mirror, int64_t words)
     {
-        // (a block of up to 1 MiB for the next plan is cleared here, see alloc_zeroed)
-        uint64_t* clear = words <= ((int64_t)1 << 17) ? (uint64_t*)next_zeroed(sizeof(uint64_t) * (size_t)words) : nullptr;
+        // (the block of the next plan is cleared here, see alloc_zeroed)
+        uint64_t* clear = words > 0 ? (uint64_t*)next_zeroed(sizeof(uint64_t) * (size_t)words) : nullptr;
         hipLaunchKernelGGL((k_scan_counted_then_each<Step, F>), dim3(1), dim3(256), 0, stream_, in, out, bound, count, mult, rows,
                            row_len, nrows, m, f, blk, mirror, words, clear);
         VPS_HIP_CHECK(hipGetLastError());

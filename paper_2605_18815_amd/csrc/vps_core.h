@@ -687,16 +687,6 @@ VPS_HD int plan_lane_boxes(const PlanCtx& c, int mode, int64_t lane, F f, int pa
 constexpr int PLAN_PART_BITS = 3;
 VPS_HD int plan_part_bits(int mode) { return mode == PLAN_ALL ? 0 : PLAN_PART_BITS; }
 
-// *out = *in, as 64-bit words.
-VPS_HD void copy_box_words(vps_box* out, const vps_box* in)
-{
-    static_assert(sizeof(vps_box) % 8 == 0 && alignof(vps_box) == 8, "a whole number of 64-bit words");
-    const uint64_t* from = reinterpret_cast<const uint64_t*>(in);
-    uint64_t* to = reinterpret_cast<uint64_t*>(out);
-    VPS_UNROLL(32)
-    for (unsigned i = 0; i < sizeof(vps_box) / 8; ++i) to[i] = from[i];
-}
-
 VPS_HD uint64_t box_volume(const vps_box& b)
 {
     return (uint64_t)b.ext[0] * (uint64_t)b.ext[1] * (uint64_t)b.ext[2] * (uint64_t)b.ext[3];
@@ -1340,6 +1330,7 @@ VPS_HD TileRef make_tile(const CopyDesc& d, uint32_t di, uint32_t q)
 struct FinishCtx {
     int32_t rank, wa, wb;
     bool through_buffers, routes_only;
+    bool count_kinds;   // account_box also counts retained / sent / received boxes (else the caller has them)
     PtrLayout layout;
     uint32_t tile_bytes, xpose_shape;
     uint64_t* sum;      // summary block (SUM_* counters at its head)
@@ -1359,6 +1350,7 @@ VPS_HD void account_box(const FinishCtx& c, const vps_box& b)
         if (b.dst_rank == c.rank) be_atomic_add(&c.pairs[b.src_rank], bytes);
         if (b.src_rank == c.rank) be_atomic_add(&c.pairs[c.wa + b.dst_rank], bytes);
     }
+    if (!c.count_kinds) return;
     const bool retained = box_retained(b, c.through_buffers);
     be_atomic_count(&c.sum[SUM_NRETAIN], retained);
     be_atomic_count(&c.sum[SUM_NSEND], !retained && (c.rank < 0 || b.src_rank == c.rank));

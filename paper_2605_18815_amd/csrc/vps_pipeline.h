@@ -273,6 +273,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
 
     FinishCtx fc;
     fc.rank = rank; fc.wa = WA; fc.wb = WB; fc.through_buffers = through_buffers; fc.routes_only = routes_only;
+    fc.count_kinds = true;
     fc.layout = layout; fc.tile_bytes = tile_bytes; fc.xpose_shape = xpose_shape;
     fc.sum = sum; fc.pairs = pairs; fc.used = used; fc.nslots = nslots;
 
@@ -320,43 +321,29 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     // (3) tile bases by a prefix sum, and per rank: first box, buffer offset and first tile of
     // every operation
     int64_t* rt = (int64_t*)(sum + SL.rank_tables());
-    auto rank_row = [=] VPS_LAMBDA(int64_t r, int64_t n, const vps_box* sboxes, const uint32_t* perm, const uint64_t* gsend,
-                                   const uint64_t* grecv, const int64_t* tbase) {
+    // (rows 0 and 1 of the tables, the first box of every rank in the two orders, are there before)
+    auto rank_row = [=] VPS_LAMBDA(int64_t r, int64_t n, const uint64_t* gsend, const uint64_t* grecv, const int64_t* tbase) {
         if (n == 0) {   // nothing is routed at all: no box has written the cumulative positions
-            for (int c = 0; c < 7; ++c) rt[c * (W + 1) + r] = 0;
+            for (int c = 2; c < 7; ++c) rt[c * (W + 1) + r] = 0;
             return;
         }
-        int64_t lo = 0, hi = n;
-        while (lo < hi) { const int64_t mid = (lo + hi) / 2; if (sboxes[mid].src_rank < r) lo = mid + 1; else hi = mid; }
-        const int64_t fs = lo;
-        lo = 0; hi = n;
-        while (lo < hi) { const int64_t mid = (lo + hi) / 2; if (sboxes[perm[mid]].dst_rank < r) lo = mid + 1; else hi = mid; }
-        const int64_t fr = lo;
-        rt[0 * (W + 1) + r] = fs;
-        rt[1 * (W + 1) + r] = fr;
+        const int64_t fs = rt[0 * (W + 1) + r], fr = rt[1 * (W + 1) + r];
         rt[2 * (W + 1) + r] = (int64_t)gsend[fs];
         rt[3 * (W + 1) + r] = (int64_t)grecv[fr];
         rt[4 * (W + 1) + r] = tbase[fs];
         rt[5 * (W + 1) + r] = tbase[n + fs];
         rt[6 * (W + 1) + r] = tbase[2 * n + fr];
     };
-    // (the same launch leaves a copy of the summary block in pinned host memory)
+    // (the same launch leaves a copy of the summary block in pinned host memory, unless the block
+    // is large, i.e. holds the byte matrix of an all-ranks plan: one workgroup would take longer
+    // over that than a copy command)
     std::vector<uint64_t> hsum((size_t)SL.words());
-    uint64_t* hmirror = (uint64_t*)be.host_mirror(hsum.data(), sizeof(uint64_t) * hsum.size());
+    const bool mirrored = SL.words() <= 4096;
+    uint64_t* hmirror = mirrored ? (uint64_t*)be.host_mirror(hsum.data(), sizeof(uint64_t) * hsum.size()) : nullptr;
     be.exclusive_scan_counted_then_each(step::plan_rank_tables(), ntl, tb, 3 * ns + 1, nbox, 3, rt, W + 1, 2, W + 1, [=] VPS_LAMBDA(int64_t r) {
         // (rows 0 and 1 hold the first boxes by now: the counts of the ordering pass, summed)
-        const int64_t n = (int64_t)*nbox;
-        if (n == 0) {   // nothing is routed at all: no box has written the cumulative positions
-            for (int c = 2; c < 7; ++c) rt[c * (W + 1) + r] = 0;
-            return;
-        }
-        const int64_t fs = rt[0 * (W + 1) + r], fr = rt[1 * (W + 1) + r];
-        rt[2 * (W + 1) + r] = (int64_t)gs[fs];
-        rt[3 * (W + 1) + r] = (int64_t)gr[fr];
-        rt[4 * (W + 1) + r] = tb[fs];
-        rt[5 * (W + 1) + r] = tb[n + fs];
-        rt[6 * (W + 1) + r] = tb[2 * n + fr];
-    }, sum, hmirror, SL.words());
+        rank_row(r, (int64_t)*nbox, gs, gr, tb);
+    }, sum, hmirror, mirrored ? SL.words() : 0);
 
     // (4) the tile table.  Its size is only known on the device so far; when the caller has seen
     // this transition before it passes the size as a hint and the table is built before the host
@@ -369,7 +356,8 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         be.tile_table(tb, descs, nbox, 0, ns, tiles, tiles_cap, tiles_cap);
     }
 
-    be.sync();   // the one synchronisation
+    if (mirrored) be.sync();   // the one synchronisation
+    else be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());
     if (listed && hsum[SUM_NLISTED] > BE::PLAN_LIST_CAP) {
         // more busy lanes than the list holds: nothing was emitted, so plan again without the list
         be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);
@@ -437,6 +425,13 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
                     for (int64_t d = 0; d < WB; ++d) { const uint64_t c = pcount[i * WB + d]; cn += c; cb += pbytes[i * WB + d]; sq += c * c; }
                     rows_n[i] = (int64_t)cn; rows_b[i] = (int64_t)cb;
                     if (sq) be_atomic_add(work, sq);
+                    // the statistics by kind of box fall out of the row: what a rank sends to itself
+                    // is retained, everything else is sent by it and received by a resident rank
+                    // (three counters in one memory line, bumped once per wavefront of boxes, were
+                    // the longest wait of the pass over the boxes)
+                    const uint64_t own = (!through_buffers && i < WB) ? pcount[i * WB + i] : 0;
+                    if (own) be_atomic_add(sum + SUM_NRETAIN, own);
+                    if (cn - own) { be_atomic_add(sum + SUM_NSEND, cn - own); be_atomic_add(sum + SUM_NRECV, cn - own); }
                 } else {
                     const int64_t d = i - WA;
                     VPS_UNROLL(8)
@@ -444,10 +439,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
                     cols_n[d] = (int64_t)cn; cols_b[d] = (int64_t)cb;
                 }
             });
-            be.exclusive_scan(rows_n, rows_n0, W);
-            be.exclusive_scan(cols_n, cols_n0, W);
-            be.exclusive_scan(rows_b, rows_b0, W);
-            be.exclusive_scan(cols_b, cols_b0, W);
+            be.exclusive_scan_rows(edge, edge + 4 * (W + 1), W, W + 1, 4);   // rows_n0, cols_n0, rows_b0, cols_b0
             if (W <= 256) {
                 // one lane per pair: it adds up its row to the left of it and its column above it
                 be.for_each(step::plan_pair_starts(), np, [=] VPS_LAMBDA(int64_t pr) {
@@ -498,10 +490,10 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
                 const vps_box* in = raw + me.box;
                 const uint64_t is = pstart_s[pr] + before, ir = pstart_r[pr] + before;
                 const uint64_t ps = poff_s[pr] + bytes, pq = poff_r[pr] + bytes;
-                // (word by word, then the two positions: a box changed in a local copy and stored
-                // whole would pass through scratch memory)
+                // (copied as it is, then the two positions: a box changed in a local copy and
+                // stored whole would pass through scratch memory)
                 vps_box* out = sorted + is;
-                copy_box_words(out, in);
+                *out = *in;
                 if (me.bytes_flags & ORD_SENDS) out->send_pos = ps;
                 if (me.bytes_flags & ORD_RECEIVES) out->recv_pos = pq;
                 rperm[ir] = (uint32_t)is;
@@ -514,6 +506,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             ordered = true;
         }
         const bool pair_ordered = ordered;
+        fc.count_kinds = !pair_ordered;
         if (!ordered) {
             uint64_t* kmin = be.template alloc<uint64_t>(n);
             uint64_t* kmaj = be.template alloc<uint64_t>(n);
@@ -576,16 +569,35 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         ntl = be.template alloc<int64_t>(3 * n + 1);
         tb = be.template alloc<int64_t>(3 * n + 1);
         fc.descs = descs; fc.ntiles = ntl;
-        be.for_each(step::plan_copy_descs(), 3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
-            if (i == 3 * n) { ntl[i] = 0; return; }
-            const int op = (int)(i / n);
-            const int64_t k = i - op * n;
-            const vps_box& b = sorted[op == OP_UNPACK ? rperm[k] : k];
-            if (op == OP_RETAIN) account_box(fc, b);
-            describe_box_op(fc, b, op, i);
-        });
-        be.exclusive_scan(ntl, tb, 3 * n);
-        be.for_each(step::plan_rank_tables(), W + 1, [=] VPS_LAMBDA(int64_t r) { rank_row(r, n, sorted, rperm, gs, gr, tb); });
+        // Every rank's first box in the two orders: position k is the first box of the ranks
+        // after its predecessor's up to its own (boxes ascend by rank in either order; k = n
+        // closes the tables).  One lane per position instead of a search per rank, whose
+        // dependent loads would take longer than all positions together.
+        auto first_boxes_at = [=] VPS_LAMBDA(int64_t k) {
+            const int32_t ps = k ? sorted[k - 1].src_rank : -1, cs = k < n ? sorted[k].src_rank : W;
+            for (int32_t r = ps + 1; r <= cs; ++r) rt[0 * (W + 1) + r] = k;
+            const int32_t pd = k ? sorted[rperm[k - 1]].dst_rank : -1, cd = k < n ? sorted[rperm[k]].dst_rank : W;
+            for (int32_t r = pd + 1; r <= cd; ++r) rt[1 * (W + 1) + r] = k;
+        };
+        if (routes_only) {
+            // no copy descriptors, no tiles: statistics and first boxes only
+            be.zero(tb, sizeof(int64_t) * (size_t)(3 * n + 1));
+            be.for_each(step::plan_copy_descs(), n + 1, [=] VPS_LAMBDA(int64_t k) {
+                if (k < n) account_box(fc, sorted[k]);
+                first_boxes_at(k);
+            });
+        } else {
+            be.for_each(step::plan_copy_descs(), 3 * n + 1, [=] VPS_LAMBDA(int64_t i) {
+                if (i == 3 * n) { ntl[i] = 0; first_boxes_at(n); return; }
+                const int op = (int)(i / n);
+                const int64_t k = i - op * n;
+                const vps_box& b = sorted[op == OP_UNPACK ? rperm[k] : k];
+                if (op == OP_RETAIN) { account_box(fc, b); first_boxes_at(k); }
+                describe_box_op(fc, b, op, i);
+            });
+            be.exclusive_scan(ntl, tb, 3 * n);
+        }
+        be.for_each(step::plan_rank_tables(), W + 1, [=] VPS_LAMBDA(int64_t r) { rank_row(r, n, gs, gr, tb); });
         be.download(hsum.data(), sum, sizeof(uint64_t) * hsum.size());
         if ((int64_t)hsum[SUM_NBOXES] != n) throw Error{ VPS_ERR_HIP, "planning passes disagree on the number of boxes" };
         if (pair_ordered && hsum[SUM_PAIR_WORK] > pair_work_max) {

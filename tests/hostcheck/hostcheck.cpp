@@ -86,6 +86,10 @@ public:
         int64_t acc = 0;
         for (int64_t i = 0; i <= n; ++i) { out[i] = acc; acc += in[i]; }
     }
+    void exclusive_scan_rows(const int64_t* in, int64_t* out, int64_t n, int64_t stride, int rows)
+    {
+        for (int r = 0; r < rows; ++r) exclusive_scan(in + r * stride, out + r * stride, n);
+    }
     void sort_pairs(uint64_t*& keys, uint32_t*& vals, int64_t n, int bits = 64)
     {
         for (int64_t i = 0; bits < 64 && i < n; ++i)

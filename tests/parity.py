@@ -186,8 +186,27 @@ def gather_box(buf_words, off, strides, ext):
     return buf_words[idx.ravel()]
 
 
-def validate_boxes(a, b, boxes, planned_rank, samples=0, through=False):
-    """Per-element validation of the plan by the oracle, plus exact coverage counts."""
+def check_stats(plan, boxes, planned_rank, through=False):
+    """The plan's box counts against their definitions over the box list: a box is retained when
+    its source rank is its destination rank (unless everything goes through the buffers); any
+    other box counts as sent when its source rank is resident on this GPU (the planned rank, or
+    every rank of an all-ranks plan) and as received when its destination rank is."""
+    st = plan.stats()
+    same = boxes["src_rank"] == boxes["dst_rank"]
+    retained = same & (not through)
+    src_res = np.ones(len(boxes), bool) if planned_rank < 0 else boxes["src_rank"] == planned_rank
+    dst_res = np.ones(len(boxes), bool) if planned_rank < 0 else boxes["dst_rank"] == planned_rank
+    want = dict(num_boxes=len(boxes), num_retain_boxes=int(retained.sum()), num_send_boxes=int((~retained & src_res).sum()),
+                num_recv_boxes=int((~retained & dst_res).sum()))
+    got = {k: int(st[k]) for k in want}
+    assert got == want, f"plan statistics {got}, the boxes give {want}"
+
+
+def validate_boxes(a, b, boxes, planned_rank, samples=0, through=False, plan=None):
+    """Per-element validation of the plan by the oracle, plus exact coverage counts (and the
+    plan's statistics when the plan is given)."""
+    if plan is not None:
+        check_stats(plan, boxes, planned_rank, through)
     ints, offs = boxes_to_oracle_arrays(boxes)
     bad, first = oracle.check_boxes(a, b, ints, offs, samples=samples)
     assert bad == 0, f"{bad} element violations, first bad box {first}: {boxes[first] if first >= 0 else None}"
@@ -236,7 +255,7 @@ def run_all_ranks(lib, mem, model, pa, pb, seed, rank_salt=0x9E37, check_send_pa
     check_config_against_oracle(cb, b)
     plan = lib.plan_intersections_ex(ca, cb, -1, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, -1)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, -1, through=through)
+    validate_boxes(a, b, boxes, -1, through=through, plan=plan)
     travels = (boxes["src_rank"] != boxes["dst_rank"]) | through
 
     src_host = {(r, buf): a.fill(r, buf, seed, rank_salt, pad_word=0x3C3C3C3C) for r in range(a.world) for buf in range(8)}
@@ -377,7 +396,7 @@ def run_single_rank(lib, mem, model, pa, pb, rank, seed, rank_salt=0x9E37, box_s
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
     plan = lib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through, plan=plan)
     info = plan.buffer_bytes(rank)
     if through:
         assert info["retain_total"] == 0 and plan.stats()["num_retain_tiles"] == 0
@@ -566,7 +585,7 @@ def run_single_rank_fullsize(lib, mem, model, pa, pb, rank, seed, fraction=0.05,
     ca, cb = lib.describe_config(model, pa), lib.describe_config(model, pb)
     plan = lib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else lib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through, plan=plan)
     info = plan.buffer_bytes(rank)
     log(f"  plan: {len(boxes)} boxes, send {info['send_total'] >> 20} MiB, recv {info['recv_total'] >> 20} MiB, "
         f"retain {info['retain_total'] >> 20} MiB ({time.time() - t0:.1f}s)")
@@ -635,7 +654,7 @@ def run_all_ranks_fullsize(lib, mem, model, pa, pb, seed, fraction=1.0, chunk=1 
     check_config_against_oracle(cb, b)
     plan = lib.plan_intersections(ca, cb, -1)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, -1, samples=box_samples)
+    validate_boxes(a, b, boxes, -1, samples=box_samples, plan=plan)
     info = plan.buffer_bytes(-1)
     log(f"  plan: {len(boxes)} boxes, exchanged {info['send_total'] >> 20} MiB, retained {info['retain_total'] >> 20} MiB ({time.time() - t0:.1f}s)")
     src, dst = {}, {}
@@ -771,7 +790,7 @@ def dry_run_single_rank(hlib, model, pa, pb, rank, box_samples=16, through=False
     ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
     plan = hlib.plan_intersections_ex(ca, cb, rank, PLAN_THROUGH_BUFFERS) if through else hlib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through)
+    validate_boxes(a, b, boxes, rank, samples=box_samples, through=through, plan=plan)
     info = plan.buffer_bytes(rank)
     dry = DryRun(hlib)
     es = oracle.KIND_BYTES
@@ -799,7 +818,7 @@ def dry_run_all_ranks(hlib, model, pa, pb, staged_budget=None, box_samples=4):
     ca, cb = hlib.describe_config(model, pa), hlib.describe_config(model, pb)
     plan = hlib.plan_intersections(ca, cb, -1)
     boxes = plan.get_boxes()
-    validate_boxes(a, b, boxes, -1, samples=box_samples)
+    validate_boxes(a, b, boxes, -1, samples=box_samples, plan=plan)
     es = oracle.KIND_BYTES
     dry = DryRun(hlib)
     src = [dry.buffer(dry.SRC, a.buffer_elems(r, k) * es[k % 4]) for r in range(a.world) for k in range(8)]

@@ -192,7 +192,7 @@ def test_all_ranks_planning_at_scale(lib, name):
     boxes = plan.get_boxes()
     print(f"\n{name}: {ca.num_pieces} + {cb.num_pieces} pieces in {t1 - t0:.3f}s, {len(boxes)} boxes in {t2 - t1:.3f}s "
           f"({len(boxes) / (t2 - t1) / 1e6:.2f} M boxes/s)", flush=True)
-    parity.validate_boxes(a, b, boxes, -1, samples=8)
+    parity.validate_boxes(a, b, boxes, -1, samples=8, plan=plan)
     # one rank's plan is the restriction of the all-ranks plan
     r = w["rank"]
     one = lib.plan_intersections_ex(ca, cb, r, flags=B.PLAN_ROUTES_ONLY).get_boxes()
@@ -229,7 +229,7 @@ def test_contiguous_run_beyond_32_bit_extent(lib):
     ca, cb = lib.describe_config(m, pa), lib.describe_config(m, pb)
     plan = lib.plan_intersections(ca, cb, rank)
     boxes = plan.get_boxes()
-    parity.validate_boxes(a, b, boxes, rank, samples=16)
+    parity.validate_boxes(a, b, boxes, rank, samples=16, plan=plan)
     info = plan.buffer_bytes(rank)
     assert info["send_total"] == 0 and info["recv_total"] == 0
     assert int(np.prod(boxes["ext"].astype(np.int64), axis=1).max()) > 1 << 32

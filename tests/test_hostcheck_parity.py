@@ -403,7 +403,7 @@ def test_tensors_beyond_32_bit_sizes(hlib):
     assert a.total_params > 1.6e11
     ca, cb = hlib.describe_config(m, pa), hlib.describe_config(m, pb)
     routes = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
-    parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=16)
+    parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=16, plan=routes)
     # rank 0 with copy descriptors and the tile table: its embedding shard is one contiguous
     # stretch of 8.2e9 elements, more than a 32-bit extent holds
     out = parity.dry_run_single_rank(hlib, m, pa, pb, 0)
@@ -475,7 +475,7 @@ def test_paper_table_transitions_at_model_scale(hlib, name, reverse):
     assert (a.world != b.world) == ("-to-" in name)
     ca, cb = hlib.describe_config(w["model"], pa), hlib.describe_config(w["model"], pb)
     routes = hlib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
-    parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=2)
+    parity.validate_boxes(a, b, routes.get_boxes(), -1, samples=2, plan=routes)
     if not reverse:
         # ordered by the radix sort instead of pair by pair: the same table
         hlib.set_option(B.OPT_PAIR_ORDER_WORK, 0)

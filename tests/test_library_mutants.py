@@ -51,6 +51,11 @@ MUTANTS = [m for m in [
     ("axes merged when only the source side is contiguous", "vps_core.h",
      "if (m > 0 && o3.s == x[i].s * x[i].e && o3.d == x[i].d * x[i].e && o3.e * x[i].e < ((int64_t)1 << 31)) {",
      "if (m > 0 && o3.s == x[i].s * x[i].e && o3.e * x[i].e < ((int64_t)1 << 31)) {"),
+    ("large plans: a rank's first box moved to its last", "vps_pipeline.h",
+     "for (int32_t r = ps + 1; r <= cs; ++r) rt[0 * (W + 1) + r] = k;",
+     "for (int32_t r = ps < 0 ? 0 : ps; r <= cs; ++r) rt[0 * (W + 1) + r] = k;"),
+    ("pair by pair: what a rank keeps counted as sent", "vps_pipeline.h",
+     "const uint64_t own = (!through_buffers && i < WB) ? pcount[i * WB + i] : 0;", "const uint64_t own = 0;"),
     ("block extent of a transpose not clipped", "vps_core.h",
      "ta = ext_xa - a0 < (uint32_t)XPOSE_T ? ext_xa - a0 : (uint32_t)XPOSE_T;", "ta = (uint32_t)XPOSE_T;"),
 ] if m[2] is not None]   # (entries without a site are mistakes only a device build could hold)
@@ -62,6 +67,8 @@ FIRST = {
     "pair by pair: receive offsets from the box counts": "beyond_the_counting_limit and pairs",
     "pair by pair: a box counts itself among those before it": "beyond_the_counting_limit and pairs",
     "cuts of a long run follow the descriptor to its new place": "moves_long_runs",
+    "large plans: a rank's first box moved to its last": "beyond_the_counting_limit",
+    "pair by pair: what a rank keeps counted as sent": "beyond_the_counting_limit and pairs",
 }
 
 
