@@ -126,6 +126,43 @@ def test_random_transitions(lib):
     assert ran >= 40
 
 
+def test_plans_from_two_threads_on_two_streams(lib):
+    """Calls are thread-safe on distinct handles: two host threads map and plan in loops, each on
+    a stream of its own (single ranks and all ranks, so every planner path runs), while the
+    library's pools, its cache of table sizes and the summary block that one plan clears for the
+    next are shared.  Every plan must hold the boxes of the plan made alone."""
+    import threading
+    import torch
+    cases = [(m, pa, pb, r) for _, m, pa, pb in MEDIUM[:3] for r in (-1, 0, 1)]
+    cases += [(m, pb, pa, r) for _, m, pa, pb in MEDIUM[:3] for r in (-1, 1)]
+
+    def boxes_of(m, pa, pb, r, stream):
+        plan = lib.plan_intersections(lib.describe_config(m, pa), lib.describe_config(m, pb), r, stream)
+        return plan.get_boxes(), plan.buffer_bytes(r)
+
+    alone = [boxes_of(*c, 0) for c in cases]
+    problems = []
+
+    def work(first):
+        try:
+            stream = torch.cuda.Stream()
+            for it in range(25):
+                k = (first + 7 * it) % len(cases)
+                boxes, info = boxes_of(*cases[k], stream.cuda_stream)
+                if not np.array_equal(boxes, alone[k][0]) or info != alone[k][1]:
+                    problems.append(("plan differs from the one made alone", first, it, k))
+            stream.synchronize()
+        except Exception as e:   # (an assertion in a thread would not fail the test by itself)
+            problems.append((repr(e), first))
+
+    threads = [threading.Thread(target=work, args=(f,)) for f in (0, 3)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not problems, problems[:3]
+
+
 def test_largest_world(lib):
     m = cf.model(cf.FAMILY_GPT, 8, 32, 8, 8, 4, 64, 64)
     pa, pb = cf.parallel(tp=4, pp=8, dp=1024, zero=1), cf.parallel(tp=8, pp=8, dp=512, zero=1)
