@@ -113,7 +113,10 @@ VPS_HD int32_t stage_of_layer(const ParConst& P, int32_t layer)
 {
     if (layer < 0) return 0;
     if (layer >= P.layers) return P.pp - 1;
-    return (int32_t)((((int64_t)layer + 1) * P.pp + P.layers - 1) / P.layers) - 1;
+    const int64_t num = ((int64_t)layer + 1) * P.pp + P.layers - 1;
+    // (in 32 bits when it fits: the GPU divides in software, the 64-bit form is several times the work)
+    if (num <= 0x7fffffffll) return (int32_t)((uint32_t)num / (uint32_t)P.layers) - 1;
+    return (int32_t)(num / P.layers) - 1;
 }
 
 // The tensor ids [lo, hi) that live on pipeline stage p: its layers, the embedding on the first
@@ -150,7 +153,11 @@ VPS_HD uint64_t numel4(const int32_t* s)
 
 VPS_HD uint64_t shard_elems(const ParConst& P, const TensorRec& x)
 {
-    return numel4(x.shape) / (uint64_t)(x.tp_axis >= 0 ? group_tp(P, x.group) : 1);
+    const uint64_t n = numel4(x.shape);
+    if (x.tp_axis < 0) return n;
+    const uint32_t tp = (uint32_t)group_tp(P, x.group);
+    if (n <= 0xffffffffull) return (uint32_t)n / tp;   // (see stage_of_layer)
+    return n / tp;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -375,23 +382,29 @@ VPS_HD int32_t floor_div(int32_t a, int32_t b) { return a / b - ((a % b != 0) &&
 // Evaluated in closed form: the candidates form a grid (tp range x data-parallel range) whose
 // ranks are, for every data-parallel index, one run of consecutive integers; a node is an
 // interval of ranks, so only the few runs that can touch the node are looked at.
-VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const TensorRec& x,
-                                  int32_t kind, int32_t i, int32_t j)
+//
+// Source rank i is given by its coordinates in the tensor's group (tensor-parallel index ti,
+// data-parallel index di, stage, expert-parallel index): the callers have them, and a rank number
+// would only be taken apart again.  ja / jb: j's coordinates under A and B when the caller holds
+// them (the planned rank of a single-rank plan), else nullptr.
+VPS_HD int32_t select_source_rank(const ParConst& A, const ParConst& B, const TensorRec& x, int32_t kind,
+                                  int32_t ti, int32_t di, int32_t ppi, int32_t epi, int32_t j,
+                                  const RankCoord* ja = nullptr, const RankCoord* jb = nullptr)
 {
-    const RankCoord ci = decode_rank(A, i);
+    RankCoord ci;
+    ci.pp = ppi; ci.ep = epi;
     const bool sharded = A.zero == 1 && kind != 0;
     const int32_t D = group_dp(A, x.group), T = group_tp(A, x.group);
-    const int32_t di = x.group ? ci.edp : ci.ddp, ti = x.group ? ci.etp : ci.tp;
     const int32_t t0 = x.tp_axis < 0 ? 0 : ti, t1 = x.tp_axis < 0 ? T : ti + 1;
     const int32_t d0 = sharded ? di : 0, d1 = sharded ? di + 1 : D;
     // (1) the destination rank itself, if it is one of the candidates
     if (j < A.world) {
-        const RankCoord cj = decode_rank(A, j);
+        const RankCoord cj = ja ? *ja : decode_rank(A, j);
         const int32_t dj = x.group ? cj.edp : cj.ddp, tj = x.group ? cj.etp : cj.tp;
         if (cj.pp == ci.pp && tj >= t0 && tj < t1 && dj >= d0 && dj < d1 && (!x.group || cj.ep == ci.ep))
             return j;
     }
-    const RankCoord cb = decode_rank(B, j);
+    const RankCoord cb = jb ? *jb : decode_rank(B, j);
     const int32_t dpj = x.group ? cb.edp : cb.ddp;
     const int32_t nt = t1 - t0;
     // (2) candidates on j's node.  Row q holds the ranks T*q + t: q = d + DDP*pp for dense
@@ -638,7 +651,9 @@ VPS_HD int plan_item_boxes(const PlanCtx& c, const LaneItem& it, F f, int part =
     const TensorRec& x = it.x;
     const int32_t t = it.t, kind = it.kind, tpb = it.tpb, db = it.db, dst_rank = it.dst_rank;
     const int32_t ppa = c.ma.TL[t].stage, epa = x.group ? x.expert / (A.experts / A.ep) : 0;
-    const int32_t src = select_source_rank(A, B, x, kind, encode_rank(A, x.group, it.tp_rep, it.d_rep, ppa, epa), dst_rank);
+    const bool planned_dst = c.rank >= 0 && dst_rank == c.rank;   // (then its coordinates are at hand)
+    const int32_t src = select_source_rank(A, B, x, kind, it.tp_rep, it.d_rep, ppa, epa, dst_rank,
+                                           planned_dst && c.rank < A.world ? &c.ra : nullptr, planned_dst ? &c.rb : nullptr);
     if (c.rank >= 0 && dst_rank != c.rank && src != c.rank) return 0;
     const RankCoord cs = decode_rank(A, src);
     const int32_t tps = x.group ? cs.etp : cs.tp, ds = x.group ? cs.edp : cs.ddp;
