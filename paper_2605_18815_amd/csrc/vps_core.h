@@ -78,6 +78,19 @@ struct RankCoord {
     int32_t tp, ddp, pp, ep, edp, etp;
 };
 
+// 64-bit division, out of line on the device.  The GPU divides integers in software, and a
+// 64-bit division is about a kilobyte of instructions wherever it is expanded; the planner needs
+// one only for tensors or item grids above 2^32, next to a 32-bit form that nearly always runs.
+// Its kernels run once per plan, from a cold instruction cache: what they do not have to fetch
+// is the time they save.
+#if defined(__HIP_DEVICE_COMPILE__)
+__device__ __attribute__((noinline)) uint64_t udiv64(uint64_t a, uint64_t b) { return a / b; }
+#else
+inline uint64_t udiv64(uint64_t a, uint64_t b) { return a / b; }
+#endif
+template <class U> VPS_HD U quot(U a, U b) { return a / b; }
+template <> VPS_HD uint64_t quot<uint64_t>(uint64_t a, uint64_t b) { return udiv64(a, b); }
+
 // Dense tensors see a rank as tp + TP*(ddp + DDP*pp).  The expert group sees the rank's position
 // inside its pipeline stage as etp + ETP*(ep + EP*edp): with EP and expert-DP as a grid beside TP
 // (ETP = TP, EDP = DP, DDP = EP*DP) or with EP carved out of the TP x DP ranks (ETP = 1,
@@ -116,7 +129,7 @@ VPS_HD int32_t stage_of_layer(const ParConst& P, int32_t layer)
     const int64_t num = ((int64_t)layer + 1) * P.pp + P.layers - 1;
     // (in 32 bits when it fits: the GPU divides in software, the 64-bit form is several times the work)
     if (num <= 0x7fffffffll) return (int32_t)((uint32_t)num / (uint32_t)P.layers) - 1;
-    return (int32_t)(num / P.layers) - 1;
+    return (int32_t)udiv64((uint64_t)num, (uint64_t)P.layers) - 1;
 }
 
 // The tensor ids [lo, hi) that live on pipeline stage p: its layers, the embedding on the first
@@ -141,8 +154,8 @@ VPS_HD ClassRec make_class_rec(const ParConst& P, int32_t cls, uint64_t len)
     ClassRec r;
     r.len = len;
     const uint64_t quantum = 8ull * (uint64_t)(cls < P.pp ? P.ddp : P.edp);
-    r.padded = (len + quantum - 1) / quantum * quantum;
-    r.per = r.padded / (uint64_t)(cls < P.pp ? P.ddp : P.edp);
+    r.padded = udiv64(len + quantum - 1, quantum) * quantum;
+    r.per = udiv64(r.padded, (uint64_t)(cls < P.pp ? P.ddp : P.edp));
     return r;
 }
 
@@ -157,7 +170,7 @@ VPS_HD uint64_t shard_elems(const ParConst& P, const TensorRec& x)
     if (x.tp_axis < 0) return n;
     const uint32_t tp = (uint32_t)group_tp(P, x.group);
     if (n <= 0xffffffffull) return (uint32_t)n / tp;   // (see stage_of_layer)
-    return n / tp;
+    return udiv64(n, tp);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -198,17 +211,19 @@ VPS_HD int split_linear_range_t(const int64_t* n, U v0, U v1, Emit emit)
     U cur = v0;
     while (cur < v1) {
         int q = 3;   // the coarsest axis on whose unit `cur` is aligned and whose unit still fits
-        if (cur % st2 == 0 && v1 - cur >= st2) {
+        auto multiple_of = [](U a, U b) { return a - quot(a, b) * b == 0; };
+        if (v1 - cur >= st2 && multiple_of(cur, st2)) {
             q = 2;
-            if (cur % st1 == 0 && v1 - cur >= st1) {
+            if (v1 - cur >= st1 && multiple_of(cur, st1)) {
                 q = 1;
-                if (cur % st0 == 0 && v1 - cur >= st0) q = 0;
+                if (v1 - cur >= st0 && multiple_of(cur, st0)) q = 0;
             }
         }
         const U sq = pick4(q, st0, st1, st2, st3), nq = pick4(q, n0, n1, n2, n3);
-        const U cq = (cur / sq) % nq;
+        const U units = quot(cur, sq);
+        const U cq = units - quot(units, nq) * nq;
         U cnt = nq - cq;
-        const U fit = (v1 - cur) / sq;
+        const U fit = quot((U)(v1 - cur), sq);
         if (fit < cnt) cnt = fit;
         emit((uint64_t)cur, q, (uint64_t)cnt);
         cur += cnt * sq;
@@ -304,7 +319,7 @@ VPS_HD int map_item_each_piece(const MapCtx& c, int32_t t, int32_t kind, int32_t
                     VPS_UNROLL(4)
                     for (int q = 0; q < 4; ++q) {
                         const int64_t c = bvol <= 0xffffffffull ? (int64_t)((uint32_t)rem / (uint32_t)st[q])
-                                                                : (int64_t)(rem / (uint64_t)st[q]);
+                                                                : (int64_t)udiv64(rem, (uint64_t)st[q]);
                         rem -= (uint64_t)c * (uint64_t)st[q];
                         cq[q] = (int32_t)c;
                         xq[q] = q < axis ? 1 : (q == axis ? (int32_t)cnt : (int32_t)n[q]);
@@ -344,7 +359,7 @@ VPS_HD int64_t div_small(int64_t a, int32_t b, int32_t& rem)
         rem = (int32_t)((uint32_t)a - q * (uint32_t)b);
         return (int64_t)q;
     }
-    const int64_t q = a / b;
+    const int64_t q = (int64_t)udiv64((uint64_t)a, (uint64_t)b);
     rem = (int32_t)(a - q * b);
     return q;
 }
@@ -1079,7 +1094,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
     if (d.sstr[3] == 1 && d.dstr[3] == 1) {
         d.mode = MODE_RUN;
         const uint64_t run_bytes = (uint64_t)d.ext[3] * d.es;
-        const uint64_t rows = vol / d.ext[3];
+        const uint64_t rows = udiv64(vol, d.ext[3]);
         if (rows >= (1ull << 31)) { d.ntiles = clamp_tiles(rows); return; }  // run index is 32-bit
         // 16-byte destination vectors a run can touch, counted from the 16-byte boundary at or
         // below its first byte: exact when every run of the box starts on such a boundary
@@ -1098,7 +1113,7 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
                 if (d.ext[a] > 1 && ((uint64_t)(d.dstr[a] * (int64_t)d.es) & (cut - 1))) same_phase = false;
             const uint64_t pre = same_phase ? (d.dst_byte & (cut - 1)) : cut - d.es;
             d.xa = (uint32_t)(d.dst_byte & (cut - 1));   // kept with the descriptor: see make_tile
-            d.chunks_per_row = (uint32_t)((pre + run_bytes + vt * 16 - 1) / (vt * 16));
+            d.chunks_per_row = (uint32_t)udiv64(pre + run_bytes + vt * 16 - 1, vt * 16);
             d.vec_window = (uint32_t)vt;
             d.rows_per_tile = 1;
             d.ntiles = clamp_tiles(rows * d.chunks_per_row);
@@ -1107,11 +1122,11 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
             // (fixed coordinates on axes 0 and 1), so that run addresses are affine in a tile
             d.chunks_per_row = 0;
             d.vec_window = (uint32_t)nv_max;
-            uint64_t k = vt / nv_max;
+            uint64_t k = udiv64(vt, nv_max);
             if (k < 1) k = 1;
             if (k > d.ext[2]) k = d.ext[2];
             d.rows_per_tile = (uint32_t)k;
-            const uint64_t tps = (d.ext[2] + k - 1) / k;
+            const uint64_t tps = udiv64(d.ext[2] + k - 1, k);
             d.ntiles = clamp_tiles((uint64_t)d.ext[0] * d.ext[1] * tps);
         }
     } else if (d.dstr[3] == 1 && ((d.sstr[2] == 1 && d.ext[2] > 1) || (d.sstr[1] == 1 && d.ext[1] > 1) ||
@@ -1126,13 +1141,13 @@ VPS_HD void make_copy_desc(const vps_box& b, int op, const PtrLayout& L, int32_t
         d.chunks_per_row = (uint32_t)na;
         d.vec_window = (uint32_t)nb;
         d.rows_per_tile = xpose_shape ? xpose_shape : xpose_auto_shape(d.sstr[3] * (int64_t)d.es, dstr_xa * (int64_t)d.es);
-        d.ntiles = clamp_tiles(vol / ext_xa / d.ext[3] * na * nb);
+        d.ntiles = clamp_tiles(udiv64(udiv64(vol, ext_xa), d.ext[3]) * na * nb);
     } else {
         d.mode = MODE_ELEM;
         uint64_t per = tile_bytes / (4 * d.es);
         if (per < 256) per = 256;
         d.rows_per_tile = (uint32_t)per;
-        d.ntiles = clamp_tiles((vol + per - 1) / per);
+        d.ntiles = clamp_tiles(udiv64(vol + per - 1, per));
     }
 }
 
