@@ -139,7 +139,7 @@ __device__ __forceinline__ uint64_t take_box_slot(unsigned long long* counter)
 // Boxes beyond the table's capacity are counted but not written.
 __global__ __launch_bounds__(256) void k_plan_emit(PlanCtx pc, int mode, int through, int64_t lanes,
                                                    vps_box* __restrict__ raw, OrderRec* __restrict__ recs,
-                                                   uint64_t cap, unsigned long long* counter)
+                                                   uint64_t cap, unsigned long long* counter, PairCounts pairs)
 {
     // a workgroup walks many lanes: millions of short-lived workgroups would be bound by the rate
     // at which the hardware starts them
@@ -148,10 +148,7 @@ __global__ __launch_bounds__(256) void k_plan_emit(PlanCtx pc, int mode, int thr
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < lanes; e += (int64_t)gridDim.x * 256)
         plan_lane_boxes(pc, mode, e >> pb, [&](const vps_box& b) {
             const uint64_t k = take_box_slot(counter);
-            if (k < cap) {
-                raw[k] = b;
-                recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
-            }
+            emit_box(b, make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0), k, raw, recs, cap, pairs);
         }, (int)(e & ((1 << pb) - 1)), 1 << pb);
 }
 
@@ -257,7 +254,7 @@ __global__ __launch_bounds__(256) void k_plan_filter_groups(PlanCtx pc, PlanGrou
 __global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, int through, const uint64_t* __restrict__ list,
                                                           uint64_t list_cap, const unsigned long long* __restrict__ count,
                                                           vps_box* __restrict__ raw, OrderRec* __restrict__ recs,
-                                                          uint64_t cap, unsigned long long* counter)
+                                                          uint64_t cap, unsigned long long* counter, PairCounts pairs)
 {
     uint64_t n = *count;
     if (n > list_cap) return;   // the list overflowed: the caller plans again in one launch
@@ -266,10 +263,7 @@ __global__ __launch_bounds__(256) void k_plan_emit_listed(PlanCtx pc, int mode, 
     for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256)
         plan_lane_boxes(pc, mode, (int64_t)list[i >> pb], [&](const vps_box& b) {
             const uint64_t k = take_box_slot(counter);
-            if (k < cap) {
-                raw[k] = b;
-                recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0);
-            }
+            emit_box(b, make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through != 0), k, raw, recs, cap, pairs);
         }, (int)(i & ((1u << pb) - 1)), 1 << pb);
 }
 
@@ -542,6 +536,11 @@ __device__ __forceinline__ void scan_by_one_group(const int64_t* in, int64_t* ou
 __global__ __launch_bounds__(256) void k_scan_one_group(const int64_t* in, int64_t* out, int64_t n)
 {
     scan_by_one_group(in, out, n);
+}
+
+__global__ __launch_bounds__(256) void k_zero_words(uint64_t* __restrict__ p, uint64_t n)
+{
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) p[i] = 0;
 }
 
 // Several short arrays at a constant distance from each other, one workgroup each.
@@ -859,7 +858,7 @@ public:
     static constexpr int64_t PLAN_LIST_FROM_ALL = 1ll << 13;   // the same for all-ranks plans
 
     bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
-                   uint64_t* listed, bool two_launches)
+                   uint64_t* listed, bool two_launches, const PairCounts& pairs)
     {
         const int64_t lanes = plan_num_lanes(pc, mode);
         if (lanes <= 0) return false;
@@ -880,7 +879,7 @@ public:
             }
             hipLaunchKernelGGL(k_plan_emit_listed, dim3(2048), dim3(256), 0, stream_, pc, mode, through ? 1 : 0,
                                (const uint64_t*)list, PLAN_LIST_CAP, (const unsigned long long*)listed, raw, recs, cap,
-                               (unsigned long long*)counter);
+                               (unsigned long long*)counter, pairs);
             VPS_HIP_CHECK(hipGetLastError());
             free(list);
             return true;
@@ -889,7 +888,7 @@ public:
         blocks = (callers + 255) / 256;
         if (blocks > 8192) blocks = 8192;
         hipLaunchKernelGGL(k_plan_emit, dim3((unsigned)blocks), dim3(256), 0, stream_, pc, mode, through ? 1 : 0, callers,
-                           raw, recs, cap, (unsigned long long*)counter);
+                           raw, recs, cap, (unsigned long long*)counter, pairs);
         VPS_HIP_CHECK(hipGetLastError());
         return false;
     }
@@ -1007,10 +1006,21 @@ public:
         VPS_HIP_CHECK(hipMemcpyAsync(stage, dev, bytes, hipMemcpyDeviceToHost, stream_));
     }
 
+    // (a kernel of this library when the range is a whole number of aligned 64-bit words, which
+    // the planner's tables are: the runtime's memset costs the host three times a kernel launch,
+    // and a large plan clears several small tables between its passes)
     void zero(void* dev, size_t bytes)
     {
         if (!bytes) return;
-        VPS_HIP_CHECK(hipMemsetAsync(dev, 0, bytes, stream_));
+        if (((uintptr_t)dev | bytes) & 7u) {
+            VPS_HIP_CHECK(hipMemsetAsync(dev, 0, bytes, stream_));
+            return;
+        }
+        const uint64_t words = bytes / 8;
+        uint64_t blocks = (words + 1023) / 1024;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_zero_words, dim3((unsigned)blocks), dim3(256), 0, stream_, (uint64_t*)dev, words);
+        VPS_HIP_CHECK(hipGetLastError());
     }
 
     void sync()

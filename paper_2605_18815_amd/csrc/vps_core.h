@@ -831,6 +831,31 @@ VPS_HD OrderPlace order_by_counting(const OrderRec* recs, uint32_t n, uint32_t k
     return o;
 }
 
+// Where the emission also counts its boxes per (source, destination) pair (all-ranks plans that
+// are known to be large: the pair-by-pair ordering then starts from these counts instead of a
+// pass of its own over the boxes).  count == nullptr: not counted.
+struct PairCounts {
+    uint64_t* count;   // [src * wb + dst] boxes
+    uint64_t* bytes;   // [src * wb + dst] 16-byte-rounded bytes of the boxes that travel
+    int32_t wb;
+};
+
+VPS_HD void be_atomic_add_runs(uint64_t* base, int64_t index, uint64_t v);
+
+// One emitted box: its slot k of the raw table (boxes beyond the capacity are counted only).
+VPS_HD void emit_box(const vps_box& b, const OrderRec& rec, uint64_t k, vps_box* raw, OrderRec* recs, uint64_t cap, const PairCounts& pc)
+{
+    if (k < cap) {
+        raw[k] = b;
+        recs[k] = rec;
+    }
+    if (pc.count) {
+        const int64_t pr = (int64_t)b.src_rank * pc.wb + b.dst_rank;
+        be_atomic_add_runs(pc.count, pr, 1);
+        be_atomic_add_runs(pc.bytes, pr, (rec.bytes_flags & ORD_SENDS) ? (rec.bytes_flags & ~(uint64_t)15) : 0);
+    }
+}
+
 // Words at the head of a plan's summary block.
 enum { SUM_NBOXES = 0, SUM_NRETAIN = 1, SUM_NSEND = 2, SUM_NRECV = 3, SUM_NLISTED = 4, SUM_PAIR_WORK = 5, SUM_HEADER = 8 };
 

@@ -265,9 +265,22 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     vps_box* raw = be.template alloc<vps_box>(cap);
     OrderRec* recs = be.template alloc<OrderRec>(cap);
     bool listed = false;
+    // An all-ranks plan that is known to be large (the caller has seen the transition before) is
+    // going to be ordered pair by pair: then the emission counts its boxes per pair as it makes
+    // them, which saves that ordering its first pass over the box table.
+    const bool pair_path = pair_work_log2 > 0 && rank < 0 && (int64_t)WA * WB <= PAIR_BUCKET_MAX_PAIRS;
+    const int64_t np = (int64_t)WA * WB;
+    uint64_t* pcount = nullptr;   // [4 np]: boxes per pair, buffer bytes per pair, scatter cursors, first places in the send order
+    PairCounts counted;
+    counted.count = counted.bytes = nullptr; counted.wb = WB;
+    if (pair_path && box_hint > (int64_t)small_limit) {
+        pcount = be.template alloc<uint64_t>(4 * np);
+        be.zero(pcount, sizeof(uint64_t) * (size_t)(3 * np));
+        counted.count = pcount; counted.bytes = pcount + np;
+    }
     auto emit = [&](bool two_launches) {
         listed = be.plan_emit(pc, rank < 0 ? PLAN_ALL : PLAN_RANK, through_buffers, raw, recs, (uint64_t)cap, sum + SUM_NBOXES,
-                              sum + SUM_NLISTED, two_launches);
+                              sum + SUM_NLISTED, two_launches, counted);
     };
     emit(lane_list);
 
@@ -361,7 +374,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
     if (listed && hsum[SUM_NLISTED] > BE::PLAN_LIST_CAP) {
         // more busy lanes than the list holds: nothing was emitted, so plan again without the list
         be.free(sum); be.free(raw); be.free(recs); be.free(sorted); be.free(rperm); be.free(gs); be.free(gr);
-        be.free(descs); be.free(ntl); be.free(tb); be.free(tiles);
+        be.free(descs); be.free(ntl); be.free(tb); be.free(tiles); be.free(pcount);
         build_plan(be, ca, cb, rank, tile_bytes, xpose_shape, small_limit, routes_only, through_buffers, tile_hint, box_hint, p, false,
                    pair_work_log2);
         return;
@@ -382,6 +395,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             raw = be.template alloc<vps_box>(cap);
             recs = be.template alloc<OrderRec>(cap);
             be.zero(sum, sizeof(uint64_t) * (size_t)SL.words());
+            if (pcount) be.zero(pcount, sizeof(uint64_t) * (size_t)(3 * np));
             emit(lane_list);
         } else {
             be.zero(sum + 1, sizeof(uint64_t) * (size_t)(SL.words() - 1));
@@ -394,9 +408,9 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         // that is out of proportion (or the matrix too large) the radix path below takes over.
         bool ordered = false;
         const uint64_t pair_work_max = pair_work_log2 > 0 ? (uint64_t)1 << pair_work_log2 : 0;
-        if (pair_work_log2 > 0 && rank < 0 && (int64_t)WA * WB <= PAIR_BUCKET_MAX_PAIRS) {
-            const int64_t np = (int64_t)WA * WB;
-            uint64_t* pcount = be.template alloc<uint64_t>(4 * np);     // boxes per pair
+        if (pair_path) {
+            const bool counted_already = pcount != nullptr;
+            if (!pcount) pcount = be.template alloc<uint64_t>(4 * np);  // boxes per pair
             uint64_t* pbytes = pcount + np;                               // buffer bytes per pair
             uint64_t* pcur = pbytes + np;                                 // scatter cursors
             uint64_t* pstart_s = pcur + np;                               // first place of the pair in the send order
@@ -408,15 +422,17 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             int64_t* rows_n0 = edge + 4 * (W + 1), *cols_n0 = edge + 5 * (W + 1), *rows_b0 = edge + 6 * (W + 1), *cols_b0 = edge + 7 * (W + 1);
             PairRec* bucket = be.template alloc<PairRec>(n);
             uint64_t* work = sum + SUM_PAIR_WORK;
-            be.zero(pcount, sizeof(uint64_t) * (size_t)(3 * np));
             be.zero(edge, sizeof(int64_t) * (size_t)(4 * (W + 1)));
-            be.for_each(step::plan_pair_counts(), n, [=] VPS_LAMBDA(int64_t k) {
-                const vps_box& b = raw[k];
-                const int64_t pr = (int64_t)b.src_rank * WB + b.dst_rank;
-                be_atomic_add_runs(pcount, pr, 1);
-                const uint64_t bf = recs[k].bytes_flags;
-                be_atomic_add_runs(pbytes, pr, (bf & ORD_SENDS) ? (bf & ~(uint64_t)15) : 0);
-            });
+            if (!counted_already) {
+                be.zero(pcount, sizeof(uint64_t) * (size_t)(3 * np));
+                be.for_each(step::plan_pair_counts(), n, [=] VPS_LAMBDA(int64_t k) {
+                    const vps_box& b = raw[k];
+                    const int64_t pr = (int64_t)b.src_rank * WB + b.dst_rank;
+                    be_atomic_add_runs(pcount, pr, 1);
+                    const uint64_t bf = recs[k].bytes_flags;
+                    be_atomic_add_runs(pbytes, pr, (bf & ORD_SENDS) ? (bf & ~(uint64_t)15) : 0);
+                });
+            }
             // sums of the rows (one source rank each) and of the columns (one destination rank each)
             be.for_each(step::plan_pair_sums(), (int64_t)WA + WB, [=] VPS_LAMBDA(int64_t i) {
                 uint64_t cn = 0, cb = 0, sq = 0;
@@ -503,6 +519,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
             });
             be.free(before_of);
             be.free(pcount); be.free(pstart_r); be.free(edge); be.free(bucket);
+            pcount = nullptr;
             ordered = true;
         }
         const bool pair_ordered = ordered;
@@ -611,6 +628,7 @@ void build_plan(BE& be, const ConfigData& ca, const ConfigData& cb, int32_t rank
         }
     }
     be.free(raw); be.free(recs); be.free(gs); be.free(gr); be.free(ntl);
+    be.free(pcount);   // (counted for nothing when the plan turned out small)
 
     // (5) the host's view of the plan
     {

@@ -136,17 +136,14 @@ public:
 
     static constexpr uint64_t PLAN_LIST_CAP = 1ull << 22;
     bool plan_emit(const PlanCtx& pc, int mode, bool through, vps_box* raw, OrderRec* recs, uint64_t cap, uint64_t* counter,
-                   uint64_t*, bool)
+                   uint64_t*, bool, const PairCounts& pairs)
     {
         const int pb = plan_part_bits(mode);
         const int64_t callers = plan_num_lanes(pc, mode) << pb;
         for (int64_t e = 0; e < callers; ++e)
             plan_lane_boxes(pc, mode, e >> pb, [&](const vps_box& b) {
                 const uint64_t k = (*counter)++;
-                if (k < cap) {
-                    raw[k] = b;
-                    recs[k] = make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through);
-                }
+                emit_box(b, make_order_rec(b, pc.ma.T[b.tensor], pc.rank, through), k, raw, recs, cap, pairs);
             }, (int)(e & ((1 << pb) - 1)), 1 << pb);
         return false;
     }

@@ -56,6 +56,9 @@ MUTANTS = [m for m in [
      "for (int32_t r = ps < 0 ? 0 : ps; r <= cs; ++r) rt[0 * (W + 1) + r] = k;"),
     ("pair by pair: what a rank keeps counted as sent", "vps_pipeline.h",
      "const uint64_t own = (!through_buffers && i < WB) ? pcount[i * WB + i] : 0;", "const uint64_t own = 0;"),
+    ("pairs counted by the emission: every box counts as travelling", "vps_core.h",
+     "be_atomic_add_runs(pc.bytes, pr, (rec.bytes_flags & ORD_SENDS) ? (rec.bytes_flags & ~(uint64_t)15) : 0);",
+     "be_atomic_add_runs(pc.bytes, pr, rec.bytes_flags & ~(uint64_t)15);"),
     ("block extent of a transpose not clipped", "vps_core.h",
      "ta = ext_xa - a0 < (uint32_t)XPOSE_T ? ext_xa - a0 : (uint32_t)XPOSE_T;", "ta = (uint32_t)XPOSE_T;"),
 ] if m[2] is not None]   # (entries without a site are mistakes only a device build could hold)
@@ -69,6 +72,7 @@ FIRST = {
     "cuts of a long run follow the descriptor to its new place": "moves_long_runs",
     "large plans: a rank's first box moved to its last": "beyond_the_counting_limit",
     "pair by pair: what a rank keeps counted as sent": "beyond_the_counting_limit and pairs",
+    "pairs counted by the emission: every box counts as travelling": "beyond_the_counting_limit and pairs",
 }
 
 
