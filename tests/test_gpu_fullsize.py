@@ -202,13 +202,18 @@ def test_all_ranks_planning_at_scale(lib, name):
     assert np.array_equal(np.sort(one[keys], order=keys), np.sort(sel[keys], order=keys))
     # the two ways of ordering a large all-ranks plan (pair by pair, radix sort) and the switch from
     # the first to the second give the same table, positions included
-    for work in (0, 1):
+    # (and, with the default bound again, the plan that knows its size from the ones before and
+    # counts its boxes per pair while it emits them)
+    for work in (0, 1, 32):
         lib.set_option(B.OPT_PAIR_ORDER_WORK, work)
         try:
-            again = lib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY).get_boxes()
+            replan = lib.plan_intersections_ex(ca, cb, -1, flags=B.PLAN_ROUTES_ONLY)
+            again = replan.get_boxes()
         finally:
             lib.set_option(B.OPT_PAIR_ORDER_WORK, 32)
         assert again.tobytes() == boxes.tobytes(), f"ordering with work bound 2^{work} differs"
+        parity.check_stats(replan, again, -1)
+        assert replan.buffer_bytes(-1) == plan.buffer_bytes(-1)
     cls = plan.classify_collectives(ca)
     print("  collective intent per (tensor, kind) [none, p2p, broadcast, scatter, gather]:", np.bincount(cls, minlength=5), flush=True)
 
